@@ -1,0 +1,247 @@
+/*
+ * CPU oracle for the CDQuant hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, scalar C that states what the path computes, written from the
+ * paper (arXiv 2406.17542).  Nothing in the product path may call it: only
+ * tests, the smoke check and the benchmark's cpu_baseline leg do.  It shares
+ * no code, header, table or helper with the HIP library.
+ *
+ * Conventions (weight space, one Hessian for every output column):
+ *   Wt, Q        [d_out][d_in] row-major: row j is output column j of the
+ *                paper's W (Section 3, Notation), so every row is one
+ *                independent problem of the form of Eq. (1).
+ *   scale, zero  [d_out][d_in/group]: the paper's a and b, one pair per group
+ *                of `group` consecutive input coordinates (Section 3.2);
+ *                group == d_in is per-channel quantization.
+ *   e = a*q + b - w   (the quantization residual of one column)
+ *   g = H e           (half the gradient of Eq. (1) with respect to a*q)
+ *
+ * The paper's Algorithm 1 keeps g_p = 2H(q - (w-b)/a) = (2/a) H e and scores a
+ * move of coordinate i to level r by u^2 H_ii + u g_p,i with u = r - q_i.
+ * Multiplying by the positive per-column constant a^2 gives
+ *   s(i,r) = delta^2 H_ii + 2 delta g_i,  delta = a u,
+ * which is the exact change of the loss of Eq. (1).  With per-group scales the
+ * appendix's Algorithm 4 rescales X by diag(a); substituting H~ = D_a H D_a
+ * into its score gives the same s(i,r) with delta = a_grp(i) u.  So one routine
+ * serves Algorithm 1 and Algorithm 4.
+ *
+ * Readings where the paper is silent:
+ *   - arg-min ties: smallest score, then smallest i, then smallest r.
+ *   - a move is committed only if its score is < 0; otherwise the column has
+ *     reached a coordinate-wise optimum and stops (later iterations are no-ops).
+ *   - "canonical" fp32 arithmetic of the *_f32 routines, so that another fp32
+ *     implementation can reproduce them bit for bit:
+ *         e_i   = fmaf(a, (float)q_i, b) - w_i
+ *         g_i   = (float) sum_k (double)H_ik * (double)e_k     (k ascending)
+ *         delta = a * (float)(r - q_i)
+ *         s     = delta * fmaf(delta, H_ii, 2*g_i)
+ *         g_k  <- fmaf(delta*, H[i*][k], g_k)
+ *
+ * Pins (tests/test_oracle_*.py): brute force over all codes on tiny layers,
+ * score == recomputed loss change, monotone loss, diagonal-H closed form,
+ * agreement with a literal code-space transcription of Algorithms 1 and 4
+ * (oracle/paper_form.py), ||XE||^2 == tr(E^T H E).  The paper prints no worked
+ * numeric example, so no value here is pinned to a printed number.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+/* ---- residual e = a q + b - w  (Section 3, Notation; groups: Section 3.2) ---- */
+
+void cdqo_residual_f32(const float *Wt, const uint8_t *Q, const float *scale, const float *zero,
+                       int64_t d_out, int64_t d_in, int64_t group, float *E)
+{
+    const int64_t n_grp = d_in / group;
+    for (int64_t j = 0; j < d_out; ++j)
+        for (int64_t i = 0; i < d_in; ++i) {
+            const float a = scale[j * n_grp + i / group];
+            const float b = zero[j * n_grp + i / group];
+            E[j * d_in + i] = fmaf(a, (float)Q[j * d_in + i], b) - Wt[j * d_in + i];
+        }
+}
+
+void cdqo_residual_f64(const double *Wt, const uint8_t *Q, const double *scale, const double *zero,
+                       int64_t d_out, int64_t d_in, int64_t group, double *E)
+{
+    const int64_t n_grp = d_in / group;
+    for (int64_t j = 0; j < d_out; ++j)
+        for (int64_t i = 0; i < d_in; ++i) {
+            const double a = scale[j * n_grp + i / group];
+            const double b = zero[j * n_grp + i / group];
+            E[j * d_in + i] = a * (double)Q[j * d_in + i] + b - Wt[j * d_in + i];
+        }
+}
+
+/* ---- g = H e for every column (Algorithm 1, "Compute gradient", rescaled) ---- */
+
+void cdqo_gradient_f32(const float *H, const float *E, int64_t d_out, int64_t d_in, float *G)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < d_out; ++j)
+        for (int64_t i = 0; i < d_in; ++i) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < d_in; ++k)
+                acc += (double)H[i * d_in + k] * (double)E[j * d_in + k];
+            G[j * d_in + i] = (float)acc;
+        }
+}
+
+void cdqo_gradient_f64(const double *H, const double *E, int64_t d_out, int64_t d_in, double *G)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < d_out; ++j)
+        for (int64_t i = 0; i < d_in; ++i) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < d_in; ++k)
+                acc += H[i * d_in + k] * E[j * d_in + k];
+            G[j * d_in + i] = acc;
+        }
+}
+
+/* ---- loss_j = e_j^T H e_j  (Eq. (1) written with H = X^T X) ---- */
+
+void cdqo_loss_f64(const double *H, const double *E, int64_t d_out, int64_t d_in, double *loss)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < d_out; ++j) {
+        double tot = 0.0;
+        for (int64_t i = 0; i < d_in; ++i) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < d_in; ++k)
+                acc += H[i * d_in + k] * E[j * d_in + k];
+            tot += E[j * d_in + i] * acc;
+        }
+        loss[j] = tot;
+    }
+}
+
+/* ---- greedy coordinate descent (Algorithm 1; Algorithm 4 for groups) ----
+ *
+ * G holds g = H e of the initial codes on entry and of the final codes on
+ * exit; Q holds q_0 on entry and q_T on exit.  Per column: moves[j] = number
+ * of committed moves, converged[j] = 1 if the column stopped because no move
+ * lowers the loss.  If trace_cap > 0 the committed moves of column j are
+ * recorded in trace_i/trace_r/trace_s[j*trace_cap + m] for m < trace_cap.
+ */
+
+void cdqo_greedy_cd_f32(const float *H, const float *scale, uint8_t *Q, float *G,
+                        int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T,
+                        int32_t *moves, int32_t *converged,
+                        int32_t *trace_i, int32_t *trace_r, float *trace_s, int64_t trace_cap)
+{
+    const int levels = 1 << bits;
+    const int64_t n_grp = d_in / group;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t j = 0; j < d_out; ++j) {
+        uint8_t *q = Q + j * d_in;
+        float *g = G + j * d_in;
+        const float *a = scale + j * n_grp;
+        int32_t n_moves = 0, done = 0;
+        for (int64_t t = 0; t < T; ++t) {
+            /* arg-min over every coordinate and every level (Algorithm 1, the arg-min step) */
+            float best_s = 0.0f;
+            int64_t best_i = -1;
+            int best_r = -1;
+            for (int64_t i = 0; i < d_in; ++i) {
+                const float ai = a[i / group];
+                const float hii = H[i * d_in + i];
+                const float two_g = 2.0f * g[i];
+                for (int r = 0; r < levels; ++r) {
+                    if (r == (int)q[i]) continue;
+                    const float delta = ai * (float)(r - (int)q[i]);
+                    const float s = delta * fmaf(delta, hii, two_g);
+                    if (s < best_s) { best_s = s; best_i = i; best_r = r; }
+                }
+            }
+            if (best_i < 0) { done = 1; break; }          /* coordinate-wise optimum */
+            const float delta = a[best_i / group] * (float)(best_r - (int)q[best_i]);
+            if (n_moves < trace_cap) {
+                trace_i[j * trace_cap + n_moves] = (int32_t)best_i;
+                trace_r[j * trace_cap + n_moves] = best_r;
+                trace_s[j * trace_cap + n_moves] = best_s;
+            }
+            q[best_i] = (uint8_t)best_r;                   /* code update */
+            const float *hrow = H + best_i * d_in;         /* H symmetric: row = column */
+            for (int64_t k = 0; k < d_in; ++k)             /* gradient update */
+                g[k] = fmaf(delta, hrow[k], g[k]);
+            ++n_moves;
+        }
+        moves[j] = n_moves;
+        converged[j] = done;
+    }
+}
+
+void cdqo_greedy_cd_f64(const double *H, const double *scale, uint8_t *Q, double *G,
+                        int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T,
+                        int32_t *moves, int32_t *converged,
+                        int32_t *trace_i, int32_t *trace_r, double *trace_s, int64_t trace_cap)
+{
+    const int levels = 1 << bits;
+    const int64_t n_grp = d_in / group;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t j = 0; j < d_out; ++j) {
+        uint8_t *q = Q + j * d_in;
+        double *g = G + j * d_in;
+        const double *a = scale + j * n_grp;
+        int32_t n_moves = 0, done = 0;
+        for (int64_t t = 0; t < T; ++t) {
+            double best_s = 0.0;
+            int64_t best_i = -1;
+            int best_r = -1;
+            for (int64_t i = 0; i < d_in; ++i) {
+                const double ai = a[i / group];
+                const double hii = H[i * d_in + i];
+                for (int r = 0; r < levels; ++r) {
+                    if (r == (int)q[i]) continue;
+                    const double delta = ai * (double)(r - (int)q[i]);
+                    const double s = delta * (delta * hii + 2.0 * g[i]);
+                    if (s < best_s) { best_s = s; best_i = i; best_r = r; }
+                }
+            }
+            if (best_i < 0) { done = 1; break; }
+            const double delta = a[best_i / group] * (double)(best_r - (int)q[best_i]);
+            if (n_moves < trace_cap) {
+                trace_i[j * trace_cap + n_moves] = (int32_t)best_i;
+                trace_r[j * trace_cap + n_moves] = best_r;
+                trace_s[j * trace_cap + n_moves] = best_s;
+            }
+            q[best_i] = (uint8_t)best_r;
+            const double *hrow = H + best_i * d_in;
+            for (int64_t k = 0; k < d_in; ++k)
+                g[k] += delta * hrow[k];
+            ++n_moves;
+        }
+        moves[j] = n_moves;
+        converged[j] = done;
+    }
+}
+
+/* ---- one arg-min step on its own (Algorithm 1, the arg-min step), for
+ * checking a score/arg-min kernel in isolation: returns per column the best
+ * (i, r, s) or i = -1 when no move has a negative score. ---- */
+
+void cdqo_argmin_f32(const float *Hdiag, const float *scale, const uint8_t *Q, const float *G,
+                     int64_t d_out, int64_t d_in, int bits, int64_t group,
+                     int32_t *out_i, int32_t *out_r, float *out_s)
+{
+    const int levels = 1 << bits;
+    const int64_t n_grp = d_in / group;
+    for (int64_t j = 0; j < d_out; ++j) {
+        float best_s = 0.0f;
+        int32_t best_i = -1, best_r = -1;
+        for (int64_t i = 0; i < d_in; ++i) {
+            const float ai = scale[j * n_grp + i / group];
+            const int qi = Q[j * d_in + i];
+            const float two_g = 2.0f * G[j * d_in + i];
+            for (int r = 0; r < levels; ++r) {
+                if (r == qi) continue;
+                const float delta = ai * (float)(r - qi);
+                const float s = delta * fmaf(delta, Hdiag[i], two_g);
+                if (s < best_s) { best_s = s; best_i = (int32_t)i; best_r = r; }
+            }
+        }
+        out_i[j] = best_i; out_r[j] = best_r; out_s[j] = best_s;
+    }
+}

@@ -1,0 +1,80 @@
+"""Literal fp64 transcriptions of the paper's own formulations.  TEST INFRASTRUCTURE ONLY.
+
+These follow the paper's notation (code space: the gradient is taken with
+respect to the integer codes q, the score is u^2 H_ii + u g_i) rather than the
+weight-space form the C oracle and the HIP library use.  They exist so the
+C oracle can be pinned against an independent statement of the same method:
+the two forms must select the same sequence of moves.
+
+One column at a time, numpy fp64, tiny sizes only.
+"""
+from __future__ import annotations
+
+import itertools
+
+import numpy as np
+
+
+def layer_loss(X, w, a, b, q):
+    """Eq. (1): ||X (w - a q - b)||_2^2 for one column; a, b scalars or per-coordinate
+    vectors (the sub-channel form, appendix 'CDQuant for sub-channel quantization')."""
+    r = X @ (w - a * q - b)
+    return float(r @ r)
+
+
+def greedy_cd_code_space(X, w, a, b, q0, T, bits):
+    """Algorithm 1, step by step as printed: H = X^T X, g = 2H(q0 - (w-b)/a),
+    then T times: arg-min over (i, r) of (r-q_i)^2 H_ii + (r-q_i) g_i, gradient
+    update with column i* of H, code update.  The table of scores contains
+    r = q_i (score 0); when its minimum is not negative the step is a no-op, so
+    the loop stops there.  Returns (q_T, list of (i*, r*, score))."""
+    X = np.asarray(X, np.float64)
+    H = X.T @ X
+    q = np.asarray(q0, np.float64).copy()
+    g = 2.0 * H @ (q - (w - b) / a)
+    levels = np.arange(1 << bits, dtype=np.float64)
+    moves = []
+    for _ in range(T):
+        u = levels[None, :] - q[:, None]
+        score = u * u * np.diag(H)[:, None] + u * g[:, None]
+        flat = int(np.argmin(score))            # first minimum in (i, r) order
+        i, r = divmod(flat, 1 << bits)
+        if not score[i, r] < 0.0:
+            break
+        g = g + 2.0 * (r - q[i]) * H[:, i]
+        moves.append((i, r, float(score[i, r])))
+        q[i] = r
+    return q.astype(np.int64), moves
+
+
+def greedy_cd_sub_channel(X, w, a_vec, b_vec, q0, T, bits):
+    """Algorithm 4: rescale X~ = X diag(a), w~ = w / a, b~ = b / a (as the
+    appendix text defines them) and run Algorithm 1 on the rescaled problem with
+    unit scale.  Scores returned are those of the rescaled problem, which equal
+    the true loss change."""
+    a_vec = np.asarray(a_vec, np.float64)
+    Xt = np.asarray(X, np.float64) * a_vec[None, :]
+    return greedy_cd_code_space(Xt, np.asarray(w, np.float64) / a_vec, 1.0,
+                                np.asarray(b_vec, np.float64) / a_vec, q0, T, bits)
+
+
+def brute_force_best(X, w, a, b, bits):
+    """Global minimum of Eq. (1) over all codes, by enumeration (d_in <= 8 or so)."""
+    d = X.shape[1]
+    best, best_q = np.inf, None
+    for code in itertools.product(range(1 << bits), repeat=d):
+        q = np.array(code, np.float64)
+        v = layer_loss(X, w, a, b, q)
+        if v < best:
+            best, best_q = v, q
+    return best, best_q.astype(np.int64)
+
+
+def clip_grid(w, bits, gamma):
+    """Eq. (2): a = gamma (max w - min w) / (2^c - 1), b = min w,
+    q = clamp(round((w - b)/a), 0, 2^c - 1).  fp64, one group."""
+    w = np.asarray(w, np.float64)
+    a = gamma * (w.max() - w.min()) / ((1 << bits) - 1)
+    b = w.min()
+    q = np.clip(np.rint((w - b) / a), 0, (1 << bits) - 1)
+    return a, b, q.astype(np.int64)

@@ -1,0 +1,437 @@
+"""Pins for the CPU oracle: each test checks it against something other than itself --
+a hand-worked fixture, the loss recomputed from X, brute force over all codes, a closed
+form, or the paper's own code-space formulation (oracle/paper_form.py).
+
+The paper (arXiv 2406.17542) prints no numeric worked example of Algorithm 1, so none of
+these expected values is a printed number; they are what the definitions fix.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import paper_form as pf
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _read_fixture(name):
+    out = {}
+    with open(os.path.join(GOLD, name)) as f:
+        lines = [l.strip() for l in f if l.strip() and not l.startswith("#")]
+    i = 0
+    while i < len(lines):
+        tok = lines[i].split()
+        key = tok[0]
+        if key in ("X", "H"):
+            r, c = int(tok[1]), int(tok[2])
+            out[key] = np.array([[float(v) for v in lines[i + 1 + k].split()] for k in range(r)])
+            assert out[key].shape == (r, c)
+            i += 1 + r
+        elif key == "move":
+            out.setdefault("move", []).append((int(tok[1]), int(tok[2]), float(tok[3])))
+            i += 1
+        else:
+            vals = [float(v) for v in tok[1:]]
+            out[key] = vals[0] if len(vals) == 1 else np.array(vals)
+            i += 1
+    return out
+
+
+def _rand_layer(rng, d_in, d_out, n, corr=0.0):
+    """Random X with optional shared component (correlated channels make CD move)."""
+    X = rng.standard_normal((n, d_in))
+    if corr:
+        X = X + corr * rng.standard_normal((n, 1))
+    Wt = (rng.standard_normal((d_out, d_in)) / np.sqrt(d_in)).astype(np.float32)
+    return X, Wt
+
+
+# ----------------------------------------------------------------------------- Hessian
+
+def test_hessian_worked_example(oracle):
+    fx = _read_fixture("hessian_2x2.txt")
+    assert np.array_equal(oracle.hessian(fx["X"]), fx["H"])
+
+
+def test_hessian_properties(oracle):
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((37, 11))
+    H = oracle.hessian(X)
+    assert np.array_equal(H, H.T)
+    np.testing.assert_allclose(np.diag(H), (X * X).sum(0), rtol=1e-13)
+    # entry (i,k) is the inner product of columns i and k -- not of rows
+    np.testing.assert_allclose(H[2, 7], float(X[:, 2] @ X[:, 7]), rtol=1e-13)
+    assert np.linalg.eigvalsh(H).min() > -1e-9
+    Hl = oracle.hessian(X, lambda_rel=0.25)
+    np.testing.assert_allclose(Hl - H, 0.25 * np.mean(np.diag(H)) * np.eye(11), atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- grid / RTN (Eq. 2)
+
+@pytest.mark.parametrize("bits,group", [(2, 8), (3, 24), (4, 12)])
+def test_rtn_is_nearest_level(oracle, bits, group):
+    """Eq. (2) with gamma = 1: every code is the grid level nearest to w (checked by
+    searching all 2^c levels), scale/bias are the min-max ones."""
+    rng = np.random.default_rng(bits)
+    Wt = rng.standard_normal((5, 24)).astype(np.float32)
+    a, b, q = oracle.init_grid(Wt, bits, group)
+    L = 1 << bits
+    n_grp = 24 // group
+    for j in range(5):
+        for gi in range(n_grp):
+            w = Wt[j, gi * group:(gi + 1) * group].astype(np.float64)
+            assert b[j, gi] == np.float32(w.min())
+            np.testing.assert_allclose(a[j, gi], (w.max() - w.min()) / (L - 1), rtol=3e-7)
+            levels = float(a[j, gi]) * np.arange(L) + float(b[j, gi])
+            nearest = np.abs(w[:, None] - levels[None, :]).argmin(1)
+            got = q[j, gi * group:(gi + 1) * group]
+            # a point within rounding distance of a midpoint may go either way in fp32
+            d = np.abs(w[:, None] - levels[None, :])
+            d.sort(axis=1)
+            clear = (d[:, 1] - d[:, 0]) > 1e-5 * float(a[j, gi])
+            assert np.array_equal(got[clear], nearest[clear])
+            assert got.min() == 0 and got.max() == L - 1      # min and max map to the end levels
+
+
+def test_rtn_half_to_even_and_constant_group(oracle):
+    # w - b = k + 0.5 exactly with a = 1: halves go to the even neighbour
+    Wt = np.array([[0.0, 0.5, 1.5, 2.5, 3.0, 1.0]], np.float32)
+    a, b, q = oracle.init_grid(Wt, 2, 6)
+    assert a[0, 0] == 1.0 and b[0, 0] == 0.0
+    assert q.tolist() == [[0, 0, 2, 2, 3, 1]]
+    # constant group: scale 1, all codes 0, reproduces w exactly
+    Wc = np.full((1, 4), 0.3, np.float32)
+    a, b, q = oracle.init_grid(Wc, 3, 4)
+    assert a[0, 0] == 1.0 and b[0, 0] == np.float32(0.3) and not q.any()
+
+
+def test_clip_grid_matches_paper_form(oracle):
+    """Eq. (2) with gamma < 1: only the upper end is clipped (b stays min w)."""
+    rng = np.random.default_rng(5)
+    Wt = rng.standard_normal((3, 16)).astype(np.float32)
+    for gam in (0.3, 0.62, 1.0):
+        a, b, q = oracle.init_grid(Wt, 3, 16, np.float32(gam))
+        for j in range(3):
+            a64, b64, q64 = pf.clip_grid(Wt[j], 3, float(np.float32(gam)))
+            np.testing.assert_allclose(a[j, 0], a64, rtol=3e-7)
+            assert b[j, 0] == np.float32(b64)
+            assert (q[j] != q64).sum() <= 1        # fp32 vs fp64 may differ at a midpoint
+            assert q[j].max() == 7                 # clipped values saturate at the top level
+
+
+# ----------------------------------------------------------------------------- residual / gradient / loss
+
+def test_residual_gradient_loss_against_X(oracle):
+    """e = a q + b - w with per-group a, b; g = H e; loss = ||X e||^2 = e^T H e."""
+    rng = np.random.default_rng(7)
+    X, Wt = _rand_layer(rng, 12, 5, 40, corr=1.0)       # d_out != d_in: a transposed layout would fail
+    H = oracle.hessian(X)
+    a, b, q = oracle.init_grid(Wt, 3, 4)
+    q = rng.integers(0, 8, q.shape).astype(np.uint8)
+    E = oracle.residual(Wt, q, a, b, 4, "f64")
+    for j in range(5):
+        for i in range(12):
+            assert E[j, i] == float(a[j, i // 4]) * q[j, i] + float(b[j, i // 4]) - float(Wt[j, i])
+    G = oracle.gradient(H, E, "f64")
+    np.testing.assert_allclose(G, (X.T @ (X @ E.T)).T, rtol=1e-11, atol=1e-11)
+    l = oracle.loss(H, Wt, q, a, b, 4)
+    np.testing.assert_allclose(l, ((X @ E.T) ** 2).sum(0), rtol=1e-11)
+    # fp32 flavour: fmaf residual, fp64 accumulation rounded once
+    E32 = oracle.residual(Wt, q, a, b, 4, "f32")
+    np.testing.assert_allclose(E32, E, rtol=0, atol=2e-7)
+    H32 = H.astype(np.float32)
+    G32 = oracle.gradient(H32, E32, "f32")
+    exact = np.array([[float(sum(Fraction(float(H32[i, k])) * Fraction(float(E32[j, k])) for k in range(12)))
+                       for i in range(12)] for j in range(5)])
+    assert np.array_equal(G32, exact.astype(np.float32))
+
+
+# ----------------------------------------------------------------------------- greedy CD
+
+def test_cd_hand_worked_example(oracle):
+    fx = _read_fixture("greedy_cd_2coord.txt")
+    H = fx["H"]
+    w = np.asarray(fx["w"], np.float32)[None, :]
+    a = np.array([[fx["scale"]]], np.float32)
+    b = np.array([[fx["zero"]]], np.float32)
+    q0 = np.asarray(fx["q0"], np.uint8)[None, :]
+    bits = int(fx["bits"])
+    assert oracle.loss(H, w, q0, a, b, 2)[0] == fx["loss_initial"]
+    for prec in ("f32", "f64"):
+        r = oracle.greedy_cd(H, w, a, b, q0, bits, 2, 8, precision=prec, trace_cap=8)
+        assert r["moves"][0] == int(fx["moves"]) and r["converged"][0] == 1
+        i, rr, s = fx["move"][0]
+        assert (r["trace_i"][0, 0], r["trace_r"][0, 0], r["trace_s"][0, 0]) == (i, rr, s)
+        assert r["Q"][0].tolist() == list(fx["q_final"])
+        assert r["G"][0].tolist() == list(fx["g_final"])
+        assert oracle.loss(H, w, r["Q"], a, b, 2)[0] == fx["loss_final"]
+
+
+def _exact_greedy(Hq, w, a_vec, b_vec, q0, bits, T):
+    """Greedy CD from its definition in exact rational arithmetic: at every step recompute
+    the full loss e^T H e of every single-coordinate change and take the largest decrease
+    (ties: smallest i, then smallest level)."""
+    d = len(w)
+    q = list(q0)
+
+    def L(qq):
+        e = [a_vec[i] * qq[i] + b_vec[i] - w[i] for i in range(d)]
+        return sum(e[i] * Hq[i][k] * e[k] for i in range(d) for k in range(d))
+
+    seq = []
+    for _ in range(T):
+        base = L(q)
+        best = (Fraction(0), -1, -1)
+        for i in range(d):
+            for r in range(1 << bits):
+                if r == q[i]:
+                    continue
+                qq = list(q)
+                qq[i] = r
+                dl = L(qq) - base
+                if dl < best[0]:
+                    best = (dl, i, r)
+        if best[1] < 0:
+            break
+        q[best[1]] = best[2]
+        seq.append((best[1], best[2], best[0]))
+    return q, seq
+
+
+@pytest.mark.parametrize("seed,bits,group", [(0, 2, 6), (1, 3, 6), (2, 2, 3), (3, 4, 2)])
+def test_cd_equals_exact_greedy_definition(oracle, seed, bits, group):
+    """The closed-form score (Section 3.1) selects the same moves as recomputing the loss of
+    every candidate exactly; the recorded score is that loss change."""
+    rng = np.random.default_rng(seed)
+    d = 6
+    X = np.round(rng.standard_normal((12, d)) * 8) / 8 + np.round(rng.standard_normal((12, 1)) * 8) / 8
+    Wt = (np.round(rng.standard_normal((3, d)) * 64) / 64).astype(np.float32)
+    H = oracle.hessian(X)
+    a, b, _ = oracle.init_grid(Wt, bits, group)
+    q0 = rng.integers(0, 1 << bits, (3, d)).astype(np.uint8)
+    r = oracle.greedy_cd(H, Wt, a, b, q0, bits, group, 40, precision="f64", trace_cap=40)
+    Hq = [[Fraction(float(v)) for v in row] for row in H]
+    for j in range(3):
+        av = [Fraction(float(a[j, i // group])) for i in range(d)]
+        bv = [Fraction(float(b[j, i // group])) for i in range(d)]
+        qf, seq = _exact_greedy(Hq, [Fraction(float(v)) for v in Wt[j]], av, bv, q0[j].tolist(), bits, 40)
+        m = r["moves"][j]
+        assert m == len(seq) and r["converged"][j] == 1
+        assert [(int(r["trace_i"][j, k]), int(r["trace_r"][j, k])) for k in range(m)] == [(s[0], s[1]) for s in seq]
+        np.testing.assert_allclose(r["trace_s"][j, :m], [float(s[2]) for s in seq], rtol=1e-9)
+        assert r["Q"][j].tolist() == qf
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_cd_brute_force_tiny(oracle, seed):
+    """d_in <= 6, 2 bits: the end point is a coordinate-wise optimum of Eq. (1) and
+    global minimum <= CD <= RTN."""
+    rng = np.random.default_rng(100 + seed)
+    d = 5 + seed % 2
+    X, Wt = _rand_layer(rng, d, 2, 4 * d, corr=1.5)
+    H = oracle.hessian(X)
+    a, b, q0 = oracle.init_grid(Wt, 2, d)
+    r = oracle.greedy_cd(H.astype(np.float32), Wt, a, b, q0, 2, d, 4 * d, trace_cap=4 * d)
+    for j in range(2):
+        w = Wt[j].astype(np.float64)
+        aj, bj = float(a[j, 0]), float(b[j, 0])
+        l_rtn = pf.layer_loss(X, w, aj, bj, q0[j].astype(np.float64))
+        l_cd = pf.layer_loss(X, w, aj, bj, r["Q"][j].astype(np.float64))
+        l_opt, _ = pf.brute_force_best(X, w, aj, bj, 2)
+        assert l_opt <= l_cd * (1 + 1e-9) and l_cd <= l_rtn * (1 + 1e-9)
+        assert r["converged"][j] == 1
+        for i in range(d):                         # no single-coordinate change lowers the loss
+            for lev in range(4):
+                qq = r["Q"][j].astype(np.float64)
+                qq[i] = lev
+                assert pf.layer_loss(X, w, aj, bj, qq) >= l_cd * (1 - 1e-6)
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_cd_scores_are_loss_changes_and_monotone(oracle, prec):
+    """Each committed score equals L(after) - L(before) recomputed from X (Section 3.1,
+    closed form of the loss change); hence the loss never increases."""
+    rng = np.random.default_rng(11)
+    d_in, d_out, n, bits, group = 24, 4, 96, 3, 8
+    X, Wt = _rand_layer(rng, d_in, d_out, n, corr=1.0)
+    H = oracle.hessian(X)
+    a, b, q0 = oracle.init_grid(Wt, bits, group)
+    q0[1:] = rng.integers(0, 1 << bits, q0[1:].shape)   # column 0 from RTN, the rest from arbitrary codes
+    Hin = H.astype(np.float32) if prec == "f32" else H
+    r = oracle.greedy_cd(Hin, Wt, a, b, q0, bits, group, 3 * d_in, precision=prec, trace_cap=3 * d_in)
+    assert r["moves"].sum() > d_out           # the case must exercise the loop
+    for j in range(d_out):
+        av = np.repeat(a[j].astype(np.float64), group)
+        bv = np.repeat(b[j].astype(np.float64), group)
+        w = Wt[j].astype(np.float64)
+        q = q0[j].astype(np.float64)
+        prev = pf.layer_loss(X, w, av, bv, q)
+        for k in range(r["moves"][j]):
+            q[r["trace_i"][j, k]] = r["trace_r"][j, k]
+            cur = pf.layer_loss(X, w, av, bv, q)
+            assert cur < prev
+            tol = 1e-9 if prec == "f64" else 2e-4
+            np.testing.assert_allclose(r["trace_s"][j, k], cur - prev, rtol=tol, atol=tol * prev)
+            prev = cur
+        assert np.array_equal(q.astype(np.uint8), r["Q"][j])
+        # the maintained g equals H e of the final codes
+        E = oracle.residual(Wt[j:j + 1], r["Q"][j:j + 1], a[j:j + 1], b[j:j + 1], group, "f64")
+        np.testing.assert_allclose(r["G"][j], H @ E[0], rtol=1e-4 if prec == "f32" else 1e-10,
+                                   atol=1e-4 if prec == "f32" else 1e-10)
+
+
+def test_cd_iteration_budget_and_prefix(oracle):
+    """T bounds the number of moves; a run with smaller T is a prefix of a longer one."""
+    rng = np.random.default_rng(12)
+    X, Wt = _rand_layer(rng, 32, 3, 128, corr=2.0)
+    H = oracle.hessian(X).astype(np.float32)
+    a, b, _ = oracle.init_grid(Wt, 3, 32)
+    q0 = rng.integers(0, 8, (3, 32)).astype(np.uint8)
+    full = oracle.greedy_cd(H, Wt, a, b, q0, 3, 32, 200, trace_cap=200)
+    part = oracle.greedy_cd(H, Wt, a, b, q0, 3, 32, 5, trace_cap=200)
+    assert (part["moves"] == np.minimum(full["moves"], 5)).all()
+    assert (part["converged"] == (full["moves"] < 5)).all()
+    assert np.array_equal(part["trace_i"][:, :5], full["trace_i"][:, :5])
+    zero = oracle.greedy_cd(H, Wt, a, b, q0, 3, 32, 0)
+    assert np.array_equal(zero["Q"], q0) and not zero["moves"].any()
+    # resuming from the partial codes continues the same trajectory (codes are the whole state)
+    rest = oracle.greedy_cd(H, Wt, a, b, part["Q"], 3, 32, 200, precision="f64")
+    full64 = oracle.greedy_cd(H, Wt, a, b, q0, 3, 32, 200, precision="f64")
+    assert np.array_equal(rest["Q"], full64["Q"])
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_cd_diagonal_hessian_closed_form(oracle, bits):
+    """Diagonal H makes Eq. (1) separable: round-to-nearest is optimal.  From RTN, CD makes no
+    move; from arbitrary codes it reaches exactly the RTN codes, touching each coordinate once."""
+    rng = np.random.default_rng(20 + bits)
+    d_in, d_out = 40, 6
+    Wt = rng.standard_normal((d_out, d_in)).astype(np.float32)
+    H = np.diag(rng.uniform(0.5, 4.0, d_in))
+    a, b, q_rtn = oracle.init_grid(Wt, bits, d_in)
+    for prec in ("f32", "f64"):
+        r0 = oracle.greedy_cd(H, Wt, a, b, q_rtn, bits, d_in, d_in, precision=prec)
+        assert not r0["moves"].any() and r0["converged"].all()
+        q0 = rng.integers(0, 1 << bits, (d_out, d_in)).astype(np.uint8)
+        r = oracle.greedy_cd(H, Wt, a, b, q0, bits, d_in, 2 * d_in, precision=prec, trace_cap=2 * d_in)
+        assert np.array_equal(r["Q"], q_rtn)
+        assert (r["moves"] == (q0 != q_rtn).sum(1)).all()
+        for j in range(d_out):
+            ti = r["trace_i"][j, :r["moves"][j]]
+            assert len(set(ti.tolist())) == len(ti)
+
+
+def test_cd_single_coordinate(oracle):
+    """d_in = 1: one move to the level nearest to w (H is a positive scalar)."""
+    Wt = np.array([[0.1], [0.9], [2.6]], np.float32)
+    a = np.ones((3, 1), np.float32)
+    b = np.zeros((3, 1), np.float32)
+    q0 = np.array([[3], [3], [0]], np.uint8)
+    r = oracle.greedy_cd(np.array([[2.5]]), Wt, a, b, q0, 2, 1, 4)
+    assert r["Q"][:, 0].tolist() == [0, 1, 3] and r["moves"].tolist() == [1, 1, 1]
+
+
+def test_cd_dead_channel_never_moves(oracle):
+    """An all-zero input channel has H_ii = 0 and a zero row: every score is 0, never selected."""
+    rng = np.random.default_rng(31)
+    X, Wt = _rand_layer(rng, 10, 3, 50, corr=1.0)
+    X[:, 4] = 0.0
+    H = oracle.hessian(X).astype(np.float32)
+    a, b, _ = oracle.init_grid(Wt, 3, 10)
+    q0 = rng.integers(0, 8, (3, 10)).astype(np.uint8)
+    r = oracle.greedy_cd(H, Wt, a, b, q0, 3, 10, 100, trace_cap=100)
+    assert np.array_equal(r["Q"][:, 4], q0[:, 4])
+    assert np.isfinite(r["G"]).all() and (r["G"][:, 4] == 0).all()
+
+
+@pytest.mark.parametrize("group", [16, 4])
+def test_weight_space_equals_paper_code_space(oracle, group):
+    """Algorithm 1 (per-channel) and Algorithm 4 (sub-channel, X~ = X diag(a)) as printed,
+    in code space, select the same moves and scores as the weight-space form."""
+    rng = np.random.default_rng(40 + group)
+    d_in, d_out, n, bits = 16, 3, 64, 3
+    X, Wt = _rand_layer(rng, d_in, d_out, n, corr=1.0)
+    H = oracle.hessian(X)
+    a, b, q0 = oracle.init_grid(Wt, bits, group)
+    r = oracle.greedy_cd(H, Wt, a, b, q0, bits, group, 4 * d_in, precision="f64", trace_cap=4 * d_in)
+    assert r["moves"].sum() > 0
+    for j in range(d_out):
+        av = np.repeat(a[j].astype(np.float64), group)
+        bv = np.repeat(b[j].astype(np.float64), group)
+        w = Wt[j].astype(np.float64)
+        if group == d_in:
+            qf, mv = pf.greedy_cd_code_space(X, w, av[0], bv[0], q0[j], 4 * d_in, bits)
+            sc = av[0] ** 2                     # paper's score is the loss change divided by a^2
+        else:
+            qf, mv = pf.greedy_cd_sub_channel(X, w, av, bv, q0[j], 4 * d_in, bits)
+            sc = 1.0
+        m = r["moves"][j]
+        assert len(mv) == m
+        assert [(x[0], x[1]) for x in mv] == [(int(r["trace_i"][j, k]), int(r["trace_r"][j, k])) for k in range(m)]
+        np.testing.assert_allclose([x[2] * sc for x in mv], r["trace_s"][j, :m], rtol=1e-8)
+        assert np.array_equal(qf, r["Q"][j])
+
+
+def test_argmin_step_is_first_move(oracle):
+    rng = np.random.default_rng(50)
+    X, Wt = _rand_layer(rng, 48, 7, 200, corr=1.0)
+    H = oracle.hessian(X).astype(np.float32)
+    a, b, q0 = oracle.init_grid(Wt, 3, 16)
+    r = oracle.greedy_cd(H, Wt, a, b, q0, 3, 16, 1, trace_cap=1)
+    E = oracle.residual(Wt, q0, a, b, 16)
+    G = oracle.gradient(H, E)
+    oi, orr, os_ = oracle.argmin_step(np.diag(H).copy(), a, q0, G, 3, 16)
+    for j in range(7):
+        if r["moves"][j]:
+            assert (oi[j], orr[j], os_[j]) == (r["trace_i"][j, 0], r["trace_r"][j, 0], r["trace_s"][j, 0])
+        else:
+            assert oi[j] == -1
+
+
+def test_f32_tracks_f64_on_tiny_config(oracle):
+    """Canonical fp32 arithmetic is not fragile: on the tiny configuration it ends within
+    1e-4 relative of the fp64 run's loss and agrees on nearly all codes."""
+    from paper_2406_17542_amd import inputs
+    cfg = inputs.CONFIGS["tiny"]
+    X, Wt = inputs.make_layer(cfg)
+    H = oracle.hessian(X)
+    a, b, q0 = oracle.init_grid(Wt, cfg.bits, cfg.group)
+    r32 = oracle.greedy_cd(H.astype(np.float32), Wt, a, b, q0, cfg.bits, cfg.group, cfg.T)
+    r64 = oracle.greedy_cd(H, Wt, a, b, q0, cfg.bits, cfg.group, cfg.T, precision="f64")
+    agree = (r32["Q"] == r64["Q"]).mean()
+    l32 = oracle.loss(H, Wt, r32["Q"], a, b, cfg.group).sum()
+    l64 = oracle.loss(H, Wt, r64["Q"], a, b, cfg.group).sum()
+    l0 = oracle.loss(H, Wt, q0, a, b, cfg.group).sum()
+    assert agree >= 0.99
+    assert abs(l32 - l64) <= 1e-4 * l64
+    assert l64 <= l0
+
+
+# ----------------------------------------------------------------------------- OWC
+
+def test_owc_grid_search(oracle):
+    """OWC (Section 3.1): per column the chosen gamma minimises Eq. (1) over the grid, as
+    recomputed from X with the fp64 paper form; gamma = 1 is on the grid, so OWC <= MinMax."""
+    rng = np.random.default_rng(60)
+    d_in, d_out, n, bits = 20, 4, 80, 3
+    X, Wt = _rand_layer(rng, d_in, d_out, n, corr=0.5)
+    Wt[:, 3] *= 6.0                                # an outlier weight makes clipping pay off
+    H = oracle.hessian(X)
+    a, b, q, gam, all_loss = oracle.init_owc(H, Wt, bits, d_in, 50)
+    gammas = oracle.owc_gammas(50)
+    assert gammas[-1] == 1.0 and gammas[0] == np.float32(0.02) and len(gammas) == 50
+    a1, b1, q1 = oracle.init_grid(Wt, bits, d_in)
+    l_owc = oracle.loss(H, Wt, q, a, b, d_in)
+    assert (l_owc <= oracle.loss(H, Wt, q1, a1, b1, d_in) * (1 + 1e-12)).all()
+    assert (gam < 1).any()
+    for j in range(d_out):
+        w = Wt[j].astype(np.float64)
+        ref = []
+        for g_ in gammas:
+            aa, bb, qq = pf.clip_grid(w, bits, float(g_))
+            ref.append(pf.layer_loss(X, w, aa, bb, qq.astype(np.float64)))
+        ref = np.array(ref)
+        np.testing.assert_allclose(l_owc[j], ref.min(), rtol=1e-3)
+        np.testing.assert_allclose(all_loss[:, j], ref, rtol=2e-2)
