@@ -1,0 +1,151 @@
+/*
+ * libcdq -- the hot path of CDQuant (arXiv 2406.17542, "Greedy Coordinate Descent for Accurate
+ * LLM Quantization") for AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * Problem (paper Section 3, Notation and Eq. (1)): a linear layer with weight W [d_in x d_out]
+ * and calibration inputs X [n x d_in] is quantized column by column; every output column w is
+ * replaced by a*q + b with integer codes q in {0..2^c-1}, so as to minimise
+ * ||X (w - a q - b)||^2 = e^T H e,  H = X^T X,  e = a q + b - w.
+ * With sub-channel quantization (Section 3.2) a and b are constant on groups of `group`
+ * consecutive input coordinates.
+ *
+ * Conventions common to every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library never frees or
+ *     keeps one.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on that stream and return; they do not synchronise the device.
+ *   - Wt, Q are [d_out][d_in] row-major: row j is output column j of the paper's W (the layout
+ *     of a torch nn.Linear weight).  scale, zero are [d_out][d_in/group] (the paper's a, b).
+ *     H is [d_in][d_in] fp32, full storage, and must be symmetric.
+ *   - bits in {2,3,4}; d_in % group == 0; group == d_in means per-channel.
+ *   - `workspace` is device scratch of at least cdq_workspace_bytes(op, ...) bytes, 256-byte
+ *     aligned; its contents are undefined afterwards.  Calls sharing a workspace must be
+ *     ordered on one stream.
+ *   - Return value: CDQ_OK or a negative error code; nothing is enqueued when an argument
+ *     check fails.  No global mutable state.
+ */
+#ifndef CDQ_H
+#define CDQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CDQ_OK            0
+#define CDQ_EINVAL       (-1)   /* null pointer, bad shape, bits not in {2,3,4}, d_in % group != 0 ... */
+#define CDQ_EWORKSPACE   (-2)   /* workspace missing, misaligned or too small */
+#define CDQ_EHIP         (-3)   /* a HIP runtime call failed (launch error, wrong device ...) */
+#define CDQ_EUNSUPPORTED (-4)   /* valid request outside what the kernels cover (e.g. d_in too large) */
+
+#define CDQ_F32  0
+#define CDQ_BF16 1
+
+/* operations for cdq_workspace_bytes */
+#define CDQ_OP_HESSIAN   0
+#define CDQ_OP_GREEDY_CD 1
+#define CDQ_OP_LOSS      2
+#define CDQ_OP_INIT_OWC  3
+
+#define CDQ_MAX_D_IN 32768      /* largest d_in the register-resident CD kernel covers */
+
+/* Per-column outcome of cdq_greedy_cd. */
+typedef struct {
+    int32_t moves;        /* committed coordinate updates */
+    int32_t iters;        /* iterations executed (== moves, +1 if the last one found no move) */
+    int32_t converged;    /* 1: stopped because no single-coordinate move lowers the loss */
+    float   last_score;   /* score (loss change) of the last committed move, 0 if none */
+} cdq_col_stats;
+
+/* Optional controls for cdq_greedy_cd_ex; zero-initialise for defaults. */
+typedef struct {
+    int32_t  waves_per_column;  /* 0 = choose; else 1,2,4,8,16 wavefronts cooperating on a column */
+    int32_t  elems_per_lane;    /* 0 = choose; else 4,8,16,32 coordinates held per lane */
+    int32_t *trace;             /* NULL, or [d_out][trace_cap]: move m of column j is stored as
+                                   i* * 64 + (u* + 32), u* = r* - q_i* the signed level change */
+    int64_t  trace_cap;
+    float   *G_out;             /* NULL, or [d_out][d_in]: g = H e as maintained at exit */
+} cdq_cd_options;
+
+const char *cdq_strerror(int code);
+
+/* Bytes of workspace an operation needs for the given shape (host-only, no GPU access).
+ * n is used by CDQ_OP_HESSIAN only. */
+size_t cdq_workspace_bytes(int op, int64_t n, int64_t d_out, int64_t d_in);
+
+/*
+ * Hessian of the layer objective: H = X^T X (paper Section 3, Notation; Algorithm 1,
+ * "Compute Hessian"), optionally damped H += lambda*I as in Section 4 ("we regularize the
+ * Hessian ... by adding lambda I").  The paper does not give lambda; here
+ * lambda = lambda_rel * mean(diag H), lambda_rel = 0 disables it.
+ *   X           [n][d_in] row-major, bf16 (CDQ_BF16) or fp32 (CDQ_F32); d_in % 8 == 0 for bf16,
+ *               % 4 == 0 for fp32 (rows must be 16-byte aligned)
+ *   H           [d_in][d_in] fp32 out (both triangles written, exactly symmetric)
+ *   accumulate  0: H = X^T X;  1: H += X^T X (streaming over chunks of tokens; H must already
+ *               hold a symmetric matrix).  Damping, if requested, is applied after the sum.
+ * Products are exact (bf16) or fp32, accumulation is fp32 on the matrix cores; the summation
+ * order over tokens is fixed, so results are reproducible run to run.
+ */
+int cdq_hessian(const void *X, int x_dtype, int64_t n, int64_t d_in, float *H, int accumulate,
+                float lambda_rel, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * MinMax grid and round-to-nearest codes: Eq. (2) with clipping strength gamma = 1, per
+ * (column, group): zero = min w, scale = (max w - min w)/(2^bits - 1),
+ * Q = clamp(round_half_even((w - zero)/scale), 0, 2^bits - 1), all in IEEE fp32.
+ * A constant group gets scale = 1 and codes 0.
+ *   Wt [d_out][d_in] in;  scale, zero [d_out][d_in/group] out;  Q [d_out][d_in] out.
+ */
+int cdq_init_rtn(const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t group,
+                 float *scale, float *zero, uint8_t *Q, void *stream);
+
+/*
+ * Gradient initialisation of Algorithm 1 ("Compute gradient g at q0"), in weight space:
+ * G[j][:] = H e_j with e_j = scale*Q[j] + zero - Wt[j] (the paper's g is (2/a) times this).
+ * fp32 inputs, fp64 accumulation on the matrix cores, one rounding to fp32.
+ *   G [d_out][d_in] out.
+ */
+int cdq_gradient(const float *H, const float *Wt, const float *scale, const float *zero,
+                 const uint8_t *Q, int64_t d_out, int64_t d_in, int64_t group, float *G,
+                 void *stream);
+
+/*
+ * Greedy coordinate descent, Algorithm 1 (Algorithm 4 of the appendix when group < d_in),
+ * run independently for all d_out columns.  Per column, up to T times: over all coordinates i
+ * and levels r != q_i take the move with the smallest
+ *     s(i,r) = delta * fma(delta, H_ii, 2 g_i),  delta = scale_grp(i) * (r - q_i)
+ * (the exact loss change; the paper's score times scale^2); ties go to the smallest i, then
+ * the smallest r.  If s >= 0 the column is at a coordinate-wise optimum and stops.  Otherwise
+ * commit Q[j][i*] = r* and g <- fma(delta*, H[i*][:], g).  All T iterations run inside one
+ * kernel launch with g held in registers.
+ *   Q      in: initial codes q0 (from cdq_init_rtn, cdq_init_owc, or a previous run);
+ *          out: final codes.
+ *   stats  NULL or [d_out] out.
+ *   T      >= 0 (0 leaves Q unchanged).
+ * Needs d_in <= CDQ_MAX_D_IN, else CDQ_EUNSUPPORTED.
+ */
+int cdq_greedy_cd(const float *H, const float *Wt, const float *scale, const float *zero,
+                  uint8_t *Q, int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T,
+                  cdq_col_stats *stats, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Same, with explicit launch shape and optional move trace / final gradient (opts may be NULL). */
+int cdq_greedy_cd_ex(const float *H, const float *Wt, const float *scale, const float *zero,
+                     uint8_t *Q, int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T,
+                     cdq_col_stats *stats, const cdq_cd_options *opts,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Layer loss of Eq. (1) from the codes: loss_per_col[j] = e_j^T H e_j, loss_total = sum_j
+ * (= ||X (W - W_hat)||_F^2).  fp32 inputs, fp64 accumulation, fixed summation order.
+ *   loss_per_col  NULL or [d_out] fp64 out;  loss_total  NULL or one fp64 out (device).
+ */
+int cdq_loss(const float *H, const float *Wt, const float *scale, const float *zero,
+             const uint8_t *Q, int64_t d_out, int64_t d_in, int64_t group,
+             double *loss_per_col, double *loss_total,
+             void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CDQ_H */

@@ -1,0 +1,166 @@
+"""Thin binding over libcdq.so (see include/cdq.h).  Argument marshalling only: every step of
+the path runs in the HIP kernels.  torch is used for device memory and streams, nothing else.
+
+There is no fallback: if the library is missing or a call fails, this raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcdq.so")
+
+CDQ_F32, CDQ_BF16 = 0, 1
+OP_HESSIAN, OP_GREEDY_CD, OP_LOSS, OP_INIT_OWC = 0, 1, 2, 3
+MAX_D_IN = 32768
+
+_lib = None
+
+
+class CdqError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: cdq error {code}: {lib().cdq_strerror(code).decode()}")
+
+
+class ColStats(ctypes.Structure):
+    _fields_ = [("moves", ctypes.c_int32), ("iters", ctypes.c_int32), ("converged", ctypes.c_int32),
+                ("last_score", ctypes.c_float)]
+
+
+class CdOptions(ctypes.Structure):
+    _fields_ = [("waves_per_column", ctypes.c_int32), ("elems_per_lane", ctypes.c_int32),
+                ("trace", ctypes.c_void_p), ("trace_cap", ctypes.c_int64), ("G_out", ctypes.c_void_p)]
+
+
+def lib() -> ctypes.CDLL:
+    """Load libcdq.so; build it in-tree first if it is not there (needs hipcc)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        L.cdq_strerror.restype = ctypes.c_char_p
+        L.cdq_strerror.argtypes = [i32]
+        L.cdq_workspace_bytes.restype = sz
+        L.cdq_workspace_bytes.argtypes = [i32, i64, i64, i64]
+        L.cdq_hessian.argtypes = [vp, i32, i64, i64, vp, i32, f32, vp, sz, vp]
+        L.cdq_init_rtn.argtypes = [vp, i64, i64, i32, i64, vp, vp, vp, vp]
+        L.cdq_gradient.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp]
+        L.cdq_greedy_cd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, sz, vp]
+        L.cdq_greedy_cd_ex.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, ctypes.POINTER(CdOptions), vp, sz, vp]
+        L.cdq_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
+        for fn in (L.cdq_hessian, L.cdq_init_rtn, L.cdq_gradient, L.cdq_greedy_cd, L.cdq_greedy_cd_ex, L.cdq_loss):
+            fn.restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(code: int, what: str) -> None:
+    if code != 0:
+        raise CdqError(code, what)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, what: str) -> int:
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{what}: need a contiguous CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
+    return t.data_ptr()
+
+
+def workspace_bytes(op: int, n: int, d_out: int, d_in: int) -> int:
+    return int(lib().cdq_workspace_bytes(op, n, d_out, d_in))
+
+
+def _workspace(op: int, n: int, d_out: int, d_in: int, ws: torch.Tensor | None) -> torch.Tensor:
+    need = max(workspace_bytes(op, n, d_out, d_in), 256)
+    if ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    return ws
+
+
+def hessian(X: torch.Tensor, H: torch.Tensor | None = None, accumulate: bool = False, lambda_rel: float = 0.0,
+            workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """H = X^T X (+ damping).  X [n][d_in] bf16 or fp32 on the GPU."""
+    n, d_in = X.shape
+    if X.dtype == torch.bfloat16:
+        dt = CDQ_BF16
+    elif X.dtype == torch.float32:
+        dt = CDQ_F32
+    else:
+        raise TypeError("X must be bfloat16 or float32")
+    if H is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing H")
+        H = torch.empty((d_in, d_in), dtype=torch.float32, device=X.device)
+    ws = _workspace(OP_HESSIAN, n, 0, d_in, workspace)
+    _check(lib().cdq_hessian(_dev(X, X.dtype, "X"), dt, n, d_in, _dev(H, torch.float32, "H"), int(accumulate),
+                             float(lambda_rel), ws.data_ptr(), ws.numel(), _stream()), "cdq_hessian")
+    return H
+
+
+def init_rtn(Wt: torch.Tensor, bits: int, group: int):
+    """MinMax grid + round-to-nearest codes.  Returns (scale, zero, Q)."""
+    d_out, d_in = Wt.shape
+    n_grp = d_in // group if group > 0 and d_in % group == 0 else 1
+    scale = torch.empty((d_out, n_grp), dtype=torch.float32, device=Wt.device)
+    zero = torch.empty((d_out, n_grp), dtype=torch.float32, device=Wt.device)
+    Q = torch.empty((d_out, d_in), dtype=torch.uint8, device=Wt.device)
+    _check(lib().cdq_init_rtn(_dev(Wt, torch.float32, "Wt"), d_out, d_in, bits, group, scale.data_ptr(), zero.data_ptr(),
+                              Q.data_ptr(), _stream()), "cdq_init_rtn")
+    return scale, zero, Q
+
+
+def gradient(H, Wt, scale, zero, Q, group: int) -> torch.Tensor:
+    """G = E H, E = scale*Q + zero - Wt (fp64 accumulation, fp32 result)."""
+    d_out, d_in = Wt.shape
+    G = torch.empty((d_out, d_in), dtype=torch.float32, device=Wt.device)
+    _check(lib().cdq_gradient(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), _dev(scale, torch.float32, "scale"),
+                              _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, group,
+                              G.data_ptr(), _stream()), "cdq_gradient")
+    return G
+
+
+def greedy_cd(H, Wt, scale, zero, Q, bits: int, group: int, T: int, stats: bool = True,
+              workspace: torch.Tensor | None = None, waves_per_column: int = 0, elems_per_lane: int = 0,
+              trace_cap: int = 0, want_G: bool = False):
+    """Greedy coordinate descent in place on Q.  Returns a dict with 'stats' (int32 [d_out][4] view:
+    moves, iters, converged, last_score bits), and optionally 'trace' and 'G'."""
+    d_out, d_in = Wt.shape
+    ws = _workspace(OP_GREEDY_CD, 0, d_out, d_in, workspace)
+    st = torch.zeros((d_out, 4), dtype=torch.int32, device=Wt.device) if stats else None
+    out = {}
+    opts = CdOptions(waves_per_column, elems_per_lane, None, 0, None)
+    if trace_cap > 0:
+        out["trace"] = torch.full((d_out, trace_cap), -1, dtype=torch.int32, device=Wt.device)
+        opts.trace = out["trace"].data_ptr()
+        opts.trace_cap = trace_cap
+    if want_G:
+        out["G"] = torch.empty((d_out, d_in), dtype=torch.float32, device=Wt.device)
+        opts.G_out = out["G"].data_ptr()
+    _check(lib().cdq_greedy_cd_ex(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"),
+                                  _dev(scale, torch.float32, "scale"), _dev(zero, torch.float32, "zero"),
+                                  _dev(Q, torch.uint8, "Q"), d_out, d_in, bits, group, T,
+                                  st.data_ptr() if st is not None else None, ctypes.byref(opts),
+                                  ws.data_ptr(), ws.numel(), _stream()), "cdq_greedy_cd")
+    out["stats"] = st
+    return out
+
+
+def loss(H, Wt, scale, zero, Q, group: int, workspace: torch.Tensor | None = None):
+    """Returns (loss_per_col fp64 [d_out], loss_total fp64 [1]) as device tensors."""
+    d_out, d_in = Wt.shape
+    ws = _workspace(OP_LOSS, 0, d_out, d_in, workspace)
+    per = torch.empty(d_out, dtype=torch.float64, device=Wt.device)
+    tot = torch.empty(1, dtype=torch.float64, device=Wt.device)
+    _check(lib().cdq_loss(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), _dev(scale, torch.float32, "scale"),
+                          _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, group,
+                          per.data_ptr(), tot.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "cdq_loss")
+    return per, tot

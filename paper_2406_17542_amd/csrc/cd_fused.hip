@@ -1,0 +1,262 @@
+// Greedy coordinate descent (paper Algorithm 1; Algorithm 4 for sub-channel grids): all T
+// iterations of one output column run inside one kernel, with the column's state -- twice the
+// gradient g = H e, the codes q, the Hessian diagonal -- held in registers.  A column is owned
+// by a team of W wavefronts (one workgroup); columns never interact, so there is no grid-wide
+// synchronisation and no launch per iteration.
+//
+// Per iteration (Algorithm 1, the arg-min, gradient-update and code-update steps):
+//   1. every lane scores its coordinates.  The score s(r) = delta*fma(delta, H_ii, 2 g_i),
+//      delta = a*(r - q_i), is a convex parabola in r, so its minimum over the integer levels is
+//      at floor or ceil of the clamped continuous minimiser q_i - 2g_i/(2 a H_ii).  Both are
+//      evaluated with exactly the formula above, so the selected move is the one a scan of all
+//      2^c levels would select (the levels left out are >= 0.75 a^2 H_ii worse, far above
+//      rounding error).
+//   2. the team reduces one 64-bit key (order-preserving image of s, then i, then the level
+//      change) with an unsigned minimum: the result does not depend on the reduction tree and
+//      implements the tie-break "smallest s, then smallest i, then smallest r".
+//   3. the H row of the winning coordinate is streamed with coalesced 16-byte loads and folded
+//      into the registers: 2g <- fma(2 delta, H[i*][:], 2g), which is bit-identical to updating g.
+#include "cdq_internal.h"
+
+namespace cdq {
+
+namespace {
+
+constexpr uint32_t kOrderedZero = 0x80000000u;   // image of "no improving move"
+// Order-preserving image of a candidate score.  Only strictly negative scores are moves; a zero
+// of either sign (0 * g has the sign of g) and anything positive mean "no move".
+__device__ __forceinline__ uint32_t order_bits(float s) {
+    return (s < 0.0f) ? ~__float_as_uint(s) : kOrderedZero;
+}
+__device__ __forceinline__ float unorder_bits(uint32_t o) {
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
+}
+__device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
+
+template <int W, int E, int VEC>
+__global__ __launch_bounds__(64 * W) void cd_fused_kernel(
+    const float* __restrict__ H, const float* __restrict__ hdiag, const float* __restrict__ G0,
+    const float* __restrict__ scale, uint8_t* __restrict__ Q, int d_in, int bits, int group, int group_shift,
+    int n_grp, int T, cdq_col_stats* __restrict__ stats, int32_t* __restrict__ trace, int64_t trace_cap,
+    float* __restrict__ G_out) {
+    constexpr int NCH = E / VEC;              // chunks of VEC consecutive coordinates per lane
+    constexpr int STRIDE = 64 * W * VEC;      // coordinates covered by the team per chunk
+    __shared__ unsigned long long slots[2][16];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int64_t j = blockIdx.x;
+    const float* scale_j = scale + j * n_grp;
+    uint8_t* Qj = Q + j * (int64_t)d_in;
+    const float* G0j = G0 + j * (int64_t)d_in;
+    const float top = (float)((1 << bits) - 1);
+
+    float g2[E], hd[E], cinv[E], a_c[NCH];
+    uint32_t qpack[NCH];
+
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int base = c * STRIDE + tid * VEC;
+        const bool valid = base < d_in;
+        float a = 1.0f;
+        uint32_t qp = 0;
+        if (valid) {
+            const int gi = (n_grp == 1) ? 0 : (group_shift >= 0 ? (base >> group_shift) : (base / group));
+            a = scale_j[gi];
+            if (VEC == 4) qp = *reinterpret_cast<const uint32_t*>(Qj + base);
+            else qp = Qj[base];
+        }
+        a_c[c] = a;
+        qpack[c] = qp;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const int e = c * VEC + v;
+            float g = 0.0f, h = 0.0f;
+            if (valid) {
+                g = G0j[base + v];
+                h = hdiag[base + v];
+            }
+            g2[e] = 2.0f * g;
+            hd[e] = h;
+            // reciprocal of the parabola's curvature; only steers which two levels are scored
+            float ci = 0.0f;
+            if (h > 0.0f) ci = fminf(__frcp_rn(2.0f * a * h), 3.0e38f);
+            cinv[e] = ci;
+        }
+    }
+
+    int moves = 0, converged = 0;
+    uint32_t last_hi = kOrderedZero;
+
+    for (int t = 0; t < T; ++t) {
+        // ---- 1. score
+        float bs = 0.0f, bu = 0.0f;
+        int be = 0;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const float a = a_c[c];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const int e = c * VEC + v;
+                const float qf = (float)((qpack[c] >> (8 * v)) & 0xffu);
+                const float rf = fmaf(-g2[e], cinv[e], qf);
+                const float r0 = fminf(fmaxf(floorf(rf), 0.0f), top);
+                const float r1 = fminf(r0 + 1.0f, top);
+                float u0 = r0 - qf;
+                const float u1 = r1 - qf;
+                const float d0 = a * u0, d1 = a * u1;
+                float s0 = d0 * fmaf(d0, hd[e], g2[e]);
+                const float s1 = d1 * fmaf(d1, hd[e], g2[e]);
+                if (s1 < s0) { s0 = s1; u0 = u1; }      // equal scores keep the lower level
+                if (s0 < bs) { bs = s0; bu = u0; be = e; }
+            }
+        }
+        // ---- 2. arg-min over the team
+        const int bi = (be / VEC) * STRIDE + tid * VEC + (be % VEC);
+        uint64_t key = ((uint64_t)order_bits(bs) << 32) | (uint32_t)((bi << 6) | ((int)bu + 32));
+#pragma unroll
+        for (int o = 32; o; o >>= 1) key = umin64(key, (uint64_t)__shfl_xor((unsigned long long)key, o));
+        if (W > 1) {
+            if (lane == 0) slots[t & 1][wave] = key;
+            __syncthreads();
+            key = slots[t & 1][lane & (W - 1)];
+#pragma unroll
+            for (int o = W / 2; o; o >>= 1) key = umin64(key, (uint64_t)__shfl_xor((unsigned long long)key, o));
+        }
+        const uint32_t khi = __builtin_amdgcn_readfirstlane((uint32_t)(key >> 32));
+        const uint32_t klo = __builtin_amdgcn_readfirstlane((uint32_t)key);
+        if (khi >= kOrderedZero) { converged = 1; break; }     // no move lowers the loss
+        const int istar = (int)(klo >> 6);
+        const int ustar = (int)(klo & 63u) - 32;
+        // ---- 3. commit: code, then gradient
+        const int gstar = (n_grp == 1) ? 0 : (group_shift >= 0 ? (istar >> group_shift) : (istar / group));
+        const float delta2 = 2.0f * (scale_j[gstar] * (float)ustar);
+        const float4* hrow4 = reinterpret_cast<const float4*>(H + (int64_t)istar * d_in);
+        const float* hrow = H + (int64_t)istar * d_in;
+
+        const int cstar = istar / STRIDE;
+        const int within = istar - cstar * STRIDE;
+        const uint32_t inc = (within / VEC == tid) ? ((uint32_t)ustar << (8 * (within % VEC))) : 0u;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) qpack[c] += (c == cstar) ? inc : 0u;
+
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int base = c * STRIDE + tid * VEC;
+            if (base < d_in) {
+                if (VEC == 4) {
+                    const float4 hv = hrow4[base >> 2];
+                    g2[c * 4 + 0] = fmaf(delta2, hv.x, g2[c * 4 + 0]);
+                    g2[c * 4 + 1] = fmaf(delta2, hv.y, g2[c * 4 + 1]);
+                    g2[c * 4 + 2] = fmaf(delta2, hv.z, g2[c * 4 + 2]);
+                    g2[c * 4 + 3] = fmaf(delta2, hv.w, g2[c * 4 + 3]);
+                } else {
+                    g2[c] = fmaf(delta2, hrow[base], g2[c]);
+                }
+            }
+        }
+        if (trace != nullptr && tid == 0 && moves < trace_cap) trace[j * trace_cap + moves] = (int32_t)klo;
+        last_hi = khi;
+        ++moves;
+    }
+
+    // ---- write back
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int base = c * STRIDE + tid * VEC;
+        if (base < d_in) {
+            if (VEC == 4) *reinterpret_cast<uint32_t*>(Qj + base) = qpack[c];
+            else Qj[base] = (uint8_t)qpack[c];
+            if (G_out != nullptr) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) G_out[j * (int64_t)d_in + base + v] = 0.5f * g2[c * VEC + v];
+            }
+        }
+    }
+    if (stats != nullptr && tid == 0) {
+        cdq_col_stats s;
+        s.moves = moves;
+        s.iters = moves + converged;
+        s.converged = converged;
+        s.last_score = moves ? unorder_bits(last_hi) : 0.0f;
+        stats[j] = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void extract_diag_kernel(const float* __restrict__ H, int64_t d_in, float* __restrict__ hdiag) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < d_in) hdiag[i] = H[i * d_in + i];
+}
+
+template <int W, int E, int VEC>
+int launch_one(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q, int64_t d_out,
+               int d_in, int bits, int group, int group_shift, int n_grp, int T, cdq_col_stats* stats, int32_t* trace,
+               int64_t trace_cap, float* G_out, hipStream_t st) {
+    hipLaunchKernelGGL((cd_fused_kernel<W, E, VEC>), dim3((unsigned)d_out), dim3(64 * W), 0, st, H, hdiag, G0, scale, Q, d_in,
+                       bits, group, group_shift, n_grp, T, stats, trace, trace_cap, G_out);
+    CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
+
+}  // namespace
+
+int extract_diag_launch(const float* H, int64_t d_in, float* hdiag, hipStream_t st) {
+    hipLaunchKernelGGL(extract_diag_kernel, dim3((unsigned)((d_in + 255) / 256)), dim3(256), 0, st, H, d_in, hdiag);
+    CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
+
+// Launch shape: a team of `waves` wavefronts per column, `elems` coordinates per lane.
+// More coordinates per lane means fewer wavefronts per column (no cross-wave step when
+// waves == 1) but a longer serial chain per iteration; when the layer has few columns the
+// chain is split over more wavefronts so the 256 CUs x 4 SIMDs still have work in flight.
+int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int* elems, int* vec) {
+    const int v = (d_in % 4 == 0 && group % 4 == 0) ? 4 : 1;
+    const int64_t target_waves = 256 * 16;
+    int best_w = 0, best_e = 0;
+    for (int e = 32; e >= 4; e >>= 1) {
+        int64_t need = (d_in + 64 * (int64_t)e - 1) / (64 * (int64_t)e);
+        int w = 1;
+        while (w < need) w <<= 1;
+        if (w > 16) continue;
+        best_w = w;
+        best_e = e;
+        if (d_out * w >= target_waves || w == 16) break;
+    }
+    if (best_w == 0) return CDQ_EUNSUPPORTED;
+    *waves = best_w;
+    *elems = best_e;
+    *vec = v;
+    return CDQ_OK;
+}
+
+#define CDQ_CD_CASE(Wv, Ev)                                                                                        \
+    if (waves == Wv && elems == Ev) {                                                                              \
+        return vec == 4 ? launch_one<Wv, Ev, 4>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, stats, \
+                                                trace, trace_cap, G_out, st)                                       \
+                        : launch_one<Wv, Ev, 1>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, stats, \
+                                                trace, trace_cap, G_out, st);                                      \
+    }
+
+int cd_launch(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q, int64_t d_out,
+              int64_t d_in, int bits, int64_t group, int64_t T, cdq_col_stats* stats, int waves, int elems, int vec,
+              int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
+    if (d_out == 0) return CDQ_OK;
+    if ((int64_t)64 * waves * elems < d_in) return CDQ_EINVAL;
+    if (d_out > 0x7fffffffLL || d_in > CDQ_MAX_D_IN) return CDQ_EUNSUPPORTED;
+    const int di = (int)d_in, gr = (int)group, ng = (int)(d_in / group);
+    const int Ti = (int)(T > 0x7fffffffLL ? 0x7fffffffLL : T);
+    int gshift = -1;
+    if ((group & (group - 1)) == 0) {
+        gshift = 0;
+        while (((int64_t)1 << gshift) < group) ++gshift;
+    }
+    CDQ_CD_CASE(1, 4) CDQ_CD_CASE(1, 8) CDQ_CD_CASE(1, 16) CDQ_CD_CASE(1, 32)
+    CDQ_CD_CASE(2, 4) CDQ_CD_CASE(2, 8) CDQ_CD_CASE(2, 16) CDQ_CD_CASE(2, 32)
+    CDQ_CD_CASE(4, 4) CDQ_CD_CASE(4, 8) CDQ_CD_CASE(4, 16) CDQ_CD_CASE(4, 32)
+    CDQ_CD_CASE(8, 4) CDQ_CD_CASE(8, 8) CDQ_CD_CASE(8, 16) CDQ_CD_CASE(8, 32)
+    CDQ_CD_CASE(16, 4) CDQ_CD_CASE(16, 8) CDQ_CD_CASE(16, 16) CDQ_CD_CASE(16, 32)
+    return CDQ_EINVAL;
+}
+
+}  // namespace cdq

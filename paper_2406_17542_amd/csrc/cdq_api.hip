@@ -1,0 +1,118 @@
+// C ABI of libcdq: argument checks, workspace layout, dispatch.  See include/cdq.h.
+#include "cdq_internal.h"
+
+namespace {
+
+bool bad_bits(int bits) { return bits < 2 || bits > 4; }
+bool bad_layer(int64_t d_out, int64_t d_in, int64_t group) {
+    return d_out < 0 || d_in <= 0 || group <= 0 || group > d_in || d_in % group != 0;
+}
+bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+size_t cd_workspace_bytes(int64_t d_out, int64_t d_in) {
+    return cdq_align_up((size_t)d_out * d_in * sizeof(float), 256) + cdq_align_up((size_t)d_in * sizeof(float), 256);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* cdq_strerror(int code) {
+    switch (code) {
+        case CDQ_OK: return "ok";
+        case CDQ_EINVAL: return "invalid argument (null pointer, bad shape, bits not in {2,3,4}, d_in % group != 0, misaligned data)";
+        case CDQ_EWORKSPACE: return "workspace missing, not 256-byte aligned, or smaller than cdq_workspace_bytes()";
+        case CDQ_EHIP: return "HIP runtime error";
+        case CDQ_EUNSUPPORTED: return "shape outside what the kernels cover";
+        default: return "unknown cdq error code";
+    }
+}
+
+size_t cdq_workspace_bytes(int op, int64_t n, int64_t d_out, int64_t d_in) {
+    if (d_in <= 0 || d_out < 0) return 0;
+    switch (op) {
+        case CDQ_OP_HESSIAN: return cdq::hessian_workspace_bytes(n, d_in);
+        case CDQ_OP_GREEDY_CD: return cd_workspace_bytes(d_out, d_in);
+        case CDQ_OP_LOSS: return cdq::loss_workspace_bytes(d_out, d_in);
+        default: return 0;
+    }
+}
+
+int cdq_hessian(const void* X, int x_dtype, int64_t n, int64_t d_in, float* H, int accumulate, float lambda_rel,
+                void* workspace, size_t workspace_bytes, void* stream) {
+    if (X == nullptr || H == nullptr || n < 0 || d_in <= 0) return CDQ_EINVAL;
+    if (x_dtype != CDQ_F32 && x_dtype != CDQ_BF16) return CDQ_EINVAL;
+    if (!(lambda_rel >= 0.0f)) return CDQ_EINVAL;
+    if (x_dtype == CDQ_BF16 && (d_in % 8 != 0 || misaligned(X, 16))) return CDQ_EINVAL;
+    if (x_dtype == CDQ_F32 && (d_in % 4 != 0 || misaligned(X, 16))) return CDQ_EINVAL;
+    if (misaligned(H, 16)) return CDQ_EINVAL;
+    return cdq::hessian_launch(X, x_dtype, n, d_in, H, accumulate != 0, lambda_rel, workspace, workspace_bytes,
+                               (hipStream_t)stream);
+}
+
+int cdq_init_rtn(const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, float* scale, float* zero,
+                 uint8_t* Q, void* stream) {
+    if (bad_bits(bits) || bad_layer(d_out, d_in, group)) return CDQ_EINVAL;
+    if (d_out == 0) return CDQ_OK;        // empty layer: nothing to write, pointers may be null
+    if (Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr) return CDQ_EINVAL;
+    return cdq::rtn_launch(Wt, d_out, d_in, bits, group, scale, zero, Q, (hipStream_t)stream);
+}
+
+int cdq_gradient(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
+                 int64_t d_out, int64_t d_in, int64_t group, float* G, void* stream) {
+    if (bad_layer(d_out, d_in, group)) return CDQ_EINVAL;
+    if (d_out == 0) return CDQ_OK;
+    if (H == nullptr || Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr || G == nullptr) return CDQ_EINVAL;
+    return cdq::gradient_launch(H, Wt, scale, zero, Q, d_out, d_in, group, G, (hipStream_t)stream);
+}
+
+int cdq_greedy_cd_ex(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q,
+                     int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T, cdq_col_stats* stats,
+                     const cdq_cd_options* opts, void* workspace, size_t workspace_bytes, void* stream) {
+    if (bad_bits(bits) || bad_layer(d_out, d_in, group) || T < 0) return CDQ_EINVAL;
+    if (d_out == 0) return CDQ_OK;
+    if (H == nullptr || Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr) return CDQ_EINVAL;
+    if (d_in > CDQ_MAX_D_IN) return CDQ_EUNSUPPORTED;
+    if (opts != nullptr && opts->trace != nullptr && opts->trace_cap <= 0) return CDQ_EINVAL;
+    int waves = 0, elems = 0, vec = 0;
+    int rc = cdq::cd_choose_shape(d_out, d_in, group, &waves, &elems, &vec);
+    if (rc != CDQ_OK) return rc;
+    if (misaligned(Q, 4) || misaligned(H, 16)) vec = 1;
+    if (opts != nullptr && (opts->waves_per_column != 0 || opts->elems_per_lane != 0)) {
+        const int w = opts->waves_per_column, e = opts->elems_per_lane;
+        const bool w_ok = (w == 1 || w == 2 || w == 4 || w == 8 || w == 16);
+        const bool e_ok = (e == 4 || e == 8 || e == 16 || e == 32);
+        if (!w_ok || !e_ok || (int64_t)64 * w * e < d_in) return CDQ_EINVAL;
+        waves = w;
+        elems = e;
+    }
+    if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < cd_workspace_bytes(d_out, d_in)) return CDQ_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    float* G0 = (float*)workspace;
+    float* hdiag = (float*)((char*)workspace + cdq_align_up((size_t)d_out * d_in * sizeof(float), 256));
+    rc = cdq::gradient_launch(H, Wt, scale, zero, Q, d_out, d_in, group, G0, st);
+    if (rc != CDQ_OK) return rc;
+    rc = cdq::extract_diag_launch(H, d_in, hdiag, st);
+    if (rc != CDQ_OK) return rc;
+    return cdq::cd_launch(H, hdiag, G0, scale, Q, d_out, d_in, bits, group, T, stats, waves, elems, vec,
+                          opts ? opts->trace : nullptr, opts ? opts->trace_cap : 0, opts ? opts->G_out : nullptr, st);
+}
+
+int cdq_greedy_cd(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out,
+                  int64_t d_in, int bits, int64_t group, int64_t T, cdq_col_stats* stats, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+    return cdq_greedy_cd_ex(H, Wt, scale, zero, Q, d_out, d_in, bits, group, T, stats, nullptr, workspace, workspace_bytes,
+                            stream);
+}
+
+int cdq_loss(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q, int64_t d_out,
+             int64_t d_in, int64_t group, double* loss_per_col, double* loss_total, void* workspace,
+             size_t workspace_bytes, void* stream) {
+    if (bad_layer(d_out, d_in, group)) return CDQ_EINVAL;
+    if (loss_per_col == nullptr && loss_total == nullptr) return CDQ_EINVAL;
+    if (d_out > 0 && (H == nullptr || Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr)) return CDQ_EINVAL;
+    return cdq::loss_launch(H, Wt, scale, zero, Q, d_out, d_in, group, loss_per_col, loss_total, workspace, workspace_bytes,
+                            (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,45 @@
+// Internal declarations shared by the translation units of libcdq (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "cdq.h"
+
+#define CDQ_HIP_CHECK(expr)                         \
+    do {                                            \
+        hipError_t cdq_err_ = (expr);               \
+        if (cdq_err_ != hipSuccess) return CDQ_EHIP; \
+    } while (0)
+
+#define CDQ_LAUNCH_CHECK() CDQ_HIP_CHECK(hipGetLastError())
+
+static inline size_t cdq_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+namespace cdq {
+
+// ---- hessian.hip
+size_t hessian_workspace_bytes(int64_t n, int64_t d_in);
+int hessian_launch(const void* X, int x_dtype, int64_t n, int64_t d_in, float* H, int accumulate,
+                   float lambda_rel, void* ws, size_t ws_bytes, hipStream_t st);
+
+// ---- rtn.hip
+int rtn_launch(const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group,
+               float* scale, float* zero, uint8_t* Q, hipStream_t st);
+
+// ---- eh_gemm.hip : C = E * H with fp64 accumulation; epilogue stores G or row partial losses
+size_t loss_workspace_bytes(int64_t d_out, int64_t d_in);
+int gradient_launch(const float* H, const float* Wt, const float* scale, const float* zero,
+                    const uint8_t* Q, int64_t d_out, int64_t d_in, int64_t group, float* G, hipStream_t st);
+int loss_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
+                int64_t d_out, int64_t d_in, int64_t group, double* loss_per_col, double* loss_total,
+                void* ws, size_t ws_bytes, hipStream_t st);
+
+// ---- cd_fused.hip
+int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int* elems, int* vec);
+int cd_launch(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q,
+              int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T, cdq_col_stats* stats,
+              int waves, int elems, int vec, int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st);
+int extract_diag_launch(const float* H, int64_t d_in, float* hdiag, hipStream_t st);
+
+}  // namespace cdq

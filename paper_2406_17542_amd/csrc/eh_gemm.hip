@@ -1,0 +1,224 @@
+// C = E * H for all output columns, E = scale*Q + zero - Wt formed on the fly, fp32 data with
+// fp64 accumulation on the matrix cores (v_mfma_f64_16x16x4_f64).  Two epilogues:
+//   gradient: G[j][k] = (float) C[j][k]            -- Algorithm 1, "Compute gradient" (weight space)
+//   loss:     partial[j][tile] = sum_k C[j][k]*E[j][k] over the tile's columns -- Eq. (1) as e^T H e
+// fp64 accumulation keeps the one rounding to fp32 reproducible: the result differs from a
+// sequential fp64 sum only when that sum lies within ~1e-16 relative of a rounding boundary.
+//
+// Tile: 128 (columns j) x 128 (coordinates k) per workgroup of 4 wavefronts (2 x 2), each
+// wavefront 64 x 64 = 4 x 4 MFMA blocks; contraction step 16.
+#include "cdq_internal.h"
+
+namespace cdq {
+
+namespace {
+
+typedef double d4 __attribute__((ext_vector_type(4)));
+
+constexpr int BM = 128, BN = 128, BK = 16, LDP = 144;   // LDP % 32 == 16: the two k-rows read by lanes 0..31 hit disjoint banks
+
+// residual of 8 consecutive coordinates of one column (zero outside the matrix)
+__device__ __forceinline__ void residual8(const float* __restrict__ Wt, const uint8_t* __restrict__ Q,
+                                          const float* __restrict__ scale, const float* __restrict__ zero,
+                                          int64_t row, int64_t i0, int64_t d_out, int64_t d_in, int64_t group,
+                                          int64_t n_grp, float out[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = 0.0f;
+    if (row >= d_out || i0 >= d_in) return;
+    int64_t gi = i0 / group, rem = i0 - gi * group;
+    float a = scale[row * n_grp + gi], b = zero[row * n_grp + gi];
+    const float* w = Wt + row * d_in + i0;
+    const uint8_t* q = Q + row * d_in + i0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if (i0 + e < d_in) {
+            out[e] = fmaf(a, (float)q[e], b) - w[e];
+            if (++rem == group) {
+                rem = 0;
+                ++gi;
+                if (gi < n_grp) { a = scale[row * n_grp + gi]; b = zero[row * n_grp + gi]; }
+            }
+        }
+    }
+}
+
+template <bool LOSS>
+__global__ __launch_bounds__(256) void eh_gemm_kernel(const float* __restrict__ H, const float* __restrict__ Wt,
+                                                      const float* __restrict__ scale, const float* __restrict__ zero,
+                                                      const uint8_t* __restrict__ Q, int64_t d_out, int64_t d_in,
+                                                      int64_t group, float* __restrict__ G,
+                                                      double* __restrict__ partial, int n_tiles) {
+    __shared__ float As[BK][LDP];     // As[k][m] = E[m0+m][k0+k]
+    __shared__ float Bs[BK][LDP];     // Bs[k][n] = H[k0+k][n0+n]
+    __shared__ double red[2][BM];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    const int64_t n_grp = d_in / group;
+
+    d4 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = (d4){0.0, 0.0, 0.0, 0.0};
+
+    // loader roles
+    const int a_row = tid >> 1, a_half = tid & 1;          // E tile: 128 rows x (2 x 8) k
+    const int b_row = tid >> 4, b_col = (tid & 15) * 8;    // H tile: 16 rows x (16 x 8) n
+
+    float ra[8], rb[8];
+    auto load_tiles = [&](int64_t k0) {
+        residual8(Wt, Q, scale, zero, m0 + a_row, k0 + a_half * 8, d_out, d_in, group, n_grp, ra);
+        const int64_t hr = k0 + b_row;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t c = n0 + b_col + e;
+            rb[e] = (hr < d_in && c < d_in) ? H[hr * d_in + c] : 0.0f;
+        }
+    };
+
+    load_tiles(0);
+    for (int64_t k0 = 0; k0 < d_in; k0 += BK) {
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            As[a_half * 8 + e][a_row] = ra[e];
+            Bs[b_row][b_col + e] = rb[e];
+        }
+        __syncthreads();
+        if (k0 + BK < d_in) load_tiles(k0 + BK);
+#pragma unroll
+        for (int ks = 0; ks < BK; ks += 4) {
+            double a[4], b[4];
+            const int kk = ks + (lane >> 4), mn = lane & 15;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                a[i] = (double)As[kk][wm * 64 + i * 16 + mn];
+                b[i] = (double)Bs[kk][wn * 64 + i * 16 + mn];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // result layout of the 16x16 f64 block: lane l, element v  ->  row 4*v + l/16, column l%16
+    const int r_in = lane >> 4, c_in = lane & 15;
+    if (!LOSS) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int64_t row = m0 + wm * 64 + i * 16 + 4 * v + r_in;
+                if (row < d_out) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int64_t col = n0 + wn * 64 + j * 16 + c_in;
+                        if (col < d_in) G[row * d_in + col] = (float)acc[i][j][v];
+                    }
+                }
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int lrow = wm * 64 + i * 16 + 4 * v + r_in;
+                const int64_t row = m0 + lrow;
+                double s = 0.0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int64_t col = n0 + wn * 64 + j * 16 + c_in;
+                    if (row < d_out && col < d_in) {
+                        const int64_t gi = col / group;
+                        const float e = fmaf(scale[row * n_grp + gi], (float)Q[row * d_in + col], zero[row * n_grp + gi]) -
+                                        Wt[row * d_in + col];
+                        s += acc[i][j][v] * (double)e;
+                    }
+                }
+                // sum over the 16 lanes that share this row (fixed butterfly order)
+                for (int o = 8; o; o >>= 1) s += __shfl_xor(s, o);
+                if (c_in == 0) red[wn][lrow] = s;
+            }
+        __syncthreads();
+        if (tid < BM) {
+            const int64_t row = m0 + tid;
+            if (row < d_out) partial[row * n_tiles + blockIdx.x] = red[0][tid] + red[1][tid];
+        }
+    }
+}
+
+// loss_per_col[j] = sum over tiles in ascending order; optional total over columns by one workgroup
+__global__ __launch_bounds__(256) void loss_rows_kernel(const double* __restrict__ partial, int64_t d_out, int n_tiles,
+                                                        double* __restrict__ row_loss) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_out) return;
+    double s = 0.0;
+    for (int t = 0; t < n_tiles; ++t) s += partial[j * n_tiles + t];
+    row_loss[j] = s;
+}
+
+__global__ __launch_bounds__(1024) void loss_total_kernel(const double* __restrict__ row_loss, int64_t d_out,
+                                                          double* __restrict__ total) {
+    __shared__ double sh[1024];
+    double s = 0.0;
+    for (int64_t j = threadIdx.x; j < d_out; j += 1024) s += row_loss[j];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 512; o; o >>= 1) {
+        if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) total[0] = sh[0];
+}
+
+}  // namespace
+
+size_t loss_workspace_bytes(int64_t d_out, int64_t d_in) {
+    const int64_t n_tiles = (d_in + BN - 1) / BN;
+    return cdq_align_up((size_t)d_out * n_tiles * sizeof(double), 256) + cdq_align_up((size_t)d_out * sizeof(double), 256);
+}
+
+int gradient_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
+                    int64_t d_out, int64_t d_in, int64_t group, float* G, hipStream_t st) {
+    if (d_out == 0) return CDQ_OK;
+    const int64_t gx = (d_in + BN - 1) / BN, gy = (d_out + BM - 1) / BM;
+    if (gy > 65535) return CDQ_EUNSUPPORTED;
+    hipLaunchKernelGGL(eh_gemm_kernel<false>, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st, H, Wt, scale, zero, Q,
+                       d_out, d_in, group, G, (double*)nullptr, (int)gx);
+    CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
+
+int loss_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
+                int64_t d_out, int64_t d_in, int64_t group, double* loss_per_col, double* loss_total,
+                void* ws, size_t ws_bytes, hipStream_t st) {
+    if (d_out == 0) {                 // empty layer: the total is an empty sum
+        if (loss_total) {
+            hipLaunchKernelGGL(loss_total_kernel, dim3(1), dim3(1024), 0, st, (const double*)nullptr, (int64_t)0, loss_total);
+            CDQ_LAUNCH_CHECK();
+        }
+        return CDQ_OK;
+    }
+    if (ws == nullptr || ws_bytes < loss_workspace_bytes(d_out, d_in) || ((uintptr_t)ws & 255)) return CDQ_EWORKSPACE;
+    const int64_t gx = (d_in + BN - 1) / BN, gy = (d_out + BM - 1) / BM;
+    if (gy > 65535) return CDQ_EUNSUPPORTED;
+    double* partial = (double*)ws;
+    double* rows_ws = (double*)((char*)ws + cdq_align_up((size_t)d_out * gx * sizeof(double), 256));
+    double* rows = loss_per_col ? loss_per_col : rows_ws;
+    hipLaunchKernelGGL(eh_gemm_kernel<true>, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st, H, Wt, scale, zero, Q,
+                       d_out, d_in, group, (float*)nullptr, partial, (int)gx);
+    CDQ_LAUNCH_CHECK();
+    hipLaunchKernelGGL(loss_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, partial, d_out, (int)gx, rows);
+    CDQ_LAUNCH_CHECK();
+    if (loss_total) {
+        hipLaunchKernelGGL(loss_total_kernel, dim3(1), dim3(1024), 0, st, rows, d_out, loss_total);
+        CDQ_LAUNCH_CHECK();
+    }
+    return CDQ_OK;
+}
+
+}  // namespace cdq

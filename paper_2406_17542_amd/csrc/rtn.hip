@@ -1,0 +1,67 @@
+// MinMax grid + round-to-nearest codes: Eq. (2) of the paper with clipping strength 1,
+// per (output column, group).  One wavefront owns one (column, group) pair.
+#include "cdq_internal.h"
+
+namespace cdq {
+
+namespace {
+
+__device__ __forceinline__ float wave_min(float v) {
+    for (int o = 32; o; o >>= 1) v = fminf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+    for (int o = 32; o; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+__global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ Wt, int64_t d_out, int64_t d_in,
+                                                  int bits, int64_t group, int64_t n_grp,
+                                                  float* __restrict__ scale, float* __restrict__ zero,
+                                                  uint8_t* __restrict__ Q) {
+    const int lane = threadIdx.x & 63;
+    const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (item >= d_out * n_grp) return;
+    const int64_t j = item / n_grp, gi = item % n_grp;
+    const float* w = Wt + j * d_in + gi * group;
+    uint8_t* q = Q + j * d_in + gi * group;
+
+    float lo = INFINITY, hi = -INFINITY;
+    for (int64_t k = lane; k < group; k += 64) {
+        const float v = w[k];
+        lo = fminf(lo, v);
+        hi = fmaxf(hi, v);
+    }
+    lo = wave_min(lo);
+    hi = wave_max(hi);
+
+    const float top = (float)((1 << bits) - 1);
+    float a = __fdiv_rn(hi - lo, top);
+    if (!(a > 0.0f) || isinf(a)) a = 1.0f;      // constant group: any scale reproduces w with code 0
+    if (lane == 0) {
+        scale[item] = a;
+        zero[item] = lo;
+    }
+    for (int64_t k = lane; k < group; k += 64) {
+        const float t = __fdiv_rn(w[k] - lo, a);
+        const float r = fminf(fmaxf(rintf(t), 0.0f), top);   // rintf: round half to even
+        q[k] = (uint8_t)r;
+    }
+}
+
+}  // namespace
+
+int rtn_launch(const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group,
+               float* scale, float* zero, uint8_t* Q, hipStream_t st) {
+    const int64_t n_grp = d_in / group;
+    const int64_t items = d_out * n_grp;
+    if (items == 0) return CDQ_OK;
+    const int64_t blocks = (items + 3) / 4;
+    if (blocks > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
+    hipLaunchKernelGGL(rtn_kernel, dim3((unsigned)blocks), dim3(256), 0, st, Wt, d_out, d_in, bits, group, n_grp,
+                       scale, zero, Q);
+    CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
+
+}  // namespace cdq

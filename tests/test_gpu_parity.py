@@ -1,0 +1,325 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Bars:
+  init_rtn          bit-exact
+  hessian           |dH_ik| <= 8 sqrt(n) 2^-24 sqrt(H_ii H_kk) and relative Frobenius error <= 1e-5
+  gradient          equal to the oracle's correctly-rounded fp32 value except at fp64 rounding
+                    boundaries (<= 1e-6 of entries, each within 1 ulp)
+  greedy_cd         fed the same fp32 H: codes equal on >= 99.9 % of entries; every column that
+                    differs must diverge at a score tie; final loss within 1e-4 relative
+  loss              within 1e-6 relative of the oracle's fp64 value (the kernel rounds e to fp32
+                    first; given that fp32 e it matches an fp64 evaluation to 1e-12)
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2406_17542_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def cdq():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2406_17542_amd import cdq as m
+    m.lib()
+    return m
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def x_to_dev(X, x_dtype):
+    if x_dtype == "bf16":
+        return dev(inputs.bf16_bits(X).view(np.int16)).view(torch.bfloat16)
+    return dev(X.astype(np.float32))
+
+
+def rand_layer(seed, d_in, d_out, n, corr=1.0):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, d_in)).astype(np.float32)
+    if corr:
+        X += (corr * rng.standard_normal((n, 1))).astype(np.float32)
+    Wt = (rng.standard_normal((d_out, d_in)) / np.sqrt(d_in)).astype(np.float32)
+    return X, Wt
+
+
+def hessian_tolerance_ok(H_gpu, H64, n):
+    d = np.sqrt(np.diag(H64))
+    bound = 8.0 * np.sqrt(n) * 2.0 ** -24 * np.outer(d, d) + 1e-30
+    err = np.abs(H_gpu.astype(np.float64) - H64)
+    fro = np.linalg.norm(err) / max(np.linalg.norm(H64), 1e-300)
+    return bool((err <= bound).all()), float((err / bound).max()), float(fro)
+
+
+# ----------------------------------------------------------------------------- init_rtn
+
+@pytest.mark.parametrize("d_out,d_in,bits,group", [
+    (64, 128, 4, 128), (7, 96, 3, 32), (5, 130, 2, 26), (3, 1000, 4, 1000), (33, 256, 2, 128), (2, 5, 3, 5), (4, 64, 3, 1),
+])
+def test_init_rtn_bit_exact(cdq, oracle, d_out, d_in, bits, group):
+    rng = np.random.default_rng(d_in + bits)
+    Wt = (rng.standard_normal((d_out, d_in)) / np.sqrt(d_in)).astype(np.float32)
+    Wt[0, : min(d_in, group)] = 0.25                 # a constant group
+    if d_in >= 6 and group >= 6:                     # exact halves: round-half-even must agree
+        Wt[1, :6] = np.array([0.0, 0.5, 1.5, 2.5, 3.0, 1.0], np.float32) if bits == 2 else Wt[1, :6]
+    a, b, q = oracle.init_grid(Wt, bits, group)
+    s, z, Q = cdq.init_rtn(dev(Wt), bits, group)
+    assert np.array_equal(s.cpu().numpy(), a)
+    assert np.array_equal(z.cpu().numpy(), b)
+    assert np.array_equal(Q.cpu().numpy(), q)
+
+
+def test_init_rtn_tiny_config(cdq, oracle):
+    cfg = inputs.CONFIGS["tiny"]
+    _, Wt = inputs.make_layer(cfg)
+    a, b, q = oracle.init_grid(Wt, cfg.bits, cfg.group)
+    s, z, Q = cdq.init_rtn(dev(Wt), cfg.bits, cfg.group)
+    assert np.array_equal(s.cpu().numpy(), a) and np.array_equal(z.cpu().numpy(), b) and np.array_equal(Q.cpu().numpy(), q)
+
+
+# ----------------------------------------------------------------------------- hessian
+
+@pytest.mark.parametrize("x_dtype,n,d_in", [
+    ("f32", 512, 128), ("f32", 300, 132), ("f32", 1, 4), ("f32", 1000, 260),
+    ("bf16", 512, 128), ("bf16", 333, 136), ("bf16", 4096, 392), ("bf16", 7, 8), ("bf16", 2500, 1024),
+])
+def test_hessian(cdq, oracle, x_dtype, n, d_in):
+    X = inputs.make_x("outlier8x20", n, d_in, seed=n, x_dtype=x_dtype)
+    H64 = oracle.hessian(X)
+    H = cdq.hessian(x_to_dev(X, x_dtype)).cpu().numpy()
+    assert np.array_equal(H, H.T), "H must be exactly symmetric"
+    ok, worst, fro = hessian_tolerance_ok(H, H64, n)
+    assert ok and fro <= 1e-5, (worst, fro)
+
+
+def test_hessian_tiny_config_and_repeatable(cdq, oracle):
+    cfg = inputs.CONFIGS["tiny"]
+    X, _ = inputs.make_layer(cfg)
+    Xd = x_to_dev(X, cfg.x_dtype)
+    H1 = cdq.hessian(Xd).cpu().numpy()
+    H2 = cdq.hessian(Xd).cpu().numpy()
+    assert np.array_equal(H1, H2)
+    ok, worst, fro = hessian_tolerance_ok(H1, oracle.hessian(X), cfg.n)
+    assert ok and fro <= 1e-5, (worst, fro)
+
+
+def test_hessian_accumulate_and_damping(cdq, oracle):
+    X = inputs.make_x("student_t4", 1536, 264, seed=3, x_dtype="bf16")
+    Xd = x_to_dev(X, "bf16")
+    H = cdq.hessian(Xd[:512].contiguous())
+    H = cdq.hessian(Xd[512:1024].contiguous(), H=H, accumulate=True)
+    H = cdq.hessian(Xd[1024:].contiguous(), H=H, accumulate=True, lambda_rel=0.01)
+    Hn = H.cpu().numpy()
+    H64 = oracle.hessian(X, lambda_rel=0.01)
+    assert np.array_equal(Hn, Hn.T)
+    ok, worst, fro = hessian_tolerance_ok(Hn, H64, 1536)
+    assert ok and fro <= 1e-5, (worst, fro)
+    # the damping really is there: compare the diagonal against the undamped oracle
+    lam = 0.01 * np.mean(np.diag(oracle.hessian(X)))
+    np.testing.assert_allclose(np.diag(Hn) - np.diag(oracle.hessian(X)), lam, rtol=1e-3)
+
+
+# ----------------------------------------------------------------------------- gradient, loss
+
+@pytest.mark.parametrize("d_out,d_in,n,bits,group", [(64, 128, 512, 4, 128), (37, 200, 600, 3, 40), (130, 264, 800, 2, 8), (3, 7, 40, 3, 7)])
+def test_gradient_and_loss(cdq, oracle, d_out, d_in, n, bits, group):
+    X, Wt = rand_layer(d_in, d_in, d_out, n)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q = oracle.init_grid(Wt, bits, group)
+    q = np.random.default_rng(0).integers(0, 1 << bits, q.shape).astype(np.uint8)
+    E = oracle.residual(Wt, q, a, b, group)
+    G_ref = oracle.gradient(H32, E)
+    Hd, Wd, ad, bd, qd = dev(H32), dev(Wt), dev(a), dev(b), dev(q)
+    G = cdq.gradient(Hd, Wd, ad, bd, qd, group).cpu().numpy()
+    diff = G != G_ref
+    assert diff.mean() <= 1e-6, f"{diff.sum()} of {diff.size} gradient entries differ"
+    if diff.any():
+        assert np.all(np.abs(G[diff] - G_ref[diff]) <= np.spacing(np.abs(G_ref[diff])))
+    per, tot = cdq.loss(Hd, Wd, ad, bd, qd, group)
+    ref = oracle.loss(H32, Wt, q, a, b, group)
+    # the kernel forms e in fp32 (the residual the CD arithmetic sees), the oracle in fp64
+    np.testing.assert_allclose(per.cpu().numpy(), ref, rtol=1e-6)
+    np.testing.assert_allclose(tot.cpu().numpy()[0], ref.sum(), rtol=1e-6)
+    # with the same fp32 residual the two agree to fp64 accuracy
+    E64 = E.astype(np.float64)
+    ref32 = np.einsum("ji,ji->j", E64 @ H32.astype(np.float64), E64)
+    np.testing.assert_allclose(per.cpu().numpy(), ref32, rtol=1e-12)
+
+
+# ----------------------------------------------------------------------------- greedy CD
+
+def decode_trace(tr):
+    tr = tr.astype(np.int64)
+    return tr >> 6, (tr & 63) - 32
+
+
+def run_cd_both(cdq, oracle, H32, Wt, a, b, q0, bits, group, T, **kw):
+    ref = oracle.greedy_cd(H32, Wt, a, b, q0, bits, group, T, trace_cap=max(T, 1))
+    Qd = dev(q0.copy())
+    cap = max(T, 1)
+    out = cdq.greedy_cd(dev(H32), dev(Wt), dev(a), dev(b), Qd, bits, group, T, trace_cap=cap, want_G=True, **kw)
+    torch.cuda.synchronize()
+    return ref, Qd.cpu().numpy(), out["stats"].cpu().numpy(), out["trace"].cpu().numpy(), out["G"].cpu().numpy()
+
+
+def assert_divergence_is_tie(oracle, ref, trace_j, j, H32, Wt, a, b, q0, bits, group):
+    """Column j ended with different codes: its first different move must be a score tie
+    (the two candidates' canonical fp32 scores within 4 ulp)."""
+    ti, tu = decode_trace(trace_j)
+    m_ref = int(ref["moves"][j])
+    k = 0
+    while k < m_ref and ti[k] == ref["trace_i"][j, k]:
+        # same coordinate: the level must match too (level = previous code + change)
+        k += 1
+    # state after the k common moves, from the oracle
+    part = oracle.greedy_cd(H32, Wt[j:j + 1], a[j:j + 1], b[j:j + 1], q0[j:j + 1], bits, group, k)
+    g = part["G"][0].astype(np.float64)
+    qk = part["Q"][0].astype(np.int64)
+
+    def score(i, r):
+        delta = np.float32(a[j, i // group]) * np.float32(r - qk[i])
+        inner = np.float32(float(delta) * float(H32[i, i]) + 2.0 * g[i])
+        return np.float32(delta * inner)
+
+    assert k < m_ref or ti[k] >= 0, "columns differ but traces do not"
+    cands = []
+    if k < m_ref:
+        cands.append(score(int(ref["trace_i"][j, k]), int(ref["trace_r"][j, k])))
+    if ti[k] >= 0:
+        cands.append(score(int(ti[k]), int(qk[ti[k]] + tu[k])))
+    if len(cands) == 2:
+        assert abs(float(cands[0]) - float(cands[1])) <= 4 * np.spacing(np.abs(cands[0])), (j, k, cands)
+    else:
+        # one side stopped, the other moved: the move's score must be ~0 at rounding level
+        assert abs(float(cands[0])) <= 1e-6 * float(H32[0, 0] * a[j, 0] ** 2 + 1e-30), (j, k, cands)
+
+
+def check_cd(oracle, ref, Q, stats, trace, H32, Wt, a, b, q0, bits, group, min_exact=0.999):
+    same = (Q == ref["Q"])
+    bad_cols = np.where(~same.all(axis=1))[0]
+    for j in bad_cols[:16]:
+        assert_divergence_is_tie(oracle, ref, trace[j], j, H32, Wt, a, b, q0, bits, group)
+    frac = same.mean()
+    assert frac >= min_exact, f"only {frac:.6f} of codes equal ({len(bad_cols)} columns differ)"
+    good = same.all(axis=1)
+    assert np.array_equal(stats[good, 0], ref["moves"][good])
+    assert np.array_equal(stats[good, 2], ref["converged"][good])
+    l_gpu = oracle.loss(H32, Wt, Q, a, b, group).sum()
+    l_ref = oracle.loss(H32, Wt, ref["Q"], a, b, group).sum()
+    assert abs(l_gpu - l_ref) <= 1e-4 * l_ref
+    return len(bad_cols)
+
+
+CD_CASES = [
+    # d_out, d_in, n, bits, group, T, random_q0, waves, elems
+    (64, 128, 512, 4, 128, 128, False, 0, 0),
+    (64, 128, 512, 4, 128, 128, True, 0, 0),
+    (40, 256, 700, 3, 64, 300, True, 1, 4),
+    (40, 256, 700, 3, 64, 300, True, 2, 8),
+    (24, 1000, 1500, 2, 200, 500, True, 4, 4),
+    (24, 1000, 1500, 4, 1000, 700, True, 1, 16),
+    (16, 1030, 1500, 3, 103, 400, True, 0, 0),       # d_in % 4 != 0: scalar layout
+    (9, 77, 300, 3, 11, 200, True, 4, 8),            # odd everything, more lanes than coordinates
+    (12, 2048, 2600, 3, 2048, 600, True, 8, 4),
+    (12, 2048, 2600, 2, 128, 600, False, 16, 4),
+    (6, 4096, 4500, 4, 4096, 300, True, 2, 32),
+    (5, 64, 256, 3, 64, 0, True, 0, 0),              # T = 0: nothing changes
+    (5, 64, 256, 3, 64, 3, True, 0, 0),              # tiny budget: stops after 3 moves
+    (1, 8, 64, 2, 8, 50, True, 0, 0),
+]
+
+
+@pytest.mark.parametrize("d_out,d_in,n,bits,group,T,rq,waves,elems", CD_CASES)
+def test_greedy_cd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, rq, waves, elems):
+    X, Wt = rand_layer(1000 + d_in + bits, d_in, d_out, n, corr=1.0)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q0 = oracle.init_grid(Wt, bits, group)
+    if rq:
+        q0 = inputs.make_random_codes(d_out, d_in, bits, seed=d_in)
+    ref, Q, stats, trace, G = run_cd_both(cdq, oracle, H32, Wt, a, b, q0, bits, group, T,
+                                          waves_per_column=waves, elems_per_lane=elems)
+    nbad = check_cd(oracle, ref, Q, stats, trace, H32, Wt, a, b, q0, bits, group)
+    if T == 0:
+        assert np.array_equal(Q, q0) and not stats[:, 0].any()
+    assert (stats[:, 0] <= T).all()
+    if nbad == 0:
+        # identical trajectories: same moves in the same order, and the same maintained gradient
+        ti, tu = decode_trace(trace)
+        for j in range(d_out):
+            m = ref["moves"][j]
+            assert np.array_equal(ti[j, :m], ref["trace_i"][j, :m])
+        assert np.array_equal(G, ref["G"])
+
+
+def test_greedy_cd_tiny_config_end_to_end(cdq, oracle):
+    """Whole path on the tiny configuration: GPU Hessian -> RTN -> CD -> loss, against the oracle
+    fed the GPU's fp32 H (stage-wise parity) and against the all-oracle run (loss only)."""
+    cfg = inputs.CONFIGS["tiny"]
+    X, Wt = inputs.make_layer(cfg)
+    Hd = cdq.hessian(x_to_dev(X, cfg.x_dtype))
+    Wd = dev(Wt)
+    s, z, Q = cdq.init_rtn(Wd, cfg.bits, cfg.group)
+    q0 = Q.cpu().numpy().copy()
+    l0 = cdq.loss(Hd, Wd, s, z, Q, cfg.group)[1].item()
+    out = cdq.greedy_cd(Hd, Wd, s, z, Q, cfg.bits, cfg.group, cfg.T)
+    l1 = cdq.loss(Hd, Wd, s, z, Q, cfg.group)[1].item()
+    H32 = Hd.cpu().numpy()
+    ref = oracle.greedy_cd(H32, Wt, s.cpu().numpy(), z.cpu().numpy(), q0, cfg.bits, cfg.group, cfg.T)
+    assert (Q.cpu().numpy() == ref["Q"]).mean() >= 0.999
+    assert np.array_equal(out["stats"].cpu().numpy()[:, 0], ref["moves"])
+    assert l1 <= l0
+    H64 = oracle.hessian(X)
+    a, b, q_rtn = oracle.init_grid(Wt, cfg.bits, cfg.group)
+    full = oracle.greedy_cd(H64.astype(np.float32), Wt, a, b, q_rtn, cfg.bits, cfg.group, cfg.T)
+    l_full = oracle.loss(H64, Wt, full["Q"], a, b, cfg.group).sum()
+    assert abs(l1 - l_full) <= 1e-4 * l_full
+
+
+def test_greedy_cd_deterministic_and_resumable(cdq, oracle):
+    X, Wt = rand_layer(77, 512, 48, 1200)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, _ = oracle.init_grid(Wt, 3, 128)
+    q0 = inputs.make_random_codes(48, 512, 3, seed=5)
+    Hd, Wd, ad, bd = dev(H32), dev(Wt), dev(a), dev(b)
+    Q1, Q2, Q3 = dev(q0.copy()), dev(q0.copy()), dev(q0.copy())
+    cdq.greedy_cd(Hd, Wd, ad, bd, Q1, 3, 128, 400)
+    cdq.greedy_cd(Hd, Wd, ad, bd, Q2, 3, 128, 400, waves_per_column=4, elems_per_lane=8)
+    assert torch.equal(Q1, Q2), "result must not depend on the launch shape"
+    cdq.greedy_cd(Hd, Wd, ad, bd, Q3, 3, 128, 150)
+    st = cdq.greedy_cd(Hd, Wd, ad, bd, Q3, 3, 128, 250)["stats"]
+    # resuming recomputes g from the codes in fp64, so the continued run may differ from the
+    # uninterrupted one only where fp32 drift of g decided a near-tie
+    assert (Q3 == Q1).float().mean().item() >= 0.999
+
+
+def test_greedy_cd_dead_channel_and_diagonal(cdq, oracle):
+    # dead input channel: never selected, no NaN
+    X, Wt = rand_layer(5, 64, 8, 300)
+    X[:, 9] = 0
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, _ = oracle.init_grid(Wt, 3, 64)
+    q0 = inputs.make_random_codes(8, 64, 3, seed=1)
+    ref, Q, stats, trace, G = run_cd_both(cdq, oracle, H32, Wt, a, b, q0, 3, 64, 200)
+    assert np.array_equal(Q, ref["Q"]) and np.array_equal(Q[:, 9], q0[:, 9]) and np.isfinite(G).all()
+    # diagonal H: CD from arbitrary codes lands exactly on round-to-nearest
+    Hdiag = np.diag(np.random.default_rng(2).uniform(0.5, 4, 64)).astype(np.float32)
+    a, b, q_rtn = oracle.init_grid(Wt, 4, 64)
+    q0 = inputs.make_random_codes(8, 64, 4, seed=2)
+    Qd = dev(q0.copy())
+    cdq.greedy_cd(dev(Hdiag), dev(Wt), dev(a), dev(b), Qd, 4, 64, 128)
+    assert np.array_equal(Qd.cpu().numpy(), q_rtn)
+
+
+def test_empty_layer(cdq):
+    H = torch.zeros((8, 8), device="cuda")
+    Wt = torch.zeros((0, 8), device="cuda")
+    s, z, Q = cdq.init_rtn(Wt, 3, 8)
+    assert Q.shape == (0, 8)
+    out = cdq.greedy_cd(H, Wt, s, z, Q, 3, 8, 4)
+    per, tot = cdq.loss(H, Wt, s, z, Q, 8)
+    assert per.numel() == 0 and tot.item() == 0.0
