@@ -66,6 +66,9 @@ typedef struct {
                                    i* * 64 + (u* + 32), u* = r* - q_i* the signed level change */
     int64_t  trace_cap;
     float   *G_out;             /* NULL, or [d_out][d_in]: g = H e as maintained at exit */
+    void    *ev_loop_begin;     /* NULL, or hipEvent_t recorded on `stream` just before ... */
+    void    *ev_loop_end;       /* ... and just after the iteration-loop kernel, so a caller can
+                                   time the loop apart from the gradient initialisation */
 } cdq_cd_options;
 
 const char *cdq_strerror(int code);
