@@ -62,6 +62,10 @@ typedef struct {
 typedef struct {
     int32_t  waves_per_column;  /* 0 = choose; else 1,2,4,8,16 wavefronts cooperating on a column */
     int32_t  elems_per_lane;    /* 0 = choose; else 4,8,16,32 coordinates held per lane */
+    int32_t  exact_scorer_only; /* 0 = nearest-level scorer with the two-level scorer as arbiter
+                                   (default); 1 = two-level scorer on every iteration.  Both
+                                   select the same moves; 1 exists for testing and timing. */
+    int32_t  reserved;
     int32_t *trace;             /* NULL, or [d_out][trace_cap]: move m of column j is stored as
                                    i* * 64 + (u* + 32), u* = r* - q_i* the signed level change */
     int64_t  trace_cap;

@@ -32,6 +32,7 @@ class ColStats(ctypes.Structure):
 
 class CdOptions(ctypes.Structure):
     _fields_ = [("waves_per_column", ctypes.c_int32), ("elems_per_lane", ctypes.c_int32),
+                ("exact_scorer_only", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("trace", ctypes.c_void_p), ("trace_cap", ctypes.c_int64), ("G_out", ctypes.c_void_p),
                 ("ev_loop_begin", ctypes.c_void_p), ("ev_loop_end", ctypes.c_void_p)]
 
@@ -131,7 +132,7 @@ def gradient(H, Wt, scale, zero, Q, group: int) -> torch.Tensor:
 
 def greedy_cd(H, Wt, scale, zero, Q, bits: int, group: int, T: int, stats: bool = True,
               workspace: torch.Tensor | None = None, waves_per_column: int = 0, elems_per_lane: int = 0,
-              trace_cap: int = 0, want_G: bool = False, loop_events=None):
+              trace_cap: int = 0, want_G: bool = False, loop_events=None, exact_scorer_only: bool = False):
     """Greedy coordinate descent in place on Q.  Returns a dict with 'stats' (int32 [d_out][4] view:
     moves, iters, converged, last_score bits), and optionally 'trace' and 'G'.  loop_events is an
     optional pair of raw hipEvent_t handles recorded around the iteration-loop kernel."""
@@ -139,7 +140,7 @@ def greedy_cd(H, Wt, scale, zero, Q, bits: int, group: int, T: int, stats: bool 
     ws = _workspace(OP_GREEDY_CD, 0, d_out, d_in, workspace)
     st = torch.zeros((d_out, 4), dtype=torch.int32, device=Wt.device) if stats else None
     out = {}
-    opts = CdOptions(waves_per_column, elems_per_lane, None, 0, None, None, None)
+    opts = CdOptions(waves_per_column, elems_per_lane, int(exact_scorer_only), 0, None, 0, None, None, None)
     if loop_events is not None:            # (begin, end) raw hipEvent_t handles
         opts.ev_loop_begin, opts.ev_loop_end = loop_events
     if trace_cap > 0:

@@ -6,14 +6,21 @@
 //
 // Per iteration (Algorithm 1, the arg-min, gradient-update and code-update steps):
 //   1. every lane scores its coordinates.  The score s(r) = delta*fma(delta, H_ii, 2 g_i),
-//      delta = a*(r - q_i), is a convex parabola in r, so its minimum over the integer levels is
-//      at floor or ceil of the clamped continuous minimiser q_i - 2g_i/(2 a H_ii).  Both are
-//      evaluated with exactly the formula above, so the selected move is the one a scan of all
-//      2^c levels would select (the levels left out are >= 0.75 a^2 H_ii worse, far above
-//      rounding error).
-//   2. the team reduces one 64-bit key (order-preserving image of s, then i, then the level
-//      change) with an unsigned minimum: the result does not depend on the reduction tree and
-//      implements the tie-break "smallest s, then smallest i, then smallest r".
+//      delta = a*(r - q_i), is a convex parabola in r, so its minimum over the integer levels
+//      sits next to the clamped continuous minimiser rf = q_i - 2g_i/(2 a H_ii).
+//        fast scorer : scores only the level nearest to rf (about 12 VALU ops per coordinate).
+//        exact scorer: scores floor(rf) and ceil(rf), both with exactly the formula above, so it
+//                      selects what a scan of all 2^c levels would select (the levels left out
+//                      are >= 0.75 a^2 H_ii worse, far above rounding error).
+//      The two can only disagree when rf is within rounding distance of a half-integer (the two
+//      neighbouring levels tie) or when no strictly improving move is left.  The fast scorer
+//      therefore flags a winner whose rf lies within 2^-9 of a half-integer, and the iteration is
+//      redone with the exact scorer when the winner is flagged or when no move was found.
+//   2. the team reduces (ordered score, then i, then level change) with unsigned minima: the
+//      result does not depend on the reduction tree and implements the tie-break "smallest s,
+//      then smallest i, then smallest r".  Within a wavefront: DPP minima over the 32-bit score
+//      image, then the payload of the winning lane by readlane; across wavefronts: one 64-bit
+//      slot per wavefront in LDS, double-buffered, one barrier.
 //   3. the H row of the winning coordinate is streamed with coalesced 16-byte loads and folded
 //      into the registers: 2g <- fma(2 delta, H[i*][:], 2g), which is bit-identical to updating g.
 #include "cdq_internal.h"
@@ -31,14 +38,45 @@ __device__ __forceinline__ uint32_t order_bits(float s) {
 __device__ __forceinline__ float unorder_bits(uint32_t o) {
     return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
 }
+__device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
 __device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_min(uint32_t v) {
+    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+    return umin32(v, o);
+}
+
+// Minimum of (k32, payload) in lexicographic order over one wavefront; the result is uniform.
+__device__ __forceinline__ uint64_t wave_min_key(uint32_t k32, uint32_t payload) {
+    uint32_t m = k32;
+    m = dpp_min<0xB1>(m);     // quad_perm [1,0,3,2]
+    m = dpp_min<0x4E>(m);     // quad_perm [2,3,0,1]
+    m = dpp_min<0x141>(m);    // row_half_mirror
+    m = dpp_min<0x140>(m);    // row_mirror: every lane of a 16-lane row now holds the row minimum
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)m, 0), r1 = (uint32_t)__builtin_amdgcn_readlane((int)m, 16);
+    const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)m, 32), r3 = (uint32_t)__builtin_amdgcn_readlane((int)m, 48);
+    const uint32_t best = umin32(umin32(r0, r1), umin32(r2, r3));
+    uint32_t pay = 0xffffffffu;
+    if (best < kOrderedZero) {
+        unsigned long long tied = __ballot(k32 == best);
+        do {                                  // almost always a single lane
+            const int l = __builtin_ctzll(tied);
+            pay = umin32(pay, (uint32_t)__builtin_amdgcn_readlane((int)payload, l));
+            tied &= tied - 1;
+        } while (tied);
+    }
+    return ((uint64_t)best << 32) | pay;
+}
+
+constexpr float kHalfWindow = 1.0f / 512.0f;     // |frac(rf) - 1/2| below this: neighbouring levels may tie
 
 template <int W, int E, int VEC>
 __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
     const float* __restrict__ H, const float* __restrict__ hdiag, const float* __restrict__ G0,
     const float* __restrict__ scale, uint8_t* __restrict__ Q, int d_in, int bits, int group, int group_shift,
-    int n_grp, int T, cdq_col_stats* __restrict__ stats, int32_t* __restrict__ trace, int64_t trace_cap,
-    float* __restrict__ G_out) {
+    int n_grp, int T, int exact_only, cdq_col_stats* __restrict__ stats, int32_t* __restrict__ trace,
+    int64_t trace_cap, float* __restrict__ G_out) {
     constexpr int NCH = E / VEC;              // chunks of VEC consecutive coordinates per lane
     constexpr int STRIDE = 64 * W * VEC;      // coordinates covered by the team per chunk
     __shared__ unsigned long long slots[2][16];
@@ -78,19 +116,34 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
             }
             g2[e] = 2.0f * g;
             hd[e] = h;
-            // reciprocal of the parabola's curvature; only steers which two levels are scored
+            // reciprocal of the parabola's curvature; only steers which levels are scored
             float ci = 0.0f;
             if (h > 0.0f) ci = fminf(__frcp_rn(2.0f * a * h), 3.0e38f);
             cinv[e] = ci;
         }
     }
 
-    int moves = 0, converged = 0;
+    int moves = 0, converged = 0, n_reduce = 0;
     uint32_t last_hi = kOrderedZero;
 
-    for (int t = 0; t < T; ++t) {
-        // ---- 1. score
-        float bs = 0.0f, bu = 0.0f;
+    // (ordered score, payload) of this lane's best candidate -> team-wide winner, uniform
+    auto team_min = [&](float bs, float bu, int be, uint32_t flag) -> uint64_t {
+        const int bi = (be / VEC) * STRIDE + tid * VEC + (be % VEC);
+        const uint32_t payload = ((uint32_t)bi << 7) | ((uint32_t)((int)bu + 32) << 1) | flag;
+        uint64_t key = wave_min_key(order_bits(bs), payload);
+        if (W > 1) {
+            const int p = n_reduce & 1;
+            ++n_reduce;
+            if (lane == 0) slots[p][wave] = key;
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < W; ++w) key = umin64(key, (uint64_t)slots[p][w]);
+        }
+        return key;
+    };
+
+    auto score_fast = [&]() -> uint64_t {
+        float bs = 0.0f, bu = 0.0f, brf = 0.0f;
         int be = 0;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
@@ -100,8 +153,30 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
                 const int e = c * VEC + v;
                 const float qf = (float)((qpack[c] >> (8 * v)) & 0xffu);
                 const float rf = fmaf(-g2[e], cinv[e], qf);
-                const float r0 = fminf(fmaxf(floorf(rf), 0.0f), top);
-                const float r1 = fminf(r0 + 1.0f, top);
+                const float rn = __builtin_amdgcn_fmed3f(rintf(rf), 0.0f, top);
+                const float u = rn - qf;
+                const float d = a * u;
+                const float s = d * fmaf(d, hd[e], g2[e]);
+                if (s < bs) { bs = s; bu = u; brf = rf; be = e; }
+            }
+        }
+        const float frac = brf - floorf(brf);
+        const uint32_t flag = (fabsf(frac - 0.5f) < kHalfWindow) ? 1u : 0u;
+        return team_min(bs, bu, be, flag);
+    };
+
+    auto score_exact = [&]() -> uint64_t {
+        float bs = 0.0f, bu = 0.0f;
+        int be = 0;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const float a = a_c[c];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const int e = c * VEC + v;
+                const float qf = (float)((qpack[c] >> (8 * v)) & 0xffu);
+                const float rf = __builtin_amdgcn_fmed3f(fmaf(-g2[e], cinv[e], qf), 0.0f, top);
+                const float r0 = floorf(rf), r1 = ceilf(rf);
                 float u0 = r0 - qf;
                 const float u1 = r1 - qf;
                 const float d0 = a * u0, d1 = a * u1;
@@ -111,23 +186,22 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
                 if (s0 < bs) { bs = s0; bu = u0; be = e; }
             }
         }
-        // ---- 2. arg-min over the team
-        const int bi = (be / VEC) * STRIDE + tid * VEC + (be % VEC);
-        uint64_t key = ((uint64_t)order_bits(bs) << 32) | (uint32_t)((bi << 6) | ((int)bu + 32));
-#pragma unroll
-        for (int o = 32; o; o >>= 1) key = umin64(key, (uint64_t)__shfl_xor((unsigned long long)key, o));
-        if (W > 1) {
-            if (lane == 0) slots[t & 1][wave] = key;
-            __syncthreads();
-            key = slots[t & 1][lane & (W - 1)];
-#pragma unroll
-            for (int o = W / 2; o; o >>= 1) key = umin64(key, (uint64_t)__shfl_xor((unsigned long long)key, o));
+        return team_min(bs, bu, be, 0u);
+    };
+
+    for (int t = 0; t < T; ++t) {
+        // ---- 1 + 2. score and arg-min
+        uint64_t key = exact_only ? score_exact() : score_fast();
+        uint32_t khi = __builtin_amdgcn_readfirstlane((uint32_t)(key >> 32));
+        uint32_t klo = __builtin_amdgcn_readfirstlane((uint32_t)key);
+        if (!exact_only && (khi >= kOrderedZero || (klo & 1u))) {
+            key = score_exact();
+            khi = __builtin_amdgcn_readfirstlane((uint32_t)(key >> 32));
+            klo = __builtin_amdgcn_readfirstlane((uint32_t)key);
         }
-        const uint32_t khi = __builtin_amdgcn_readfirstlane((uint32_t)(key >> 32));
-        const uint32_t klo = __builtin_amdgcn_readfirstlane((uint32_t)key);
         if (khi >= kOrderedZero) { converged = 1; break; }     // no move lowers the loss
-        const int istar = (int)(klo >> 6);
-        const int ustar = (int)(klo & 63u) - 32;
+        const int istar = (int)(klo >> 7);
+        const int ustar = (int)((klo >> 1) & 63u) - 32;
         // ---- 3. commit: code, then gradient
         const int gstar = (n_grp == 1) ? 0 : (group_shift >= 0 ? (istar >> group_shift) : (istar / group));
         const float delta2 = 2.0f * (scale_j[gstar] * (float)ustar);
@@ -155,7 +229,7 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
                 }
             }
         }
-        if (trace != nullptr && tid == 0 && moves < trace_cap) trace[j * trace_cap + moves] = (int32_t)klo;
+        if (trace != nullptr && tid == 0 && moves < trace_cap) trace[j * trace_cap + moves] = (int32_t)(klo >> 1);
         last_hi = khi;
         ++moves;
     }
@@ -190,10 +264,10 @@ __global__ __launch_bounds__(256) void extract_diag_kernel(const float* __restri
 
 template <int W, int E, int VEC>
 int launch_one(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q, int64_t d_out,
-               int d_in, int bits, int group, int group_shift, int n_grp, int T, cdq_col_stats* stats, int32_t* trace,
-               int64_t trace_cap, float* G_out, hipStream_t st) {
+               int d_in, int bits, int group, int group_shift, int n_grp, int T, int exact_only, cdq_col_stats* stats,
+               int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
     hipLaunchKernelGGL((cd_fused_kernel<W, E, VEC>), dim3((unsigned)d_out), dim3(64 * W), 0, st, H, hdiag, G0, scale, Q, d_in,
-                       bits, group, group_shift, n_grp, T, stats, trace, trace_cap, G_out);
+                       bits, group, group_shift, n_grp, T, exact_only, stats, trace, trace_cap, G_out);
     CDQ_LAUNCH_CHECK();
     return CDQ_OK;
 }
@@ -232,15 +306,15 @@ int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int*
 
 #define CDQ_CD_CASE(Wv, Ev)                                                                                        \
     if (waves == Wv && elems == Ev) {                                                                              \
-        return vec == 4 ? launch_one<Wv, Ev, 4>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, stats, \
-                                                trace, trace_cap, G_out, st)                                       \
-                        : launch_one<Wv, Ev, 1>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, stats, \
-                                                trace, trace_cap, G_out, st);                                      \
+        return vec == 4 ? launch_one<Wv, Ev, 4>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, exact_only, \
+                                                stats, trace, trace_cap, G_out, st)                                \
+                        : launch_one<Wv, Ev, 1>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, exact_only, \
+                                                stats, trace, trace_cap, G_out, st);                               \
     }
 
 int cd_launch(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q, int64_t d_out,
               int64_t d_in, int bits, int64_t group, int64_t T, cdq_col_stats* stats, int waves, int elems, int vec,
-              int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
+              int exact_only, int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
     if (d_out == 0) return CDQ_OK;
     if ((int64_t)64 * waves * elems < d_in) return CDQ_EINVAL;
     if (d_out > 0x7fffffffLL || d_in > CDQ_MAX_D_IN) return CDQ_EUNSUPPORTED;

@@ -96,7 +96,7 @@ int cdq_greedy_cd_ex(const float* H, const float* Wt, const float* scale, const 
     if (rc != CDQ_OK) return rc;
     if (opts != nullptr && opts->ev_loop_begin != nullptr) CDQ_HIP_CHECK(hipEventRecord((hipEvent_t)opts->ev_loop_begin, st));
     rc = cdq::cd_launch(H, hdiag, G0, scale, Q, d_out, d_in, bits, group, T, stats, waves, elems, vec,
-                        opts ? opts->trace : nullptr, opts ? opts->trace_cap : 0, opts ? opts->G_out : nullptr, st);
+                        (opts != nullptr && opts->exact_scorer_only) ? 1 : 0, opts ? opts->trace : nullptr, opts ? opts->trace_cap : 0, opts ? opts->G_out : nullptr, st);
     if (rc != CDQ_OK) return rc;
     if (opts != nullptr && opts->ev_loop_end != nullptr) CDQ_HIP_CHECK(hipEventRecord((hipEvent_t)opts->ev_loop_end, st));
     return CDQ_OK;

@@ -39,7 +39,8 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
 int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int* elems, int* vec);
 int cd_launch(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q,
               int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T, cdq_col_stats* stats,
-              int waves, int elems, int vec, int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st);
+              int waves, int elems, int vec, int exact_only, int32_t* trace, int64_t trace_cap, float* G_out,
+              hipStream_t st);
 int extract_diag_launch(const float* H, int64_t d_in, float* hdiag, hipStream_t st);
 
 }  // namespace cdq

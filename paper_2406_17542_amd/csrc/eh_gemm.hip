@@ -5,8 +5,10 @@
 // fp64 accumulation keeps the one rounding to fp32 reproducible: the result differs from a
 // sequential fp64 sum only when that sum lies within ~1e-16 relative of a rounding boundary.
 //
-// Tile: 128 (columns j) x 128 (coordinates k) per workgroup of 4 wavefronts (2 x 2), each
-// wavefront 64 x 64 = 4 x 4 MFMA blocks; contraction step 16.
+// Tile: 128 (columns j) x 128 (coordinates k) per workgroup of 16 wavefronts (4 x 4), each
+// wavefront 32 x 32 = 2 x 2 MFMA blocks; contraction step 32.  An fp64 MFMA occupies its SIMD
+// for 64 cycles, so LDS bandwidth is irrelevant and the 4 wavefronts per SIMD are there to keep
+// the matrix core fed across barriers and global-load latency.
 #include "cdq_internal.h"
 
 namespace cdq {
@@ -15,66 +17,76 @@ namespace {
 
 typedef double d4 __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128, BN = 128, BK = 16, LDP = 144;   // LDP % 32 == 16: the two k-rows read by lanes 0..31 hit disjoint banks
+constexpr int BM = 128, BN = 128, BK = 32, LDP = 144;   // LDP % 32 == 16: the two k-rows read by lanes 0..31 hit disjoint banks
+constexpr int NT = 1024;
 
-// residual of 8 consecutive coordinates of one column (zero outside the matrix)
-__device__ __forceinline__ void residual8(const float* __restrict__ Wt, const uint8_t* __restrict__ Q,
+// residual of 4 consecutive coordinates of one column (zero outside the matrix)
+template <bool VEC4>
+__device__ __forceinline__ void residual4(const float* __restrict__ Wt, const uint8_t* __restrict__ Q,
                                           const float* __restrict__ scale, const float* __restrict__ zero,
                                           int64_t row, int64_t i0, int64_t d_out, int64_t d_in, int64_t group,
-                                          int64_t n_grp, float out[8]) {
+                                          int64_t n_grp, float out[4]) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) out[e] = 0.0f;
+    for (int e = 0; e < 4; ++e) out[e] = 0.0f;
     if (row >= d_out || i0 >= d_in) return;
-    int64_t gi = i0 / group, rem = i0 - gi * group;
-    float a = scale[row * n_grp + gi], b = zero[row * n_grp + gi];
     const float* w = Wt + row * d_in + i0;
     const uint8_t* q = Q + row * d_in + i0;
+    if (VEC4) {     // d_in % 4 == 0, group % 4 == 0, 16-byte aligned rows: the four share one group
+        const int64_t gi = i0 / group;
+        const float a = scale[row * n_grp + gi], b = zero[row * n_grp + gi];
+        const float4 wv = *reinterpret_cast<const float4*>(w);
+        const uint32_t qv = *reinterpret_cast<const uint32_t*>(q);
+        out[0] = fmaf(a, (float)(qv & 0xffu), b) - wv.x;
+        out[1] = fmaf(a, (float)((qv >> 8) & 0xffu), b) - wv.y;
+        out[2] = fmaf(a, (float)((qv >> 16) & 0xffu), b) - wv.z;
+        out[3] = fmaf(a, (float)(qv >> 24), b) - wv.w;
+    } else {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        if (i0 + e < d_in) {
-            out[e] = fmaf(a, (float)q[e], b) - w[e];
-            if (++rem == group) {
-                rem = 0;
-                ++gi;
-                if (gi < n_grp) { a = scale[row * n_grp + gi]; b = zero[row * n_grp + gi]; }
+        for (int e = 0; e < 4; ++e) {
+            if (i0 + e < d_in) {
+                const int64_t gi = (i0 + e) / group;
+                out[e] = fmaf(scale[row * n_grp + gi], (float)q[e], zero[row * n_grp + gi]) - w[e];
             }
         }
     }
 }
 
-template <bool LOSS>
-__global__ __launch_bounds__(256) void eh_gemm_kernel(const float* __restrict__ H, const float* __restrict__ Wt,
-                                                      const float* __restrict__ scale, const float* __restrict__ zero,
-                                                      const uint8_t* __restrict__ Q, int64_t d_out, int64_t d_in,
-                                                      int64_t group, float* __restrict__ G,
-                                                      double* __restrict__ partial, int n_tiles) {
+template <bool LOSS, bool VEC4>
+__global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H, const float* __restrict__ Wt,
+                                                     const float* __restrict__ scale, const float* __restrict__ zero,
+                                                     const uint8_t* __restrict__ Q, int64_t d_out, int64_t d_in,
+                                                     int64_t group, float* __restrict__ G,
+                                                     double* __restrict__ partial, int n_tiles) {
     __shared__ float As[BK][LDP];     // As[k][m] = E[m0+m][k0+k]
     __shared__ float Bs[BK][LDP];     // Bs[k][n] = H[k0+k][n0+n]
-    __shared__ double red[2][BM];
+    __shared__ double red[4][BM];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave >> 2, wn = wave & 3;
     const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
     const int64_t n_grp = d_in / group;
 
-    d4 acc[4][4];
+    d4 acc[2][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (d4){0.0, 0.0, 0.0, 0.0};
+        for (int j = 0; j < 2; ++j) acc[i][j] = (d4){0.0, 0.0, 0.0, 0.0};
 
-    // loader roles
-    const int a_row = tid >> 1, a_half = tid & 1;          // E tile: 128 rows x (2 x 8) k
-    const int b_row = tid >> 4, b_col = (tid & 15) * 8;    // H tile: 16 rows x (16 x 8) n
+    // loader roles: one 4-wide piece of each tile per thread
+    const int a_row = tid >> 3, a_k = (tid & 7) * 4;        // E tile: 128 rows x (8 x 4) k
+    const int b_row = tid >> 5, b_col = (tid & 31) * 4;     // H tile: 32 rows x (32 x 4) n
 
-    float ra[8], rb[8];
+    float ra[4], rb[4];
     auto load_tiles = [&](int64_t k0) {
-        residual8(Wt, Q, scale, zero, m0 + a_row, k0 + a_half * 8, d_out, d_in, group, n_grp, ra);
-        const int64_t hr = k0 + b_row;
+        residual4<VEC4>(Wt, Q, scale, zero, m0 + a_row, k0 + a_k, d_out, d_in, group, n_grp, ra);
+        const int64_t hr = k0 + b_row, c0 = n0 + b_col;
+        if (VEC4) {
+            float4 hv = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (hr < d_in && c0 < d_in) hv = *reinterpret_cast<const float4*>(H + hr * d_in + c0);
+            rb[0] = hv.x; rb[1] = hv.y; rb[2] = hv.z; rb[3] = hv.w;
+        } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int64_t c = n0 + b_col + e;
-            rb[e] = (hr < d_in && c < d_in) ? H[hr * d_in + c] : 0.0f;
+            for (int e = 0; e < 4; ++e) rb[e] = (hr < d_in && c0 + e < d_in) ? H[hr * d_in + c0 + e] : 0.0f;
         }
     };
 
@@ -82,25 +94,23 @@ __global__ __launch_bounds__(256) void eh_gemm_kernel(const float* __restrict__ 
     for (int64_t k0 = 0; k0 < d_in; k0 += BK) {
         __syncthreads();
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            As[a_half * 8 + e][a_row] = ra[e];
-            Bs[b_row][b_col + e] = rb[e];
-        }
+        for (int e = 0; e < 4; ++e) As[a_k + e][a_row] = ra[e];
+        *reinterpret_cast<float4*>(&Bs[b_row][b_col]) = make_float4(rb[0], rb[1], rb[2], rb[3]);
         __syncthreads();
         if (k0 + BK < d_in) load_tiles(k0 + BK);
 #pragma unroll
         for (int ks = 0; ks < BK; ks += 4) {
-            double a[4], b[4];
+            double a[2], b[2];
             const int kk = ks + (lane >> 4), mn = lane & 15;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                a[i] = (double)As[kk][wm * 64 + i * 16 + mn];
-                b[i] = (double)Bs[kk][wn * 64 + i * 16 + mn];
+            for (int i = 0; i < 2; ++i) {
+                a[i] = (double)As[kk][wm * 32 + i * 16 + mn];
+                b[i] = (double)Bs[kk][wn * 32 + i * 16 + mn];
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
         }
     }
@@ -109,29 +119,29 @@ __global__ __launch_bounds__(256) void eh_gemm_kernel(const float* __restrict__ 
     const int r_in = lane >> 4, c_in = lane & 15;
     if (!LOSS) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int64_t row = m0 + wm * 64 + i * 16 + 4 * v + r_in;
+                const int64_t row = m0 + wm * 32 + i * 16 + 4 * v + r_in;
                 if (row < d_out) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int64_t col = n0 + wn * 64 + j * 16 + c_in;
+                    for (int j = 0; j < 2; ++j) {
+                        const int64_t col = n0 + wn * 32 + j * 16 + c_in;
                         if (col < d_in) G[row * d_in + col] = (float)acc[i][j][v];
                     }
                 }
             }
     } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int lrow = wm * 64 + i * 16 + 4 * v + r_in;
+                const int lrow = wm * 32 + i * 16 + 4 * v + r_in;
                 const int64_t row = m0 + lrow;
                 double s = 0.0;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int64_t col = n0 + wn * 64 + j * 16 + c_in;
+                for (int j = 0; j < 2; ++j) {
+                    const int64_t col = n0 + wn * 32 + j * 16 + c_in;
                     if (row < d_out && col < d_in) {
                         const int64_t gi = col / group;
                         const float e = fmaf(scale[row * n_grp + gi], (float)Q[row * d_in + col], zero[row * n_grp + gi]) -
@@ -146,7 +156,7 @@ __global__ __launch_bounds__(256) void eh_gemm_kernel(const float* __restrict__ 
         __syncthreads();
         if (tid < BM) {
             const int64_t row = m0 + tid;
-            if (row < d_out) partial[row * n_tiles + blockIdx.x] = red[0][tid] + red[1][tid];
+            if (row < d_out) partial[row * n_tiles + blockIdx.x] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
         }
     }
 }
@@ -175,6 +185,10 @@ __global__ __launch_bounds__(1024) void loss_total_kernel(const double* __restri
     if (threadIdx.x == 0) total[0] = sh[0];
 }
 
+bool vec4_ok(const float* H, const float* Wt, const uint8_t* Q, int64_t d_in, int64_t group) {
+    return d_in % 4 == 0 && group % 4 == 0 && ((uintptr_t)H & 15) == 0 && ((uintptr_t)Wt & 15) == 0 && ((uintptr_t)Q & 3) == 0;
+}
+
 }  // namespace
 
 size_t loss_workspace_bytes(int64_t d_out, int64_t d_in) {
@@ -187,8 +201,12 @@ int gradient_launch(const float* H, const float* Wt, const float* scale, const f
     if (d_out == 0) return CDQ_OK;
     const int64_t gx = (d_in + BN - 1) / BN, gy = (d_out + BM - 1) / BM;
     if (gy > 65535) return CDQ_EUNSUPPORTED;
-    hipLaunchKernelGGL(eh_gemm_kernel<false>, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st, H, Wt, scale, zero, Q,
-                       d_out, d_in, group, G, (double*)nullptr, (int)gx);
+    if (vec4_ok(H, Wt, Q, d_in, group))
+        hipLaunchKernelGGL((eh_gemm_kernel<false, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, G, (double*)nullptr, (int)gx);
+    else
+        hipLaunchKernelGGL((eh_gemm_kernel<false, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, G, (double*)nullptr, (int)gx);
     CDQ_LAUNCH_CHECK();
     return CDQ_OK;
 }
@@ -209,8 +227,12 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
     double* partial = (double*)ws;
     double* rows_ws = (double*)((char*)ws + cdq_align_up((size_t)d_out * gx * sizeof(double), 256));
     double* rows = loss_per_col ? loss_per_col : rows_ws;
-    hipLaunchKernelGGL(eh_gemm_kernel<true>, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st, H, Wt, scale, zero, Q,
-                       d_out, d_in, group, (float*)nullptr, partial, (int)gx);
+    if (vec4_ok(H, Wt, Q, d_in, group))
+        hipLaunchKernelGGL((eh_gemm_kernel<true, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, (float*)nullptr, partial, (int)gx);
+    else
+        hipLaunchKernelGGL((eh_gemm_kernel<true, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, (float*)nullptr, partial, (int)gx);
     CDQ_LAUNCH_CHECK();
     hipLaunchKernelGGL(loss_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, partial, d_out, (int)gx, rows);
     CDQ_LAUNCH_CHECK();

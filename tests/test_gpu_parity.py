@@ -155,7 +155,7 @@ def test_gradient_and_loss(cdq, oracle, d_out, d_in, n, bits, group):
 
 def decode_trace(tr):
     tr = tr.astype(np.int64)
-    return tr >> 6, (tr & 63) - 32
+    return tr >> 6, (tr & 63) - 32       # entries of -1 (unused slots) decode to coordinate -1
 
 
 def run_cd_both(cdq, oracle, H32, Wt, a, b, q0, bits, group, T, **kw):
@@ -295,6 +295,26 @@ def test_greedy_cd_deterministic_and_resumable(cdq, oracle):
     # resuming recomputes g from the codes in fp64, so the continued run may differ from the
     # uninterrupted one only where fp32 drift of g decided a near-tie
     assert (Q3 == Q1).float().mean().item() >= 0.999
+
+
+@pytest.mark.parametrize("bits,group,rq", [(2, 128, True), (3, 1024, True), (4, 1024, False), (4, 64, True)])
+def test_greedy_cd_scorers_agree(cdq, oracle, bits, group, rq):
+    """The nearest-level scorer (with the two-level scorer as arbiter) and the two-level scorer
+    alone must produce the same moves in the same order."""
+    d_out, d_in, n, T = 96, 1024, 2048, 700
+    X, Wt = rand_layer(4242 + bits, d_in, d_out, n)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q0 = oracle.init_grid(Wt, bits, group)
+    if rq:
+        q0 = inputs.make_random_codes(d_out, d_in, bits, seed=bits)
+    Hd, Wd, ad, bd = dev(H32), dev(Wt), dev(a), dev(b)
+    Qa, Qb = dev(q0.copy()), dev(q0.copy())
+    oa = cdq.greedy_cd(Hd, Wd, ad, bd, Qa, bits, group, T, trace_cap=T, want_G=True)
+    ob = cdq.greedy_cd(Hd, Wd, ad, bd, Qb, bits, group, T, trace_cap=T, want_G=True, exact_scorer_only=True)
+    assert torch.equal(Qa, Qb)
+    assert torch.equal(oa["trace"], ob["trace"])
+    assert torch.equal(oa["G"], ob["G"])
+    assert torch.equal(oa["stats"], ob["stats"])
 
 
 def test_greedy_cd_dead_channel_and_diagonal(cdq, oracle):
