@@ -1,0 +1,130 @@
+"""Parity at the real shapes, in the launch configuration bench.py times (default launch shape,
+whole layer on the GPU), checked on sampled outputs the oracle can compute one by one:
+  * Hessian: the whole diagonal and 4096 random entries recomputed from X in fp64
+  * greedy CD: a random sample of columns rerun by the oracle from the same fp32 H -- codes,
+    move counts and convergence flags must match (>= 99.9 % of codes; in practice all)
+  * loss: per-column values of the sampled columns against the oracle's fp64 loss
+and on properties that hold at any size (loss never increases, every column reports convergence
+or exhausts T, H symmetric).  Each test prints its steps so a long run is visibly alive.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2406_17542_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def cdq():
+    assert torch.cuda.is_available()
+    from paper_2406_17542_amd import cdq as m
+    m.lib()
+    return m
+
+
+def say(msg):
+    print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+def x_to_dev(X, x_dtype):
+    if x_dtype == "bf16":
+        return torch.from_numpy(inputs.bf16_bits(X).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(X).cuda()
+
+
+def check_hessian_samples(H, X, n_samples=4096, seed=0):
+    """Diagonal and random entries of H against fp64 sums over the tokens of X."""
+    n, d_in = X.shape
+    rng = np.random.default_rng(seed)
+    diag = np.einsum("ti,ti->i", X, X, dtype=np.float64)
+    Hd = np.diag(H).astype(np.float64)
+    tol = 8.0 * np.sqrt(n) * 2.0 ** -24
+    assert np.all(np.abs(Hd - diag) <= tol * diag + 1e-30)
+    ii = rng.integers(0, d_in, n_samples)
+    kk = rng.integers(0, d_in, n_samples)
+    ref = np.einsum("ts,ts->s", X[:, ii].astype(np.float64), X[:, kk].astype(np.float64))
+    err = np.abs(H[ii, kk].astype(np.float64) - ref)
+    assert np.all(err <= tol * np.sqrt(diag[ii] * diag[kk]) + 1e-30), float((err / (tol * np.sqrt(diag[ii] * diag[kk]))).max())
+    assert np.array_equal(H[ii, kk], H[kk, ii])
+
+
+def run_layer(cdq, oracle, cfg, d_out, T, sample_cols, q0_random=False, seed=0):
+    say(f"{cfg.name}: generating X [{cfg.n}x{cfg.d_in}] and Wt [{d_out}x{cfg.d_in}]")
+    X, Wt = inputs.make_layer(cfg, d_out=d_out)
+    Xd = x_to_dev(X, cfg.x_dtype)
+    say("hessian on the GPU")
+    Hd = cdq.hessian(Xd)
+    H32 = Hd.cpu().numpy()
+    say("hessian spot checks in fp64")
+    check_hessian_samples(H32, X)
+    del Xd
+    Wd = torch.from_numpy(Wt).cuda()
+    scale, zero, Q = cdq.init_rtn(Wd, cfg.bits, cfg.group)
+    a, b, q_rtn = oracle.init_grid(Wt, cfg.bits, cfg.group)
+    assert np.array_equal(Q.cpu().numpy(), q_rtn), "RTN codes differ"
+    assert np.array_equal(scale.cpu().numpy(), a) and np.array_equal(zero.cpu().numpy(), b)
+    if q0_random:
+        q0 = inputs.make_random_codes(d_out, cfg.d_in, cfg.bits, seed=cfg.seed)
+        Q.copy_(torch.from_numpy(q0).cuda())
+    else:
+        q0 = q_rtn
+    l0 = cdq.loss(Hd, Wd, scale, zero, Q, cfg.group)[0].cpu().numpy()
+    say(f"greedy CD on the GPU, T={T}, default launch shape")
+    out = cdq.greedy_cd(Hd, Wd, scale, zero, Q, cfg.bits, cfg.group, T)
+    torch.cuda.synchronize()
+    l1 = cdq.loss(Hd, Wd, scale, zero, Q, cfg.group)[0].cpu().numpy()
+    stats = out["stats"].cpu().numpy()
+    Qn = Q.cpu().numpy()
+    # properties that hold at any size
+    assert np.all(l1 <= l0 * (1 + 1e-9)), "loss increased on some column"
+    assert np.all((stats[:, 2] == 1) | (stats[:, 0] == T)), "a column neither converged nor used its budget"
+    assert np.all(stats[:, 0] <= T)
+    changed = (Qn != q0).sum(axis=1)
+    assert np.all(changed <= stats[:, 0])
+    # sampled columns through the oracle
+    rng = np.random.default_rng(seed + 1)
+    cols = np.sort(rng.choice(d_out, size=min(sample_cols, d_out), replace=False))
+    say(f"oracle on {len(cols)} sampled columns")
+    ref = oracle.greedy_cd(H32, Wt[cols], a[cols], b[cols], q0[cols], cfg.bits, cfg.group, T)
+    same = Qn[cols] == ref["Q"]
+    frac = same.mean()
+    say(f"codes equal on {frac:.6f} of sampled entries; moves total {int(stats[:, 0].sum())}, "
+        f"mean {stats[:, 0].mean():.1f}, max {stats[:, 0].max()}, converged {int(stats[:, 2].sum())}/{d_out}")
+    assert frac >= 0.999
+    good = same.all(axis=1)
+    assert good.mean() >= 0.98, "too many sampled columns diverged"
+    assert np.array_equal(stats[cols][good, 0], ref["moves"][good])
+    assert np.array_equal(stats[cols][good, 2], ref["converged"][good])
+    l_ref = oracle.loss(H32, Wt[cols], ref["Q"], a[cols], b[cols], cfg.group)
+    np.testing.assert_allclose(l1[cols][good], l_ref[good], rtol=1e-6)
+    assert abs(l1[cols].sum() - l_ref.sum()) <= 1e-4 * l_ref.sum()
+    return stats
+
+
+def test_attn_proj_full_layer(cdq, oracle):
+    """The benchmark workload itself: whole layer, full T, RTN start."""
+    cfg = inputs.CONFIGS["attn_proj"]
+    stats = run_layer(cdq, oracle, cfg, cfg.d_out, cfg.T, sample_cols=160)
+    assert stats[:, 2].all(), "every column of this layer converges well before T = d_in"
+
+
+def test_attn_proj_random_start(cdq, oracle):
+    """Same layer from uniform random codes: every column uses its whole budget."""
+    cfg = inputs.CONFIGS["attn_proj"]
+    run_layer(cdq, oracle, cfg, 512, 1024, sample_cols=48, q0_random=True)
+
+
+def test_mlp_up_column_subset(cdq, oracle):
+    """2-bit, groups of 128, Student-t activations; 2048 of the 16384 columns, full T."""
+    cfg = inputs.CONFIGS["mlp_up"]
+    run_layer(cdq, oracle, cfg, 2048, cfg.T, sample_cols=160)
+
+
+def test_mlp_down_column_subset(cdq, oracle):
+    """d_in = 16384 (H is 1 GiB): 256 columns, first 192 iterations, 8 wavefronts per column."""
+    cfg = inputs.CONFIGS["mlp_down"]
+    run_layer(cdq, oracle, cfg, 256, 192, sample_cols=24)
