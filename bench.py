@@ -118,6 +118,7 @@ def main():
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--elems", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the achievable-bandwidth probes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (columns would shard with no communication; "
@@ -172,6 +173,14 @@ def main():
         rec(6)
         state.update(stats=out["stats"], loss=tot, Q=Q, scale=scale, zero=zero)
 
+    # a copy of known size (256 MiB read + 256 MiB written): reference dispatch for scaling the
+    # FETCH_SIZE / WRITE_SIZE counters when this command runs under rocprofv3 --pmc
+    cal_src = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cdq.probe_copy(cal_src, cal_dst)
+    torch.cuda.synchronize()
+    del cal_dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -204,12 +213,47 @@ def main():
     h_tflops_eff = flop_eff / (stages["hessian"] * 1e-3) * 1e-12
     mfma_peak = MFMA_PEAK_TFLOPS[cfg.x_dtype]
 
+    # achievable bandwidth on this machine, same process: streaming read from HBM, and the loop's
+    # access pattern (independent random rows of H, same row length and team width) without its
+    # arithmetic
+    achievable = {}
+    if not args.no_probes:
+        sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+        big = torch.empty(1 << 30, dtype=torch.float32, device="cuda")       # 4 GiB
+        big.zero_()
+        e0, e1 = ev.create(), ev.create()
+        cdq.probe_read(big, big.numel() * 4, sink)
+        torch.cuda.synchronize()
+        ev.record(e0, stream)
+        for _ in range(5):
+            cdq.probe_read(big, big.numel() * 4, sink)
+        ev.record(e1, stream)
+        achievable["hbm_stream_read_GBps"] = 5 * big.numel() * 4 / (ev.elapsed_ms(e0, e1) * 1e-3) * 1e-9
+        del big
+        waves_used = args.waves
+        if waves_used == 0:
+            waves_used = 1
+            while 64 * waves_used * 32 < cfg.d_in or (cfg.d_out * waves_used < 4096 and waves_used < 16 and 64 * waves_used * 4 < cfg.d_in):
+                waves_used *= 2
+        teams = 256 * max(1, 16 // waves_used)
+        row_bytes = 4 * cfg.d_in
+        iters = max(50, int(2e11 / (teams * row_bytes)))
+        cdq.probe_gather(H, cfg.d_in, row_bytes, teams, waves_used, iters, sink)
+        torch.cuda.synchronize()
+        ev.record(e0, stream)
+        cdq.probe_gather(H, cfg.d_in, row_bytes, teams, waves_used, iters, sink)
+        ev.record(e1, stream)
+        achievable["h_row_gather_GBps"] = teams * iters * row_bytes / (ev.elapsed_ms(e0, e1) * 1e-3) * 1e-9
+        achievable["h_row_gather_shape"] = f"H {cfg.d_in}x{cfg.d_in} fp32, rows of {row_bytes} B, {teams} teams x {waves_used} wavefronts"
+
     workload = (f"{cfg.name}: d_in={cfg.d_in} d_out={cfg.d_out} n={cfg.n} X={cfg.x_dtype}/{cfg.x_kind} bits={cfg.bits} "
                 f"group={'per-channel' if cfg.group == cfg.d_in else cfg.group} T={cfg.T} init={'random codes' if args.mode == 'stress' else cfg.init}")
     if stages["cd_loop"] >= stages["hessian"]:
         roofline = {"kernel": "cd_fused_kernel", "bound": "hbm", "achieved": cd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": cd_gbs / HBM_PEAK_GBS, "traffic": load_traffic("cd_fused_kernel", f"{cfg.name}:{args.mode}"),
                     "algorithmic_bytes_per_launch": cd_bytes, "avg_launch_ms": stages["cd_loop"]}
+        if "h_row_gather_GBps" in achievable:
+            roofline["frac_of_achievable_gather"] = cd_gbs / achievable["h_row_gather_GBps"]
     else:
         roofline = {"kernel": "hessian_kernel", "bound": "mfma", "achieved": h_tflops_exec, "peak": mfma_peak, "unit": "TFLOP/s",
                     "frac": h_tflops_exec / mfma_peak, "traffic": load_traffic("hessian_kernel", f"{cfg.name}:{args.mode}"),
@@ -228,6 +272,7 @@ def main():
         "hessian": {"tflops_executed": h_tflops_exec, "tflops_effective": h_tflops_eff, "mfma_peak_tflops": mfma_peak,
                     "frac_of_mfma_peak": h_tflops_exec / mfma_peak},
         "loss_final": loss_final,
+        "achievable": achievable,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, args.mode)

@@ -56,7 +56,11 @@ def lib() -> ctypes.CDLL:
         L.cdq_greedy_cd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, sz, vp]
         L.cdq_greedy_cd_ex.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, ctypes.POINTER(CdOptions), vp, sz, vp]
         L.cdq_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
-        for fn in (L.cdq_hessian, L.cdq_init_rtn, L.cdq_gradient, L.cdq_greedy_cd, L.cdq_greedy_cd_ex, L.cdq_loss):
+        L.cdq_probe_copy.argtypes = [vp, vp, sz, vp]
+        L.cdq_probe_read.argtypes = [vp, sz, vp, vp]
+        L.cdq_probe_gather.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
+        for fn in (L.cdq_hessian, L.cdq_init_rtn, L.cdq_gradient, L.cdq_greedy_cd, L.cdq_greedy_cd_ex, L.cdq_loss,
+                   L.cdq_probe_copy, L.cdq_probe_read, L.cdq_probe_gather):
             fn.restype = i32
         _lib = L
     return _lib
@@ -169,3 +173,20 @@ def loss(H, Wt, scale, zero, Q, group: int, workspace: torch.Tensor | None = Non
                           _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, group,
                           per.data_ptr(), tot.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "cdq_loss")
     return per, tot
+
+
+# ---- measurement helpers (see include/cdq.h): thin wrappers, used by bench.py only
+
+def probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib().cdq_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream()), "cdq_probe_copy")
+
+
+def probe_read(src: torch.Tensor, nbytes: int, sink: torch.Tensor) -> None:
+    _check(lib().cdq_probe_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream()), "cdq_probe_read")
+
+
+def probe_gather(H: torch.Tensor, n_rows: int, row_bytes: int, teams: int, waves_per_row: int, iters: int,
+                 sink: torch.Tensor) -> None:
+    _check(lib().cdq_probe_gather(H.data_ptr(), n_rows, row_bytes, teams, waves_per_row, iters, sink.data_ptr(),
+                                  _stream()), "cdq_probe_gather")

@@ -1,0 +1,85 @@
+// Measurement helpers: plain memory kernels that give the achievable-bandwidth denominators the
+// benchmark quotes next to the coordinate-descent loop, and a copy of known size used to scale
+// hardware byte counters.  They compute nothing of the method.
+#include "cdq_internal.h"
+
+namespace cdq {
+namespace {
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst, size_t n4) {
+    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n4; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void probe_read_kernel(const float4* __restrict__ src, size_t n4, float* __restrict__ sink) {
+    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    float acc = 0.0f;
+    for (; i < n4; i += stride) {
+        const float4 v = src[i];
+        acc += (v.x + v.y) + (v.z + v.w);
+    }
+    if (acc == 1.2345678e-30f) sink[0] = acc;     // keeps the loads alive; practically never true
+}
+
+// Every team of `wpr` wavefronts reads `iters` pseudo-random rows of `row_f4` float4 each, one
+// after the other, with no dependence between rows: the access pattern of the gradient update
+// without its arithmetic.
+__global__ __launch_bounds__(1024) void probe_gather_kernel(const float4* __restrict__ H, unsigned n_rows, int row_f4, int iters,
+                                                            int wpr, float* __restrict__ sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int waves_per_block = blockDim.x >> 6;
+    const unsigned team = (blockIdx.x * waves_per_block + wave) / wpr;
+    const int wi = wave % wpr;
+    unsigned s = team * 2654435761u + 12345u;
+    float acc = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+        s = s * 1664525u + 1013904223u;
+        const float4* r = H + (size_t)((s >> 8) % n_rows) * row_f4;
+        for (int k = wi * 64 + lane; k < row_f4; k += 64 * wpr) {
+            const float4 v = r[k];
+            acc += (v.x + v.y) + (v.z + v.w);
+        }
+    }
+    if (acc == 1.2345678e-30f) sink[0] = acc;
+}
+
+}  // namespace
+}  // namespace cdq
+
+extern "C" {
+
+int cdq_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (src == nullptr || dst == nullptr || bytes % 16 != 0 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return CDQ_EINVAL;
+    if (bytes == 0) return CDQ_OK;
+    hipLaunchKernelGGL(cdq::probe_copy_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const float4*)src, (float4*)dst, bytes / 16);
+    CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
+
+int cdq_probe_read(const void* src, size_t bytes, float* sink, void* stream) {
+    if (src == nullptr || sink == nullptr || bytes % 16 != 0 || ((uintptr_t)src & 15)) return CDQ_EINVAL;
+    if (bytes == 0) return CDQ_OK;
+    hipLaunchKernelGGL(cdq::probe_read_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const float4*)src, bytes / 16, sink);
+    CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
+
+int cdq_probe_gather(const void* H, int64_t n_rows, int64_t row_bytes, int64_t teams, int waves_per_row, int64_t iters,
+                     float* sink, void* stream) {
+    if (H == nullptr || sink == nullptr || n_rows <= 0 || n_rows > 0x7fffffffLL || row_bytes <= 0 || row_bytes % 16 != 0 ||
+        ((uintptr_t)H & 15) || teams <= 0 || iters < 0 || iters > 0x7fffffffLL)
+        return CDQ_EINVAL;
+    if (waves_per_row != 1 && waves_per_row != 2 && waves_per_row != 4 && waves_per_row != 8 && waves_per_row != 16) return CDQ_EINVAL;
+    const int threads = waves_per_row >= 4 ? 64 * waves_per_row : 256;      // whole teams per block
+    const int teams_per_block = threads / (64 * waves_per_row);
+    const int64_t blocks = (teams + teams_per_block - 1) / teams_per_block;
+    if (blocks > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
+    hipLaunchKernelGGL(cdq::probe_gather_kernel, dim3((unsigned)blocks), dim3(threads), 0, (hipStream_t)stream, (const float4*)H,
+                       (unsigned)n_rows, (int)(row_bytes / 16), (int)iters, waves_per_row, sink);
+    CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
+
+}  // extern "C"
