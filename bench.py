@@ -207,8 +207,9 @@ def main():
     cd_bytes = moves * 4.0 * cfg.d_in                         # one H row (4*d_in bytes) per committed update
     cd_gbs = cd_bytes / (stages["cd_loop"] * 1e-3) * 1e-9
     flop_eff = 2.0 * cfg.n * cfg.d_in * cfg.d_in
-    n_t = (cfg.d_in + 127) // 128
-    flop_exec = 2.0 * cfg.n * (n_t * (n_t + 1) // 2) * 128 * 128   # upper-triangular tiles only
+    tile = 256 if cfg.x_dtype == "bf16" else 128                  # tile edge of the Hessian kernels
+    n_t = (cfg.d_in + tile - 1) // tile
+    flop_exec = 2.0 * cfg.n * (n_t * (n_t + 1) // 2) * tile * tile   # upper-triangular tiles only
     h_tflops_exec = flop_exec / (stages["hessian"] * 1e-3) * 1e-12
     h_tflops_eff = flop_eff / (stages["hessian"] * 1e-3) * 1e-12
     mfma_peak = MFMA_PEAK_TFLOPS[cfg.x_dtype]

@@ -21,9 +21,7 @@ typedef float f16v __attribute__((ext_vector_type(16)));
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
-constexpr int TB = 128;                 // tile of H: TB x TB per workgroup
-constexpr int BK16 = 64;                // tokens per step, bf16 path
-constexpr int ROWB = BK16 * 2 + 16;     // LDS bytes per column of the transposed tile (padded)
+constexpr int TB = 128;                 // tile of H per workgroup, fp32 path
 constexpr int BK32 = 16;                // tokens per step, fp32 path
 constexpr int LDF = TB + 16;            // LDS floats per token row, fp32 path (LDF % 32 == 16)
 
@@ -36,97 +34,127 @@ __device__ __forceinline__ void tile_from_linear(int lin, int n_t, int* I, int* 
 }
 
 // ------------------------------------------------------------------------------------------ bf16
+//
+// 256 x 256 tile of H per workgroup of 8 wavefronts (two per SIMD, so one can issue MFMAs while
+// the other waits on LDS or the barrier), each wavefront 128 x 64 = 4 x 2 MFMA blocks, 64 tokens
+// per step, LDS double-buffered (one barrier per step), next step's global loads in flight
+// during the current step's MFMAs.
+// LDS holds each operand tile transposed: 128 bytes (64 tokens) per column, the 16-byte token
+// octets of a column XOR-swizzled with ((col >> 3) ^ col) & 7 so that both the transposing stores
+// (8 consecutive lanes = 8 column octets) and the fragment reads (8 consecutive lanes = 8
+// consecutive columns) touch 8 distinct bank groups.
 
-// 8 tokens x 1 column pair (two adjacent bf16 columns as one 32-bit word per token)
-__device__ __forceinline__ void load_pair8(const uint16_t* __restrict__ X, int64_t n, int64_t d_in, int64_t t0,
-                                           int64_t col, uint32_t w[8]) {
+constexpr int T2 = 256;                 // tile of H: T2 x T2 per workgroup
+constexpr int BK16 = 64;                // tokens per step
+constexpr int COLB = BK16 * 2;          // LDS bytes per column of the transposed tile
+constexpr int TILE_BYTES = T2 * COLB;   // 32 KiB per operand per buffer
+
+__device__ __forceinline__ int swz(int col, int octet) { return col * COLB + ((octet ^ (((col >> 3) ^ col) & 7)) << 4); }
+
+// 8 tokens x 8 adjacent bf16 columns (16 bytes per token)
+__device__ __forceinline__ void load_oct8(const uint16_t* __restrict__ X, int64_t t_end, int64_t d_in, int64_t t0,
+                                          int64_t col, u4 w[8]) {
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         const int64_t t = t0 + r;
-        w[r] = (t < n && col < d_in) ? *reinterpret_cast<const uint32_t*>(X + t * d_in + col) : 0u;
+        if (t < t_end && col < d_in) w[r] = *reinterpret_cast<const u4*>(X + t * d_in + col);
+        else w[r] = (u4){0u, 0u, 0u, 0u};
     }
 }
-__device__ __forceinline__ void store_pair8(char* tile, int colpair, int tgroup, const uint32_t w[8]) {
-    u4 lo, hi;
+// transpose the 8x8 block in registers and store one 8-token run (16 bytes) per column
+__device__ __forceinline__ void store_oct8(char* tile, int col_octet, int tok_octet, const u4 w[8]) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        lo[k] = (w[2 * k] & 0xffffu) | (w[2 * k + 1] << 16);
-        hi[k] = (w[2 * k] >> 16) | (w[2 * k + 1] & 0xffff0000u);
+    for (int c = 0; c < 8; ++c) {
+        u4 o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t x = w[2 * k][c >> 1], y = w[2 * k + 1][c >> 1];
+            o[k] = (c & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
+        }
+        *reinterpret_cast<u4*>(tile + swz(col_octet * 8 + c, tok_octet)) = o;
     }
-    *reinterpret_cast<u4*>(tile + (2 * colpair) * ROWB + tgroup * 16) = lo;
-    *reinterpret_cast<u4*>(tile + (2 * colpair + 1) * ROWB + tgroup * 16) = hi;
 }
 
-__global__ __launch_bounds__(256) void hessian_bf16_kernel(const uint16_t* __restrict__ X, int64_t n, int64_t d_in,
+__global__ __launch_bounds__(512) void hessian_bf16_kernel(const uint16_t* __restrict__ X, int64_t n, int64_t d_in,
                                                            int n_t, int64_t tokens_per_split,
                                                            float* __restrict__ out, int64_t split_stride) {
-    __shared__ __attribute__((aligned(16))) char As[TB * ROWB];
-    __shared__ __attribute__((aligned(16))) char Bs[TB * ROWB];
+    extern __shared__ __attribute__((aligned(16))) char lds[];       // [2 buffers][A tile | B tile]
     int I, J;
     tile_from_linear(blockIdx.x, n_t, &I, &J);
     const bool diag = (I == J);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int64_t i0 = (int64_t)I * TB, j0 = (int64_t)J * TB;
+    const int wm = wave >> 2, wn = wave & 3;           // 2 x 4 wavefronts, each 128 rows x 64 columns
+    const int64_t i0 = (int64_t)I * T2, j0 = (int64_t)J * T2;
     const int64_t t_begin = (int64_t)blockIdx.z * tokens_per_split;
     const int64_t t_end = (t_begin + tokens_per_split < n) ? t_begin + tokens_per_split : n;
 
-    f16v acc[2][2];
+    f16v acc[4][2];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    const int cp = tid & 63, tg = tid >> 6;          // column pair, token group (and tg + 4)
-    uint32_t ra0[8], ra1[8], rb0[8], rb1[8];
-    auto gload = [&](int64_t t0) {
-        load_pair8(X, t_end, d_in, t0 + tg * 8, i0 + 2 * cp, ra0);
-        load_pair8(X, t_end, d_in, t0 + (tg + 4) * 8, i0 + 2 * cp, ra1);
-        if (!diag) {
-            load_pair8(X, t_end, d_in, t0 + tg * 8, j0 + 2 * cp, rb0);
-            load_pair8(X, t_end, d_in, t0 + (tg + 4) * 8, j0 + 2 * cp, rb1);
+    // staging roles: threads 0..255 move the A tile (columns of block I), 256..511 the B tile
+    const int half = tid >> 8;
+    const int co = tid & 31, to = (tid >> 5) & 7;      // column octet, token octet
+    const int64_t c0 = (half ? j0 : i0) + co * 8;
+    const bool active = !(half && diag);               // a diagonal tile needs one operand only
+    const bool interior = (i0 + T2 <= d_in) && (j0 + T2 <= d_in);
+    u4 r[8];
+    auto gload = [&](int64_t t0, bool full) {
+        if (!active) return;
+        if (full && interior) {                        // no bounds checks on the common path
+            const uint16_t* p = X + (t0 + to * 8) * d_in + c0;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) r[q] = *reinterpret_cast<const u4*>(p + q * d_in);
+        } else {
+            load_oct8(X, t_end, d_in, t0 + to * 8, c0, r);
         }
     };
+    auto lstore = [&](int buf) {
+        if (active) store_oct8(lds + buf * 2 * TILE_BYTES + half * TILE_BYTES, co, to, r);
+    };
 
-    if (t_begin < t_end) gload(t_begin);
+    if (t_begin < t_end) {
+        gload(t_begin, t_begin + BK16 <= t_end);
+        lstore(0);
+    }
+    __syncthreads();
+    int buf = 0;
     for (int64_t t0 = t_begin; t0 < t_end; t0 += BK16) {
-        __syncthreads();
-        store_pair8(As, cp, tg, ra0);
-        store_pair8(As, cp, tg + 4, ra1);
-        if (!diag) {
-            store_pair8(Bs, cp, tg, rb0);
-            store_pair8(Bs, cp, tg + 4, rb1);
-        }
-        __syncthreads();
-        if (t0 + BK16 < t_end) gload(t0 + BK16);
-        const char* Bsrc = diag ? As : Bs;
+        const bool more = t0 + BK16 < t_end;
+        if (more) gload(t0 + BK16, t0 + 2 * BK16 <= t_end);
+        const char* At = lds + buf * 2 * TILE_BYTES;
+        const char* Bt = diag ? At : At + TILE_BYTES;
 #pragma unroll
         for (int ks = 0; ks < BK16 / 16; ++ks) {
-            bf8 af[2], bfr[2];
-            const int koff = ks * 32 + (lane >> 5) * 16;
+            bf8 af[4], bfr[2];
+            const int oct = ks * 2 + (lane >> 5);
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                af[b] = *reinterpret_cast<const bf8*>(As + (wm * 64 + b * 32 + (lane & 31)) * ROWB + koff);
-                bfr[b] = *reinterpret_cast<const bf8*>(Bsrc + (wn * 64 + b * 32 + (lane & 31)) * ROWB + koff);
-            }
+            for (int b = 0; b < 4; ++b) af[b] = *reinterpret_cast<const bf8*>(At + swz(wm * 128 + b * 32 + (lane & 31), oct));
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int b = 0; b < 2; ++b) bfr[b] = *reinterpret_cast<const bf8*>(Bt + swz(wn * 64 + b * 32 + (lane & 31), oct));
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
         }
+        if (more) lstore(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
     }
     // 32x32 result block: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
     float* dst = out + (int64_t)blockIdx.z * split_stride;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int64_t row = i0 + wm * 64 + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
+                const int64_t row = i0 + wm * 128 + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
                 const int64_t col = j0 + wn * 64 + b * 32 + (lane & 31);
                 if (row < d_in && col < d_in) dst[row * d_in + col] = acc[a][b][v];
             }
@@ -209,14 +237,14 @@ __global__ __launch_bounds__(256) void hessian_f32_kernel(const float* __restric
 
 // ------------------------------------------------------------------------------------------ finalize
 
-// One workgroup per 32x32 block on or above the diagonal: sum the splits (ascending), add the
+// One workgroup per 32x32 block on or above the diagonal (2-D grid, blocks below it exit): sum the splits (ascending), add the
 // previous H if accumulating, write the block and its mirror image (through LDS, so both
 // writes are coalesced).  `parts` may alias H when there is a single split and no accumulation.
 __global__ __launch_bounds__(256) void hessian_finalize_kernel(const float* parts, int splits, int64_t split_stride,
                                                                float* H, int64_t d_in, int nb, int accumulate) {
     __shared__ float tile[32][33];
-    int I, J;
-    tile_from_linear(blockIdx.x, nb, &I, &J);
+    const int I = blockIdx.y, J = blockIdx.x;
+    if (I > J) return;                                    // blocks below the diagonal are written as mirrors
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
     for (int r = ty; r < 32; r += 8) {
         const int64_t row = (int64_t)I * 32 + r, col = (int64_t)J * 32 + tx;
@@ -258,27 +286,44 @@ __global__ __launch_bounds__(256) void add_damping_kernel(float* __restrict__ H,
     if (i < d_in) H[i * d_in + i] += lambda_rel * mean[0];
 }
 
-int choose_splits(int64_t n, int64_t d_in, int bk) {
-    const int64_t n_t = (d_in + TB - 1) / TB;
+int choose_splits(int64_t n, int64_t d_in, int bk, int tile) {
+    const int64_t n_t = (d_in + tile - 1) / tile;
     const int64_t tiles = n_t * (n_t + 1) / 2;
-    int splits = 1;
-    // enough workgroups for two per CU, but keep at least 8 steps of tokens per split
-    while (tiles * splits < 512 && splits < 32 && n / (splits * 2) >= (int64_t)bk * 8) splits *= 2;
-    return splits;
+    const int64_t max_splits = n / ((int64_t)bk * 16) > 0 ? n / ((int64_t)bk * 16) : 1;   // >= 16 steps per split
+    int64_t splits = 1;
+    if (tile == TB) {                     // small fp32 tiles, several workgroups per CU: just fill the chip twice
+        while (tiles * splits < 512 && splits < 32) splits *= 2;
+    } else if (tiles <= 256) {            // one workgroup per CU: fill exactly one round
+        splits = 256 / tiles;
+    } else {                              // few rounds: pick the split count that wastes least of the last round
+        double best = 0.0;
+        for (int64_t sp = 1; sp <= 4; ++sp) {
+            const double rounds = (double)(tiles * sp) / 256.0;
+            const double eff = rounds / (double)((tiles * sp + 255) / 256);
+            if (eff > best + 0.03) { best = eff; splits = sp; }
+            if (best >= 0.9) break;
+        }
+    }
+    if (splits > max_splits) splits = max_splits;
+    if (splits > 32) splits = 32;
+    if (splits < 1) splits = 1;
+    return (int)splits;
 }
 
 }  // namespace
 
 size_t hessian_workspace_bytes(int64_t n, int64_t d_in) {
-    const int splits = choose_splits(n, d_in, BK32 /* the smaller step: never under-estimates */);
+    const int s32 = choose_splits(n, d_in, BK32, TB), s16 = choose_splits(n, d_in, BK16, T2);
+    const int splits = s32 > s16 ? s32 : s16;          // the dtype is not known here: cover both paths
     return cdq_align_up((size_t)splits * d_in * d_in * sizeof(float), 256) + 256;
 }
 
 int hessian_launch(const void* X, int x_dtype, int64_t n, int64_t d_in, float* H, int accumulate, float lambda_rel,
                    void* ws, size_t ws_bytes, hipStream_t st) {
     const int bk = (x_dtype == CDQ_BF16) ? BK16 : BK32;
-    int splits = choose_splits(n, d_in, bk);
-    const int64_t n_t = (d_in + TB - 1) / TB;
+    const int tile = (x_dtype == CDQ_BF16) ? T2 : TB;
+    int splits = choose_splits(n, d_in, bk, tile);
+    const int64_t n_t = (d_in + tile - 1) / tile;
     const int64_t tiles = n_t * (n_t + 1) / 2;
     if (tiles > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
     const size_t part_bytes = cdq_align_up((size_t)splits * d_in * d_in * sizeof(float), 256);
@@ -292,15 +337,18 @@ int hessian_launch(const void* X, int x_dtype, int64_t n, int64_t d_in, float* H
     if (per == 0) per = bk;
     const int64_t stride = d_in * d_in;
     dim3 grid((unsigned)tiles, 1, (unsigned)splits);
-    if (x_dtype == CDQ_BF16)
-        hipLaunchKernelGGL(hessian_bf16_kernel, grid, dim3(256), 0, st, (const uint16_t*)X, n, d_in, (int)n_t, per, parts, stride);
+    if (x_dtype == CDQ_BF16) {
+        static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(hessian_bf16_kernel),
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILE_BYTES);
+        if (attr_rc != hipSuccess) return CDQ_EHIP;
+        hipLaunchKernelGGL(hessian_bf16_kernel, grid, dim3(512), 4 * TILE_BYTES, st, (const uint16_t*)X, n, d_in, (int)n_t, per, parts, stride);
+    }
     else
         hipLaunchKernelGGL(hessian_f32_kernel, grid, dim3(256), 0, st, (const float*)X, n, d_in, (int)n_t, per, parts, stride);
     CDQ_LAUNCH_CHECK();
     const int64_t nb = (d_in + 31) / 32;
-    const int64_t fblocks = nb * (nb + 1) / 2;
-    if (fblocks > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
-    hipLaunchKernelGGL(hessian_finalize_kernel, dim3((unsigned)fblocks), dim3(256), 0, st, parts, splits, stride, H, d_in,
+    if (nb > 65535) return CDQ_EUNSUPPORTED;
+    hipLaunchKernelGGL(hessian_finalize_kernel, dim3((unsigned)nb, (unsigned)nb), dim3(256), 0, st, parts, splits, stride, H, d_in,
                        (int)nb, accumulate);
     CDQ_LAUNCH_CHECK();
     if (lambda_rel != 0.0f) {
