@@ -108,6 +108,22 @@ int cdq_init_rtn(const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t
                  float *scale, float *zero, uint8_t *Q, void *stream);
 
 /*
+ * Optimal Weight Clipping, the paper's initialisation for per-channel CD (Section 3.1,
+ * "Initializing a, b, q"; Section 4: grid size 50): Eq. (2) with the clipping strength gamma
+ * chosen per column by grid search on the layer loss of Eq. (1):
+ *   zero = min w, scale = gamma (max w - min w)/(2^bits - 1), Q = clamp(round((w-zero)/scale)),
+ *   gamma = argmin over {k/n_gamma : k = 1..n_gamma} of e^T H e (fp64); equal losses keep the
+ *   larger gamma.  Only the upper end is clipped, as Eq. (2) is written.
+ * Needs group == d_in (one clipping strength per column), else CDQ_EUNSUPPORTED.
+ *   scale, zero [d_out] out; Q [d_out][d_in] out; gamma_out NULL or [d_out] fp32;
+ *   loss_out NULL or [d_out] fp64 (loss of the chosen grid).
+ * Cost: n_gamma passes of the loss kernel (2 d_out d_in^2 fp64 FLOP each).
+ */
+int cdq_init_owc(const float *H, const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t group,
+                 int n_gamma, float *scale, float *zero, uint8_t *Q, float *gamma_out, double *loss_out,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Gradient initialisation of Algorithm 1 ("Compute gradient g at q0"), in weight space:
  * G[j][:] = H e_j with e_j = scale*Q[j] + zero - Wt[j] (the paper's g is (2/a) times this).
  * fp32 inputs, fp64 accumulation on the matrix cores, one rounding to fp32.

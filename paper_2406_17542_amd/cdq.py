@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
         L.cdq_greedy_cd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, sz, vp]
         L.cdq_greedy_cd_ex.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, ctypes.POINTER(CdOptions), vp, sz, vp]
         L.cdq_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
+        L.cdq_init_owc.argtypes = [vp, vp, i64, i64, i32, i64, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.cdq_init_owc.restype = i32
         L.cdq_probe_copy.argtypes = [vp, vp, sz, vp]
         L.cdq_probe_read.argtypes = [vp, sz, vp, vp]
         L.cdq_probe_gather.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
@@ -122,6 +124,21 @@ def init_rtn(Wt: torch.Tensor, bits: int, group: int):
     _check(lib().cdq_init_rtn(_dev(Wt, torch.float32, "Wt"), d_out, d_in, bits, group, scale.data_ptr(), zero.data_ptr(),
                               Q.data_ptr(), _stream()), "cdq_init_rtn")
     return scale, zero, Q
+
+
+def init_owc(H, Wt, bits: int, group: int, n_gamma: int = 50, workspace: torch.Tensor | None = None):
+    """OWC grid search (per-channel).  Returns (scale, zero, Q, gamma, loss_per_col)."""
+    d_out, d_in = Wt.shape
+    scale = torch.empty((d_out, 1), dtype=torch.float32, device=Wt.device)
+    zero = torch.empty((d_out, 1), dtype=torch.float32, device=Wt.device)
+    Q = torch.empty((d_out, d_in), dtype=torch.uint8, device=Wt.device)
+    gamma = torch.empty(d_out, dtype=torch.float32, device=Wt.device)
+    per = torch.empty(d_out, dtype=torch.float64, device=Wt.device)
+    ws = _workspace(OP_INIT_OWC, 0, d_out, d_in, workspace)
+    _check(lib().cdq_init_owc(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), d_out, d_in, bits, group, n_gamma,
+                              scale.data_ptr(), zero.data_ptr(), Q.data_ptr(), gamma.data_ptr(), per.data_ptr(),
+                              ws.data_ptr(), ws.numel(), _stream()), "cdq_init_owc")
+    return scale, zero, Q, gamma, per
 
 
 def gradient(H, Wt, scale, zero, Q, group: int) -> torch.Tensor:

@@ -34,6 +34,7 @@ size_t cdq_workspace_bytes(int op, int64_t n, int64_t d_out, int64_t d_in) {
         case CDQ_OP_HESSIAN: return cdq::hessian_workspace_bytes(n, d_in);
         case CDQ_OP_GREEDY_CD: return cd_workspace_bytes(d_out, d_in);
         case CDQ_OP_LOSS: return cdq::loss_workspace_bytes(d_out, d_in);
+        case CDQ_OP_INIT_OWC: return cdq::owc_workspace_bytes(d_out, d_in);
         default: return 0;
     }
 }
@@ -56,6 +57,17 @@ int cdq_init_rtn(const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t
     if (d_out == 0) return CDQ_OK;        // empty layer: nothing to write, pointers may be null
     if (Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr) return CDQ_EINVAL;
     return cdq::rtn_launch(Wt, d_out, d_in, bits, group, scale, zero, Q, (hipStream_t)stream);
+}
+
+int cdq_init_owc(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, int n_gamma,
+                 float* scale, float* zero, uint8_t* Q, float* gamma_out, double* loss_out, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+    if (bad_bits(bits) || bad_layer(d_out, d_in, group) || n_gamma < 1 || n_gamma > 4096) return CDQ_EINVAL;
+    if (group != d_in) return CDQ_EUNSUPPORTED;       // Eq. (2) has one clipping strength per column
+    if (d_out == 0) return CDQ_OK;
+    if (H == nullptr || Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr) return CDQ_EINVAL;
+    return cdq::owc_launch(H, Wt, d_out, d_in, bits, n_gamma, scale, zero, Q, gamma_out, loss_out, workspace, workspace_bytes,
+                           (hipStream_t)stream);
 }
 
 int cdq_gradient(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,

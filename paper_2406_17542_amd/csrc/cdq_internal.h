@@ -35,6 +35,11 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
                 int64_t d_out, int64_t d_in, int64_t group, double* loss_per_col, double* loss_total,
                 void* ws, size_t ws_bytes, hipStream_t st);
 
+// ---- owc.hip
+size_t owc_workspace_bytes(int64_t d_out, int64_t d_in);
+int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, float* scale, float* zero,
+               uint8_t* Q, float* gamma_out, double* loss_out, void* ws, size_t ws_bytes, hipStream_t st);
+
 // ---- cd_fused.hip
 int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int* elems, int* vec);
 int cd_launch(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q,

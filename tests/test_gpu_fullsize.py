@@ -128,3 +128,43 @@ def test_mlp_down_column_subset(cdq, oracle):
     """d_in = 16384 (H is 1 GiB): 256 columns, first 192 iterations, 8 wavefronts per column."""
     cfg = inputs.CONFIGS["mlp_down"]
     run_layer(cdq, oracle, cfg, 256, 192, sample_cols=24)
+
+
+def test_large_owc_init_column_subset(cdq, oracle):
+    """d_in = 8192, 3-bit per-channel with the scale chosen by OWC (grid of 50), then greedy CD:
+    256 columns on the GPU, 16 of them through the oracle (OWC and 256 CD iterations)."""
+    cfg = inputs.CONFIGS["large"]
+    d_out, T = 256, 256
+    say(f"{cfg.name}: generating X [{cfg.n}x{cfg.d_in}] and Wt [{d_out}x{cfg.d_in}]")
+    X, Wt = inputs.make_layer(cfg, d_out=d_out)
+    Xd = x_to_dev(X, cfg.x_dtype)
+    Hd = cdq.hessian(Xd)
+    H32 = Hd.cpu().numpy()
+    say("hessian spot checks in fp64")
+    check_hessian_samples(H32, X, n_samples=1024)
+    del Xd, X
+    Wd = torch.from_numpy(Wt).cuda()
+    say("OWC grid search on the GPU")
+    scale, zero, Q, gamma, per = cdq.init_owc(Hd, Wd, cfg.bits, cfg.group, 50)
+    s_rtn, z_rtn, Q_rtn = cdq.init_rtn(Wd, cfg.bits, cfg.group)
+    l_rtn = cdq.loss(Hd, Wd, s_rtn, z_rtn, Q_rtn, cfg.group)[0]
+    assert torch.all(per <= l_rtn * (1 + 1e-9)), "gamma = 1 is on the grid, so OWC can not be worse than MinMax"
+    q0 = Q.cpu().numpy().copy()
+    say(f"greedy CD on the GPU, T={T}")
+    out = cdq.greedy_cd(Hd, Wd, scale, zero, Q, cfg.bits, cfg.group, T)
+    l1 = cdq.loss(Hd, Wd, scale, zero, Q, cfg.group)[0].cpu().numpy()
+    assert np.all(l1 <= per.cpu().numpy() * (1 + 1e-9))
+    cols = np.sort(np.random.default_rng(5).choice(d_out, size=16, replace=False))
+    say("oracle OWC + CD on 16 sampled columns")
+    a, b, q, gam, _ = oracle.init_owc(H32, Wt[cols], cfg.bits, cfg.group, 50)
+    g_gpu = gamma.cpu().numpy()[cols]
+    same = g_gpu == gam
+    say(f"gamma equal on {int(same.sum())}/16 sampled columns; gamma range {gam.min():.2f}..{gam.max():.2f}")
+    assert same.sum() >= 15
+    assert np.array_equal(scale.cpu().numpy()[cols][same, 0], a[same, 0])
+    assert np.array_equal(q0[cols][same], q[same])
+    ref = oracle.greedy_cd(H32, Wt[cols][same], a[same], b[same], q[same], cfg.bits, cfg.group, T)
+    eq = (Q.cpu().numpy()[cols][same] == ref["Q"]).mean()
+    say(f"CD codes equal on {eq:.6f} of sampled entries")
+    assert eq >= 0.999
+    assert np.array_equal(out["stats"].cpu().numpy()[cols][same, 0], ref["moves"])

@@ -124,6 +124,36 @@ def test_hessian_accumulate_and_damping(cdq, oracle):
     np.testing.assert_allclose(np.diag(Hn) - np.diag(oracle.hessian(X)), lam, rtol=1e-3)
 
 
+# ----------------------------------------------------------------------------- OWC
+
+@pytest.mark.parametrize("d_out,d_in,n,bits,n_gamma", [(48, 256, 600, 3, 50), (20, 1000, 1500, 4, 50), (7, 64, 200, 2, 10), (130, 128, 400, 3, 50)])
+def test_init_owc(cdq, oracle, d_out, d_in, n, bits, n_gamma):
+    """Eq. (2) grid search: min-max and the scale of the chosen gamma bit-exact, the chosen gamma
+    equal to the oracle's except where two grid points have (nearly) the same loss."""
+    X, Wt = rand_layer(7 + d_in, d_in, d_out, n, corr=0.5)
+    rng = np.random.default_rng(d_in)
+    Wt[:, rng.integers(0, d_in, 3)] *= 5.0           # outlier weights make clipping pay off
+    Wt[0, :] = 0.125                                 # a constant column
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q, gam, all_loss = oracle.init_owc(H32, Wt, bits, d_in, n_gamma)
+    s, z, Q, g, per = cdq.init_owc(dev(H32), dev(Wt), bits, d_in, n_gamma)
+    s, z, Q, g, per = (t.cpu().numpy() for t in (s, z, Q, g, per))
+    assert np.array_equal(z, b)
+    same = g == gam
+    # a different gamma is acceptable only when the two grid points tie within fp32 residual rounding
+    gammas = oracle.owc_gammas(n_gamma)
+    for j in np.where(~same)[0]:
+        k_gpu = int(np.argmin(np.abs(gammas - g[j])))
+        k_ref = int(np.argmin(np.abs(gammas - gam[j])))
+        assert abs(all_loss[k_gpu, j] - all_loss[k_ref, j]) <= 1e-6 * abs(all_loss[k_ref, j]) + 1e-30, (j, g[j], gam[j])
+    assert same.mean() >= 0.98
+    assert np.array_equal(s[same], a[same])
+    assert np.array_equal(Q[same], q[same])
+    ref_loss = oracle.loss(H32, Wt, q, a, b, d_in)
+    np.testing.assert_allclose(per[same], ref_loss[same], rtol=1e-6, atol=1e-30)
+    assert (gam < 1).any(), "the case should exercise clipping"
+
+
 # ----------------------------------------------------------------------------- gradient, loss
 
 @pytest.mark.parametrize("d_out,d_in,n,bits,group", [(64, 128, 512, 4, 128), (37, 200, 600, 3, 40), (130, 264, 800, 2, 8), (3, 7, 40, 3, 7)])
