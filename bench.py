@@ -150,8 +150,11 @@ def main():
     ws_h = torch.empty(max(cdq.workspace_bytes(cdq.OP_HESSIAN, cfg.n, 0, cfg.d_in), 256), dtype=torch.uint8, device="cuda")
     ws_cd = torch.empty(max(cdq.workspace_bytes(cdq.OP_GREEDY_CD, 0, cfg.d_out, cfg.d_in), 256), dtype=torch.uint8, device="cuda")
     ws_l = torch.empty(max(cdq.workspace_bytes(cdq.OP_LOSS, 0, cfg.d_out, cfg.d_in), 256), dtype=torch.uint8, device="cuda")
+    ws_owc = None
+    if cfg.init == "owc":
+        ws_owc = torch.empty(max(cdq.workspace_bytes(cdq.OP_INIT_OWC, 0, cfg.d_out, cfg.d_in), 256), dtype=torch.uint8, device="cuda")
 
-    stage_names = ["hessian", "init_rtn", "cd_gradient_init", "cd_loop", "loss"]
+    stage_names = ["hessian", "init_grid", "cd_gradient_init", "cd_loop", "loss"]
     n_ev = 7
     events = [[ev.create() for _ in range(n_ev)] for _ in range(args.steps)]
     state = {}
@@ -161,7 +164,10 @@ def main():
         rec(0)
         cdq.hessian(Xd, H=H, workspace=ws_h)
         rec(1)
-        scale, zero, Q = cdq.init_rtn(Wd, cfg.bits, cfg.group)
+        if cfg.init == "owc" and q_stress is None:
+            scale, zero, Q, _, _ = cdq.init_owc(H, Wd, cfg.bits, cfg.group, 50, workspace=ws_owc)
+        else:
+            scale, zero, Q = cdq.init_rtn(Wd, cfg.bits, cfg.group)
         if q_stress is not None:
             Q.copy_(q_stress)
         rec(2)
@@ -197,7 +203,7 @@ def main():
 
     # per-stage device time from the events: [0,1] hessian, [1,2] rtn, [2,3] gradient init (+diag),
     # [3,4] the iteration-loop kernel, [5,6] loss
-    spans = {"hessian": (0, 1), "init_rtn": (1, 2), "cd_gradient_init": (2, 3), "cd_loop": (3, 4), "loss": (5, 6)}
+    spans = {"hessian": (0, 1), "init_grid": (1, 2), "cd_gradient_init": (2, 3), "cd_loop": (3, 4), "loss": (5, 6)}
     stages = {}
     for name in stage_names:
         a, b = spans[name]
@@ -232,9 +238,9 @@ def main():
         achievable["hbm_stream_read_GBps"] = 5 * big.numel() * 4 / (ev.elapsed_ms(e0, e1) * 1e-3) * 1e-9
         del big
         waves_used = args.waves
-        if waves_used == 0:
+        if waves_used == 0:                     # mirrors the library's default: 16 coordinates per lane
             waves_used = 1
-            while 64 * waves_used * 32 < cfg.d_in or (cfg.d_out * waves_used < 4096 and waves_used < 16 and 64 * waves_used * 4 < cfg.d_in):
+            while 64 * waves_used * 16 < cfg.d_in and waves_used < 16:
                 waves_used *= 2
         teams = 256 * max(1, 16 // waves_used)
         row_bytes = 4 * cfg.d_in

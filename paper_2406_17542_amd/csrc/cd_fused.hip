@@ -281,25 +281,31 @@ int extract_diag_launch(const float* H, int64_t d_in, float* hdiag, hipStream_t 
 }
 
 // Launch shape: a team of `waves` wavefronts per column, `elems` coordinates per lane.
-// More coordinates per lane means fewer wavefronts per column (no cross-wave step when
-// waves == 1) but a longer serial chain per iteration; when the layer has few columns the
-// chain is split over more wavefronts so the 256 CUs x 4 SIMDs still have work in flight.
+// Measured on MI355X: 16 coordinates per lane is the best trade between the serial scoring chain
+// of a lane, registers (occupancy) and the cost of the cross-wavefront step, for every d_in from
+// 2048 to 16384; 32 per lane is only used beyond 16384.  With few columns the chain is split
+// over more wavefronts so the 256 CUs x 4 SIMDs still have work in flight.
 int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int* elems, int* vec) {
     const int v = (d_in % 4 == 0 && group % 4 == 0) ? 4 : 1;
-    const int64_t target_waves = 256 * 16;
-    int best_w = 0, best_e = 0;
-    for (int e = 32; e >= 4; e >>= 1) {
-        int64_t need = (d_in + 64 * (int64_t)e - 1) / (64 * (int64_t)e);
+    auto team = [&](int e) {
+        const int64_t need = (d_in + 64 * (int64_t)e - 1) / (64 * (int64_t)e);
         int w = 1;
         while (w < need) w <<= 1;
-        if (w > 16) continue;
-        best_w = w;
-        best_e = e;
-        if (d_out * w >= target_waves || w == 16) break;
+        return w;
+    };
+    int e = (d_in <= 1024) ? 8 : 16;
+    int w = team(e);
+    if (w > 16) {
+        e = 32;
+        w = team(e);
+        if (w > 16) return CDQ_EUNSUPPORTED;
     }
-    if (best_w == 0) return CDQ_EUNSUPPORTED;
-    *waves = best_w;
-    *elems = best_e;
+    while (e > 4 && d_out * w < 2048 && team(e / 2) <= 8) {
+        e /= 2;
+        w = team(e);
+    }
+    *waves = w;
+    *elems = e;
     *vec = v;
     return CDQ_OK;
 }
