@@ -159,6 +159,30 @@ int cdq_greedy_cd_ex(const float *H, const float *Wt, const float *scale, const 
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * One iteration of Algorithm 1 as separate steps, on a gradient G = E H kept in global memory
+ * (from cdq_gradient).  Any d_in; one launch each.
+ *   cdq_score_argmin   the arg-min step: per column the move (i, r) with the smallest score
+ *                      s = delta*fma(delta, Hdiag_i, 2 G_ji), ties to the smallest i then r;
+ *                      best_i = best_r = -1 and best_s = 0 when no move has s < 0.
+ *                      Hdiag [d_in] is the diagonal of H.  best_i, best_r [d_out] int32, best_s [d_out].
+ *   cdq_gather_update  the code- and gradient-update steps for those moves: Q[j][i] = r,
+ *                      G[j][:] = fma(delta, H[i][:], G[j][:]); columns with best_i < 0 are left
+ *                      alone.  moves: NULL or [d_out] int32 counters, incremented per committed move.
+ *   cdq_greedy_cd_stepwise  gradient init + T such iteration pairs (2T launches, no host sync);
+ *                      same results as cdq_greedy_cd; workspace of CDQ_OP_GREEDY_CD size.
+ *                      `moves` (NULL or [d_out], zeroed by the caller) counts committed moves.
+ */
+int cdq_score_argmin(const float *Hdiag, const float *scale, const uint8_t *Q, const float *G,
+                     int64_t d_out, int64_t d_in, int bits, int64_t group,
+                     int32_t *best_i, int32_t *best_r, float *best_s, void *stream);
+int cdq_gather_update(const float *H, const float *scale, uint8_t *Q, float *G, int64_t d_out,
+                      int64_t d_in, int64_t group, const int32_t *best_i, const int32_t *best_r,
+                      int32_t *moves, void *stream);
+int cdq_greedy_cd_stepwise(const float *H, const float *Wt, const float *scale, const float *zero,
+                           uint8_t *Q, int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T,
+                           int32_t *moves, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Layer loss of Eq. (1) from the codes: loss_per_col[j] = e_j^T H e_j, loss_total = sum_j
  * (= ||X (W - W_hat)||_F^2).  fp32 inputs, fp64 accumulation, fixed summation order.
  *   loss_per_col  NULL or [d_out] fp64 out;  loss_total  NULL or one fp64 out (device).

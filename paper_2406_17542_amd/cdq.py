@@ -58,6 +58,11 @@ def lib() -> ctypes.CDLL:
         L.cdq_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
         L.cdq_init_owc.argtypes = [vp, vp, i64, i64, i32, i64, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cdq_init_owc.restype = i32
+        L.cdq_score_argmin.argtypes = [vp, vp, vp, vp, i64, i64, i32, i64, vp, vp, vp, vp]
+        L.cdq_gather_update.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp]
+        L.cdq_greedy_cd_stepwise.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, sz, vp]
+        for fn in (L.cdq_score_argmin, L.cdq_gather_update, L.cdq_greedy_cd_stepwise):
+            fn.restype = i32
         L.cdq_probe_copy.argtypes = [vp, vp, sz, vp]
         L.cdq_probe_read.argtypes = [vp, sz, vp, vp]
         L.cdq_probe_gather.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
@@ -178,6 +183,38 @@ def greedy_cd(H, Wt, scale, zero, Q, bits: int, group: int, T: int, stats: bool 
                                   ws.data_ptr(), ws.numel(), _stream()), "cdq_greedy_cd")
     out["stats"] = st
     return out
+
+
+def score_argmin(Hdiag, scale, Q, G, bits: int, group: int):
+    """Arg-min step of one iteration.  Returns (best_i int32, best_r int32, best_s fp32), each [d_out]."""
+    d_out, d_in = Q.shape
+    bi = torch.empty(d_out, dtype=torch.int32, device=Q.device)
+    br = torch.empty(d_out, dtype=torch.int32, device=Q.device)
+    bs = torch.empty(d_out, dtype=torch.float32, device=Q.device)
+    _check(lib().cdq_score_argmin(_dev(Hdiag, torch.float32, "Hdiag"), _dev(scale, torch.float32, "scale"), _dev(Q, torch.uint8, "Q"),
+                                  _dev(G, torch.float32, "G"), d_out, d_in, bits, group, bi.data_ptr(), br.data_ptr(),
+                                  bs.data_ptr(), _stream()), "cdq_score_argmin")
+    return bi, br, bs
+
+
+def gather_update(H, scale, Q, G, group: int, best_i, best_r, moves=None) -> None:
+    """Code and gradient update of one iteration, in place on Q and G."""
+    d_out, d_in = Q.shape
+    _check(lib().cdq_gather_update(_dev(H, torch.float32, "H"), _dev(scale, torch.float32, "scale"), _dev(Q, torch.uint8, "Q"),
+                                   _dev(G, torch.float32, "G"), d_out, d_in, group, _dev(best_i, torch.int32, "best_i"),
+                                   _dev(best_r, torch.int32, "best_r"), moves.data_ptr() if moves is not None else None,
+                                   _stream()), "cdq_gather_update")
+
+
+def greedy_cd_stepwise(H, Wt, scale, zero, Q, bits: int, group: int, T: int, workspace: torch.Tensor | None = None):
+    """Greedy CD as 2T separate launches (general path, any d_in).  Returns per-column move counts."""
+    d_out, d_in = Wt.shape
+    ws = _workspace(OP_GREEDY_CD, 0, d_out, d_in, workspace)
+    moves = torch.zeros(d_out, dtype=torch.int32, device=Wt.device)
+    _check(lib().cdq_greedy_cd_stepwise(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), _dev(scale, torch.float32, "scale"),
+                                        _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, bits, group, T,
+                                        moves.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "cdq_greedy_cd_stepwise")
+    return moves
 
 
 def loss(H, Wt, scale, zero, Q, group: int, workspace: torch.Tensor | None = None):

@@ -10,7 +10,9 @@ bool bad_layer(int64_t d_out, int64_t d_in, int64_t group) {
 bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
 size_t cd_workspace_bytes(int64_t d_out, int64_t d_in) {
-    return cdq_align_up((size_t)d_out * d_in * sizeof(float), 256) + cdq_align_up((size_t)d_in * sizeof(float), 256);
+    // G0 [d_out][d_in], diag(H) [d_in], and three per-column arrays used by the stepwise path
+    return cdq_align_up((size_t)d_out * d_in * sizeof(float), 256) + cdq_align_up((size_t)d_in * sizeof(float), 256) +
+           3 * cdq_align_up((size_t)d_out * sizeof(int32_t), 256);
 }
 
 }  // namespace
@@ -111,6 +113,54 @@ int cdq_greedy_cd_ex(const float* H, const float* Wt, const float* scale, const 
                         (opts != nullptr && opts->exact_scorer_only) ? 1 : 0, opts ? opts->trace : nullptr, opts ? opts->trace_cap : 0, opts ? opts->G_out : nullptr, st);
     if (rc != CDQ_OK) return rc;
     if (opts != nullptr && opts->ev_loop_end != nullptr) CDQ_HIP_CHECK(hipEventRecord((hipEvent_t)opts->ev_loop_end, st));
+    return CDQ_OK;
+}
+
+int cdq_score_argmin(const float* Hdiag, const float* scale, const uint8_t* Q, const float* G, int64_t d_out, int64_t d_in,
+                     int bits, int64_t group, int32_t* best_i, int32_t* best_r, float* best_s, void* stream) {
+    if (bad_bits(bits) || bad_layer(d_out, d_in, group)) return CDQ_EINVAL;
+    if (d_out == 0) return CDQ_OK;
+    if (Hdiag == nullptr || scale == nullptr || Q == nullptr || G == nullptr || best_i == nullptr || best_r == nullptr ||
+        best_s == nullptr)
+        return CDQ_EINVAL;
+    return cdq::score_argmin_launch(Hdiag, scale, Q, G, d_out, d_in, bits, group, best_i, best_r, best_s, (hipStream_t)stream);
+}
+
+int cdq_gather_update(const float* H, const float* scale, uint8_t* Q, float* G, int64_t d_out, int64_t d_in, int64_t group,
+                      const int32_t* best_i, const int32_t* best_r, int32_t* moves, void* stream) {
+    if (bad_layer(d_out, d_in, group)) return CDQ_EINVAL;
+    if (d_out == 0) return CDQ_OK;
+    if (H == nullptr || scale == nullptr || Q == nullptr || G == nullptr || best_i == nullptr || best_r == nullptr) return CDQ_EINVAL;
+    return cdq::gather_update_launch(H, scale, Q, G, d_out, d_in, group, best_i, best_r, moves, (hipStream_t)stream);
+}
+
+int cdq_greedy_cd_stepwise(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out,
+                           int64_t d_in, int bits, int64_t group, int64_t T, int32_t* moves, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    if (bad_bits(bits) || bad_layer(d_out, d_in, group) || T < 0) return CDQ_EINVAL;
+    if (d_out == 0) return CDQ_OK;
+    if (H == nullptr || Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr) return CDQ_EINVAL;
+    const size_t g_bytes = cdq_align_up((size_t)d_out * d_in * sizeof(float), 256);
+    const size_t h_bytes = cdq_align_up((size_t)d_in * sizeof(float), 256);
+    const size_t c_bytes = cdq_align_up((size_t)d_out * sizeof(int32_t), 256);
+    if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < g_bytes + h_bytes + 3 * c_bytes) return CDQ_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char* p = (char*)workspace;
+    float* G = (float*)p; p += g_bytes;
+    float* hdiag = (float*)p; p += h_bytes;
+    int32_t* bi = (int32_t*)p; p += c_bytes;
+    int32_t* br = (int32_t*)p; p += c_bytes;
+    float* bs = (float*)p;
+    int rc = cdq::gradient_launch(H, Wt, scale, zero, Q, d_out, d_in, group, G, st);
+    if (rc != CDQ_OK) return rc;
+    rc = cdq::extract_diag_launch(H, d_in, hdiag, st);
+    if (rc != CDQ_OK) return rc;
+    for (int64_t t = 0; t < T; ++t) {           // converged columns skip their update, so extra iterations are no-ops
+        rc = cdq::score_argmin_launch(hdiag, scale, Q, G, d_out, d_in, bits, group, bi, br, bs, st);
+        if (rc != CDQ_OK) return rc;
+        rc = cdq::gather_update_launch(H, scale, Q, G, d_out, d_in, group, bi, br, moves, st);
+        if (rc != CDQ_OK) return rc;
+    }
     return CDQ_OK;
 }
 

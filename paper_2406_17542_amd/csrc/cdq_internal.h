@@ -40,6 +40,12 @@ size_t owc_workspace_bytes(int64_t d_out, int64_t d_in);
 int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, float* scale, float* zero,
                uint8_t* Q, float* gamma_out, double* loss_out, void* ws, size_t ws_bytes, hipStream_t st);
 
+// ---- stepwise.hip
+int score_argmin_launch(const float* hdiag, const float* scale, const uint8_t* Q, const float* G, int64_t d_out, int64_t d_in,
+                        int bits, int64_t group, int32_t* out_i, int32_t* out_r, float* out_s, hipStream_t st);
+int gather_update_launch(const float* H, const float* scale, uint8_t* Q, float* G, int64_t d_out, int64_t d_in, int64_t group,
+                         const int32_t* sel_i, const int32_t* sel_r, int32_t* moves, hipStream_t st);
+
 // ---- cd_fused.hip
 int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int* elems, int* vec);
 int cd_launch(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q,

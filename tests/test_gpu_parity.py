@@ -365,6 +365,51 @@ def test_greedy_cd_dead_channel_and_diagonal(cdq, oracle):
     assert np.array_equal(Qd.cpu().numpy(), q_rtn)
 
 
+@pytest.mark.parametrize("d_out,d_in,n,bits,group", [(33, 200, 500, 3, 40), (16, 1024, 1500, 4, 1024), (5, 77, 300, 2, 7)])
+def test_single_steps_match_oracle(cdq, oracle, d_out, d_in, n, bits, group):
+    """The arg-min step and the update step of one iteration, each against the oracle."""
+    X, Wt = rand_layer(900 + d_in, d_in, d_out, n)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, _ = oracle.init_grid(Wt, bits, group)
+    q0 = inputs.make_random_codes(d_out, d_in, bits, seed=d_out)
+    E = oracle.residual(Wt, q0, a, b, group)
+    G0 = oracle.gradient(H32, E)
+    ri, rr, rs = oracle.argmin_step(np.diag(H32).copy(), a, q0, G0, bits, group)
+    Hd, ad, Qd, Gd = dev(H32), dev(a), dev(q0.copy()), dev(G0.copy())
+    bi, br, bs = cdq.score_argmin(dev(np.diag(H32).copy()), ad, Qd, Gd, bits, group)
+    assert np.array_equal(bi.cpu().numpy(), ri) and np.array_equal(br.cpu().numpy(), rr)
+    assert np.array_equal(bs.cpu().numpy(), rs)
+    moves = torch.zeros(d_out, dtype=torch.int32, device="cuda")
+    cdq.gather_update(Hd, ad, Qd, Gd, group, bi, br, moves)
+    one = oracle.greedy_cd(H32, Wt, a, b, q0, bits, group, 1)
+    assert np.array_equal(Qd.cpu().numpy(), one["Q"])
+    assert np.array_equal(Gd.cpu().numpy(), one["G"])
+    assert np.array_equal(moves.cpu().numpy(), one["moves"])
+    # a column with no improving move is reported as such and left untouched
+    Hdiag = np.diag(np.full(d_in, 2.0)).astype(np.float32)
+    a1, b1, q_rtn = oracle.init_grid(Wt, bits, group)
+    G1 = oracle.gradient(Hdiag, oracle.residual(Wt, q_rtn, a1, b1, group))
+    bi, br, bs = cdq.score_argmin(dev(np.full(d_in, 2.0, np.float32)), dev(a1), dev(q_rtn), dev(G1), bits, group)
+    assert (bi.cpu().numpy() == -1).all() and (bs.cpu().numpy() == 0).all()
+
+
+def test_stepwise_loop_equals_fused(cdq, oracle):
+    """2T separate launches give the same codes and move counts as the fused persistent kernel."""
+    d_out, d_in, n, bits, group, T = 40, 520, 1200, 3, 104, 150
+    X, Wt = rand_layer(31, d_in, d_out, n)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, _ = oracle.init_grid(Wt, bits, group)
+    q0 = inputs.make_random_codes(d_out, d_in, bits, seed=3)
+    Hd, Wd, ad, bd = dev(H32), dev(Wt), dev(a), dev(b)
+    Qf, Qs = dev(q0.copy()), dev(q0.copy())
+    st = cdq.greedy_cd(Hd, Wd, ad, bd, Qf, bits, group, T)["stats"]
+    mv = cdq.greedy_cd_stepwise(Hd, Wd, ad, bd, Qs, bits, group, T)
+    assert torch.equal(Qf, Qs)
+    assert torch.equal(st[:, 0], mv)
+    ref = oracle.greedy_cd(H32, Wt, a, b, q0, bits, group, T)
+    assert np.array_equal(Qs.cpu().numpy(), ref["Q"])
+
+
 def test_empty_layer(cdq):
     H = torch.zeros((8, 8), device="cuda")
     Wt = torch.zeros((0, 8), device="cuda")
