@@ -245,3 +245,127 @@ void cdqo_argmin_f32(const float *Hdiag, const float *scale, const uint8_t *Q, c
         out_i[j] = best_i; out_r[j] = best_r; out_s[j] = best_s;
     }
 }
+
+/* ---- OWC-CD: greedy coordinate descent over per-group clipping strengths (Algorithm 3) ----
+ *
+ * Sub-channel grids (Section 3.2, "Initialization"): every group i of `group` consecutive
+ * coordinates has its own clipping strength gamma_i on the grid {k/n_gamma : k = 1..n_gamma};
+ * Eq. (2) per group gives its scale, bias and codes, hence its residual block
+ * e^(i)(gamma) = a q + b - w  (the paper's Delta(i, gamma) with the opposite sign).
+ * Per iteration, over all groups i and grid points beta, with d = e^(i)(beta) - e^(i)(gamma_i):
+ *     score(i, beta) = d^T H_ii d + v_i^T d,   v = 2 H e,
+ * is the exact change of the loss of Eq. (1); the smallest score is taken if it is negative,
+ * then v <- v + 2 H[:, group i] d and gamma_i <- beta.
+ *
+ * Readings: the algorithm box initialises v with a leading minus sign, which contradicts both
+ * its own update line and the requirement that the score be the loss change; v = +2He is used.
+ * "Initialize clipping strengths" is not specified: every group starts at gamma = 1 (MinMax).
+ * Ties: smallest score, then smallest group, then smallest grid index.
+ *
+ * Arithmetic: Eq. (2) and the residual in fp32 exactly as in the round-to-nearest routines
+ * (a = (gamma*(hi-lo))/(2^c-1), q = clamp(rint((w-lo)/a)), e = fmaf(a,q,lo) - w); every sum
+ * (v, scores) in fp64, so that another implementation that sums in a different order agrees
+ * except at differences of order 1e-16.
+ *
+ * gamma_idx [d_out][n_grp] holds k (1..n_gamma) on exit.  trace arrays as in greedy CD
+ * (trace_r holds the chosen grid index k).
+ */
+static void owc_group_residual(const float *w, int64_t group, int bits, float lo, float hi, int k, int n_gamma,
+                               float *e_out, float *a_out, uint8_t *q_out)
+{
+    const float top = (float)((1 << bits) - 1);
+    const float gamma = (float)k / (float)n_gamma;
+    float a = (gamma * (hi - lo)) / top;
+    if (!(a > 0.0f) || isinf(a)) a = 1.0f;
+    for (int64_t m = 0; m < group; ++m) {
+        float r = rintf((w[m] - lo) / a);
+        if (r < 0.0f) r = 0.0f;
+        if (r > top) r = top;
+        if (e_out) e_out[m] = fmaf(a, r, lo) - w[m];
+        if (q_out) q_out[m] = (uint8_t)r;
+    }
+    if (a_out) *a_out = a;
+}
+
+void cdqo_owc_cd(const float *H, const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t group,
+                 int n_gamma, int64_t T, float *scale, float *zero, uint8_t *Q, int32_t *gamma_idx,
+                 int32_t *moves, int32_t *converged,
+                 int32_t *trace_i, int32_t *trace_r, double *trace_s, int64_t trace_cap)
+{
+    const int64_t n_grp = d_in / group;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t j = 0; j < d_out; ++j) {
+        const float *w = Wt + j * d_in;
+        float *tab = (float *)malloc(sizeof(float) * (size_t)n_gamma * d_in);   /* e(beta) for every beta */
+        float *lo = (float *)malloc(sizeof(float) * n_grp), *hi = (float *)malloc(sizeof(float) * n_grp);
+        float *e = (float *)malloc(sizeof(float) * d_in);
+        double *v = (double *)malloc(sizeof(double) * d_in);
+        double *d = (double *)malloc(sizeof(double) * group);
+        int32_t *cur = gamma_idx + j * n_grp;
+        for (int64_t i = 0; i < n_grp; ++i) {
+            float l = w[i * group], h = w[i * group];
+            for (int64_t m = 1; m < group; ++m) {
+                if (w[i * group + m] < l) l = w[i * group + m];
+                if (w[i * group + m] > h) h = w[i * group + m];
+            }
+            lo[i] = l; hi[i] = h;
+            for (int k = 1; k <= n_gamma; ++k)
+                owc_group_residual(w + i * group, group, bits, l, h, k, n_gamma,
+                                   tab + (size_t)(k - 1) * d_in + i * group, NULL, NULL);
+            cur[i] = n_gamma;                                   /* gamma = 1 */
+        }
+        for (int64_t m = 0; m < d_in; ++m) e[m] = tab[(size_t)(n_gamma - 1) * d_in + m];
+        for (int64_t r = 0; r < d_in; ++r) {                    /* v = 2 H e */
+            double acc = 0.0;
+            for (int64_t m = 0; m < d_in; ++m) acc += (double)H[r * d_in + m] * (double)e[m];
+            v[r] = 2.0 * acc;
+        }
+        int32_t n_moves = 0, done = 0;
+        for (int64_t t = 0; t < T; ++t) {
+            double best_s = 0.0;
+            int64_t best_i = -1;
+            int best_k = -1;
+            for (int64_t i = 0; i < n_grp; ++i)
+                for (int k = 1; k <= n_gamma; ++k) {
+                    if (k == cur[i]) continue;
+                    const float *en = tab + (size_t)(k - 1) * d_in + i * group;
+                    for (int64_t m = 0; m < group; ++m) d[m] = (double)en[m] - (double)e[i * group + m];
+                    double s = 0.0;
+                    for (int64_t m = 0; m < group; ++m) {
+                        double row = 0.0;
+                        const float *hrow = H + (i * group + m) * d_in + i * group;
+                        for (int64_t m2 = 0; m2 < group; ++m2) row += (double)hrow[m2] * d[m2];
+                        s += d[m] * (row + v[i * group + m]);
+                    }
+                    if (s < best_s) { best_s = s; best_i = i; best_k = k; }
+                }
+            if (best_i < 0) { done = 1; break; }
+            const float *en = tab + (size_t)(best_k - 1) * d_in + best_i * group;
+            for (int64_t m = 0; m < group; ++m) d[m] = (double)en[m] - (double)e[best_i * group + m];
+            for (int64_t r = 0; r < d_in; ++r) {                /* v += 2 H[:, group] d */
+                double acc = 0.0;
+                const float *hrow = H + r * d_in + best_i * group;
+                for (int64_t m = 0; m < group; ++m) acc += (double)hrow[m] * d[m];
+                v[r] += 2.0 * acc;
+            }
+            for (int64_t m = 0; m < group; ++m) e[best_i * group + m] = en[m];
+            if (n_moves < trace_cap) {
+                trace_i[j * trace_cap + n_moves] = (int32_t)best_i;
+                trace_r[j * trace_cap + n_moves] = best_k;
+                trace_s[j * trace_cap + n_moves] = best_s;
+            }
+            cur[best_i] = best_k;
+            ++n_moves;
+        }
+        for (int64_t i = 0; i < n_grp; ++i) {
+            float a;
+            owc_group_residual(w + i * group, group, bits, lo[i], hi[i], cur[i], n_gamma, NULL, &a,
+                               Q + j * d_in + i * group);
+            scale[j * n_grp + i] = a;
+            zero[j * n_grp + i] = lo[i];
+        }
+        moves[j] = n_moves;
+        converged[j] = done;
+        free(tab); free(lo); free(hi); free(e); free(v); free(d);
+    }
+}

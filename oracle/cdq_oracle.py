@@ -232,3 +232,36 @@ def init_owc(H, Wt, bits: int, group: int, n_gamma: int = 50):
             best[3][take] = gam
         best_loss = np.where(take, l, best_loss)
     return best[0], best[1], best[2], best[3], all_loss
+
+
+# --------------------------------------------------------------------------- OWC-CD (Algorithm 3)
+
+def owc_cd(H, Wt, bits: int, group: int, n_gamma: int = 50, T: int | None = None, trace_cap: int = 0):
+    """Greedy coordinate descent over per-group clipping strengths (Algorithm 3), every group
+    starting at gamma = 1.  T defaults to d_in/group as in Section 4.  Returns a dict with scale,
+    zero [d_out][n_grp], Q, gamma_idx (grid index k, gamma = k/n_gamma), moves, converged and the
+    optional trace (trace_i = group, trace_r = grid index, trace_s = fp64 score)."""
+    lib = _load()
+    Wt = np.ascontiguousarray(Wt, np.float32)
+    H = np.ascontiguousarray(H, np.float32)
+    d_out, d_in = Wt.shape
+    assert d_in % group == 0
+    n_grp = d_in // group
+    if T is None:
+        T = n_grp
+    scale = np.empty((d_out, n_grp), np.float32)
+    zero = np.empty((d_out, n_grp), np.float32)
+    Q = np.empty((d_out, d_in), np.uint8)
+    gidx = np.zeros((d_out, n_grp), np.int32)
+    moves = np.zeros(d_out, np.int32)
+    conv = np.zeros(d_out, np.int32)
+    cap = max(int(trace_cap), 0)
+    ti = np.full((d_out, max(cap, 1)), -1, np.int32)
+    tr = np.full((d_out, max(cap, 1)), -1, np.int32)
+    ts = np.zeros((d_out, max(cap, 1)), np.float64)
+    lib.cdqo_owc_cd(_p(H), _p(Wt), _I64(d_out), _I64(d_in), ctypes.c_int(bits), _I64(group), ctypes.c_int(n_gamma),
+                    _I64(T), _p(scale), _p(zero), _p(Q), _p(gidx), _p(moves), _p(conv), _p(ti), _p(tr), _p(ts), _I64(cap))
+    out = {"scale": scale, "zero": zero, "Q": Q, "gamma_idx": gidx, "moves": moves, "converged": conv}
+    if cap:
+        out.update(trace_i=ti, trace_r=tr, trace_s=ts)
+    return out

@@ -78,3 +78,47 @@ def clip_grid(w, bits, gamma):
     b = w.min()
     q = np.clip(np.rint((w - b) / a), 0, (1 << bits) - 1)
     return a, b, q.astype(np.int64)
+
+
+def owc_cd_paper_form(X, w, bits, group, gammas, T):
+    """Algorithm 3 in the paper's notation (fp64): residual table Delta(i, beta) = w - a q - b per
+    group and grid point, every group starting at the last grid point (gamma = 1), H = X^T X,
+    v = 2 H (a q + b - w)  [the sign that makes the score the loss change; the box prints a minus],
+    then T times: arg-min over (i, beta) of
+    (Delta(i,gamma_i) - Delta(i,beta))^T H_ii (...) + v_i^T (Delta(i,gamma_i) - Delta(i,beta)),
+    update v and gamma_i.  Returns (list of chosen grid indices per group, list of moves)."""
+    X = np.asarray(X, np.float64)
+    w = np.asarray(w, np.float64)
+    d = len(w)
+    n_grp = d // group
+    H = X.T @ X
+    delta = np.empty((len(gammas), d))
+    for k, beta in enumerate(gammas):
+        for i in range(n_grp):
+            sl = slice(i * group, (i + 1) * group)
+            a, b, q = clip_grid(w[sl], bits, float(beta))
+            delta[k, sl] = w[sl] - a * q - b
+    cur = [len(gammas) - 1] * n_grp
+    e = -delta[-1].copy()                     # a q + b - w
+    v = 2.0 * H @ e
+    moves = []
+    for _ in range(T):
+        best = (0.0, -1, -1)
+        for i in range(n_grp):
+            sl = slice(i * group, (i + 1) * group)
+            for k in range(len(gammas)):
+                if k == cur[i]:
+                    continue
+                diff = delta[cur[i], sl] - delta[k, sl]
+                s = diff @ H[sl, sl] @ diff + v[sl] @ diff
+                if s < best[0]:
+                    best = (s, i, k)
+        if best[1] < 0:
+            break
+        s, i, k = best
+        sl = slice(i * group, (i + 1) * group)
+        diff = delta[cur[i], sl] - delta[k, sl]
+        v = v + 2.0 * H[:, sl] @ diff
+        cur[i] = k
+        moves.append((i, k, s))
+    return cur, moves

@@ -435,3 +435,80 @@ def test_owc_grid_search(oracle):
         ref = np.array(ref)
         np.testing.assert_allclose(l_owc[j], ref.min(), rtol=1e-3)
         np.testing.assert_allclose(all_loss[:, j], ref, rtol=2e-2)
+
+
+# ----------------------------------------------------------------------------- OWC-CD (Algorithm 3)
+
+def _owc_cd_case(seed, d_in=32, group=8, d_out=3, n=128, bits=3):
+    rng = np.random.default_rng(seed)
+    X, Wt = _rand_layer(rng, d_in, d_out, n, corr=1.0)
+    Wt[:, rng.integers(0, d_in, 3)] *= 4.0            # outliers: clipping pays off in some groups
+    return X, Wt, bits, group
+
+
+def test_owc_cd_scores_are_loss_changes_and_end_point_is_groupwise_optimal(oracle):
+    """Every committed score equals the loss change recomputed from X; at the end no change of a
+    single group's clipping strength lowers the loss (checked over all groups and grid points)."""
+    X, Wt, bits, group = _owc_cd_case(70)
+    n_gamma = 20
+    H = oracle.hessian(X)
+    H32 = H.astype(np.float32)
+    r = oracle.owc_cd(H32, Wt, bits, group, n_gamma, T=64, trace_cap=64)
+    d_out, d_in = Wt.shape
+    n_grp = d_in // group
+    assert r["moves"].sum() >= d_out and r["converged"].all()
+    H32d = H32.astype(np.float64)
+
+    def loss_of(j, kidx):
+        gam = (kidx.astype(np.float32) / np.float32(n_gamma))[None, :]
+        a, b, q = oracle.init_grid(Wt[j:j + 1], bits, group, gam)
+        e = oracle.residual(Wt[j:j + 1], q, a, b, group)[0].astype(np.float64)
+        return float(e @ H32d @ e), a, b, q
+
+    for j in range(d_out):
+        k = np.full(n_grp, n_gamma, np.int32)
+        prev = loss_of(j, k)[0]
+        for m in range(r["moves"][j]):
+            k[r["trace_i"][j, m]] = r["trace_r"][j, m]
+            cur = loss_of(j, k)[0]
+            assert cur < prev
+            np.testing.assert_allclose(r["trace_s"][j, m], cur - prev, rtol=1e-7, atol=1e-9 * prev)
+            prev = cur
+        assert np.array_equal(k, r["gamma_idx"][j])
+        l, a, b, q = loss_of(j, k)
+        assert np.array_equal(q[0], r["Q"][j]) and np.array_equal(a[0], r["scale"][j]) and np.array_equal(b[0], r["zero"][j])
+        for i in range(n_grp):
+            for kk in range(1, n_gamma + 1):
+                alt = k.copy()
+                alt[i] = kk
+                assert loss_of(j, alt)[0] >= prev * (1 - 1e-9)
+
+
+def test_owc_cd_single_group_is_owc(oracle):
+    """With one group per column Algorithm 3 reduces to the OWC grid search: its first move goes
+    to OWC's clipping strength and nothing improves afterwards."""
+    rng = np.random.default_rng(71)
+    X, Wt = _rand_layer(rng, 24, 5, 96, corr=0.5)
+    Wt[:, 2] *= 6.0
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q, gam, _ = oracle.init_owc(H32, Wt, 3, 24, 50)
+    r = oracle.owc_cd(H32, Wt, 3, 24, 50, T=8)
+    assert np.array_equal(r["gamma_idx"][:, 0].astype(np.float32) / np.float32(50), gam)
+    assert np.array_equal(r["Q"], q) and np.array_equal(r["scale"], a)
+    assert (r["moves"] == (gam < 1)).all() and r["converged"].all()
+
+
+def test_owc_cd_matches_paper_form(oracle):
+    """Same sequence of (group, grid point) moves as Algorithm 3 written in the paper's notation."""
+    X, Wt, bits, group = _owc_cd_case(72, d_in=24, group=6, d_out=2, n=96)
+    n_gamma = 10
+    H32 = oracle.hessian(X).astype(np.float32)
+    r = oracle.owc_cd(H32, Wt, bits, group, n_gamma, T=30, trace_cap=30)
+    gammas = oracle.owc_gammas(n_gamma).astype(np.float64)
+    for j in range(2):
+        cur, mv = pf.owc_cd_paper_form(X, Wt[j].astype(np.float64), bits, group, gammas, 30)
+        m = r["moves"][j]
+        assert len(mv) == m and m > 0
+        assert [(x[0], x[1] + 1) for x in mv] == [(int(r["trace_i"][j, t]), int(r["trace_r"][j, t])) for t in range(m)]
+        np.testing.assert_allclose([x[2] for x in mv], r["trace_s"][j, :m], rtol=2e-4)
+        assert [c + 1 for c in cur] == r["gamma_idx"][j].tolist()
