@@ -124,6 +124,23 @@ int cdq_init_owc(const float *H, const float *Wt, int64_t d_out, int64_t d_in, i
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * OWC-CD, the paper's initialisation for sub-channel grids (Algorithm 3; Section 3.2,
+ * "Initialization"): greedy coordinate descent over one clipping strength per group, on the grid
+ * {k/n_gamma : k = 1..n_gamma}, every group starting at 1 (MinMax).  Per iteration the move
+ * (group i, grid point k) with the smallest exact loss change d^T H_ii d + 2 (H e)_i^T d,
+ * d = e_i(k) - e_i(current), is taken if negative (ties: smallest group, then smallest k);
+ * T iterations at most (the paper uses T = d_in/group).  All sums in fp64.
+ *   scale, zero [d_out][d_in/group] out; Q [d_out][d_in] out (Eq. (2) with the chosen strengths);
+ *   gamma_idx NULL or [d_out][d_in/group] int32 (chosen k); moves NULL or [d_out] int32;
+ *   trace NULL or [d_out][trace_cap] int32: move m is stored as group*4096 + k.
+ * The column's state is kept in LDS: needs roughly 16*d_in + 4*n_gamma*group +
+ * 12*n_gamma*d_in/group bytes <= 160 KiB, else CDQ_EUNSUPPORTED.
+ */
+int cdq_init_owc_cd(const float *H, const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t group,
+                    int n_gamma, int64_t T, float *scale, float *zero, uint8_t *Q, int32_t *gamma_idx,
+                    int32_t *moves, int32_t *trace, int64_t trace_cap, void *stream);
+
+/*
  * Gradient initialisation of Algorithm 1 ("Compute gradient g at q0"), in weight space:
  * G[j][:] = H e_j with e_j = scale*Q[j] + zero - Wt[j] (the paper's g is (2/a) times this).
  * fp32 inputs, fp64 accumulation on the matrix cores, one rounding to fp32.

@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.cdq_greedy_cd_stepwise.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, sz, vp]
         for fn in (L.cdq_score_argmin, L.cdq_gather_update, L.cdq_greedy_cd_stepwise):
             fn.restype = i32
+        L.cdq_init_owc_cd.argtypes = [vp, vp, i64, i64, i32, i64, i32, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+        L.cdq_init_owc_cd.restype = i32
         L.cdq_probe_copy.argtypes = [vp, vp, sz, vp]
         L.cdq_probe_read.argtypes = [vp, sz, vp, vp]
         L.cdq_probe_gather.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
@@ -144,6 +146,28 @@ def init_owc(H, Wt, bits: int, group: int, n_gamma: int = 50, workspace: torch.T
                               scale.data_ptr(), zero.data_ptr(), Q.data_ptr(), gamma.data_ptr(), per.data_ptr(),
                               ws.data_ptr(), ws.numel(), _stream()), "cdq_init_owc")
     return scale, zero, Q, gamma, per
+
+
+def init_owc_cd(H, Wt, bits: int, group: int, n_gamma: int = 50, T: int | None = None, trace_cap: int = 0):
+    """OWC-CD (Algorithm 3) for sub-channel grids.  Returns a dict: scale, zero, Q, gamma_idx, moves[, trace]."""
+    d_out, d_in = Wt.shape
+    n_grp = d_in // group
+    if T is None:
+        T = n_grp
+    dev_ = Wt.device
+    out = {"scale": torch.empty((d_out, n_grp), dtype=torch.float32, device=dev_),
+           "zero": torch.empty((d_out, n_grp), dtype=torch.float32, device=dev_),
+           "Q": torch.empty((d_out, d_in), dtype=torch.uint8, device=dev_),
+           "gamma_idx": torch.empty((d_out, n_grp), dtype=torch.int32, device=dev_),
+           "moves": torch.zeros(d_out, dtype=torch.int32, device=dev_)}
+    tr = None
+    if trace_cap > 0:
+        out["trace"] = torch.full((d_out, trace_cap), -1, dtype=torch.int32, device=dev_)
+        tr = out["trace"].data_ptr()
+    _check(lib().cdq_init_owc_cd(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), d_out, d_in, bits, group, n_gamma, T,
+                                 out["scale"].data_ptr(), out["zero"].data_ptr(), out["Q"].data_ptr(), out["gamma_idx"].data_ptr(),
+                                 out["moves"].data_ptr(), tr, trace_cap, _stream()), "cdq_init_owc_cd")
+    return out
 
 
 def gradient(H, Wt, scale, zero, Q, group: int) -> torch.Tensor:

@@ -40,6 +40,11 @@ size_t owc_workspace_bytes(int64_t d_out, int64_t d_in);
 int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, float* scale, float* zero,
                uint8_t* Q, float* gamma_out, double* loss_out, void* ws, size_t ws_bytes, hipStream_t st);
 
+// ---- owc_cd.hip
+int owc_cd_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, int n_gamma, int64_t T,
+                  float* scale, float* zero, uint8_t* Q, int32_t* gamma_idx, int32_t* moves, int32_t* trace, int64_t trace_cap,
+                  hipStream_t st);
+
 // ---- stepwise.hip
 int score_argmin_launch(const float* hdiag, const float* scale, const uint8_t* Q, const float* G, int64_t d_out, int64_t d_in,
                         int bits, int64_t group, int32_t* out_i, int32_t* out_r, float* out_s, hipStream_t st);

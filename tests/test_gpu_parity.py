@@ -154,6 +154,73 @@ def test_init_owc(cdq, oracle, d_out, d_in, n, bits, n_gamma):
     assert (gam < 1).any(), "the case should exercise clipping"
 
 
+# ----------------------------------------------------------------------------- OWC-CD (Algorithm 3)
+
+def owc_cd_score(oracle, H64, wj, bits, group, n_gamma, cur, i, k):
+    """fp64 loss change of moving group i of one column from grid index cur[i] to k, through the oracle's Eq. (2)."""
+    d_in = len(wj)
+    tab = {}
+    for kk in set(cur) | {k}:
+        a, b, q = oracle.init_grid(wj[None, :], bits, group, float(oracle.owc_gammas(n_gamma)[kk - 1]))
+        tab[kk] = oracle.residual(wj[None, :], q, a, b, group)[0].astype(np.float64)
+    e = np.concatenate([tab[cur[g]][g * group:(g + 1) * group] for g in range(d_in // group)])
+    sl = slice(i * group, (i + 1) * group)
+    d = tab[k][sl] - e[sl]
+    return float(d @ H64[sl, sl] @ d + 2.0 * (H64[sl] @ e) @ d)
+
+
+@pytest.mark.parametrize("d_out,d_in,n,bits,group,n_gamma,T", [
+    (40, 256, 600, 3, 32, 50, None), (9, 512, 900, 2, 128, 50, None), (17, 96, 300, 4, 8, 20, 30), (6, 128, 300, 3, 128, 50, 3),
+    (5, 192, 400, 2, 64, 50, 0)])
+def test_init_owc_cd(cdq, oracle, d_out, d_in, n, bits, group, n_gamma, T):
+    """Algorithm 3: the sequence of (group, grid index) moves, the final strengths, grid and codes equal the
+    oracle's; a column may differ only from a move on where the two candidates tie to fp64 rounding."""
+    X, Wt = rand_layer(11 + d_in, d_in, d_out, n, corr=0.5)
+    rng = np.random.default_rng(d_in + 1)
+    Wt[:, rng.integers(0, d_in, 6)] *= 4.0
+    Wt[0, :group] = 0.125                            # a constant group
+    H32 = oracle.hessian(X).astype(np.float32)
+    cap = (d_in // group if T is None else T) + 1
+    ref = oracle.owc_cd(H32, Wt, bits, group, n_gamma, T, trace_cap=cap)
+    out = {k: v.cpu().numpy() for k, v in cdq.init_owc_cd(dev(H32), dev(Wt), bits, group, n_gamma, T, trace_cap=cap).items()}
+    assert np.array_equal(out["zero"], ref["zero"])
+    H64 = H32.astype(np.float64)
+    n_same = 0
+    for j in range(d_out):
+        gpu_moves = [(int(x) // 4096, int(x) % 4096) for x in out["trace"][j] if x >= 0]
+        ref_moves = [(int(i), int(r)) for i, r in zip(ref["trace_i"][j], ref["trace_r"][j]) if i >= 0]
+        if gpu_moves == ref_moves:
+            n_same += 1
+            assert out["moves"][j] == ref["moves"][j]
+            assert np.array_equal(out["gamma_idx"][j], ref["gamma_idx"][j])
+            assert np.array_equal(out["scale"][j], ref["scale"][j])
+            assert np.array_equal(out["Q"][j], ref["Q"][j])
+            continue
+        m = next(t for t in range(max(len(gpu_moves), len(ref_moves)))
+                 if t >= len(gpu_moves) or t >= len(ref_moves) or gpu_moves[t] != ref_moves[t])
+        cur = [n_gamma] * (d_in // group)
+        for i, k in ref_moves[:m]:
+            cur[i] = k
+        sg = owc_cd_score(oracle, H64, Wt[j], bits, group, n_gamma, cur, *gpu_moves[m]) if m < len(gpu_moves) else 0.0
+        sr = owc_cd_score(oracle, H64, Wt[j], bits, group, n_gamma, cur, *ref_moves[m]) if m < len(ref_moves) else 0.0
+        assert abs(sg - sr) <= 1e-11 * max(abs(sr), abs(sg)) + 1e-300, (j, m, gpu_moves[m:m + 1], ref_moves[m:m + 1], sg, sr)
+    assert n_same >= 0.95 * d_out, n_same
+    if T is None:
+        assert (ref["gamma_idx"] < n_gamma).any(), "the case should exercise clipping"
+    # the result is a valid Eq. (2) grid whose loss is not above MinMax's
+    a0, b0, q0 = oracle.init_grid(Wt, bits, group)
+    l0 = oracle.loss(H32, Wt, q0, a0, b0, group)
+    l1 = oracle.loss(H32, Wt, out["Q"], out["scale"], out["zero"], group)
+    assert (l1 <= l0 * (1 + 1e-9) + 1e-30).all()
+
+
+def test_init_owc_cd_rejects_oversized_state(cdq):
+    H = torch.zeros((16384, 16384), dtype=torch.float32, device="cuda")
+    Wt = torch.zeros((1, 16384), dtype=torch.float32, device="cuda")
+    with pytest.raises(RuntimeError, match="outside"):
+        cdq.init_owc_cd(H, Wt, 2, 128)
+
+
 # ----------------------------------------------------------------------------- gradient, loss
 
 @pytest.mark.parametrize("d_out,d_in,n,bits,group", [(64, 128, 512, 4, 128), (37, 200, 600, 3, 40), (130, 264, 800, 2, 8), (3, 7, 40, 3, 7)])
