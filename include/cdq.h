@@ -47,6 +47,7 @@ extern "C" {
 #define CDQ_OP_GREEDY_CD 1
 #define CDQ_OP_LOSS      2
 #define CDQ_OP_INIT_OWC  3
+#define CDQ_OP_INIT_OWC_CD 4
 
 #define CDQ_MAX_D_IN 32768      /* largest d_in the register-resident CD kernel covers */
 
@@ -133,12 +134,18 @@ int cdq_init_owc(const float *H, const float *Wt, int64_t d_out, int64_t d_in, i
  *   scale, zero [d_out][d_in/group] out; Q [d_out][d_in] out (Eq. (2) with the chosen strengths);
  *   gamma_idx NULL or [d_out][d_in/group] int32 (chosen k); moves NULL or [d_out] int32;
  *   trace NULL or [d_out][trace_cap] int32: move m is stored as group*4096 + k.
- * The column's state is kept in LDS: needs roughly 16*d_in + 4*n_gamma*group +
- * 12*n_gamma*d_in/group bytes <= 160 KiB, else CDQ_EUNSUPPORTED.
+ *   variant 0: tiled kernel (needs group % 4 == 0 and 16-byte aligned H, Wt; otherwise the
+ *              simple kernel is taken); MinMax start and its gradient come from the RTN and
+ *              fp64 GEMM kernels, which needs a workspace of CDQ_OP_INIT_OWC_CD size.
+ *   variant 1: simple kernel (one pass per quantity, no workspace); same results up to fp64
+ *              rounding of the scores.
+ * The column's state is kept in LDS: roughly max(8*d_in + 8*n_gamma*d_in/group, 4*n_gamma*group)
+ * + 8*d_in + 16*n_gamma*d_in/group bytes <= 160 KiB, else CDQ_EUNSUPPORTED.
  */
 int cdq_init_owc_cd(const float *H, const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t group,
                     int n_gamma, int64_t T, float *scale, float *zero, uint8_t *Q, int32_t *gamma_idx,
-                    int32_t *moves, int32_t *trace, int64_t trace_cap, void *stream);
+                    int32_t *moves, int32_t *trace, int64_t trace_cap, int variant, void *workspace,
+                    size_t workspace_bytes, void *stream);
 
 /*
  * Gradient initialisation of Algorithm 1 ("Compute gradient g at q0"), in weight space:

@@ -13,7 +13,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcdq.so")
 
 CDQ_F32, CDQ_BF16 = 0, 1
-OP_HESSIAN, OP_GREEDY_CD, OP_LOSS, OP_INIT_OWC = 0, 1, 2, 3
+OP_HESSIAN, OP_GREEDY_CD, OP_LOSS, OP_INIT_OWC, OP_INIT_OWC_CD = 0, 1, 2, 3, 4
 MAX_D_IN = 32768
 
 _lib = None
@@ -63,7 +63,7 @@ def lib() -> ctypes.CDLL:
         L.cdq_greedy_cd_stepwise.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, sz, vp]
         for fn in (L.cdq_score_argmin, L.cdq_gather_update, L.cdq_greedy_cd_stepwise):
             fn.restype = i32
-        L.cdq_init_owc_cd.argtypes = [vp, vp, i64, i64, i32, i64, i32, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+        L.cdq_init_owc_cd.argtypes = [vp, vp, i64, i64, i32, i64, i32, i64, vp, vp, vp, vp, vp, vp, i64, i32, vp, sz, vp]
         L.cdq_init_owc_cd.restype = i32
         L.cdq_probe_copy.argtypes = [vp, vp, sz, vp]
         L.cdq_probe_read.argtypes = [vp, sz, vp, vp]
@@ -148,7 +148,8 @@ def init_owc(H, Wt, bits: int, group: int, n_gamma: int = 50, workspace: torch.T
     return scale, zero, Q, gamma, per
 
 
-def init_owc_cd(H, Wt, bits: int, group: int, n_gamma: int = 50, T: int | None = None, trace_cap: int = 0):
+def init_owc_cd(H, Wt, bits: int, group: int, n_gamma: int = 50, T: int | None = None, trace_cap: int = 0,
+                variant: int = 0, workspace: torch.Tensor | None = None):
     """OWC-CD (Algorithm 3) for sub-channel grids.  Returns a dict: scale, zero, Q, gamma_idx, moves[, trace]."""
     d_out, d_in = Wt.shape
     n_grp = d_in // group
@@ -160,13 +161,14 @@ def init_owc_cd(H, Wt, bits: int, group: int, n_gamma: int = 50, T: int | None =
            "Q": torch.empty((d_out, d_in), dtype=torch.uint8, device=dev_),
            "gamma_idx": torch.empty((d_out, n_grp), dtype=torch.int32, device=dev_),
            "moves": torch.zeros(d_out, dtype=torch.int32, device=dev_)}
+    ws = _workspace(OP_INIT_OWC_CD, 0, d_out, d_in, workspace)
     tr = None
     if trace_cap > 0:
         out["trace"] = torch.full((d_out, trace_cap), -1, dtype=torch.int32, device=dev_)
         tr = out["trace"].data_ptr()
     _check(lib().cdq_init_owc_cd(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), d_out, d_in, bits, group, n_gamma, T,
                                  out["scale"].data_ptr(), out["zero"].data_ptr(), out["Q"].data_ptr(), out["gamma_idx"].data_ptr(),
-                                 out["moves"].data_ptr(), tr, trace_cap, _stream()), "cdq_init_owc_cd")
+                                 out["moves"].data_ptr(), tr, trace_cap, variant, ws.data_ptr(), ws.numel(), _stream()), "cdq_init_owc_cd")
     return out
 
 

@@ -37,6 +37,7 @@ size_t cdq_workspace_bytes(int op, int64_t n, int64_t d_out, int64_t d_in) {
         case CDQ_OP_GREEDY_CD: return cd_workspace_bytes(d_out, d_in);
         case CDQ_OP_LOSS: return cdq::loss_workspace_bytes(d_out, d_in);
         case CDQ_OP_INIT_OWC: return cdq::owc_workspace_bytes(d_out, d_in);
+        case CDQ_OP_INIT_OWC_CD: return cdq::owc_cd_workspace_bytes(d_out, d_in);
         default: return 0;
     }
 }
@@ -74,13 +75,13 @@ int cdq_init_owc(const float* H, const float* Wt, int64_t d_out, int64_t d_in, i
 
 int cdq_init_owc_cd(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, int n_gamma,
                     int64_t T, float* scale, float* zero, uint8_t* Q, int32_t* gamma_idx, int32_t* moves, int32_t* trace,
-                    int64_t trace_cap, void* stream) {
-    if (bad_bits(bits) || bad_layer(d_out, d_in, group) || n_gamma < 1 || T < 0) return CDQ_EINVAL;
+                    int64_t trace_cap, int variant, void* workspace, size_t workspace_bytes, void* stream) {
+    if (bad_bits(bits) || bad_layer(d_out, d_in, group) || n_gamma < 1 || T < 0 || variant < 0 || variant > 1) return CDQ_EINVAL;
     if (trace != nullptr && trace_cap <= 0) return CDQ_EINVAL;
     if (d_out == 0) return CDQ_OK;
     if (H == nullptr || Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr) return CDQ_EINVAL;
     return cdq::owc_cd_launch(H, Wt, d_out, d_in, bits, group, n_gamma, T, scale, zero, Q, gamma_idx, moves, trace, trace_cap,
-                              (hipStream_t)stream);
+                              workspace, workspace_bytes, variant == 1, (hipStream_t)stream);
 }
 
 int cdq_gradient(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,

@@ -30,7 +30,8 @@ int rtn_launch(const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t g
 // ---- eh_gemm.hip : C = E * H with fp64 accumulation; epilogue stores G or row partial losses
 size_t loss_workspace_bytes(int64_t d_out, int64_t d_in);
 int gradient_launch(const float* H, const float* Wt, const float* scale, const float* zero,
-                    const uint8_t* Q, int64_t d_out, int64_t d_in, int64_t group, float* G, hipStream_t st);
+                    const uint8_t* Q, int64_t d_out, int64_t d_in, int64_t group, float* G, hipStream_t st,
+                    double* G64 = nullptr);   // G64 non-null: store the fp64 sums there instead of G
 int loss_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
                 int64_t d_out, int64_t d_in, int64_t group, double* loss_per_col, double* loss_total,
                 void* ws, size_t ws_bytes, hipStream_t st);
@@ -43,7 +44,8 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
 // ---- owc_cd.hip
 int owc_cd_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, int n_gamma, int64_t T,
                   float* scale, float* zero, uint8_t* Q, int32_t* gamma_idx, int32_t* moves, int32_t* trace, int64_t trace_cap,
-                  hipStream_t st);
+                  void* ws, size_t ws_bytes, bool force_simple, hipStream_t st);
+size_t owc_cd_workspace_bytes(int64_t d_out, int64_t d_in);
 
 // ---- stepwise.hip
 int score_argmin_launch(const float* hdiag, const float* scale, const uint8_t* Q, const float* G, int64_t d_out, int64_t d_in,

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
                                                      const float* __restrict__ scale, const float* __restrict__ zero,
                                                      const uint8_t* __restrict__ Q, int64_t d_out, int64_t d_in,
                                                      int64_t group, float* __restrict__ G,
-                                                     double* __restrict__ partial, int n_tiles) {
+                                                     double* __restrict__ partial, int n_tiles, double* __restrict__ G64) {
     __shared__ float As[BK][LDP];     // As[k][m] = E[m0+m][k0+k]
     __shared__ float Bs[BK][LDP];     // Bs[k][n] = H[k0+k][n0+n]
     __shared__ double red[4][BM];
@@ -127,7 +127,10 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         const int64_t col = n0 + wn * 32 + j * 16 + c_in;
-                        if (col < d_in) G[row * d_in + col] = (float)acc[i][j][v];
+                        if (col < d_in) {
+                            if (G64 != nullptr) G64[row * d_in + col] = acc[i][j][v];
+                            else G[row * d_in + col] = (float)acc[i][j][v];
+                        }
                     }
                 }
             }
@@ -197,16 +200,16 @@ size_t loss_workspace_bytes(int64_t d_out, int64_t d_in) {
 }
 
 int gradient_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
-                    int64_t d_out, int64_t d_in, int64_t group, float* G, hipStream_t st) {
+                    int64_t d_out, int64_t d_in, int64_t group, float* G, hipStream_t st, double* G64) {
     if (d_out == 0) return CDQ_OK;
     const int64_t gx = (d_in + BN - 1) / BN, gy = (d_out + BM - 1) / BM;
     if (gy > 65535) return CDQ_EUNSUPPORTED;
     if (vec4_ok(H, Wt, Q, d_in, group))
         hipLaunchKernelGGL((eh_gemm_kernel<false, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, G, (double*)nullptr, (int)gx);
+                           d_out, d_in, group, G, (double*)nullptr, (int)gx, G64);
     else
         hipLaunchKernelGGL((eh_gemm_kernel<false, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, G, (double*)nullptr, (int)gx);
+                           d_out, d_in, group, G, (double*)nullptr, (int)gx, G64);
     CDQ_LAUNCH_CHECK();
     return CDQ_OK;
 }
@@ -229,10 +232,10 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
     double* rows = loss_per_col ? loss_per_col : rows_ws;
     if (vec4_ok(H, Wt, Q, d_in, group))
         hipLaunchKernelGGL((eh_gemm_kernel<true, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, (float*)nullptr, partial, (int)gx);
+                           d_out, d_in, group, (float*)nullptr, partial, (int)gx, (double*)nullptr);
     else
         hipLaunchKernelGGL((eh_gemm_kernel<true, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, (float*)nullptr, partial, (int)gx);
+                           d_out, d_in, group, (float*)nullptr, partial, (int)gx, (double*)nullptr);
     CDQ_LAUNCH_CHECK();
     hipLaunchKernelGGL(loss_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, partial, d_out, (int)gx, rows);
     CDQ_LAUNCH_CHECK();

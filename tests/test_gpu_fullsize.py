@@ -168,3 +168,49 @@ def test_large_owc_init_column_subset(cdq, oracle):
     say(f"CD codes equal on {eq:.6f} of sampled entries")
     assert eq >= 0.999
     assert np.array_equal(out["stats"].cpu().numpy()[cols][same, 0], ref["moves"])
+
+
+def test_mlp_up_owc_cd_init(cdq, oracle):
+    """Algorithm 3 at the real shape: all 16384 columns of the 2-bit, group-128 layer on the GPU with T = d_in/group,
+    48 sampled columns through the oracle (strengths, grid and codes equal), then greedy CD from that start."""
+    cfg = inputs.CONFIGS["mlp_up"]
+    say(f"{cfg.name}: generating X [{cfg.n}x{cfg.d_in}] and Wt [{cfg.d_out}x{cfg.d_in}]")
+    X, Wt = inputs.make_layer(cfg)
+    Hd = cdq.hessian(x_to_dev(X, cfg.x_dtype))
+    H32 = Hd.cpu().numpy()
+    del X
+    Wd = torch.from_numpy(Wt).cuda()
+    say("OWC-CD on the GPU, whole layer")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    out = cdq.init_owc_cd(Hd, Wd, cfg.bits, cfg.group, 50)
+    torch.cuda.synchronize()
+    say(f"  {1e3 * (time.perf_counter() - t0):.1f} ms, {int(out['moves'].sum())} strength moves")
+    s_rtn, z_rtn, Q_rtn = cdq.init_rtn(Wd, cfg.bits, cfg.group)
+    l_rtn = cdq.loss(Hd, Wd, s_rtn, z_rtn, Q_rtn, cfg.group)[0]
+    l_owc = cdq.loss(Hd, Wd, out["scale"], out["zero"], out["Q"], cfg.group)[0]
+    assert torch.all(l_owc <= l_rtn * (1 + 1e-9)), "every move lowers the loss, so the result can not be worse than MinMax"
+    say(f"  layer loss MinMax {float(l_rtn.sum()):.6e} -> OWC-CD {float(l_owc.sum()):.6e}")
+    assert float(l_owc.sum()) < float(l_rtn.sum())
+    gi = out["gamma_idx"].cpu().numpy()
+    assert gi.min() >= 1 and gi.max() <= 50
+    assert np.array_equal((gi != 50).sum(axis=1) <= out["moves"].cpu().numpy(), np.ones(cfg.d_out, bool))
+    cols = np.sort(np.random.default_rng(9).choice(cfg.d_out, size=48, replace=False))
+    say(f"oracle OWC-CD on {len(cols)} sampled columns")
+    ref = oracle.owc_cd(H32, Wt[cols], cfg.bits, cfg.group, 50)
+    same = (gi[cols] == ref["gamma_idx"]).all(axis=1)
+    say(f"  strengths equal on {int(same.sum())}/{len(cols)} sampled columns")
+    assert same.sum() >= len(cols) - 1
+    assert np.array_equal(out["scale"].cpu().numpy()[cols][same], ref["scale"][same])
+    assert np.array_equal(out["zero"].cpu().numpy()[cols], ref["zero"])
+    assert np.array_equal(out["Q"].cpu().numpy()[cols][same], ref["Q"][same])
+    assert np.array_equal(out["moves"].cpu().numpy()[cols][same], ref["moves"][same])
+    say("greedy CD from the OWC-CD start")
+    Q = out["Q"].clone()
+    cdq.greedy_cd(Hd, Wd, out["scale"], out["zero"], Q, cfg.bits, cfg.group, cfg.T)
+    l_cd = cdq.loss(Hd, Wd, out["scale"], out["zero"], Q, cfg.group)[0]
+    assert torch.all(l_cd <= l_owc * (1 + 1e-9))
+    refcd = oracle.greedy_cd(H32, Wt[cols][same], ref["scale"][same], ref["zero"][same], ref["Q"][same], cfg.bits, cfg.group, cfg.T)
+    eq = (Q.cpu().numpy()[cols][same] == refcd["Q"]).mean()
+    say(f"  layer loss after CD {float(l_cd.sum()):.6e}; codes equal on {eq:.6f} of sampled entries")
+    assert eq >= 0.999

@@ -171,8 +171,10 @@ def owc_cd_score(oracle, H64, wj, bits, group, n_gamma, cur, i, k):
 
 @pytest.mark.parametrize("d_out,d_in,n,bits,group,n_gamma,T", [
     (40, 256, 600, 3, 32, 50, None), (9, 512, 900, 2, 128, 50, None), (17, 96, 300, 4, 8, 20, 30), (6, 128, 300, 3, 128, 50, 3),
-    (5, 192, 400, 2, 64, 50, 0)])
-def test_init_owc_cd(cdq, oracle, d_out, d_in, n, bits, group, n_gamma, T):
+    (5, 192, 400, 2, 64, 50, 0), (12, 1024, 1500, 3, 256, 50, None), (7, 1536, 2000, 2, 512, 12, None), (5, 120, 300, 3, 12, 50, None),
+    (6, 132, 300, 3, 6, 30, None)])
+@pytest.mark.parametrize("variant", [0, 1])
+def test_init_owc_cd(cdq, oracle, d_out, d_in, n, bits, group, n_gamma, T, variant):
     """Algorithm 3: the sequence of (group, grid index) moves, the final strengths, grid and codes equal the
     oracle's; a column may differ only from a move on where the two candidates tie to fp64 rounding."""
     X, Wt = rand_layer(11 + d_in, d_in, d_out, n, corr=0.5)
@@ -182,7 +184,7 @@ def test_init_owc_cd(cdq, oracle, d_out, d_in, n, bits, group, n_gamma, T):
     H32 = oracle.hessian(X).astype(np.float32)
     cap = (d_in // group if T is None else T) + 1
     ref = oracle.owc_cd(H32, Wt, bits, group, n_gamma, T, trace_cap=cap)
-    out = {k: v.cpu().numpy() for k, v in cdq.init_owc_cd(dev(H32), dev(Wt), bits, group, n_gamma, T, trace_cap=cap).items()}
+    out = {k: v.cpu().numpy() for k, v in cdq.init_owc_cd(dev(H32), dev(Wt), bits, group, n_gamma, T, trace_cap=cap, variant=variant).items()}
     assert np.array_equal(out["zero"], ref["zero"])
     H64 = H32.astype(np.float64)
     n_same = 0
