@@ -191,7 +191,7 @@ __device__ __forceinline__ float owc_resid_fast(float x, float lo, float a, floa
     return fmaf(a, q, lo) - x;
 }
 
-__global__ __launch_bounds__(ONT) void owc_cd_tiled_kernel(const float* __restrict__ H, const float* __restrict__ Wt,
+__global__ __launch_bounds__(ONT) __attribute__((amdgpu_waves_per_eu(4, 4))) void owc_cd_tiled_kernel(const float* __restrict__ H, const float* __restrict__ Wt,
                                                            const double* __restrict__ G64, int d_in, int bits, int group,
                                                            int n_gamma, int T, float* __restrict__ scale, float* __restrict__ zero,
                                                            uint8_t* __restrict__ Q, int32_t* __restrict__ gamma_idx,
@@ -265,27 +265,21 @@ __global__ __launch_bounds__(ONT) void owc_cd_tiled_kernel(const float* __restri
                     for (int cc = 0; cc < 4; ++cc) acc[kk][cc] = 0.0;
                 const float* hp = H + (int64_t)(g0 + ms * mlen) * d_in + g0 + 4 * cb;
                 for (int m = ms * mlen; m < (ms + 1) * mlen; m += 4) {
-                    float hv[4][4];
+                    float4 ev[KT];
+#pragma unroll
+                    for (int kk = 0; kk < KT; ++kk) ev[kk] = *reinterpret_cast<const float4*>(E + krow[kk] + m);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const float4 t4 = *reinterpret_cast<const float4*>(hp + (int64_t)r * d_in);
-                        hv[r][0] = t4.x; hv[r][1] = t4.y; hv[r][2] = t4.z; hv[r][3] = t4.w;
+                        const float4 h4 = *reinterpret_cast<const float4*>(hp + (int64_t)r * d_in);
+                        const double hd[4] = {(double)h4.x, (double)h4.y, (double)h4.z, (double)h4.w};
+#pragma unroll
+                        for (int kk = 0; kk < KT; ++kk) {
+                            const double ed = (double)(r == 0 ? ev[kk].x : r == 1 ? ev[kk].y : r == 2 ? ev[kk].z : ev[kk].w);
+#pragma unroll
+                            for (int cc = 0; cc < 4; ++cc) acc[kk][cc] = fma(ed, hd[cc], acc[kk][cc]);
+                        }
                     }
                     hp += 4 * (int64_t)d_in;
-                    double hd[4][4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-#pragma unroll
-                        for (int cc = 0; cc < 4; ++cc) hd[r][cc] = (double)hv[r][cc];
-#pragma unroll
-                    for (int kk = 0; kk < KT; ++kk) {
-                        const float4 ev = *reinterpret_cast<const float4*>(E + krow[kk] + m);
-                        const double ed[4] = {(double)ev.x, (double)ev.y, (double)ev.z, (double)ev.w};
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-#pragma unroll
-                            for (int cc = 0; cc < 4; ++cc) acc[kk][cc] = fma(ed[r], hd[r][cc], acc[kk][cc]);
-                    }
                 }
 #pragma unroll
                 for (int kk = 0; kk < KT; ++kk) {
@@ -328,8 +322,16 @@ __global__ __launch_bounds__(ONT) void owc_cd_tiled_kernel(const float* __restri
         for (int p = pslot; p < n_pairs; p += ONT / LPP) {
             const int i = p / n_gamma, g0 = i * group;
             const float a = a_tab[p], r = r_tab[p], l = lo[i];
-            double acc = 0.0;
-            for (int m = sub; m < group; m += LPP) acc = fma((double)owc_resid_fast(w[g0 + m], l, a, r, top), z[g0 + m], acc);
+            double acc4[4] = {0.0, 0.0, 0.0, 0.0};
+            for (int m = 4 * sub; m < group; m += 4 * LPP) {          // four consecutive weights per lane and step
+                const float4 w4 = *reinterpret_cast<const float4*>(w + g0 + m);
+                const double2 z01 = *reinterpret_cast<const double2*>(z + g0 + m), z23 = *reinterpret_cast<const double2*>(z + g0 + m + 2);
+                acc4[0] = fma((double)owc_resid_fast(w4.x, l, a, r, top), z01.x, acc4[0]);
+                acc4[1] = fma((double)owc_resid_fast(w4.y, l, a, r, top), z01.y, acc4[1]);
+                acc4[2] = fma((double)owc_resid_fast(w4.z, l, a, r, top), z23.x, acc4[2]);
+                acc4[3] = fma((double)owc_resid_fast(w4.w, l, a, r, top), z23.y, acc4[3]);
+            }
+            double acc = (acc4[0] + acc4[1]) + (acc4[2] + acc4[3]);
 #pragma unroll
             for (int o = 1; o < LPP; o <<= 1) acc += __shfl_xor(acc, o);
             if (sub == 0) F[p] = A[p] + acc;
