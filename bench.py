@@ -8,7 +8,7 @@ Prints ONE JSON line.  `value` = committed coordinate updates per second of whol
 Extra objects: `roofline` for the kernel that dominates the step, `cpu_baseline` for the CPU
 oracle timed on a bounded sample of the same workload, `stages` with per-stage times.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config attn_proj] [--mode rtn|stress]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config attn_proj] [--mode rtn|stress] [--init config|rtn|owc|owc_cd]
 """
 import argparse
 import ctypes
@@ -67,7 +67,7 @@ def load_traffic(kernel, workload):
         return None
 
 
-def cpu_baseline(cfg, mode, budget_s=20.0):
+def cpu_baseline(cfg, mode, init, budget_s=20.0):
     """The oracle, as it stands, on the host cores: Hessian on a token sample, RTN + CD + loss on a
     column sample, each extrapolated linearly to the full layer; updates/s of the whole step."""
     import numpy as np
@@ -86,7 +86,13 @@ def cpu_baseline(cfg, mode, budget_s=20.0):
     def run(cols):
         Wt = inputs.make_wt(cols, cfg.d_in, cfg.seed)
         t = time.perf_counter()
-        a, b, q = oracle.init_grid(Wt, cfg.bits, cfg.group)
+        if init == "owc" and mode != "stress":
+            a, b, q, _, _ = oracle.init_owc(H32, Wt, cfg.bits, cfg.group, 50)
+        elif init == "owc_cd" and mode != "stress":
+            o = oracle.owc_cd(H32, Wt, cfg.bits, cfg.group, 50)
+            a, b, q = o["scale"], o["zero"], o["Q"]
+        else:
+            a, b, q = oracle.init_grid(Wt, cfg.bits, cfg.group)
         if mode == "stress":
             q = inputs.make_random_codes(cols, cfg.d_in, cfg.bits, cfg.seed)
         r = oracle.greedy_cd(H32, Wt, a, b, q, cfg.bits, cfg.group, cfg.T)
@@ -101,7 +107,7 @@ def cpu_baseline(cfg, mode, budget_s=20.0):
     total_s = t_h + t_cols * scale
     return {
         "value": moves * scale / total_s, "unit": "updates/s", "cores": oracle.n_threads(), "kind": "oracle",
-        "sample": f"Hessian on {n_tok} of {cfg.n} tokens (fp64 numpy), RTN+CD+loss on the first {cols} of "
+        "sample": f"Hessian on {n_tok} of {cfg.n} tokens (fp64 numpy), {init} init+CD+loss on the first {cols} of "
                   f"{cfg.d_out} columns for the full T={cfg.T}; times scaled linearly to the full layer "
                   f"(est. {total_s:.1f} s)",
     }
@@ -115,6 +121,8 @@ def main():
     ap.add_argument("--config", default="attn_proj")
     ap.add_argument("--mode", default="rtn", choices=["rtn", "stress"],
                     help="rtn: initial codes as the configuration says; stress: uniform random initial codes")
+    ap.add_argument("--init", default="config", choices=["config", "rtn", "owc", "owc_cd"],
+                    help="initial grid: the configuration's own, MinMax/RTN, OWC (Eq. 2 grid search) or OWC-CD (Algorithm 3)")
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--elems", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -131,6 +139,9 @@ def main():
     from paper_2406_17542_amd import cdq, inputs
 
     cfg = inputs.CONFIGS[args.config]
+    init = cfg.init if args.init == "config" else args.init
+    if args.mode == "stress":
+        init = "rtn"
     torch.cuda.set_device(0)
     ev = HipEvents()
     stream = torch.cuda.current_stream().cuda_stream
@@ -151,8 +162,10 @@ def main():
     ws_cd = torch.empty(max(cdq.workspace_bytes(cdq.OP_GREEDY_CD, 0, cfg.d_out, cfg.d_in), 256), dtype=torch.uint8, device="cuda")
     ws_l = torch.empty(max(cdq.workspace_bytes(cdq.OP_LOSS, 0, cfg.d_out, cfg.d_in), 256), dtype=torch.uint8, device="cuda")
     ws_owc = None
-    if cfg.init == "owc":
+    if init == "owc":
         ws_owc = torch.empty(max(cdq.workspace_bytes(cdq.OP_INIT_OWC, 0, cfg.d_out, cfg.d_in), 256), dtype=torch.uint8, device="cuda")
+    elif init == "owc_cd":
+        ws_owc = torch.empty(max(cdq.workspace_bytes(cdq.OP_INIT_OWC_CD, 0, cfg.d_out, cfg.d_in), 256), dtype=torch.uint8, device="cuda")
 
     stage_names = ["hessian", "init_grid", "cd_gradient_init", "cd_loop", "loss"]
     n_ev = 7
@@ -164,8 +177,12 @@ def main():
         rec(0)
         cdq.hessian(Xd, H=H, workspace=ws_h)
         rec(1)
-        if cfg.init == "owc" and q_stress is None:
+        if init == "owc":
             scale, zero, Q, _, _ = cdq.init_owc(H, Wd, cfg.bits, cfg.group, 50, workspace=ws_owc)
+        elif init == "owc_cd":
+            o = cdq.init_owc_cd(H, Wd, cfg.bits, cfg.group, 50, workspace=ws_owc)
+            scale, zero, Q = o["scale"], o["zero"], o["Q"]
+            state["owc_cd_moves"] = o["moves"]
         else:
             scale, zero, Q = cdq.init_rtn(Wd, cfg.bits, cfg.group)
         if q_stress is not None:
@@ -254,8 +271,23 @@ def main():
         achievable["h_row_gather_shape"] = f"H {cfg.d_in}x{cfg.d_in} fp32, rows of {row_bytes} B, {teams} teams x {waves_used} wavefronts"
 
     workload = (f"{cfg.name}: d_in={cfg.d_in} d_out={cfg.d_out} n={cfg.n} X={cfg.x_dtype}/{cfg.x_kind} bits={cfg.bits} "
-                f"group={'per-channel' if cfg.group == cfg.d_in else cfg.group} T={cfg.T} init={'random codes' if args.mode == 'stress' else cfg.init}")
-    if stages["cd_loop"] >= stages["hessian"]:
+                f"group={'per-channel' if cfg.group == cfg.d_in else cfg.group} T={cfg.T} init={'random codes' if args.mode == 'stress' else init}")
+    owc_cd_info = None
+    if init == "owc_cd":
+        # fp64 operations of Algorithm 3 as the tiled kernel organises it: the table of self terms
+        # e_k^T H_ii e_k, one F pass per iteration, one rank-`group` update of z per move, plus He of the start
+        n_grp, n_gamma = cfg.d_in // cfg.group, 50
+        g_moves = int(state["owc_cd_moves"].sum().item())
+        iters = g_moves + cfg.d_out                      # every column runs one F pass more than it moves, up to T
+        flop = (2.0 * cfg.d_out * n_grp * n_gamma * cfg.group * cfg.group + 2.0 * cfg.d_out * cfg.d_in * cfg.d_in
+                + 2.0 * min(iters, cfg.d_out * n_grp) * n_grp * n_gamma * cfg.group + 2.0 * g_moves * cfg.group * (cfg.d_in - cfg.group))
+        owc_cd_info = {"strength_moves": g_moves, "fp64_flop": flop, "tflops": flop / (stages["init_grid"] * 1e-3) * 1e-12,
+                       "fp64_vector_peak_tflops": 78.6}
+    if owc_cd_info is not None and stages["init_grid"] >= max(stages["cd_loop"], stages["hessian"]):
+        roofline = {"kernel": "owc_cd_tiled_kernel (+ RTN and fp64 GEMM of the start)", "bound": "alu", "achieved": owc_cd_info["tflops"],
+                    "peak": 78.6, "unit": "TFLOP/s", "frac": owc_cd_info["tflops"] / 78.6, "traffic": None,
+                    "algorithmic_flop_per_launch": owc_cd_info["fp64_flop"], "avg_launch_ms": stages["init_grid"]}
+    elif stages["cd_loop"] >= stages["hessian"]:
         roofline = {"kernel": "cd_fused_kernel", "bound": "hbm", "achieved": cd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": cd_gbs / HBM_PEAK_GBS, "traffic": load_traffic("cd_fused_kernel", f"{cfg.name}:{args.mode}"),
                     "algorithmic_bytes_per_launch": cd_bytes, "avg_launch_ms": stages["cd_loop"]}
@@ -281,8 +313,10 @@ def main():
         "loss_final": loss_final,
         "achievable": achievable,
     }
+    if owc_cd_info is not None:
+        result["owc_cd"] = owc_cd_info
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, args.mode)
+        result["cpu_baseline"] = cpu_baseline(cfg, args.mode, init)
     print(json.dumps(result))
 
 
