@@ -69,6 +69,64 @@ def _pins_hold(lib):
     return bool(ok)
 
 
+OWC_CD_MUTANTS = {
+    "v_sign_as_printed": ("            v[r] = 2.0 * acc;", "            v[r] = -2.0 * acc;"),
+    "v_update_factor": ("                v[r] += 2.0 * acc;", "                v[r] += acc;"),
+    "v_update_wrong_block": ("const float *hrow = H + r * d_in + best_i * group;", "const float *hrow = H + r * d_in;"),
+    "quadratic_term_doubled": ("s += d[m] * (row + v[i * group + m]);", "s += d[m] * (2.0 * row + v[i * group + m]);"),
+    "residual_not_committed": ("for (int64_t m = 0; m < group; ++m) e[best_i * group + m] = en[m];", ""),
+}
+
+
+def _owc_cd_pins_hold(lib):
+    """Algorithm 3 through `lib` on a small layer: every committed score is the loss change recomputed
+    from X, and at a converged end point no single group can lower the loss by another grid point."""
+    rng = np.random.default_rng(5)
+    d_in, d_out, n, bits, group, n_gamma = 24, 3, 80, 2, 6, 10
+    X = rng.standard_normal((n, d_in)) + 0.5 * rng.standard_normal((n, 1))
+    Wt = (rng.standard_normal((d_out, d_in)) / 4).astype(np.float32)
+    Wt[:, ::7] *= 4.0
+    H = (X.T @ X).astype(np.float32)
+    n_grp, T = d_in // group, 40
+    p = lambda x: x.ctypes.data_as(ctypes.c_void_p)
+    I = ctypes.c_int64
+    scale = np.empty((d_out, n_grp), np.float32); zero = np.empty_like(scale)
+    Q = np.empty((d_out, d_in), np.uint8); gi = np.zeros((d_out, n_grp), np.int32)
+    mv = np.zeros(d_out, np.int32); cv = np.zeros(d_out, np.int32)
+    ti = np.full((d_out, T), -1, np.int32); tr = np.full((d_out, T), -1, np.int32); ts = np.zeros((d_out, T))
+    lib.cdqo_owc_cd(p(H), p(Wt), I(d_out), I(d_in), ctypes.c_int(bits), I(group), ctypes.c_int(n_gamma), I(T),
+                    p(scale), p(zero), p(Q), p(gi), p(mv), p(cv), p(ti), p(tr), p(ts), I(T))
+    H64 = H.astype(np.float64)
+
+    def loss_of(j, ks):
+        e = np.empty(d_in)
+        for i in range(n_grp):
+            sl = slice(i * group, (i + 1) * group)
+            w = Wt[j, sl]
+            a = np.float32(np.float32(np.float32(ks[i]) / np.float32(n_gamma)) * (w.max() - w.min())) / np.float32(3)
+            a = a if a > 0 else np.float32(1)
+            q = np.clip(np.rint((w - w.min()) / a), 0, 3).astype(np.float32)
+            e[sl] = (a * q + w.min()).astype(np.float32) - w
+        return float(e @ H64 @ e)
+
+    ok = True
+    for j in range(d_out):
+        ks = [n_gamma] * n_grp
+        prev = loss_of(j, ks)
+        for m in range(mv[j]):
+            ks[ti[j, m]] = tr[j, m]
+            now = loss_of(j, ks)
+            ok &= abs((now - prev) - ts[j, m]) <= 1e-4 * max(abs(prev), 1e-9)
+            prev = now
+        ok &= list(gi[j]) == ks
+        if cv[j]:
+            for i in range(n_grp):
+                for k in range(1, n_gamma + 1):
+                    alt = list(ks); alt[i] = k
+                    ok &= loss_of(j, alt) >= prev * (1 - 1e-6)
+    return bool(ok) and bool(mv.sum() > 0)
+
+
 def _compile(src_text, tmp_path, name):
     c = tmp_path / f"{name}.c"
     so = tmp_path / f"{name}.so"
@@ -88,3 +146,15 @@ def test_pin_catches_mutant(tmp_path, name):
     text = open(SRC).read()
     assert text.count(old) >= 1, "mutation site not found: the oracle source changed, update this test"
     assert not _pins_hold(_compile(text.replace(old, new, 1), tmp_path, name))
+
+
+def test_unmutated_source_passes_owc_cd_pins(tmp_path):
+    assert _owc_cd_pins_hold(_compile(open(SRC).read(), tmp_path, "orig_owc"))
+
+
+@pytest.mark.parametrize("name", sorted(OWC_CD_MUTANTS))
+def test_owc_cd_pin_catches_mutant(tmp_path, name):
+    old, new = OWC_CD_MUTANTS[name]
+    text = open(SRC).read()
+    assert text.count(old) == 1, "mutation site not found: the oracle source changed, update this test"
+    assert not _owc_cd_pins_hold(_compile(text.replace(old, new, 1), tmp_path, name))
