@@ -369,3 +369,89 @@ void cdqo_owc_cd(const float *H, const float *Wt, int64_t d_out, int64_t d_in, i
         free(tab); free(lo); free(hi); free(e); free(v); free(d);
     }
 }
+
+/* ---- block coordinate descent with random blocks (Algorithm 2; Algorithm 5 for groups) ----
+ *
+ * Weight-space form, canonical fp32 arithmetic as in greedy CD.  The random partitions are an
+ * input: parts[t*d_in + k*b + m] is member m of block b in iteration t (each row of parts is a
+ * permutation of 0..d_in-1).  Per iteration every block b and every level tuple
+ * r in {0..2^bits-1}^k is scored, tuples enumerated with the first member's level outermost:
+ *     delta_m = a_m (r_m - q_m),          s_m = delta_m * fmaf(delta_m, H_mm, 2 g_m)
+ *     s = s_0 + s_1 + ... (left to right), then for each pair m < m' in lexicographic order
+ *     s = fmaf(delta_m * delta_m', 2 H_mm', s)
+ * which is the loss change of moving the whole block.  The first strict minimum (block order,
+ * then tuple order) is committed if it is negative: g <- g + delta_m H[member m, :] for
+ * m = 0..k-1 in turn, codes of the block replaced.  An iteration without a negative score
+ * changes nothing, but later partitions may still find moves, so all T iterations run.
+ * k = 1 with the identity partition is greedy CD.
+ *
+ * trace_b = block index, trace_r = levels packed 4 bits per member (member 0 lowest), needs k <= 8.
+ */
+#define CDQO_MAX_K 8
+
+void cdqo_bcd_f32(const float *H, const float *scale, uint8_t *Q, float *G, const int32_t *parts,
+                  int64_t d_out, int64_t d_in, int bits, int64_t group, int k, int64_t T,
+                  int32_t *moves, int32_t *trace_t, int32_t *trace_b, int32_t *trace_r, float *trace_s,
+                  int64_t trace_cap)
+{
+    const int L = 1 << bits;
+    const int64_t n_grp = d_in / group, n_blk = d_in / k;
+    int64_t n_tuples = 1;
+    for (int m = 0; m < k; ++m) n_tuples *= L;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t j = 0; j < d_out; ++j) {
+        const float *a = scale + j * n_grp;
+        uint8_t *q = Q + j * d_in;
+        float *g = G + j * d_in;
+        int32_t n_moves = 0;
+        for (int64_t t = 0; t < T; ++t) {
+            const int32_t *part = parts + t * d_in;
+            float best_s = 0.0f;
+            int64_t best_b = -1, best_tuple = -1;
+            for (int64_t b = 0; b < n_blk; ++b) {
+                const int32_t *mem = part + b * k;
+                for (int64_t tup = 0; tup < n_tuples; ++tup) {
+                    float delta[CDQO_MAX_K];
+                    int64_t rest = tup;
+                    for (int m = k - 1; m >= 0; --m) {           /* member 0 is the most significant digit */
+                        const int r = (int)(rest % L);
+                        rest /= L;
+                        delta[m] = a[mem[m] / group] * (float)(r - (int)q[mem[m]]);
+                    }
+                    float s = 0.0f;
+                    for (int m = 0; m < k; ++m) {
+                        const int64_t c = mem[m];
+                        const float sm = delta[m] * fmaf(delta[m], H[c * d_in + c], 2.0f * g[c]);
+                        s = (m == 0) ? sm : s + sm;
+                    }
+                    for (int m = 0; m < k; ++m)
+                        for (int m2 = m + 1; m2 < k; ++m2)
+                            s = fmaf(delta[m] * delta[m2], 2.0f * H[(int64_t)mem[m] * d_in + mem[m2]], s);
+                    if (s < best_s) { best_s = s; best_b = b; best_tuple = tup; }
+                }
+            }
+            if (best_b < 0) continue;
+            const int32_t *mem = part + best_b * k;
+            int64_t rest = best_tuple;
+            int r_new[CDQO_MAX_K];
+            for (int m = k - 1; m >= 0; --m) { r_new[m] = (int)(rest % L); rest /= L; }
+            int32_t packed = 0;
+            for (int m = 0; m < k; ++m) {
+                const int64_t c = mem[m];
+                const float delta = a[c / group] * (float)(r_new[m] - (int)q[c]);
+                const float *hrow = H + c * d_in;
+                for (int64_t x = 0; x < d_in; ++x) g[x] = fmaf(delta, hrow[x], g[x]);
+                q[c] = (uint8_t)r_new[m];
+                packed |= r_new[m] << (4 * m);
+            }
+            if (n_moves < trace_cap) {
+                trace_t[j * trace_cap + n_moves] = (int32_t)t;
+                trace_b[j * trace_cap + n_moves] = (int32_t)best_b;
+                trace_r[j * trace_cap + n_moves] = packed;
+                trace_s[j * trace_cap + n_moves] = best_s;
+            }
+            ++n_moves;
+        }
+        moves[j] = n_moves;
+    }
+}

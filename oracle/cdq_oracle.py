@@ -198,6 +198,34 @@ def argmin_step(Hdiag, scale, Q, G, bits: int, group: int):
     return oi, orr, os_
 
 
+def bcd(H, Wt, scale, zero, Q0, parts, bits: int, group: int, k: int = 2, trace_cap: int = 0):
+    """Algorithm 2 (Algorithm 5 when group < d_in) in canonical fp32 for every column, block size k.
+    parts [T][d_in] int32: row t is the random partition of iteration t, block b = parts[t, k*b : k*b+k].
+    Returns Q, moves, G and, if trace_cap > 0, trace_t (iteration), trace_b (block), trace_r (levels,
+    4 bits per member, member 0 lowest), trace_s."""
+    lib = _load()
+    Q = np.ascontiguousarray(Q0, np.uint8).copy()
+    d_out, d_in = Q.shape
+    parts = np.ascontiguousarray(parts, np.int32)
+    T = parts.shape[0]
+    assert parts.shape == (T, d_in) and d_in % k == 0 and d_in % group == 0 and 1 <= k <= 8
+    assert (np.sort(parts, axis=1) == np.arange(d_in)).all(), "every row of parts must be a permutation"
+    H = np.ascontiguousarray(H, np.float32)
+    scale = np.ascontiguousarray(scale, np.float32)
+    E = residual(Wt, Q, scale, zero, group, "f32")
+    G = gradient(H, E, "f32")
+    moves = np.zeros(d_out, np.int32)
+    cap = max(int(trace_cap), 0)
+    tt, tb, tr = (np.full((d_out, max(cap, 1)), -1, np.int32) for _ in range(3))
+    ts = np.zeros((d_out, max(cap, 1)), np.float32)
+    lib.cdqo_bcd_f32(_p(H), _p(scale), _p(Q), _p(G), _p(parts), _I64(d_out), _I64(d_in), ctypes.c_int(bits), _I64(group),
+                     ctypes.c_int(k), _I64(T), _p(moves), _p(tt), _p(tb), _p(tr), _p(ts), _I64(cap))
+    out = {"Q": Q, "moves": moves, "G": G}
+    if cap:
+        out.update(trace_t=tt, trace_b=tb, trace_r=tr, trace_s=ts)
+    return out
+
+
 # --------------------------------------------------------------------------- OWC (Eq. 2 + grid search)
 
 def owc_gammas(n_gamma: int = 50) -> np.ndarray:

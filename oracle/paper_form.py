@@ -122,3 +122,41 @@ def owc_cd_paper_form(X, w, bits, group, gammas, T):
         cur[i] = k
         moves.append((i, k, s))
     return cur, moves
+
+
+def bcd_code_space(X, w, a, b, q0, parts, bits, k=2):
+    """Algorithm 2 as printed (fp64, code space): g = 2H(q0 - (w-b)/a); per iteration, for the given
+    partition into blocks of k, arg-min over blocks i and level tuples r of
+    (r - q_i)^T H_ii (r - q_i) + (r - q_i)^T g_i, then g += 2 H[:, block] (r* - q_block) and the
+    codes of the block are replaced.  A minimum that is not negative changes nothing.
+    Returns (q_T, list of (t, block, tuple of levels, score))."""
+    X = np.asarray(X, np.float64)
+    H = X.T @ X
+    q = np.asarray(q0, np.float64).copy()
+    g = 2.0 * H @ (q - (np.asarray(w, np.float64) - b) / a)
+    tuples = np.array(list(itertools.product(range(1 << bits), repeat=k)), np.float64)     # first member outermost
+    moves = []
+    for t, part in enumerate(np.asarray(parts)):
+        best = (0.0, -1, None)
+        for blk in range(len(part) // k):
+            idx = part[blk * k:(blk + 1) * k]
+            u = tuples - q[idx][None, :]
+            sc = np.einsum("tm,mn,tn->t", u, H[np.ix_(idx, idx)], u) + u @ g[idx]
+            m = int(np.argmin(sc))
+            if sc[m] < best[0]:
+                best = (float(sc[m]), blk, tuples[m].copy())
+        if best[1] < 0:
+            continue
+        s, blk, r = best
+        idx = part[blk * k:(blk + 1) * k]
+        g = g + 2.0 * H[:, idx] @ (r - q[idx])
+        q[idx] = r
+        moves.append((t, blk, tuple(int(x) for x in r), s))
+    return q.astype(np.int64), moves
+
+
+def bcd_sub_channel(X, w, a_vec, b_vec, q0, parts, bits, k=2):
+    """Algorithm 5: Algorithm 2 on X~ = X diag(a), w~ = w / a, b~ = b / a with unit scale."""
+    a_vec = np.asarray(a_vec, np.float64)
+    return bcd_code_space(np.asarray(X, np.float64) * a_vec[None, :], np.asarray(w, np.float64) / a_vec, 1.0,
+                          np.asarray(b_vec, np.float64) / a_vec, q0, parts, bits, k)

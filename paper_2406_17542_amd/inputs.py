@@ -51,7 +51,7 @@ CONFIG_ORDER = ["tiny", "attn_proj", "mlp_up", "mlp_down", "large"]
 
 
 def _rng(seed: int, stream: int) -> np.random.Generator:
-    # stream 0 = X, 1 = W, 2 = channel choice / channel scales, 3 = random codes
+    # stream 0 = X, 1 = W, 2 = channel choice / channel scales, 3 = random codes, 4 = random partitions
     return np.random.default_rng([seed, stream])
 
 
@@ -111,6 +111,17 @@ def make_random_codes(d_out: int, d_in: int, bits: int, seed: int = 0) -> np.nda
     """Uniform random codes: a free choice of the algorithm's 'initial estimate'
     input that keeps almost every iteration committing a move (stress mode)."""
     return _rng(seed, 3).integers(0, 1 << bits, size=(d_out, d_in), dtype=np.uint8)
+
+
+def make_partitions(T: int, d_in: int, seed: int = 0) -> np.ndarray:
+    """T independent uniform random permutations of 0..d_in-1 (int32 [T][d_in]): the random
+    partitions a block coordinate descent draws, one per iteration; consecutive entries of a row
+    form a block.  Drawn here so that every implementation is handed the same ones."""
+    rng = _rng(seed, 4)
+    out = np.empty((T, d_in), np.int32)
+    for t in range(T):
+        out[t] = rng.permutation(d_in)
+    return out
 
 
 def make_layer(cfg: LayerConfig, d_out: int | None = None, n: int | None = None):

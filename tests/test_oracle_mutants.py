@@ -127,6 +127,72 @@ def _owc_cd_pins_hold(lib):
     return bool(ok) and bool(mv.sum() > 0)
 
 
+BCD_MUTANTS = {
+    "cross_term_factor": ("s = fmaf(delta[m] * delta[m2], 2.0f * H[(int64_t)mem[m] * d_in + mem[m2]], s);",
+                          "s = fmaf(delta[m] * delta[m2], H[(int64_t)mem[m] * d_in + mem[m2]], s);"),
+    "cross_term_wrong_entry": ("s = fmaf(delta[m] * delta[m2], 2.0f * H[(int64_t)mem[m] * d_in + mem[m2]], s);",
+                               "s = fmaf(delta[m] * delta[m2], 2.0f * H[(int64_t)mem[m] * d_in + mem[m]], s);"),
+    "committed_block_offset": ("const int32_t *mem = part + best_b * k;\n            int64_t rest = best_tuple;",
+                               "const int32_t *mem = part + best_b;\n            int64_t rest = best_tuple;"),
+    "update_with_wrong_member_level": ("const float delta = a[c / group] * (float)(r_new[m] - (int)q[c]);",
+                                       "const float delta = a[c / group] * (float)(r_new[0] - (int)q[c]);"),
+    "gradient_update_sign": ("for (int64_t x = 0; x < d_in; ++x) g[x] = fmaf(delta, hrow[x], g[x]);",
+                             "for (int64_t x = 0; x < d_in; ++x) g[x] = fmaf(-delta, hrow[x], g[x]);"),
+}
+
+
+def _bcd_pins_hold(lib):
+    """Algorithm 2 (k = 2) through `lib`: committed scores are loss changes, and an iteration without a move
+    leaves no block of its partition improvable."""
+    import itertools
+    rng = np.random.default_rng(12)
+    d_in, d_out, n, bits, group, k, T = 8, 3, 50, 2, 4, 2, 16
+    X = rng.standard_normal((n, d_in)) + 0.7 * rng.standard_normal((n, 1))
+    Wt = (rng.standard_normal((d_out, d_in)) / 3).astype(np.float32)
+    H = (X.T @ X).astype(np.float32)
+    Wg = Wt.reshape(d_out, d_in // group, group)
+    b = Wg.min(2).astype(np.float32)
+    a = ((Wg.max(2) - b) / np.float32(3)).astype(np.float32)
+    q = rng.integers(0, 4, (d_out, d_in)).astype(np.uint8)
+    q0 = q.copy()
+    parts = np.stack([rng.permutation(d_in) for _ in range(T)]).astype(np.int32)
+    p = lambda x: x.ctypes.data_as(ctypes.c_void_p)
+    I = ctypes.c_int64
+    E = np.empty((d_out, d_in), np.float32)
+    lib.cdqo_residual_f32(p(Wt), p(q), p(a), p(b), I(d_out), I(d_in), I(group), p(E))
+    G = np.empty_like(E)
+    lib.cdqo_gradient_f32(p(H), p(E), I(d_out), I(d_in), p(G))
+    mv = np.zeros(d_out, np.int32)
+    tt, tb, tr = (np.full((d_out, T), -1, np.int32) for _ in range(3))
+    ts = np.zeros((d_out, T), np.float32)
+    lib.cdqo_bcd_f32(p(H), p(a), p(q), p(G), p(parts), I(d_out), I(d_in), ctypes.c_int(bits), I(group), ctypes.c_int(k), I(T),
+                     p(mv), p(tt), p(tb), p(tr), p(ts), I(T))
+    ok = bool(mv.sum() > 0)
+    for j in range(d_out):
+        av = np.repeat(a[j].astype(np.float64), group); bv = np.repeat(b[j].astype(np.float64), group)
+        w = Wt[j].astype(np.float64)
+        cur = q0[j].astype(np.float64)
+        prev = pf.layer_loss(X, w, av, bv, cur)
+        moved = {int(t): m for m, t in enumerate(tt[j]) if t >= 0}
+        for t in range(T):
+            if t in moved:
+                m = moved[t]
+                blk = parts[t, k * tb[j, m]: k * tb[j, m] + k]
+                for mm, c in enumerate(blk):
+                    cur[c] = (tr[j, m] >> (4 * mm)) & 15
+                now = pf.layer_loss(X, w, av, bv, cur)
+                ok &= abs((now - prev) - ts[j, m]) <= 1e-3 * max(abs(prev), 1.0)
+                prev = now
+            else:
+                for bi in range(d_in // k):
+                    blk = parts[t, k * bi: k * bi + k]
+                    for tup in itertools.product(range(4), repeat=k):
+                        alt = cur.copy(); alt[blk] = tup
+                        ok &= pf.layer_loss(X, w, av, bv, alt) >= prev * (1 - 1e-5)
+        ok &= np.array_equal(cur.astype(np.uint8), q[j])
+    return bool(ok)
+
+
 def _compile(src_text, tmp_path, name):
     c = tmp_path / f"{name}.c"
     so = tmp_path / f"{name}.so"
@@ -158,3 +224,15 @@ def test_owc_cd_pin_catches_mutant(tmp_path, name):
     text = open(SRC).read()
     assert text.count(old) == 1, "mutation site not found: the oracle source changed, update this test"
     assert not _owc_cd_pins_hold(_compile(text.replace(old, new, 1), tmp_path, name))
+
+
+def test_unmutated_source_passes_bcd_pins(tmp_path):
+    assert _bcd_pins_hold(_compile(open(SRC).read(), tmp_path, "orig_bcd"))
+
+
+@pytest.mark.parametrize("name", sorted(BCD_MUTANTS))
+def test_bcd_pin_catches_mutant(tmp_path, name):
+    old, new = BCD_MUTANTS[name]
+    text = open(SRC).read()
+    assert text.count(old) == 1, "mutation site not found: the oracle source changed, update this test"
+    assert not _bcd_pins_hold(_compile(text.replace(old, new, 1), tmp_path, name))
