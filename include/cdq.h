@@ -48,6 +48,7 @@ extern "C" {
 #define CDQ_OP_LOSS      2
 #define CDQ_OP_INIT_OWC  3
 #define CDQ_OP_INIT_OWC_CD 4
+#define CDQ_OP_BCD       5   /* n = T, the number of iterations */
 
 #define CDQ_MAX_D_IN 32768      /* largest d_in the register-resident CD kernel covers */
 
@@ -146,6 +147,28 @@ int cdq_init_owc_cd(const float *H, const float *Wt, int64_t d_out, int64_t d_in
                     int n_gamma, int64_t T, float *scale, float *zero, uint8_t *Q, int32_t *gamma_idx,
                     int32_t *moves, int32_t *trace, int64_t trace_cap, int variant, void *workspace,
                     size_t workspace_bytes, void *stream);
+
+/*
+ * Block coordinate descent with random blocks (Algorithm 2; Algorithm 5 for groups), block size
+ * k = 2 (CDQ_EUNSUPPORTED otherwise; k = 1 is cdq_greedy_cd), weight-space form, canonical fp32
+ * arithmetic.  The random partitions are an input so that every implementation sees the same
+ * ones:  parts [T][d_in] int32, device; row t is a permutation of 0..d_in-1 and block b of
+ * iteration t is (parts[t][2b], parts[t][2b+1]); all columns use the same partitions.  Rows that
+ * are not permutations are detected on the device: then nothing is changed and moves[j] = -1.
+ * Per iteration the block and level pair with the smallest loss change
+ *     s = fma(di*dk, 2 H_ik, di*fma(di, H_ii, 2 g_i) + dk*fma(dk, H_kk, 2 g_k)),  d = a (r - q),
+ * over all d_in/2 blocks and 4^bits level pairs is committed if negative (ties: first block of
+ * the partition, then smaller r_i, then smaller r_k): g += di H[i,:], then g += dk H[k,:].
+ * All T iterations run (a later partition may find moves an earlier one did not).
+ *   Q [d_out][d_in] in/out; moves NULL or [d_out] int32 out; G_out NULL or [d_out][d_in] fp32:
+ *   g = He of the final codes as maintained by the updates;
+ *   trace NULL or [d_out][trace_cap][4] int32: iteration, block, r_i | r_k<<4, score bits.
+ * Needs d_in % 4 == 0, d_in <= 8192, 16-byte aligned H; workspace of CDQ_OP_BCD size (n = T).
+ */
+int cdq_bcd(const float *H, const float *Wt, const float *scale, const float *zero, uint8_t *Q,
+            int64_t d_out, int64_t d_in, int bits, int64_t group, int k, const int32_t *parts, int64_t T,
+            int32_t *moves, float *G_out, int32_t *trace, int64_t trace_cap,
+            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Gradient initialisation of Algorithm 1 ("Compute gradient g at q0"), in weight space:

@@ -13,7 +13,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcdq.so")
 
 CDQ_F32, CDQ_BF16 = 0, 1
-OP_HESSIAN, OP_GREEDY_CD, OP_LOSS, OP_INIT_OWC, OP_INIT_OWC_CD = 0, 1, 2, 3, 4
+OP_HESSIAN, OP_GREEDY_CD, OP_LOSS, OP_INIT_OWC, OP_INIT_OWC_CD, OP_BCD = 0, 1, 2, 3, 4, 5
 MAX_D_IN = 32768
 
 _lib = None
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
             fn.restype = i32
         L.cdq_init_owc_cd.argtypes = [vp, vp, i64, i64, i32, i64, i32, i64, vp, vp, vp, vp, vp, vp, i64, i32, vp, sz, vp]
         L.cdq_init_owc_cd.restype = i32
+        L.cdq_bcd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i32, vp, i64, vp, vp, vp, i64, vp, sz, vp]
+        L.cdq_bcd.restype = i32
         L.cdq_probe_copy.argtypes = [vp, vp, sz, vp]
         L.cdq_probe_read.argtypes = [vp, sz, vp, vp]
         L.cdq_probe_gather.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
@@ -169,6 +171,30 @@ def init_owc_cd(H, Wt, bits: int, group: int, n_gamma: int = 50, T: int | None =
     _check(lib().cdq_init_owc_cd(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), d_out, d_in, bits, group, n_gamma, T,
                                  out["scale"].data_ptr(), out["zero"].data_ptr(), out["Q"].data_ptr(), out["gamma_idx"].data_ptr(),
                                  out["moves"].data_ptr(), tr, trace_cap, variant, ws.data_ptr(), ws.numel(), _stream()), "cdq_init_owc_cd")
+    return out
+
+
+def bcd(H, Wt, scale, zero, Q, bits: int, group: int, parts: torch.Tensor, k: int = 2, trace_cap: int = 0, want_G: bool = False,
+        workspace: torch.Tensor | None = None):
+    """Block coordinate descent with random blocks (Algorithm 2/5); Q is updated in place.  parts [T][d_in] int32 on
+    the GPU.  Returns a dict: moves[, trace [d_out][trace_cap][4]][, G]."""
+    d_out, d_in = Wt.shape
+    T = int(parts.shape[0])
+    if parts.dtype != torch.int32 or not parts.is_cuda or not parts.is_contiguous() or (T and parts.shape[1] != d_in):
+        raise TypeError("parts must be a contiguous int32 CUDA tensor [T][d_in]")
+    ws = _workspace(OP_BCD, T, d_out, d_in, workspace)
+    out = {"moves": torch.zeros(d_out, dtype=torch.int32, device=Wt.device)}
+    tr = g = None
+    if trace_cap > 0:
+        out["trace"] = torch.full((d_out, trace_cap, 4), -1, dtype=torch.int32, device=Wt.device)
+        tr = out["trace"].data_ptr()
+    if want_G:
+        out["G"] = torch.empty((d_out, d_in), dtype=torch.float32, device=Wt.device)
+        g = out["G"].data_ptr()
+    _check(lib().cdq_bcd(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), _dev(scale, torch.float32, "scale"),
+                         _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, bits, group, k,
+                         parts.data_ptr() if T else None, T, out["moves"].data_ptr(), g, tr, trace_cap, ws.data_ptr(), ws.numel(),
+                         _stream()), "cdq_bcd")
     return out
 
 

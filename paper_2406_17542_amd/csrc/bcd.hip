@@ -1,0 +1,251 @@
+// Block coordinate descent with random blocks of two coordinates (paper Algorithm 2; Algorithm 5
+// for groups), weight-space form.  One workgroup owns a column for all T iterations; 2g, the codes,
+// the group scales and the Hessian diagonal sit in LDS.  Per iteration:
+//   1. every thread scores its pairs (i,k) of this iteration's partition over all level pairs:
+//        delta_i = a_i (r_i - q_i),   s_i = delta_i * fma(delta_i, H_ii, 2 g_i)      (same for k)
+//        s(r_i, r_k) = fma(delta_i * delta_k, 2 H_ik, s_i + s_k)
+//      which is the loss change of moving both; the 2 H_ik of every pair of every iteration are
+//      gathered once for all columns before the loop (the partitions are shared by the columns);
+//   2. the workgroup takes the minimum of (ordered score, pair, r_i, r_k): ties go to the first
+//      pair of the partition, then the smaller r_i, then r_k;
+//   3. if negative: 2g <- fma(2 delta_i, H[i,:], 2g), then the same with k; codes replaced.
+// The partition and pair entries of the next iteration are loaded while the current one is scored.
+#include "cdq_internal.h"
+#include "wave_min.h"
+
+namespace cdq {
+namespace {
+
+constexpr int BCD_PPT = 4;          // pairs per thread at most
+
+__global__ __launch_bounds__(256) void bcd_pair_gather_kernel(const float* __restrict__ H, const int32_t* __restrict__ parts,
+                                                              const int32_t* __restrict__ bad, int64_t d_in, int64_t n_items,
+                                                              float* __restrict__ pair_h2) {
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;        // x = t * (d_in/2) + p
+    if (x >= n_items || *bad != 0) return;                            // indices are only followed once the check accepted them
+    const int32_t i = parts[2 * x], k = parts[2 * x + 1];
+    pair_h2[x] = 2.0f * H[(int64_t)i * d_in + k];
+}
+
+__global__ void bcd_fill_i32_kernel(int32_t* __restrict__ p, int64_t n, int32_t v) {
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x < n) p[x] = v;
+}
+
+// every entry of parts in range, every row a permutation (each value hit exactly once)
+__global__ __launch_bounds__(256) void bcd_check_parts_kernel(const int32_t* __restrict__ parts, int d_in, int32_t* __restrict__ bad) {
+    extern __shared__ int32_t seen[];
+    const int32_t* row = parts + (int64_t)blockIdx.x * d_in;
+    for (int c = threadIdx.x; c < d_in; c += 256) seen[c] = 0;
+    __syncthreads();
+    for (int c = threadIdx.x; c < d_in; c += 256) {
+        const int32_t v = row[c];
+        if (v < 0 || v >= d_in) atomicAdd(bad, 1);
+        else if (atomicAdd(&seen[v], 1) != 0) atomicAdd(bad, 1);
+    }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H, const float* __restrict__ hdiag,
+                                                    const float* __restrict__ G0, const float* __restrict__ scale,
+                                                    uint8_t* __restrict__ Q, const int32_t* __restrict__ parts,
+                                                    const float* __restrict__ pair_h2, const int32_t* __restrict__ bad_parts,
+                                                    int d_in, int group, int T, int32_t* __restrict__ moves_out,
+                                                    float* __restrict__ G_out, int32_t* __restrict__ trace, int trace_cap) {
+    constexpr int L = 1 << BITS;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, n_waves = nt >> 6;
+    const int n_grp = d_in / group, n_pairs = d_in / 2;
+    const int64_t j = blockIdx.x;
+    float* g2 = reinterpret_cast<float*>(smem);                  // [d_in]  2 g
+    float* hd = g2 + d_in;                                       // [d_in]
+    float* a = hd + d_in;                                        // [n_grp]
+    uint64_t* slots = reinterpret_cast<uint64_t*>(a + ((n_grp + 1) & ~1));   // [2][16] per-wavefront minima, double-buffered
+    float* commit = reinterpret_cast<float*>(slots + 32);        // [2][4]: i, k (as int bits), 2 delta_i, 2 delta_k
+    uint8_t* q = reinterpret_cast<uint8_t*>(commit + 8);         // [d_in]
+
+    if (*bad_parts != 0) {                                       // invalid partitions: leave the column untouched
+        if (tid == 0 && moves_out != nullptr) moves_out[j] = -1;
+        return;
+    }
+    for (int c = tid; c < d_in; c += nt) {
+        g2[c] = 2.0f * G0[j * (int64_t)d_in + c];
+        hd[c] = hdiag[c];
+        q[c] = Q[j * (int64_t)d_in + c];
+    }
+    for (int i = tid; i < n_grp; i += nt) a[i] = scale[j * n_grp + i];
+
+    int2 nxt_idx[BCD_PPT];
+    float nxt_h2[BCD_PPT];
+    auto prefetch = [&](int t) {
+#pragma unroll
+        for (int pp = 0; pp < BCD_PPT; ++pp) {
+            const int p = tid + pp * nt;
+            if (p < n_pairs && t < T) {
+                nxt_idx[pp] = *reinterpret_cast<const int2*>(parts + (int64_t)t * d_in + 2 * p);
+                nxt_h2[pp] = pair_h2[(int64_t)t * n_pairs + p];
+            }
+        }
+    };
+    prefetch(0);
+    __syncthreads();
+
+    int moves = 0;
+    for (int t = 0; t < T; ++t) {
+        int2 idx[BCD_PPT];
+        float h2[BCD_PPT];
+#pragma unroll
+        for (int pp = 0; pp < BCD_PPT; ++pp) { idx[pp] = nxt_idx[pp]; h2[pp] = nxt_h2[pp]; }
+        prefetch(t + 1);
+
+        float best_s = 0.0f;
+        uint32_t best_code = 0xffffffffu;
+        float best_di = 0.0f, best_dk = 0.0f;
+        int best_pp = 0;
+#pragma unroll
+        for (int pp = 0; pp < BCD_PPT; ++pp) {
+            const int p = tid + pp * nt;
+            if (p < n_pairs) {
+                const int i = idx[pp].x, k = idx[pp].y;
+                const float ai = a[i / group], ak = a[k / group];
+                const float gi = g2[i], gk = g2[k], hii = hd[i], hkk = hd[k];
+                const int qi = q[i], qk = q[k];
+                float dk[L], sk[L];
+#pragma unroll
+                for (int r = 0; r < L; ++r) {
+                    dk[r] = ak * (float)(r - qk);
+                    sk[r] = dk[r] * fmaf(dk[r], hkk, gk);
+                }
+#pragma unroll
+                for (int ri = 0; ri < L; ++ri) {
+                    const float di = ai * (float)(ri - qi);
+                    const float si = di * fmaf(di, hii, gi);
+#pragma unroll
+                    for (int rk = 0; rk < L; ++rk) {
+                        const float s = fmaf(di * dk[rk], h2[pp], si + sk[rk]);
+                        if (s < best_s) {            // pairs, r_i, r_k all ascend: the first strict minimum is kept
+                            best_s = s;
+                            best_code = ((uint32_t)p << 8) | (uint32_t)(ri << 4) | (uint32_t)rk;
+                            best_di = di; best_dk = dk[rk]; best_pp = pp;
+                        }
+                    }
+                }
+            }
+        }
+        // ---- workgroup minimum of (ordered score, code)
+        const uint64_t wkey = wave_min_key(order_bits(best_s), best_code);
+        uint64_t* slot = slots + (t & 1) * 16;
+        if (lane == 0) slot[wave] = wkey;
+        __syncthreads();
+        uint64_t key = slot[0];
+        for (int w = 1; w < n_waves; ++w) key = umin64(key, slot[w]);
+        if ((uint32_t)(key >> 32) >= kOrderedZero) continue;          // no pair lowers the loss under this partition
+        float* cm = commit + (t & 1) * 4;
+        if (best_code == (uint32_t)key && order_bits(best_s) == (uint32_t)(key >> 32)) {      // exactly one thread
+            int bi = 0, bk = 0;
+#pragma unroll
+            for (int pp = 0; pp < BCD_PPT; ++pp)
+                if (pp == best_pp) { bi = idx[pp].x; bk = idx[pp].y; }
+            cm[0] = __int_as_float(bi); cm[1] = __int_as_float(bk);
+            cm[2] = 2.0f * best_di; cm[3] = 2.0f * best_dk;
+            q[bi] = (uint8_t)((best_code >> 4) & 15u);
+            q[bk] = (uint8_t)(best_code & 15u);
+            if (trace != nullptr && moves < trace_cap) {
+                int32_t* tr = trace + (j * trace_cap + moves) * 4;
+                tr[0] = t; tr[1] = (int32_t)(best_code >> 8);
+                tr[2] = (int32_t)(((best_code >> 4) & 15u) | ((best_code & 15u) << 4));
+                tr[3] = __float_as_int(best_s);
+            }
+        }
+        ++moves;
+        __syncthreads();
+        const int ci = __float_as_int(cm[0]), ck = __float_as_int(cm[1]);
+        const float tdi = cm[2], tdk = cm[3];
+        const float* hi = H + (int64_t)ci * d_in;
+        const float* hk = H + (int64_t)ck * d_in;
+        for (int c = 4 * tid; c < d_in; c += 4 * nt) {
+            const float4 x = *reinterpret_cast<const float4*>(hi + c);
+            const float4 y = *reinterpret_cast<const float4*>(hk + c);
+            float4 g = *reinterpret_cast<float4*>(g2 + c);
+            g.x = fmaf(tdk, y.x, fmaf(tdi, x.x, g.x));
+            g.y = fmaf(tdk, y.y, fmaf(tdi, x.y, g.y));
+            g.z = fmaf(tdk, y.z, fmaf(tdi, x.z, g.z));
+            g.w = fmaf(tdk, y.w, fmaf(tdi, x.w, g.w));
+            *reinterpret_cast<float4*>(g2 + c) = g;
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+    for (int c = tid; c < d_in; c += nt) {
+        Q[j * (int64_t)d_in + c] = q[c];
+        if (G_out != nullptr) G_out[j * (int64_t)d_in + c] = 0.5f * g2[c];
+    }
+    if (tid == 0 && moves_out != nullptr) moves_out[j] = moves;
+}
+
+size_t bcd_lds_bytes(int64_t d_in, int64_t group) {
+    const int64_t n_grp = d_in / group;
+    return cdq_align_up(sizeof(float) * (2 * d_in + ((n_grp + 1) & ~(int64_t)1)) + sizeof(uint64_t) * 32 + sizeof(float) * 8 + (size_t)d_in, 16);
+}
+
+}  // namespace
+
+// workspace: G0 [d_out][d_in] fp32 | hdiag [d_in] | pair_h2 [T][d_in/2] | flag
+size_t bcd_workspace_bytes(int64_t d_out, int64_t d_in, int64_t T) {
+    return cdq_align_up((size_t)d_out * d_in * sizeof(float), 256) + cdq_align_up((size_t)d_in * sizeof(float), 256) +
+           cdq_align_up((size_t)T * (d_in / 2) * sizeof(float), 256) + 256;
+}
+
+int bcd_launch(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out, int64_t d_in,
+               int bits, int64_t group, const int32_t* parts, int64_t T, int32_t* moves, float* G_out, int32_t* trace,
+               int64_t trace_cap, void* ws, size_t ws_bytes, hipStream_t st) {
+    if (d_out == 0 || T == 0) {
+        if (T == 0 && d_out > 0 && moves != nullptr) {
+            hipLaunchKernelGGL(bcd_fill_i32_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, moves, d_out, 0);
+            CDQ_LAUNCH_CHECK();
+        }
+        if (T == 0 && d_out > 0 && G_out != nullptr) return gradient_launch(H, Wt, scale, zero, Q, d_out, d_in, group, G_out, st);
+        return CDQ_OK;
+    }
+    int nt = 256;
+    while ((int64_t)nt * BCD_PPT < d_in / 2) nt *= 2;
+    const size_t lds = bcd_lds_bytes(d_in, group);
+    if (nt > 1024 || lds > 160 * 1024 || d_in % 4 != 0 || ((uintptr_t)H & 15) || d_in >= (1 << 24) || T > 0x7fffffffLL || d_out > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
+    if (ws == nullptr || ((uintptr_t)ws & 255) || ws_bytes < bcd_workspace_bytes(d_out, d_in, T)) return CDQ_EWORKSPACE;
+    char* wp = (char*)ws;
+    float* G0 = (float*)wp;           wp += cdq_align_up((size_t)d_out * d_in * sizeof(float), 256);
+    float* hdiag = (float*)wp;        wp += cdq_align_up((size_t)d_in * sizeof(float), 256);
+    float* pair_h2 = (float*)wp;      wp += cdq_align_up((size_t)T * (d_in / 2) * sizeof(float), 256);
+    int32_t* bad = (int32_t*)wp;
+
+    hipLaunchKernelGGL(bcd_fill_i32_kernel, dim3(1), dim3(64), 0, st, bad, (int64_t)1, 0);
+    CDQ_LAUNCH_CHECK();
+    hipLaunchKernelGGL(bcd_check_parts_kernel, dim3((unsigned)T), dim3(256), sizeof(int32_t) * (size_t)d_in, st, parts, (int)d_in, bad);
+    CDQ_LAUNCH_CHECK();
+    int rc = gradient_launch(H, Wt, scale, zero, Q, d_out, d_in, group, G0, st);
+    if (rc != CDQ_OK) return rc;
+    rc = extract_diag_launch(H, d_in, hdiag, st);
+    if (rc != CDQ_OK) return rc;
+    const int64_t n_items = T * (d_in / 2);
+    hipLaunchKernelGGL(bcd_pair_gather_kernel, dim3((unsigned)((n_items + 255) / 256)), dim3(256), 0, st, H, parts,
+                       (const int32_t*)bad, d_in, n_items, pair_h2);
+    CDQ_LAUNCH_CHECK();
+#define BCD_CASE(B)                                                                                                              \
+    case B:                                                                                                                      \
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(bcd2_kernel<B>), hipFuncAttributeMaxDynamicSharedMemorySize,       \
+                                (int)lds) != hipSuccess)                                                                         \
+            return CDQ_EHIP;                                                                                                     \
+        hipLaunchKernelGGL((bcd2_kernel<B>), dim3((unsigned)d_out), dim3(nt), lds, st, H, (const float*)hdiag, (const float*)G0, \
+                           scale, Q, parts, (const float*)pair_h2, (const int32_t*)bad, (int)d_in, (int)group, (int)T, moves,    \
+                           G_out, trace, (int)(trace_cap > 0x7fffffffLL ? 0x7fffffffLL : trace_cap));                            \
+        break;
+    switch (bits) {
+        BCD_CASE(2) BCD_CASE(3) BCD_CASE(4)
+        default: return CDQ_EINVAL;
+    }
+#undef BCD_CASE
+    CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
+
+}  // namespace cdq

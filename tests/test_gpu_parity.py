@@ -223,6 +223,67 @@ def test_init_owc_cd_rejects_oversized_state(cdq):
         cdq.init_owc_cd(H, Wt, 2, 128)
 
 
+# ----------------------------------------------------------------------------- BCD (Algorithm 2 / 5), k = 2
+
+def bcd_moves_from_gpu(trace_j):
+    return [(int(t), int(b), int(r), np.int32(s).view(np.float32)) for t, b, r, s in trace_j if t >= 0]
+
+
+@pytest.mark.parametrize("d_out,d_in,n,bits,group,T,start", [
+    (24, 128, 400, 2, 128, 160, "random"), (16, 256, 700, 3, 64, 200, "random"), (10, 64, 300, 4, 16, 100, "random"),
+    (12, 512, 1200, 3, 512, 300, "cd"), (9, 136, 400, 2, 8, 80, "random"), (6, 2048, 4096, 2, 128, 64, "rtn"),
+    (5, 4096, 6000, 3, 4096, 24, "rtn")])
+def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start):
+    """Same partitions on both sides: the trajectories (iteration, block, levels, score bits), the final codes, the
+    move counts and the maintained gradient are equal bit for bit."""
+    X, Wt = rand_layer(31 + d_in + bits, d_in, d_out, n, corr=0.7)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q_rtn = oracle.init_grid(Wt, bits, group)
+    if start == "random":
+        q0 = inputs.make_random_codes(d_out, d_in, bits, seed=d_in)
+    elif start == "cd":                                   # the paper initialises BCD with CD
+        q0 = oracle.greedy_cd(H32, Wt, a, b, q_rtn, bits, group, d_in)["Q"]
+    else:
+        q0 = q_rtn
+    parts = inputs.make_partitions(T, d_in, seed=d_in + 1)
+    ref = oracle.bcd(H32, Wt, a, b, q0, parts, bits, group, k=2, trace_cap=T)
+    Q = dev(q0)
+    out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, bits, group, dev(parts), trace_cap=T, want_G=True)
+    moves = out["moves"].cpu().numpy()
+    trace = out["trace"].cpu().numpy()
+    assert ref["moves"].sum() > 0
+    assert np.array_equal(moves, ref["moves"])
+    assert np.array_equal(Q.cpu().numpy(), ref["Q"])
+    for j in range(d_out):
+        got = bcd_moves_from_gpu(trace[j])
+        want = [(int(t), int(bk), int(r), s) for t, bk, r, s in
+                zip(ref["trace_t"][j], ref["trace_b"][j], ref["trace_r"][j], ref["trace_s"][j]) if t >= 0]
+        assert [g[:3] for g in got] == [w[:3] for w in want], j
+        assert all(np.float32(g[3]).tobytes() == np.float32(w[3]).tobytes() for g, w in zip(got, want)), j
+    assert np.array_equal(out["G"].cpu().numpy(), ref["G"])
+
+
+def test_bcd_rejects_bad_partitions_and_block_sizes(cdq, oracle):
+    X, Wt = rand_layer(5, 64, 4, 200)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q = oracle.init_grid(Wt, 3, 64)
+    parts = inputs.make_partitions(8, 64, seed=1)
+    bad = parts.copy()
+    bad[3, 5] = bad[3, 6]                                  # a repeated entry: row 3 is no permutation
+    Q = dev(q)
+    out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, 64, dev(bad))
+    assert (out["moves"].cpu().numpy() == -1).all() and np.array_equal(Q.cpu().numpy(), q)
+    bad = parts.copy()
+    bad[0, 0] = 64                                         # out of range
+    out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, 64, dev(bad))
+    assert (out["moves"].cpu().numpy() == -1).all() and np.array_equal(Q.cpu().numpy(), q)
+    with pytest.raises(RuntimeError, match="outside"):
+        cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, 64, dev(parts), k=4)
+    # T = 0: nothing moves
+    out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, 64, dev(parts[:0]))
+    assert (out["moves"].cpu().numpy() == 0).all() and np.array_equal(Q.cpu().numpy(), q)
+
+
 # ----------------------------------------------------------------------------- gradient, loss
 
 @pytest.mark.parametrize("d_out,d_in,n,bits,group", [(64, 128, 512, 4, 128), (37, 200, 600, 3, 40), (130, 264, 800, 2, 8), (3, 7, 40, 3, 7)])
