@@ -65,7 +65,7 @@ def lib() -> ctypes.CDLL:
             fn.restype = i32
         L.cdq_init_owc_cd.argtypes = [vp, vp, i64, i64, i32, i64, i32, i64, vp, vp, vp, vp, vp, vp, i64, i32, vp, sz, vp]
         L.cdq_init_owc_cd.restype = i32
-        L.cdq_bcd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i32, vp, i64, vp, vp, vp, i64, vp, sz, vp]
+        L.cdq_bcd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i32, vp, i64, vp, vp, vp, i64, i32, vp, sz, vp]
         L.cdq_bcd.restype = i32
         L.cdq_probe_copy.argtypes = [vp, vp, sz, vp]
         L.cdq_probe_read.argtypes = [vp, sz, vp, vp]
@@ -175,7 +175,7 @@ def init_owc_cd(H, Wt, bits: int, group: int, n_gamma: int = 50, T: int | None =
 
 
 def bcd(H, Wt, scale, zero, Q, bits: int, group: int, parts: torch.Tensor, k: int = 2, trace_cap: int = 0, want_G: bool = False,
-        workspace: torch.Tensor | None = None):
+        score_all: bool = False, workspace: torch.Tensor | None = None):
     """Block coordinate descent with random blocks (Algorithm 2/5); Q is updated in place.  parts [T][d_in] int32 on
     the GPU.  Returns a dict: moves[, trace [d_out][trace_cap][4]][, G]."""
     d_out, d_in = Wt.shape
@@ -193,8 +193,8 @@ def bcd(H, Wt, scale, zero, Q, bits: int, group: int, parts: torch.Tensor, k: in
         g = out["G"].data_ptr()
     _check(lib().cdq_bcd(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), _dev(scale, torch.float32, "scale"),
                          _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, bits, group, k,
-                         parts.data_ptr() if T else None, T, out["moves"].data_ptr(), g, tr, trace_cap, ws.data_ptr(), ws.numel(),
-                         _stream()), "cdq_bcd")
+                         parts.data_ptr() if T else None, T, out["moves"].data_ptr(), g, tr, trace_cap, int(score_all),
+                         ws.data_ptr(), ws.numel(), _stream()), "cdq_bcd")
     return out
 
 

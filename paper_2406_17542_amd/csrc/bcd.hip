@@ -45,12 +45,21 @@ __global__ __launch_bounds__(256) void bcd_check_parts_kernel(const int32_t* __r
     }
 }
 
+// A pair can be left out of the scoring when no move of it can have a negative score.  With
+// rho = |H_ik| / sqrt(H_ii H_kk):  2 H_ik di dk >= -rho (H_ii di^2 + H_kk dk^2), so
+//   s >= (1-rho)(H_ii di^2 + H_kk dk^2) - |2 g_i| |di| - |2 g_k| |dk|,
+// and a nonzero step is at least one grid step a, so |2 g| |d| <= (|2 g| / a) d^2.  If
+// |2 g_i| <= (1 - rho - tau) H_ii a_i and the same for k, every move has s >= tau (H_ii di^2 + H_kk dk^2) > 0
+// in exact arithmetic; the fp32 evaluation differs from that by a few 1e-7 of the same magnitude, far
+// inside tau = 2^-10.  Near a coordinate-wise optimum (the start the paper uses) this removes most pairs.
+constexpr float kBcdTau = 1.0f / 1024.0f;
+
 template <int BITS>
 __global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H, const float* __restrict__ hdiag,
                                                     const float* __restrict__ G0, const float* __restrict__ scale,
                                                     uint8_t* __restrict__ Q, const int32_t* __restrict__ parts,
                                                     const float* __restrict__ pair_h2, const int32_t* __restrict__ bad_parts,
-                                                    int d_in, int group, int T, int32_t* __restrict__ moves_out,
+                                                    int d_in, int group, int T, int score_all, int32_t* __restrict__ moves_out,
                                                     float* __restrict__ G_out, int32_t* __restrict__ trace, int trace_cap) {
     constexpr int L = 1 << BITS;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -59,10 +68,12 @@ __global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H,
     const int64_t j = blockIdx.x;
     float* g2 = reinterpret_cast<float*>(smem);                  // [d_in]  2 g
     float* hd = g2 + d_in;                                       // [d_in]
-    float* a = hd + d_in;                                        // [n_grp]
+    int4* queue = reinterpret_cast<int4*>(hd + d_in);            // [n_pairs] pairs to score: p, i, k, bits of 2 H_ik
+    float* a = reinterpret_cast<float*>(queue + n_pairs);        // [n_grp]
     uint64_t* slots = reinterpret_cast<uint64_t*>(a + ((n_grp + 1) & ~1));   // [2][16] per-wavefront minima, double-buffered
     float* commit = reinterpret_cast<float*>(slots + 32);        // [2][4]: i, k (as int bits), 2 delta_i, 2 delta_k
-    uint8_t* q = reinterpret_cast<uint8_t*>(commit + 8);         // [d_in]
+    int* q_count = reinterpret_cast<int*>(commit + 8);           // [2]
+    uint8_t* q = reinterpret_cast<uint8_t*>(q_count + 2);        // [d_in]
 
     if (*bad_parts != 0) {                                       // invalid partitions: leave the column untouched
         if (tid == 0 && moves_out != nullptr) moves_out[j] = -1;
@@ -74,6 +85,7 @@ __global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H,
         q[c] = Q[j * (int64_t)d_in + c];
     }
     for (int i = tid; i < n_grp; i += nt) a[i] = scale[j * n_grp + i];
+    if (tid < 2) q_count[tid] = 0;
 
     int2 nxt_idx[BCD_PPT];
     float nxt_h2[BCD_PPT];
@@ -90,71 +102,102 @@ __global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H,
     prefetch(0);
     __syncthreads();
 
-    int moves = 0;
-    for (int t = 0; t < T; ++t) {
-        int2 idx[BCD_PPT];
-        float h2[BCD_PPT];
+    // all L*L level pairs of one pair of coordinates; TRACK also returns which one attains the minimum first
+    auto score_pair = [&](int i, int k, float h2, bool track, uint32_t& code, float& out_di, float& out_dk) -> float {
+        const float ai = a[i / group], ak = a[k / group];
+        const float gi = g2[i], gk = g2[k], hii = hd[i], hkk = hd[k];
+        const int qi = q[i], qk = q[k];
+        float dk[L], sk[L];
 #pragma unroll
-        for (int pp = 0; pp < BCD_PPT; ++pp) { idx[pp] = nxt_idx[pp]; h2[pp] = nxt_h2[pp]; }
-        prefetch(t + 1);
-
-        float best_s = 0.0f;
-        uint32_t best_code = 0xffffffffu;
-        float best_di = 0.0f, best_dk = 0.0f;
-        int best_pp = 0;
+        for (int r = 0; r < L; ++r) {
+            dk[r] = ak * (float)(r - qk);
+            sk[r] = dk[r] * fmaf(dk[r], hkk, gk);
+        }
+        float best = 0.0f;
+        if (!track) {
 #pragma unroll
-        for (int pp = 0; pp < BCD_PPT; ++pp) {
-            const int p = tid + pp * nt;
-            if (p < n_pairs) {
-                const int i = idx[pp].x, k = idx[pp].y;
-                const float ai = a[i / group], ak = a[k / group];
-                const float gi = g2[i], gk = g2[k], hii = hd[i], hkk = hd[k];
-                const int qi = q[i], qk = q[k];
-                float dk[L], sk[L];
+            for (int ri = 0; ri < L; ++ri) {
+                const float di = ai * (float)(ri - qi);
+                const float si = di * fmaf(di, hii, gi);
 #pragma unroll
-                for (int r = 0; r < L; ++r) {
-                    dk[r] = ak * (float)(r - qk);
-                    sk[r] = dk[r] * fmaf(dk[r], hkk, gk);
-                }
+                for (int rk = 0; rk < L; ++rk) best = fminf(best, fmaf(di * dk[rk], h2, si + sk[rk]));
+            }
+        } else {
 #pragma unroll
-                for (int ri = 0; ri < L; ++ri) {
-                    const float di = ai * (float)(ri - qi);
-                    const float si = di * fmaf(di, hii, gi);
+            for (int ri = 0; ri < L; ++ri) {
+                const float di = ai * (float)(ri - qi);
+                const float si = di * fmaf(di, hii, gi);
 #pragma unroll
-                    for (int rk = 0; rk < L; ++rk) {
-                        const float s = fmaf(di * dk[rk], h2[pp], si + sk[rk]);
-                        if (s < best_s) {            // pairs, r_i, r_k all ascend: the first strict minimum is kept
-                            best_s = s;
-                            best_code = ((uint32_t)p << 8) | (uint32_t)(ri << 4) | (uint32_t)rk;
-                            best_di = di; best_dk = dk[rk]; best_pp = pp;
-                        }
-                    }
+                for (int rk = 0; rk < L; ++rk) {
+                    const float s = fmaf(di * dk[rk], h2, si + sk[rk]);
+                    if (s < best) { best = s; code = (uint32_t)(ri << 4) | (uint32_t)rk; out_di = di; out_dk = dk[rk]; }
                 }
             }
         }
-        // ---- workgroup minimum of (ordered score, code)
-        const uint64_t wkey = wave_min_key(order_bits(best_s), best_code);
+        return best;
+    };
+
+    int moves = 0;
+    for (int t = 0; t < T; ++t) {
+        int* cnt = q_count + (t & 1);
+        // ---- which pairs need scoring
+#pragma unroll
+        for (int pp = 0; pp < BCD_PPT; ++pp) {
+            const int p = tid + pp * nt;
+            bool need = false;
+            int i = 0, k = 0;
+            float h2 = 0.0f;
+            if (p < n_pairs) {
+                i = nxt_idx[pp].x; k = nxt_idx[pp].y; h2 = nxt_h2[pp];
+                const float hii = hd[i], hkk = hd[k];
+                const float thr = 1.0f - (0.5f * fabsf(h2) * __frsqrt_rn(hii)) * __frsqrt_rn(hkk) - kBcdTau;
+                const bool quiet = hii > 0.0f && hkk > 0.0f && fabsf(g2[i]) <= thr * hii * a[i / group] &&
+                                   fabsf(g2[k]) <= thr * hkk * a[k / group];
+                need = score_all || !quiet;          // NaN or non-positive thr make `quiet` false
+            }
+            const unsigned long long m = __ballot(need);
+            if (m) {
+                int base = 0;
+                if (lane == __builtin_ctzll(m)) base = atomicAdd(cnt, __builtin_popcountll(m));
+                base = __builtin_amdgcn_readlane(base, __builtin_ctzll(m));
+                if (need) queue[base + __builtin_popcountll(m & ((1ull << lane) - 1ull))] = make_int4(p, i, k, __float_as_int(h2));
+            }
+        }
+        prefetch(t + 1);
+        __syncthreads();
+        // ---- score the queued pairs: minimum of (score, pair index)
+        const int n_q = *cnt;
+        float best_s = 0.0f;
+        int best_x = -1;
+        uint32_t best_p = 0xffffffffu;
+        for (int x = tid; x < n_q; x += nt) {
+            const int4 e = queue[x];
+            uint32_t dummy_c; float d0, d1;
+            const float s = score_pair(e.y, e.z, __int_as_float(e.w), false, dummy_c, d0, d1);
+            if (s < best_s || (s == best_s && s < 0.0f && (uint32_t)e.x < best_p)) { best_s = s; best_x = x; best_p = (uint32_t)e.x; }
+        }
+        const uint64_t wkey = wave_min_key(order_bits(best_s), best_p);
         uint64_t* slot = slots + (t & 1) * 16;
         if (lane == 0) slot[wave] = wkey;
+        if (tid == 0) q_count[(t + 1) & 1] = 0;
         __syncthreads();
         uint64_t key = slot[0];
         for (int w = 1; w < n_waves; ++w) key = umin64(key, slot[w]);
         if ((uint32_t)(key >> 32) >= kOrderedZero) continue;          // no pair lowers the loss under this partition
         float* cm = commit + (t & 1) * 4;
-        if (best_code == (uint32_t)key && order_bits(best_s) == (uint32_t)(key >> 32)) {      // exactly one thread
-            int bi = 0, bk = 0;
-#pragma unroll
-            for (int pp = 0; pp < BCD_PPT; ++pp)
-                if (pp == best_pp) { bi = idx[pp].x; bk = idx[pp].y; }
-            cm[0] = __int_as_float(bi); cm[1] = __int_as_float(bk);
-            cm[2] = 2.0f * best_di; cm[3] = 2.0f * best_dk;
-            q[bi] = (uint8_t)((best_code >> 4) & 15u);
-            q[bk] = (uint8_t)(best_code & 15u);
+        if (best_p == (uint32_t)key && order_bits(best_s) == (uint32_t)(key >> 32)) {      // exactly one thread: find the levels
+            const int4 e = queue[best_x];
+            uint32_t code = 0; float bdi = 0.0f, bdk = 0.0f;
+            const float s = score_pair(e.y, e.z, __int_as_float(e.w), true, code, bdi, bdk);
+            cm[0] = __int_as_float(e.y); cm[1] = __int_as_float(e.z);
+            cm[2] = 2.0f * bdi; cm[3] = 2.0f * bdk;
+            q[e.y] = (uint8_t)(code >> 4);
+            q[e.z] = (uint8_t)(code & 15u);
             if (trace != nullptr && moves < trace_cap) {
                 int32_t* tr = trace + (j * trace_cap + moves) * 4;
-                tr[0] = t; tr[1] = (int32_t)(best_code >> 8);
-                tr[2] = (int32_t)(((best_code >> 4) & 15u) | ((best_code & 15u) << 4));
-                tr[3] = __float_as_int(best_s);
+                tr[0] = t; tr[1] = e.x;
+                tr[2] = (int32_t)((code >> 4) | ((code & 15u) << 4));
+                tr[3] = __float_as_int(s);
             }
         }
         ++moves;
@@ -185,7 +228,8 @@ __global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H,
 
 size_t bcd_lds_bytes(int64_t d_in, int64_t group) {
     const int64_t n_grp = d_in / group;
-    return cdq_align_up(sizeof(float) * (2 * d_in + ((n_grp + 1) & ~(int64_t)1)) + sizeof(uint64_t) * 32 + sizeof(float) * 8 + (size_t)d_in, 16);
+    return cdq_align_up(sizeof(float) * (2 * d_in + ((n_grp + 1) & ~(int64_t)1)) + 16 * (size_t)(d_in / 2) + sizeof(uint64_t) * 32 + sizeof(float) * 8 +
+                        sizeof(int) * 2 + (size_t)d_in, 16);
 }
 
 }  // namespace
@@ -198,7 +242,7 @@ size_t bcd_workspace_bytes(int64_t d_out, int64_t d_in, int64_t T) {
 
 int bcd_launch(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out, int64_t d_in,
                int bits, int64_t group, const int32_t* parts, int64_t T, int32_t* moves, float* G_out, int32_t* trace,
-               int64_t trace_cap, void* ws, size_t ws_bytes, hipStream_t st) {
+               int64_t trace_cap, bool score_all, void* ws, size_t ws_bytes, hipStream_t st) {
     if (d_out == 0 || T == 0) {
         if (T == 0 && d_out > 0 && moves != nullptr) {
             hipLaunchKernelGGL(bcd_fill_i32_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, moves, d_out, 0);
@@ -236,7 +280,7 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
                                 (int)lds) != hipSuccess)                                                                         \
             return CDQ_EHIP;                                                                                                     \
         hipLaunchKernelGGL((bcd2_kernel<B>), dim3((unsigned)d_out), dim3(nt), lds, st, H, (const float*)hdiag, (const float*)G0, \
-                           scale, Q, parts, (const float*)pair_h2, (const int32_t*)bad, (int)d_in, (int)group, (int)T, moves,    \
+                           scale, Q, parts, (const float*)pair_h2, (const int32_t*)bad, (int)d_in, (int)group, (int)T, score_all ? 1 : 0, moves, \
                            G_out, trace, (int)(trace_cap > 0x7fffffffLL ? 0x7fffffffLL : trace_cap));                            \
         break;
     switch (bits) {

@@ -214,3 +214,43 @@ def test_mlp_up_owc_cd_init(cdq, oracle):
     eq = (Q.cpu().numpy()[cols][same] == refcd["Q"]).mean()
     say(f"  layer loss after CD {float(l_cd.sum()):.6e}; codes equal on {eq:.6f} of sampled entries")
     assert eq >= 0.999
+
+
+def test_attn_proj_bcd_after_cd(cdq, oracle):
+    """Algorithm 2 (k = 2) at the benchmark layer's shape, started from greedy CD's result as in Section 4, T = d_in
+    with d_in random partitions: whole layer on the GPU, 24 sampled columns through the oracle (codes and move counts
+    equal), loss never above CD's."""
+    cfg = inputs.CONFIGS["attn_proj"]
+    say(f"{cfg.name}: generating X and Wt")
+    X, Wt = inputs.make_layer(cfg)
+    Hd = cdq.hessian(x_to_dev(X, cfg.x_dtype))
+    H32 = Hd.cpu().numpy()
+    del X
+    Wd = torch.from_numpy(Wt).cuda()
+    scale, zero, Q = cdq.init_rtn(Wd, cfg.bits, cfg.group)
+    cdq.greedy_cd(Hd, Wd, scale, zero, Q, cfg.bits, cfg.group, cfg.T)
+    q_cd = Q.cpu().numpy().copy()
+    l_cd = cdq.loss(Hd, Wd, scale, zero, Q, cfg.group)[0].cpu().numpy()
+    T = cfg.d_in
+    parts = inputs.make_partitions(T, cfg.d_in, seed=cfg.seed)
+    pd = torch.from_numpy(parts).cuda()
+    say(f"BCD on the GPU, T={T}")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    out = cdq.bcd(Hd, Wd, scale, zero, Q, cfg.bits, cfg.group, pd)
+    torch.cuda.synchronize()
+    moves = out["moves"].cpu().numpy()
+    say(f"  {1e3 * (time.perf_counter() - t0):.1f} ms, {int(moves.sum())} block moves (max {moves.max()} per column)")
+    l_bcd = cdq.loss(Hd, Wd, scale, zero, Q, cfg.group)[0].cpu().numpy()
+    assert (moves >= 0).all()
+    assert np.all(l_bcd <= l_cd * (1 + 1e-9))
+    say(f"  layer loss CD {l_cd.sum():.6e} -> BCD {l_bcd.sum():.6e}")
+    assert l_bcd.sum() < l_cd.sum()
+    cols = np.sort(np.random.default_rng(3).choice(cfg.d_out, size=24, replace=False))
+    say(f"oracle BCD on {len(cols)} sampled columns")
+    a, b = scale.cpu().numpy(), zero.cpu().numpy()
+    ref = oracle.bcd(H32, Wt[cols], a[cols], b[cols], q_cd[cols], parts, cfg.bits, cfg.group, k=2)
+    eq = (Q.cpu().numpy()[cols] == ref["Q"])
+    say(f"  codes equal on {eq.mean():.6f} of sampled entries")
+    assert eq.all()
+    assert np.array_equal(moves[cols], ref["moves"])
