@@ -549,3 +549,45 @@ def test_empty_layer(cdq):
     out = cdq.greedy_cd(H, Wt, s, z, Q, 3, 8, 4)
     per, tot = cdq.loss(H, Wt, s, z, Q, 8)
     assert per.numel() == 0 and tot.item() == 0.0
+
+
+# ----------------------------------------------------------------------------- streaming layer driver
+
+@pytest.mark.parametrize("init,bits,group,with_bcd", [("rtn", 3, 256, True), ("owc", 4, 256, False), ("owc_cd", 2, 64, False)])
+def test_layer_driver_streams_chunks_and_matches_oracle(cdq, oracle, init, bits, group, with_bcd):
+    """quantize_layer over ragged token chunks: the accumulated, damped H matches the fp64 oracle on all tokens; with that H
+    the oracle reproduces the start, the CD codes and (when asked) the BCD codes; the reported losses are the oracle's."""
+    from paper_2406_17542_amd import layer
+    d_in, d_out, n = 256, 40, 2000
+    X = inputs.make_x("student_t4", n, d_in, seed=4, x_dtype="bf16")
+    Wt = inputs.make_wt(d_out, d_in, 5)
+    Wt[:, ::37] *= 3.0
+    Xd = x_to_dev(X, "bf16")
+    cuts = [0, 512, 1300, 1301, n]
+    chunks = [Xd[a:b].contiguous() for a, b in zip(cuts[:-1], cuts[1:])]
+    parts = inputs.make_partitions(48, d_in, seed=6)
+    r = layer.quantize_layer(iter(chunks), dev(Wt), bits, group, T=d_in, init=init, lambda_rel=0.01,
+                             bcd_parts=dev(parts) if with_bcd else None)
+    assert r["n_tokens"] == n
+    H = r["H"].cpu().numpy()
+    ok, worst, fro = hessian_tolerance_ok(H, oracle.hessian(X, lambda_rel=0.01), n)
+    assert ok and fro <= 1e-5, (worst, fro)
+    if init == "rtn":
+        a, b, q0 = oracle.init_grid(Wt, bits, group)
+    elif init == "owc":
+        a, b, q0, _, _ = oracle.init_owc(H, Wt, bits, group, 50)
+    else:
+        o = oracle.owc_cd(H, Wt, bits, group, 50)
+        a, b, q0 = o["scale"], o["zero"], o["Q"]
+    assert np.array_equal(r["scale"].cpu().numpy(), a) and np.array_equal(r["zero"].cpu().numpy(), b)
+    np.testing.assert_allclose(r["loss_init"], oracle.loss(H, Wt, q0, a, b, group).sum(), rtol=1e-6)
+    ref = oracle.greedy_cd(H, Wt, a, b, q0, bits, group, d_in)
+    np.testing.assert_allclose(r["loss_cd"], oracle.loss(H, Wt, ref["Q"], a, b, group).sum(), rtol=1e-6)
+    q_ref = ref["Q"]
+    if with_bcd:
+        q_ref = oracle.bcd(H, Wt, a, b, ref["Q"], parts, bits, group, k=2)["Q"]
+        np.testing.assert_allclose(r["loss_bcd"], oracle.loss(H, Wt, q_ref, a, b, group).sum(), rtol=1e-6)
+        assert r["loss_bcd"] <= r["loss_cd"]
+    assert (r["Q"].cpu().numpy() == q_ref).mean() >= 0.999
+    assert r["loss_cd"] <= r["loss_init"]
+    assert set(r["seconds"]) >= {"hessian", "init", "cd", "loss"}
