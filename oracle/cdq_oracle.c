@@ -455,3 +455,58 @@ void cdqo_bcd_f32(const float *H, const float *scale, uint8_t *Q, float *G, cons
         moves[j] = n_moves;
     }
 }
+
+/* ---- cyclic coordinate descent (the fixed-order variant the paper contrasts greedy CD with:
+ * Section 1 and the appendix comparison with QuantEase) ----
+ *
+ * Same single-coordinate move and the same canonical fp32 arithmetic as greedy CD, but the
+ * coordinate is not chosen by an arg-min over all of them: visit t looks at coordinate
+ * i = t mod d_in only, scores every level r (delta = a (r - q_i), s = delta * fmaf(delta, H_ii, 2 g_i)),
+ * and commits the first strict minimum if it is negative (g <- g + delta H[i, :]).  T counts visits
+ * (d_in visits = one epoch).  The column stops early once d_in consecutive visits made no move:
+ * it is then at a coordinate-wise optimum.  iters[j] = visits performed.
+ */
+void cdqo_cyclic_cd_f32(const float *H, const float *scale, uint8_t *Q, float *G,
+                        int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T,
+                        int32_t *moves, int32_t *iters, int32_t *converged,
+                        int32_t *trace_i, int32_t *trace_r, float *trace_s, int64_t trace_cap)
+{
+    const int L = 1 << bits;
+    const int64_t n_grp = d_in / group;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t j = 0; j < d_out; ++j) {
+        const float *a = scale + j * n_grp;
+        uint8_t *q = Q + j * d_in;
+        float *g = G + j * d_in;
+        int32_t n_moves = 0, done = 0;
+        int64_t idle = 0, t = 0;
+        for (; t < T; ++t) {
+            if (idle == d_in) { done = 1; break; }
+            const int64_t i = t % d_in;
+            const float ai = a[i / group], hii = H[i * d_in + i], two_g = 2.0f * g[i];
+            float best_s = 0.0f;
+            int best_r = -1;
+            for (int r = 0; r < L; ++r) {
+                const float delta = ai * (float)(r - (int)q[i]);
+                const float s = delta * fmaf(delta, hii, two_g);
+                if (s < best_s) { best_s = s; best_r = r; }
+            }
+            if (best_r < 0) { ++idle; continue; }
+            idle = 0;
+            const float delta = ai * (float)(best_r - (int)q[i]);
+            const float *hrow = H + i * d_in;
+            for (int64_t k = 0; k < d_in; ++k) g[k] = fmaf(delta, hrow[k], g[k]);
+            q[i] = (uint8_t)best_r;
+            if (n_moves < trace_cap) {
+                trace_i[j * trace_cap + n_moves] = (int32_t)i;
+                trace_r[j * trace_cap + n_moves] = best_r;
+                trace_s[j * trace_cap + n_moves] = best_s;
+            }
+            ++n_moves;
+        }
+        if (!done && idle == d_in) done = 1;
+        moves[j] = n_moves;
+        iters[j] = (int32_t)t;
+        converged[j] = done;
+    }
+}

@@ -198,6 +198,30 @@ def argmin_step(Hdiag, scale, Q, G, bits: int, group: int):
     return oi, orr, os_
 
 
+def cyclic_cd(H, Wt, scale, zero, Q0, bits: int, group: int, T: int, trace_cap: int = 0):
+    """Cyclic (fixed-order) coordinate descent in canonical fp32: visit t handles coordinate t mod d_in; T visits at
+    most; stops once d_in consecutive visits made no move.  Returns Q, moves, iters, converged, G[, trace_*]."""
+    lib = _load()
+    Q = np.ascontiguousarray(Q0, np.uint8).copy()
+    d_out, d_in = Q.shape
+    assert d_in % group == 0
+    H = np.ascontiguousarray(H, np.float32)
+    scale = np.ascontiguousarray(scale, np.float32)
+    E = residual(Wt, Q, scale, zero, group, "f32")
+    G = gradient(H, E, "f32")
+    moves, iters, conv = (np.zeros(d_out, np.int32) for _ in range(3))
+    cap = max(int(trace_cap), 0)
+    ti = np.full((d_out, max(cap, 1)), -1, np.int32)
+    tr = np.full((d_out, max(cap, 1)), -1, np.int32)
+    ts = np.zeros((d_out, max(cap, 1)), np.float32)
+    lib.cdqo_cyclic_cd_f32(_p(H), _p(scale), _p(Q), _p(G), _I64(d_out), _I64(d_in), ctypes.c_int(bits), _I64(group), _I64(T),
+                           _p(moves), _p(iters), _p(conv), _p(ti), _p(tr), _p(ts), _I64(cap))
+    out = {"Q": Q, "moves": moves, "iters": iters, "converged": conv, "G": G}
+    if cap:
+        out.update(trace_i=ti, trace_r=tr, trace_s=ts)
+    return out
+
+
 def bcd(H, Wt, scale, zero, Q0, parts, bits: int, group: int, k: int = 2, trace_cap: int = 0):
     """Algorithm 2 (Algorithm 5 when group < d_in) in canonical fp32 for every column, block size k.
     parts [T][d_in] int32: row t is the random partition of iteration t, block b = parts[t, k*b : k*b+k].

@@ -627,3 +627,76 @@ def test_bcd_matches_paper_form(oracle, group):
                zip(out["trace_t"][j], out["trace_b"][j], out["trace_r"][j]) if t >= 0]
         assert got == [(t, bk, r) for t, bk, r, _ in mv], j
         assert np.array_equal(qT, out["Q"][j])
+
+
+# ----------------------------------------------------------------------------- cyclic CD
+
+def test_cyclic_cd_moves_are_exact_coordinate_minimisations(oracle):
+    """Each visit of the fixed-order variant sets its coordinate to the level that minimises Eq. (1) with the others
+    fixed (brute force over the levels from X), the committed score is that loss change, visits come in cyclic
+    order, and a converged column is a coordinate-wise optimum."""
+    d_in, d_out, n, bits, group = 12, 4, 60, 3, 4
+    X, Wt, H32 = _bcd_case(40, d_in, d_out, n, bits, group)
+    a, b, _ = oracle.init_grid(Wt, bits, group)
+    q0 = inputs.make_random_codes(d_out, d_in, bits, seed=8)
+    T = 10 * d_in
+    out = oracle.cyclic_cd(H32, Wt, a, b, q0, bits, group, T, trace_cap=T)
+    H64 = H32.astype(np.float64)
+
+    def loss(j, q):
+        e = np.repeat(a[j].astype(np.float64), group) * q + np.repeat(b[j].astype(np.float64), group) - Wt[j]
+        return float(e @ H64 @ e)
+
+    assert out["converged"].all() and out["moves"].sum() > 2 * d_out
+    for j in range(d_out):
+        q = q0[j].astype(np.float64)
+        m = 0
+        for t in range(out["iters"][j]):
+            i = t % d_in
+            cand = []
+            for lev in range(1 << bits):
+                alt = q.copy(); alt[i] = lev
+                cand.append(loss(j, alt))
+            best = int(np.argmin(cand))
+            moved = m < out["moves"][j] and out["trace_i"][j, m] == i and cand[best] < loss(j, q) * (1 - 1e-7) - 1e-12
+            if moved:
+                assert out["trace_r"][j, m] == best or abs(cand[out["trace_r"][j, m]] - cand[best]) <= 1e-6 * abs(cand[best])
+                now = cand[out["trace_r"][j, m]]
+                assert abs((now - loss(j, q)) - out["trace_s"][j, m]) <= 2e-4 * max(loss(j, q), 1e-9)
+                q[i] = out["trace_r"][j, m]
+                m += 1
+            else:
+                assert cand[best] >= loss(j, q) * (1 - 1e-5)       # no level of this coordinate does better
+        assert m == out["moves"][j]
+        assert np.array_equal(q.astype(np.uint8), out["Q"][j])
+        assert out["iters"][j] <= T
+
+
+def test_cyclic_cd_diagonal_hessian_lands_on_rtn_in_one_epoch(oracle):
+    """With a diagonal H the coordinates do not interact: one epoch puts every coordinate on its nearest level
+    (the MinMax/RTN code), the second epoch finds nothing, so the column stops after exactly 2 d_in visits at most."""
+    d_in, d_out, bits = 16, 5, 3
+    rng = np.random.default_rng(2)
+    Wt = (rng.standard_normal((d_out, d_in)) / 4).astype(np.float32)
+    H32 = np.diag(rng.uniform(0.5, 2.0, d_in)).astype(np.float32)
+    a, b, q_rtn = oracle.init_grid(Wt, bits, d_in)
+    q0 = inputs.make_random_codes(d_out, d_in, bits, seed=9)
+    out = oracle.cyclic_cd(H32, Wt, a, b, q0, bits, d_in, 5 * d_in, trace_cap=d_in)
+    assert np.array_equal(out["Q"], q_rtn)
+    assert out["converged"].all() and (out["iters"] <= 2 * d_in).all()
+    assert np.array_equal(out["moves"], (q0 != q_rtn).sum(axis=1))
+
+
+def test_cyclic_cd_budget_and_resume(oracle):
+    """T visits are a prefix of the longer run: stopping after T1 visits and resuming at coordinate T1 mod d_in is
+    only possible when T1 is a multiple of d_in (the order restarts at 0); then the result equals one run of T1+T2."""
+    d_in, d_out, n, bits, group = 16, 3, 80, 2, 16
+    X, Wt, H32 = _bcd_case(41, d_in, d_out, n, bits, group)
+    a, b, _ = oracle.init_grid(Wt, bits, group)
+    q0 = inputs.make_random_codes(d_out, d_in, bits, seed=10)
+    one = oracle.cyclic_cd(H32, Wt, a, b, q0, bits, group, 3 * d_in)
+    first = oracle.cyclic_cd(H32, Wt, a, b, q0, bits, group, d_in)
+    assert (first["iters"] == d_in).all()
+    second = oracle.cyclic_cd(H32, Wt, a, b, first["Q"], bits, group, 2 * d_in)
+    assert np.array_equal(second["Q"], one["Q"])
+    assert np.array_equal(first["moves"] + second["moves"], one["moves"])
