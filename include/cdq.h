@@ -49,6 +49,7 @@ extern "C" {
 #define CDQ_OP_INIT_OWC  3
 #define CDQ_OP_INIT_OWC_CD 4
 #define CDQ_OP_BCD       5   /* n = T, the number of iterations */
+#define CDQ_OP_CYCLIC_CD 6
 
 #define CDQ_MAX_D_IN 32768      /* largest d_in the register-resident CD kernel covers */
 
@@ -171,6 +172,22 @@ int cdq_bcd(const float *H, const float *Wt, const float *scale, const float *ze
             int64_t d_out, int64_t d_in, int bits, int64_t group, int k, const int32_t *parts, int64_t T,
             int32_t *moves, float *G_out, int32_t *trace, int64_t trace_cap, int score_all,
             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Cyclic (fixed-order) coordinate descent: the variant without an arg-min over coordinates that the
+ * paper contrasts greedy CD with (Section 1; appendix comparison with QuantEase).  Visit t handles
+ * coordinate t mod d_in: all levels are scored with the single-coordinate score of Algorithm 1,
+ * s = delta*fma(delta, H_ii, 2 g_i), delta = a (r - q_i), and the first strict minimum is
+ * committed if negative.  T counts visits (one epoch = d_in visits); a column stops once d_in
+ * consecutive visits made no move (stats.converged = 1); stats.iters = visits performed.
+ *   Q in/out; stats NULL or [d_out]; G_out NULL or [d_out][d_in]; trace NULL or
+ *   [d_out][trace_cap] int32: move m is stored as (i << 7) | r.
+ * Needs d_in % 4 == 0, 16-byte aligned H, 9*d_in bytes of LDS; workspace of CDQ_OP_CYCLIC_CD size.
+ */
+int cdq_cyclic_cd(const float *H, const float *Wt, const float *scale, const float *zero, uint8_t *Q,
+                  int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T,
+                  cdq_col_stats *stats, float *G_out, int32_t *trace, int64_t trace_cap,
+                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Gradient initialisation of Algorithm 1 ("Compute gradient g at q0"), in weight space:

@@ -13,7 +13,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcdq.so")
 
 CDQ_F32, CDQ_BF16 = 0, 1
-OP_HESSIAN, OP_GREEDY_CD, OP_LOSS, OP_INIT_OWC, OP_INIT_OWC_CD, OP_BCD = 0, 1, 2, 3, 4, 5
+OP_HESSIAN, OP_GREEDY_CD, OP_LOSS, OP_INIT_OWC, OP_INIT_OWC_CD, OP_BCD, OP_CYCLIC_CD = 0, 1, 2, 3, 4, 5, 6
 MAX_D_IN = 32768
 
 _lib = None
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.cdq_init_owc_cd.restype = i32
         L.cdq_bcd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i32, vp, i64, vp, vp, vp, i64, i32, vp, sz, vp]
         L.cdq_bcd.restype = i32
+        L.cdq_cyclic_cd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, vp, i64, vp, sz, vp]
+        L.cdq_cyclic_cd.restype = i32
         L.cdq_probe_copy.argtypes = [vp, vp, sz, vp]
         L.cdq_probe_read.argtypes = [vp, sz, vp, vp]
         L.cdq_probe_gather.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
@@ -195,6 +197,26 @@ def bcd(H, Wt, scale, zero, Q, bits: int, group: int, parts: torch.Tensor, k: in
                          _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, bits, group, k,
                          parts.data_ptr() if T else None, T, out["moves"].data_ptr(), g, tr, trace_cap, int(score_all),
                          ws.data_ptr(), ws.numel(), _stream()), "cdq_bcd")
+    return out
+
+
+def cyclic_cd(H, Wt, scale, zero, Q, bits: int, group: int, T: int, trace_cap: int = 0, want_G: bool = False,
+              workspace: torch.Tensor | None = None):
+    """Cyclic coordinate descent in place on Q; T visits at most.  Returns a dict: stats (int32 [d_out][4] view:
+    moves, iters, converged, bits of the last score)[, trace][, G]."""
+    d_out, d_in = Wt.shape
+    ws = _workspace(OP_CYCLIC_CD, 0, d_out, d_in, workspace)
+    out = {"stats": torch.zeros((d_out, 4), dtype=torch.int32, device=Wt.device)}
+    tr = g = None
+    if trace_cap > 0:
+        out["trace"] = torch.full((d_out, trace_cap), -1, dtype=torch.int32, device=Wt.device)
+        tr = out["trace"].data_ptr()
+    if want_G:
+        out["G"] = torch.empty((d_out, d_in), dtype=torch.float32, device=Wt.device)
+        g = out["G"].data_ptr()
+    _check(lib().cdq_cyclic_cd(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), _dev(scale, torch.float32, "scale"),
+                               _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, bits, group, T,
+                               out["stats"].data_ptr(), g, tr, trace_cap, ws.data_ptr(), ws.numel(), _stream()), "cdq_cyclic_cd")
     return out
 
 

@@ -39,6 +39,7 @@ size_t cdq_workspace_bytes(int op, int64_t n, int64_t d_out, int64_t d_in) {
         case CDQ_OP_INIT_OWC: return cdq::owc_workspace_bytes(d_out, d_in);
         case CDQ_OP_INIT_OWC_CD: return cdq::owc_cd_workspace_bytes(d_out, d_in);
         case CDQ_OP_BCD: return cdq::bcd_workspace_bytes(d_out, d_in, n);
+        case CDQ_OP_CYCLIC_CD: return cdq::cyclic_workspace_bytes(d_out, d_in);
         default: return 0;
     }
 }
@@ -97,6 +98,17 @@ int cdq_bcd(const float* H, const float* Wt, const float* scale, const float* ze
     if (T > 0 && parts == nullptr) return CDQ_EINVAL;
     return cdq::bcd_launch(H, Wt, scale, zero, Q, d_out, d_in, bits, group, parts, T, moves, G_out, trace, trace_cap, score_all != 0,
                            workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int cdq_cyclic_cd(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out, int64_t d_in,
+                  int bits, int64_t group, int64_t T, cdq_col_stats* stats, float* G_out, int32_t* trace, int64_t trace_cap,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+    if (bad_bits(bits) || bad_layer(d_out, d_in, group) || T < 0) return CDQ_EINVAL;
+    if (trace != nullptr && trace_cap <= 0) return CDQ_EINVAL;
+    if (d_out == 0) return CDQ_OK;
+    if (H == nullptr || Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr) return CDQ_EINVAL;
+    return cdq::cyclic_launch(H, Wt, scale, zero, Q, d_out, d_in, bits, group, T, stats, G_out, trace, trace_cap, workspace,
+                              workspace_bytes, (hipStream_t)stream);
 }
 
 int cdq_gradient(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,

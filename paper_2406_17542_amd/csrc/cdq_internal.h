@@ -53,6 +53,12 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
                int bits, int64_t group, const int32_t* parts, int64_t T, int32_t* moves, float* G_out, int32_t* trace,
                int64_t trace_cap, bool score_all, void* ws, size_t ws_bytes, hipStream_t st);
 
+// ---- cyclic.hip
+size_t cyclic_workspace_bytes(int64_t d_out, int64_t d_in);
+int cyclic_launch(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out, int64_t d_in,
+                  int bits, int64_t group, int64_t T, cdq_col_stats* stats, float* G_out, int32_t* trace, int64_t trace_cap,
+                  void* ws, size_t ws_bytes, hipStream_t st);
+
 // ---- stepwise.hip
 int score_argmin_launch(const float* hdiag, const float* scale, const uint8_t* Q, const float* G, int64_t d_out, int64_t d_in,
                         int bits, int64_t group, int32_t* out_i, int32_t* out_r, float* out_s, hipStream_t st);

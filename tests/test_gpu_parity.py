@@ -591,3 +591,34 @@ def test_layer_driver_streams_chunks_and_matches_oracle(cdq, oracle, init, bits,
     assert (r["Q"].cpu().numpy() == q_ref).mean() >= 0.999
     assert r["loss_cd"] <= r["loss_init"]
     assert set(r["seconds"]) >= {"hessian", "init", "cd", "loss"}
+
+
+# ----------------------------------------------------------------------------- cyclic CD
+
+@pytest.mark.parametrize("d_out,d_in,n,bits,group,T,start", [
+    (20, 128, 400, 3, 128, 1280, "random"), (12, 520, 1200, 2, 40, 1500, "random"), (9, 64, 300, 4, 16, 64, "random"),
+    (16, 2048, 4096, 3, 2048, 6144, "rtn"), (7, 300, 700, 4, 300, 100, "rtn"), (5, 1024, 2000, 2, 128, 0, "rtn")])
+def test_cyclic_cd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start):
+    """Fixed-order CD: moves (coordinate, level), codes, visit counts, convergence flags and the maintained gradient
+    are bit-equal to the oracle's."""
+    X, Wt = rand_layer(50 + d_in + bits, d_in, d_out, n, corr=0.0 if d_in == 128 else 0.6)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q_rtn = oracle.init_grid(Wt, bits, group)
+    q0 = inputs.make_random_codes(d_out, d_in, bits, seed=d_in) if start == "random" else q_rtn
+    cap = max(T, 1)
+    ref = oracle.cyclic_cd(H32, Wt, a, b, q0, bits, group, T, trace_cap=cap)
+    Q = dev(q0)
+    out = cdq.cyclic_cd(dev(H32), dev(Wt), dev(a), dev(b), Q, bits, group, T, trace_cap=cap, want_G=True)
+    st = out["stats"].cpu().numpy()
+    assert np.array_equal(st[:, 0], ref["moves"])
+    assert np.array_equal(st[:, 1], ref["iters"])
+    assert np.array_equal(st[:, 2], ref["converged"])
+    assert np.array_equal(Q.cpu().numpy(), ref["Q"])
+    tr = out["trace"].cpu().numpy()
+    for j in range(d_out):
+        m = ref["moves"][j]
+        assert np.array_equal(tr[j, :m] >> 7, ref["trace_i"][j, :m])
+        assert np.array_equal(tr[j, :m] & 127, ref["trace_r"][j, :m])
+    assert np.array_equal(out["G"].cpu().numpy(), ref["G"])
+    if d_in == 128:
+        assert ref["converged"].any(), "ten epochs on the uncorrelated case should reach a coordinate-wise optimum"
