@@ -19,6 +19,7 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, BK = 32, LDP = 144;   // LDP % 32 == 16: the two k-rows read by lanes 0..31 hit disjoint banks
 constexpr int NT = 1024;
+constexpr size_t EH_LDS = 4 * sizeof(float) * BK * LDP + sizeof(double) * 4 * BM;
 
 // residual of 4 consecutive coordinates of one column (zero outside the matrix)
 template <bool VEC4>
@@ -57,9 +58,12 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
                                                      const uint8_t* __restrict__ Q, int64_t d_out, int64_t d_in,
                                                      int64_t group, float* __restrict__ G,
                                                      double* __restrict__ partial, int n_tiles, double* __restrict__ G64) {
-    __shared__ float As[BK][LDP];     // As[k][m] = E[m0+m][k0+k]
-    __shared__ float Bs[BK][LDP];     // Bs[k][n] = H[k0+k][n0+n]
-    __shared__ double red[4][BM];
+    // two stages of As[k][m] = E[m0+m][k0+k] and Bs[k][n] = H[k0+k][n0+n]: the next step's tiles are written
+    // while the current ones are multiplied, one barrier per step
+    extern __shared__ __attribute__((aligned(16))) char eh_smem[];
+    float (*As)[BK][LDP] = reinterpret_cast<float (*)[BK][LDP]>(eh_smem);
+    float (*Bs)[BK][LDP] = reinterpret_cast<float (*)[BK][LDP]>(eh_smem + 2 * sizeof(float) * BK * LDP);
+    double (*red)[BM] = reinterpret_cast<double (*)[BM]>(eh_smem + 4 * sizeof(float) * BK * LDP);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
@@ -90,22 +94,26 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
         }
     };
 
-    load_tiles(0);
-    for (int64_t k0 = 0; k0 < d_in; k0 += BK) {
-        __syncthreads();
+    auto store_tiles = [&](int st) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) As[a_k + e][a_row] = ra[e];
-        *reinterpret_cast<float4*>(&Bs[b_row][b_col]) = make_float4(rb[0], rb[1], rb[2], rb[3]);
-        __syncthreads();
-        if (k0 + BK < d_in) load_tiles(k0 + BK);
+        for (int e = 0; e < 4; ++e) As[st][a_k + e][a_row] = ra[e];
+        *reinterpret_cast<float4*>(&Bs[st][b_row][b_col]) = make_float4(rb[0], rb[1], rb[2], rb[3]);
+    };
+    load_tiles(0);
+    store_tiles(0);
+    __syncthreads();
+    int st = 0;
+    for (int64_t k0 = 0; k0 < d_in; k0 += BK) {
+        const bool more = k0 + BK < d_in;
+        if (more) load_tiles(k0 + BK);
 #pragma unroll
         for (int ks = 0; ks < BK; ks += 4) {
             double a[2], b[2];
             const int kk = ks + (lane >> 4), mn = lane & 15;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                a[i] = (double)As[kk][wm * 32 + i * 16 + mn];
-                b[i] = (double)Bs[kk][wn * 32 + i * 16 + mn];
+                a[i] = (double)As[st][kk][wm * 32 + i * 16 + mn];
+                b[i] = (double)Bs[st][kk][wn * 32 + i * 16 + mn];
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -113,6 +121,9 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
         }
+        if (more) store_tiles(st ^ 1);
+        __syncthreads();
+        st ^= 1;
     }
 
     // result layout of the 16x16 f64 block: lane l, element v  ->  row 4*v + l/16, column l%16
@@ -188,6 +199,13 @@ __global__ __launch_bounds__(1024) void loss_total_kernel(const double* __restri
     if (threadIdx.x == 0) total[0] = sh[0];
 }
 
+template <bool LOSS, bool VEC4>
+bool eh_allow_lds() {
+    static const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(eh_gemm_kernel<LOSS, VEC4>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)EH_LDS);
+    return rc == hipSuccess;
+}
+
 bool vec4_ok(const float* H, const float* Wt, const uint8_t* Q, int64_t d_in, int64_t group) {
     return d_in % 4 == 0 && group % 4 == 0 && ((uintptr_t)H & 15) == 0 && ((uintptr_t)Wt & 15) == 0 && ((uintptr_t)Q & 3) == 0;
 }
@@ -204,11 +222,12 @@ int gradient_launch(const float* H, const float* Wt, const float* scale, const f
     if (d_out == 0) return CDQ_OK;
     const int64_t gx = (d_in + BN - 1) / BN, gy = (d_out + BM - 1) / BM;
     if (gy > 65535) return CDQ_EUNSUPPORTED;
+    if (!eh_allow_lds<false, true>() || !eh_allow_lds<false, false>()) return CDQ_EHIP;
     if (vec4_ok(H, Wt, Q, d_in, group))
-        hipLaunchKernelGGL((eh_gemm_kernel<false, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
+        hipLaunchKernelGGL((eh_gemm_kernel<false, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
                            d_out, d_in, group, G, (double*)nullptr, (int)gx, G64);
     else
-        hipLaunchKernelGGL((eh_gemm_kernel<false, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
+        hipLaunchKernelGGL((eh_gemm_kernel<false, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
                            d_out, d_in, group, G, (double*)nullptr, (int)gx, G64);
     CDQ_LAUNCH_CHECK();
     return CDQ_OK;
@@ -230,11 +249,12 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
     double* partial = (double*)ws;
     double* rows_ws = (double*)((char*)ws + cdq_align_up((size_t)d_out * gx * sizeof(double), 256));
     double* rows = loss_per_col ? loss_per_col : rows_ws;
+    if (!eh_allow_lds<true, true>() || !eh_allow_lds<true, false>()) return CDQ_EHIP;
     if (vec4_ok(H, Wt, Q, d_in, group))
-        hipLaunchKernelGGL((eh_gemm_kernel<true, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
+        hipLaunchKernelGGL((eh_gemm_kernel<true, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
                            d_out, d_in, group, (float*)nullptr, partial, (int)gx, (double*)nullptr);
     else
-        hipLaunchKernelGGL((eh_gemm_kernel<true, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), 0, st, H, Wt, scale, zero, Q,
+        hipLaunchKernelGGL((eh_gemm_kernel<true, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
                            d_out, d_in, group, (float*)nullptr, partial, (int)gx, (double*)nullptr);
     CDQ_LAUNCH_CHECK();
     hipLaunchKernelGGL(loss_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, partial, d_out, (int)gx, rows);
