@@ -67,3 +67,35 @@ def test_argument_checks_need_no_gpu(L):
     assert L.cdq_loss(p, p, p, p, p, 4, 8, 8, n, n, p, 1 << 20, n) == EINVAL             # no output requested
     assert L.cdq_loss(p, p, p, p, p, 4, 8, 8, p, n, n, 0, n) == EWS
     assert L.cdq_gradient(p, p, p, p, p, 4, 8, 8, n, n) == EINVAL
+
+
+def test_argument_checks_of_the_wider_entry_points(L):
+    """OWC-CD, BCD and cyclic CD reject bad arguments on the host as well."""
+    from paper_2406_17542_amd import cdq
+    p = ctypes.c_void_p(0x1000)
+    n = ctypes.c_void_p(0)
+    EINVAL, EWS, EUNSUP = -1, -2, -4
+    i64 = ctypes.c_int64
+    # cdq_init_owc_cd(H, Wt, d_out, d_in, bits, group, n_gamma, T, scale, zero, Q, gamma_idx, moves, trace, trace_cap, variant, ws, ws_bytes, stream)
+    assert L.cdq_init_owc_cd(p, p, 4, 256, 3, 64, 0, 4, p, p, p, n, n, n, 0, 0, n, 0, n) == EINVAL       # empty grid
+    assert L.cdq_init_owc_cd(p, p, 4, 256, 3, 64, 50, -1, p, p, p, n, n, n, 0, 0, n, 0, n) == EINVAL     # T < 0
+    assert L.cdq_init_owc_cd(p, p, 4, 256, 3, 64, 50, 4, p, p, p, n, n, n, 0, 2, n, 0, n) == EINVAL      # unknown variant
+    assert L.cdq_init_owc_cd(p, p, 4, 256, 3, 64, 50, 4, p, p, p, n, n, p, 0, 0, n, 0, n) == EINVAL      # trace without capacity
+    assert L.cdq_init_owc_cd(p, p, 4, 256, 3, 64, 50, 4, n, p, p, n, n, n, 0, 0, n, 0, n) == EINVAL      # null scale
+    assert L.cdq_init_owc_cd(p, p, 4, 256, 3, 64, 50, 4, p, p, p, n, n, n, 0, 0, n, 0, n) == EWS         # tiled kernel needs G64
+    assert L.cdq_init_owc_cd(p, p, 4, 65536, 3, 128, 50, 4, p, p, p, n, n, n, 0, 1, n, 0, n) == EUNSUP   # state does not fit LDS
+    assert cdq.workspace_bytes(cdq.OP_INIT_OWC_CD, 0, 16, 256) >= 16 * 256 * 8
+    # cdq_bcd(H, Wt, scale, zero, Q, d_out, d_in, bits, group, k, parts, T, moves, G_out, trace, trace_cap, score_all, ws, ws_bytes, stream)
+    assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 0, p, 8, n, n, n, 0, 0, p, 1 << 30, n) == EINVAL     # k < 1
+    assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 3, p, 8, n, n, n, 0, 0, p, 1 << 30, n) == EUNSUP     # only pairs are built
+    assert L.cdq_bcd(p, p, p, p, p, 4, 255, 3, 255, 2, p, 8, n, n, n, 0, 0, p, 1 << 30, n) == EINVAL     # odd d_in
+    assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 2, n, 8, n, n, n, 0, 0, p, 1 << 30, n) == EINVAL     # no partitions
+    assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 2, p, 8, n, n, n, 0, 0, n, 0, n) == EWS
+    assert L.cdq_bcd(p, p, p, p, p, 4, 16384, 3, 16384, 2, p, 8, n, n, n, 0, 0, p, 1 << 40, n) == EUNSUP # more than 4 pairs per thread
+    assert cdq.workspace_bytes(cdq.OP_BCD, 8, 4, 256) >= 4 * 256 * 4 + 8 * 128 * 12
+    # cdq_cyclic_cd(H, Wt, scale, zero, Q, d_out, d_in, bits, group, T, stats, G_out, trace, trace_cap, ws, ws_bytes, stream)
+    assert L.cdq_cyclic_cd(p, p, p, p, p, 4, 256, 3, 256, i64(-1), n, n, n, 0, p, 1 << 30, n) == EINVAL
+    assert L.cdq_cyclic_cd(p, p, p, p, p, 4, 256, 7, 256, i64(8), n, n, n, 0, p, 1 << 30, n) == EINVAL   # bits
+    assert L.cdq_cyclic_cd(p, p, p, p, p, 4, 256, 3, 256, i64(8), n, n, n, 0, n, 0, n) == EWS
+    assert L.cdq_cyclic_cd(p, p, p, p, p, 4, 254, 3, 254, i64(8), n, n, n, 0, p, 1 << 30, n) == EUNSUP   # d_in % 4
+    assert L.cdq_cyclic_cd(p, p, p, p, p, 0, 256, 3, 256, i64(8), n, n, n, 0, n, 0, n) == 0             # empty layer
