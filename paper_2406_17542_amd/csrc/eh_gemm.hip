@@ -6,7 +6,7 @@
 // sequential fp64 sum only when that sum lies within ~1e-16 relative of a rounding boundary.
 //
 // Tile: 128 (columns j) x 128 (coordinates k) per workgroup of 16 wavefronts (4 x 4), each
-// wavefront 32 x 32 = 2 x 2 MFMA blocks; contraction step 32.  An fp64 MFMA occupies its SIMD
+// wavefront 32 x 32 = 2 x 2 MFMA blocks; contraction step 64, two LDS stages.  An fp64 MFMA occupies its SIMD
 // for 64 cycles, so LDS bandwidth is irrelevant and the 4 wavefronts per SIMD are there to keep
 // the matrix core fed across barriers and global-load latency.
 #include "cdq_internal.h"
@@ -17,8 +17,9 @@ namespace {
 
 typedef double d4 __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128, BN = 128, BK = 32, LDP = 144;   // LDP % 32 == 16: the two k-rows read by lanes 0..31 hit disjoint banks
+constexpr int BM = 128, BN = 128, BK = 64, LDP = 144;   // LDP % 32 == 16: the two k-rows read by lanes 0..31 hit disjoint banks
 constexpr int NT = 1024;
+constexpr int NP = BK / 32;          // 32-deep pieces of a step's tiles handled by each thread
 constexpr size_t EH_LDS = 4 * sizeof(float) * BK * LDP + sizeof(double) * 4 * BM;
 
 // residual of 4 consecutive coordinates of one column (zero outside the matrix)
@@ -76,28 +77,76 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = (d4){0.0, 0.0, 0.0, 0.0};
 
-    // loader roles: one 4-wide piece of each tile per thread
-    const int a_row = tid >> 3, a_k = (tid & 7) * 4;        // E tile: 128 rows x (8 x 4) k
-    const int b_row = tid >> 5, b_col = (tid & 31) * 4;     // H tile: 32 rows x (32 x 4) n
+    // loader roles, per 32-deep piece of the step: one 4-wide run of the E tile (128 rows x 8 runs) and one of the
+    // H tile (32 rows x 32 runs) per thread
+    const int a_row = tid >> 3, a_k = (tid & 7) * 4;
+    const int b_row = tid >> 5, b_col = (tid & 31) * 4;
 
-    float ra[4], rb[4];
+    // The loads of a step are issued before the MFMAs of the previous one and only consumed after them: the raw
+    // weights, codes and grid entries stay in registers, and the residual e = fma(a, q, b) - w is formed when the
+    // tile is written to LDS (forming it at load time would make every wavefront wait out the memory latency in
+    // front of its MFMAs).
+    float rw[NP][4], rs[NP][4], rz[NP][4], rb[NP][4];
+    uint32_t rq[NP][4];
+    bool e_valid[NP];
     auto load_tiles = [&](int64_t k0) {
-        residual4<VEC4>(Wt, Q, scale, zero, m0 + a_row, k0 + a_k, d_out, d_in, group, n_grp, ra);
-        const int64_t hr = k0 + b_row, c0 = n0 + b_col;
-        if (VEC4) {
-            float4 hv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (hr < d_in && c0 < d_in) hv = *reinterpret_cast<const float4*>(H + hr * d_in + c0);
-            rb[0] = hv.x; rb[1] = hv.y; rb[2] = hv.z; rb[3] = hv.w;
-        } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) rb[e] = (hr < d_in && c0 + e < d_in) ? H[hr * d_in + c0 + e] : 0.0f;
+        for (int p = 0; p < NP; ++p) {
+            const int64_t row = m0 + a_row, i0 = k0 + 32 * p + a_k;
+            e_valid[p] = row < d_out && i0 < d_in;
+            if (e_valid[p]) {
+                const float* w = Wt + row * d_in + i0;
+                const uint8_t* q = Q + row * d_in + i0;
+                if (VEC4) {     // d_in % 4 == 0, group % 4 == 0, 16-byte aligned rows: the four share one group
+                    const int64_t gi = i0 / group;
+                    const float4 wv = *reinterpret_cast<const float4*>(w);
+                    rq[p][0] = *reinterpret_cast<const uint32_t*>(q);
+                    rs[p][0] = scale[row * n_grp + gi];
+                    rz[p][0] = zero[row * n_grp + gi];
+                    rw[p][0] = wv.x; rw[p][1] = wv.y; rw[p][2] = wv.z; rw[p][3] = wv.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bool ok = i0 + e < d_in;
+                        const int64_t gi = ok ? (i0 + e) / group : 0;
+                        rw[p][e] = ok ? w[e] : 0.0f;
+                        rq[p][e] = ok ? q[e] : 0u;
+                        rs[p][e] = ok ? scale[row * n_grp + gi] : 0.0f;
+                        rz[p][e] = ok ? zero[row * n_grp + gi] : 0.0f;
+                    }
+                }
+            }
+            const int64_t hr = k0 + 32 * p + b_row, c0 = n0 + b_col;
+            if (VEC4) {
+                float4 hv = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (hr < d_in && c0 < d_in) hv = *reinterpret_cast<const float4*>(H + hr * d_in + c0);
+                rb[p][0] = hv.x; rb[p][1] = hv.y; rb[p][2] = hv.z; rb[p][3] = hv.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rb[p][e] = (hr < d_in && c0 + e < d_in) ? H[hr * d_in + c0 + e] : 0.0f;
+            }
         }
     };
 
     auto store_tiles = [&](int st) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) As[st][a_k + e][a_row] = ra[e];
-        *reinterpret_cast<float4*>(&Bs[st][b_row][b_col]) = make_float4(rb[0], rb[1], rb[2], rb[3]);
+        for (int p = 0; p < NP; ++p) {
+            float ra[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (e_valid[p]) {
+                if (VEC4) {
+                    ra[0] = fmaf(rs[p][0], (float)(rq[p][0] & 0xffu), rz[p][0]) - rw[p][0];
+                    ra[1] = fmaf(rs[p][0], (float)((rq[p][0] >> 8) & 0xffu), rz[p][0]) - rw[p][1];
+                    ra[2] = fmaf(rs[p][0], (float)((rq[p][0] >> 16) & 0xffu), rz[p][0]) - rw[p][2];
+                    ra[3] = fmaf(rs[p][0], (float)(rq[p][0] >> 24), rz[p][0]) - rw[p][3];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) ra[e] = fmaf(rs[p][e], (float)rq[p][e], rz[p][e]) - rw[p][e];    // zero outside the matrix
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) As[st][32 * p + a_k + e][a_row] = ra[e];
+            *reinterpret_cast<float4*>(&Bs[st][32 * p + b_row][b_col]) = make_float4(rb[p][0], rb[p][1], rb[p][2], rb[p][3]);
+        }
     };
     load_tiles(0);
     store_tiles(0);
