@@ -254,6 +254,24 @@ def main():
         ev.record(e1, stream)
         achievable["hbm_stream_read_GBps"] = 5 * big.numel() * 4 / (ev.elapsed_ms(e0, e1) * 1e-3) * 1e-9
         del big
+        # the same streaming read over a buffer that stays in the last-level cache (32 MiB, repeated)
+        small = torch.zeros(8 << 20, dtype=torch.float32, device="cuda")
+        cdq.probe_read(small, small.numel() * 4, sink)
+        torch.cuda.synchronize()
+        ev.record(e0, stream)
+        for _ in range(200):
+            cdq.probe_read(small, small.numel() * 4, sink)
+        ev.record(e1, stream)
+        achievable["cache_stream_read_GBps_32MiB"] = 200 * small.numel() * 4 / (ev.elapsed_ms(e0, e1) * 1e-3) * 1e-9
+        del small
+        # matrix cores alone (no memory traffic): what the GEMM kernels could reach at most on this machine, clock included
+        for kind, key in ((0, "mfma_bf16_only_TFLOPs"), (1, "mfma_f64_only_TFLOPs")):
+            cdq.probe_mfma(kind, 256 * 2, 200, sink)
+            torch.cuda.synchronize()
+            ev.record(e0, stream)
+            flop = cdq.probe_mfma(kind, 256 * 2, 20000 if kind == 0 else 5000, sink)
+            ev.record(e1, stream)
+            achievable[key] = flop / (ev.elapsed_ms(e0, e1) * 1e-3) * 1e-12
         waves_used = args.waves
         if waves_used == 0:                     # mirrors the library's default: 16 coordinates per lane
             waves_used = 1
@@ -309,7 +327,11 @@ def main():
                     "nominal_T_x_d_out_per_s": cfg.T * cfg.d_out / (stages["cd_loop"] * 1e-3), "H_row_GBps": cd_gbs,
                     "frac_of_hbm_peak": cd_gbs / HBM_PEAK_GBS},
         "hessian": {"tflops_executed": h_tflops_exec, "tflops_effective": h_tflops_eff, "mfma_peak_tflops": mfma_peak,
-                    "frac_of_mfma_peak": h_tflops_exec / mfma_peak},
+                    "frac_of_mfma_peak": h_tflops_exec / mfma_peak,
+                    "frac_of_measured_mfma_only": (h_tflops_exec / achievable["mfma_bf16_only_TFLOPs"])
+                    if cfg.x_dtype == "bf16" and "mfma_bf16_only_TFLOPs" in achievable else None},
+        "fp64_gemm": {"gradient_init_tflops": 2.0 * cfg.d_out * cfg.d_in * cfg.d_in / (stages["cd_gradient_init"] * 1e-3) * 1e-12,
+                      "loss_tflops": 2.0 * cfg.d_out * cfg.d_in * cfg.d_in / (stages["loss"] * 1e-3) * 1e-12, "mfma_f64_peak_tflops": 78.6},
         "loss_final": loss_final,
         "achievable": achievable,
     }

@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.cdq_bcd.restype = i32
         L.cdq_cyclic_cd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, vp, i64, vp, sz, vp]
         L.cdq_cyclic_cd.restype = i32
+        L.cdq_probe_mfma.argtypes = [i32, i64, i64, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.cdq_probe_mfma.restype = i32
         L.cdq_probe_copy.argtypes = [vp, vp, sz, vp]
         L.cdq_probe_read.argtypes = [vp, sz, vp, vp]
         L.cdq_probe_gather.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
@@ -318,3 +320,10 @@ def probe_gather(H: torch.Tensor, n_rows: int, row_bytes: int, teams: int, waves
                  sink: torch.Tensor) -> None:
     _check(lib().cdq_probe_gather(H.data_ptr(), n_rows, row_bytes, teams, waves_per_row, iters, sink.data_ptr(),
                                   _stream()), "cdq_probe_gather")
+
+
+def probe_mfma(kind: int, blocks: int, iters: int, sink: torch.Tensor) -> float:
+    """Launches the matrix-core-only loop (kind 0: bf16 32x32x16, 1: fp64 16x16x4); returns its operation count."""
+    flop = ctypes.c_double(0.0)
+    _check(lib().cdq_probe_mfma(kind, blocks, iters, sink.data_ptr(), ctypes.byref(flop), _stream()), "cdq_probe_mfma")
+    return float(flop.value)

@@ -45,10 +45,57 @@ __global__ __launch_bounds__(1024) void probe_gather_kernel(const float4* __rest
     if (acc == 1.2345678e-30f) sink[0] = acc;
 }
 
+// Matrix-core-only loops: every wavefront issues `iters` rounds of independent MFMAs on constant operands, no memory
+// traffic.  What they sustain on a box (clock under load included) is the ceiling the GEMM kernels are compared with.
+typedef float pf16v __attribute__((ext_vector_type(16)));
+typedef __bf16 pbf8 __attribute__((ext_vector_type(8)));
+typedef double pd4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(512) void probe_mfma_bf16_kernel(int iters, float* __restrict__ sink) {
+    pf16v acc[8];
+    for (int a = 0; a < 8; ++a)
+        for (int v = 0; v < 16; ++v) acc[a][v] = 0.0f;
+    pbf8 x, y;
+    for (int e = 0; e < 8; ++e) { x[e] = (__bf16)(float)(threadIdx.x & 3); y[e] = (__bf16)1.0f; }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int a = 0; a < 8; ++a) acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[a], 0, 0, 0);
+    }
+    float t = 0.0f;
+    for (int a = 0; a < 8; ++a) t += acc[a][0];
+    if (t == 1.2345678e-30f) sink[0] = t;
+}
+
+__global__ __launch_bounds__(1024) void probe_mfma_f64_kernel(int iters, float* __restrict__ sink) {
+    pd4 acc[4];
+    for (int a = 0; a < 4; ++a) acc[a] = (pd4){0.0, 0.0, 0.0, 0.0};
+    const double x = (double)(threadIdx.x & 3), y = 1.0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a) acc[a] = __builtin_amdgcn_mfma_f64_16x16x4f64(x, y, acc[a], 0, 0, 0);
+    }
+    const double t = (acc[0][0] + acc[1][0]) + (acc[2][0] + acc[3][0]);
+    if (t == 1.2345678e-300) sink[0] = (float)t;
+}
+
 }  // namespace
 }  // namespace cdq
 
 extern "C" {
+
+int cdq_probe_mfma(int kind, int64_t blocks, int64_t iters, float* sink, double* flop, void* stream) {
+    if (sink == nullptr || blocks <= 0 || blocks > 0x7fffffffLL || iters < 0 || iters > 0x7fffffffLL || (kind != 0 && kind != 1))
+        return CDQ_EINVAL;
+    if (kind == 0) {        // 8 wavefronts per block, 8 MFMAs of 32x32x16 per round
+        hipLaunchKernelGGL(cdq::probe_mfma_bf16_kernel, dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream, (int)iters, sink);
+        if (flop != nullptr) *flop = (double)blocks * 8.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
+    } else {                // 16 wavefronts per block, 4 MFMAs of 16x16x4 (fp64) per round
+        hipLaunchKernelGGL(cdq::probe_mfma_f64_kernel, dim3((unsigned)blocks), dim3(1024), 0, (hipStream_t)stream, (int)iters, sink);
+        if (flop != nullptr) *flop = (double)blocks * 16.0 * (double)iters * 4.0 * (2.0 * 16 * 16 * 4);
+    }
+    CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
 
 int cdq_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
     if (src == nullptr || dst == nullptr || bytes % 16 != 0 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return CDQ_EINVAL;
