@@ -2,10 +2,11 @@
 //
 // X is [n][d_in] row-major and the contraction runs over the n tokens, so both MFMA operands
 // are read "down the columns" of X.  bf16 path: v_mfma_f32_32x32x16_bf16 wants, per lane, 8
-// consecutive tokens of one column; tiles of X are therefore transposed on their way into LDS
-// (each lane loads one 32-bit column pair for 8 tokens, regroups the 16-bit halves in
-// registers and stores one 16-byte token run per column).  fp32 path: v_mfma_f32_32x32x2_f32
-// takes one element per lane, no transposition needed.
+// tokens of one column.  Tiles of X are copied into LDS as they lie in memory (token rows) by
+// gfx950's direct global->LDS loads, several steps ahead and without passing through registers,
+// and the fragments are read with the transposing LDS load (ds_read_b64_tr_b16), which hands each
+// lane four tokens of one column out of a 4-token x 16-column block addressed by 16 lanes.
+// fp32 path: v_mfma_f32_32x32x2_f32 takes one element per lane, no transposition needed.
 //
 // Only tiles on or above the diagonal are computed (H is symmetric); the token range may be
 // split over grid.z, each split writing its partial tile; a second kernel sums the splits in a
@@ -35,127 +36,234 @@ __device__ __forceinline__ void tile_from_linear(int lin, int n_t, int* I, int* 
 
 // ------------------------------------------------------------------------------------------ bf16
 //
-// 256 x 256 tile of H per workgroup of 8 wavefronts (two per SIMD, so one can issue MFMAs while
-// the other waits on LDS or the barrier), each wavefront 128 x 64 = 4 x 2 MFMA blocks, 64 tokens
-// per step, LDS double-buffered (one barrier per step), next step's global loads in flight
-// during the current step's MFMAs.
-// LDS holds each operand tile transposed: 128 bytes (64 tokens) per column, the 16-byte token
-// octets of a column XOR-swizzled with ((col >> 3) ^ col) & 7 so that both the transposing stores
-// (8 consecutive lanes = 8 column octets) and the fragment reads (8 consecutive lanes = 8
-// consecutive columns) touch 8 distinct bank groups.
+// 256 x 256 tile of H per workgroup of 4 wavefronts (one per SIMD), each wavefront 128 x 128 =
+// 4 x 4 MFMA blocks with the 256 accumulator registers in AGPRs (a third less LDS traffic per FLOP
+// than 128 x 64 on 8 wavefronts).  The token range is consumed in steps of 32; LDS is a ring of NSTAGE stages,
+// each holding the two operand tiles of one step as 32 token rows of 256 columns (512 bytes).
+// Loads run NSTAGE-1 steps ahead: a wavefront's direct global->LDS load moves 64 x 16 bytes = two
+// token rows; lane l writes chunk position l%32 of row l/32 and fetches the global 16-byte chunk
+// (l%32) ^ 4(row%4), i.e. the chunks of a row are XOR-swizzled by the row.  A transposing read by
+// the 16 lanes j of a group fetches the 8-byte pieces (token tb + j/4, columns fb + 4(j%4) .. +3)
+// and returns to lane j the tokens tb .. tb+3 of column fb + j; with the swizzle, the four token
+// rows of a group fall into four different 64-byte bank groups, so reads and writes are
+// conflict-free.  With a single wavefront per SIMD nothing else hides a stall, so the loop is a
+// software pipeline over 16-token halves: the fragments of the next half are read while the MFMAs
+// of the current one run (scheduling hints interleave one read behind each MFMA), the one barrier
+// per step sits between the two halves, and issuing a step's loads costs a few scalar
+// instructions (fixed per-lane offsets, a scalar base per step).  Tiles that stick out of the
+// matrix, and a token range that is not a multiple of 32, take a plain path through registers
+// with zero fill (same layout).
 
 constexpr int T2 = 256;                 // tile of H: T2 x T2 per workgroup
-constexpr int BK16 = 64;                // tokens per step
-constexpr int COLB = BK16 * 2;          // LDS bytes per column of the transposed tile
-constexpr int TILE_BYTES = T2 * COLB;   // 32 KiB per operand per buffer
+constexpr int BK16 = 64;                // granularity of the token split (two steps)
+constexpr int BKS = 32;                 // tokens per step
+constexpr int ROWB = T2 * 2;            // LDS bytes per token row of a tile
+constexpr int TILE_BYTES = BKS * ROWB;  // 16 KiB per operand per stage
+constexpr int NSTAGE = 4;
+constexpr int HESS_LDS = NSTAGE * 2 * TILE_BYTES;      // 128 KiB
 
-__device__ __forceinline__ int swz(int col, int octet) { return col * COLB + ((octet ^ (((col >> 3) ^ col) & 7)) << 4); }
+typedef short s4v __attribute__((ext_vector_type(4)));
+typedef short s8v __attribute__((ext_vector_type(8)));
 
-// 8 tokens x 8 adjacent bf16 columns (16 bytes per token)
-__device__ __forceinline__ void load_oct8(const uint16_t* __restrict__ X, int64_t t_end, int64_t d_in, int64_t t0,
-                                          int64_t col, u4 w[8]) {
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const int64_t t = t0 + r;
-        if (t < t_end && col < d_in) w[r] = *reinterpret_cast<const u4*>(X + t * d_in + col);
-        else w[r] = (u4){0u, 0u, 0u, 0u};
-    }
-}
-// transpose the 8x8 block in registers and store one 8-token run (16 bytes) per column
-__device__ __forceinline__ void store_oct8(char* tile, int col_octet, int tok_octet, const u4 w[8]) {
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-        u4 o;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t x = w[2 * k][c >> 1], y = w[2 * k + 1][c >> 1];
-            o[k] = (c & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
-        }
-        *reinterpret_cast<u4*>(tile + swz(col_octet * 8 + c, tok_octet)) = o;
-    }
+// tokens tb..tb+3 (first read) and tb+4..tb+7 (second read) of this lane's column: the 8 contraction
+// elements one lane feeds to v_mfma_f32_32x32x16_bf16
+__device__ __forceinline__ bf8 read_frag(const char* p) {
+    const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4v*)(p));
+    const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4v*)(p + 4 * ROWB));
+    const s8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf8, both);
 }
 
-__global__ __launch_bounds__(512) void hessian_bf16_kernel(const uint16_t* __restrict__ X, int64_t n, int64_t d_in,
+// 16 bytes per lane from global memory straight into LDS at dst + 16 * lane (dst uniform over the wavefront).
+// Written as assembly so that the waits stay ours: the compiler would make every LDS read wait for all
+// direct loads in flight, the ones for later stages included.
+__device__ __forceinline__ void lds_direct_load16(const void* src, const char* dst) {
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)dst);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src) : "m0", "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmem() {          // until at most N of this wavefront's vector-memory operations are pending
+    if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+}
+
+__global__ __launch_bounds__(256) void hessian_bf16_kernel(const uint16_t* __restrict__ X, int64_t n, int64_t d_in,
                                                            int n_t, int64_t tokens_per_split,
                                                            float* __restrict__ out, int64_t split_stride) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];       // [2 buffers][A tile | B tile]
+    extern __shared__ __attribute__((aligned(16))) char lds[];       // [NSTAGE][A tile | B tile]
     int I, J;
     tile_from_linear(blockIdx.x, n_t, &I, &J);
     const bool diag = (I == J);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3;           // 2 x 4 wavefronts, each 128 rows x 64 columns
+    const int wm = wave >> 1, wn = wave & 1;           // 2 x 2 wavefronts, each 128 rows x 128 columns
     const int64_t i0 = (int64_t)I * T2, j0 = (int64_t)J * T2;
     const int64_t t_begin = (int64_t)blockIdx.z * tokens_per_split;
     const int64_t t_end = (t_begin + tokens_per_split < n) ? t_begin + tokens_per_split : n;
+    const int n_steps = (int)((t_end - t_begin + BKS - 1) / BKS);
 
-    f16v acc[4][2];
+    f16v acc[4][4];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    // staging roles: threads 0..255 move the A tile (columns of block I), 256..511 the B tile
-    const int half = tid >> 8;
-    const int co = tid & 31, to = (tid >> 5) & 7;      // column octet, token octet
-    const int64_t c0 = (half ? j0 : i0) + co * 8;
-    const bool active = !(half && diag);               // a diagonal tile needs one operand only
-    const bool interior = (i0 + T2 <= d_in) && (j0 + T2 <= d_in);
-    u4 r[8];
-    auto gload = [&](int64_t t0, bool full) {
-        if (!active) return;
-        if (full && interior) {                        // no bounds checks on the common path
-            const uint16_t* p = X + (t0 + to * 8) * d_in + c0;
+    // fragment read roles: 16-lane group g = lane/16 takes columns 16 (g%2) .. +15 of a 32-column fragment and the
+    // token half g/2 of a 16-token sub-step; lane j of the group addresses token j/4, columns 4 (j%4) .. +3
+    const int jj = lane & 15, gg = lane >> 4;
+    const int rd_row = (8 * (gg >> 1) + (jj >> 2)) * ROWB + 8 * (jj & 1);
+    const int rd_chunk = 2 * (gg & 1) + ((jj & 3) >> 1), rd_swz = jj & 12;
+    int offA[4], offB[4];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) r[q] = *reinterpret_cast<const u4*>(p + q * d_in);
-        } else {
-            load_oct8(X, t_end, d_in, t0 + to * 8, c0, r);
+    for (int b = 0; b < 4; ++b) offA[b] = rd_row + (((wm * 16 + 4 * b + rd_chunk) ^ rd_swz) << 4);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) offB[b] = rd_row + (((wn * 16 + 4 * b + rd_chunk) ^ rd_swz) << 4);
+
+    // one wavefront per SIMD: the fragments of the next 16-token sub-step are fetched while the MFMAs of the
+    // current one run (the matrix core works asynchronously to the wavefront's instruction stream)
+    auto load_frags = [&](const char* At, const char* Bt, int ks, bf8 (&af)[4], bf8 (&bfr)[4]) {
+        // in the order the MFMAs below want them: the first row block, all column blocks, the other row blocks
+        af[0] = read_frag(At + offA[0] + ks * 16 * ROWB);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) bfr[b] = read_frag(Bt + offB[b] + ks * 16 * ROWB);
+#pragma unroll
+        for (int b = 1; b < 4; ++b) af[b] = read_frag(At + offA[b] + ks * 16 * ROWB);
+    };
+    auto mfmas = [&](const bf8 (&af)[4], const bf8 (&bfr)[4]) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+    };
+    auto interleave = [&]() {          // ask for one LDS read behind each MFMA instead of a block of reads, then a block of MFMAs
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
-    auto lstore = [&](int buf) {
-        if (active) store_oct8(lds + buf * 2 * TILE_BYTES + half * TILE_BYTES, co, to, r);
+    auto compute = [&](int stage) {    // plain form, for the path through registers
+        const char* At = lds + stage * 2 * TILE_BYTES;
+        const char* Bt = diag ? At : At + TILE_BYTES;
+        static_assert(BKS == 32, "two sub-steps per step");
+        bf8 a0[4], b0[4], a1[4], b1[4];
+        load_frags(At, Bt, 0, a0, b0);
+        load_frags(At, Bt, 1, a1, b1);
+        mfmas(a0, b0);
+        mfmas(a1, b1);
     };
 
-    if (t_begin < t_end) {
-        gload(t_begin, t_begin + BK16 <= t_end);
-        lstore(0);
-    }
-    __syncthreads();
-    int buf = 0;
-    for (int64_t t0 = t_begin; t0 < t_end; t0 += BK16) {
-        const bool more = t0 + BK16 < t_end;
-        if (more) gload(t0 + BK16, t0 + 2 * BK16 <= t_end);
-        const char* At = lds + buf * 2 * TILE_BYTES;
-        const char* Bt = diag ? At : At + TILE_BYTES;
+    const bool interior = (i0 + T2 <= d_in) && (j0 + T2 <= d_in);
+    if (n_steps <= 0) {
+        // empty token range: the partial tile is zero
+    } else if (interior && (t_end - t_begin) % BKS == 0) {
+        // ---- direct global->LDS loads, NSTAGE-1 steps ahead.  A step's tiles are 32 (16 on the diagonal) loads of two
+        // token rows each; wavefront w issues loads w, w+8, ... so every wavefront has the same number in flight.
+        // Per load q the lane's byte offset from the first token row of the step is fixed; only a scalar base moves
+        // from step to step, so issuing a step's loads costs a handful of scalar instructions.
+        const int per_wave = diag ? 4 : 8;
+        const int lrow = lane >> 5, lpos = lane & 31;
+        uint32_t src_off[8];
+        uint32_t dst_off[8];
 #pragma unroll
-        for (int ks = 0; ks < BK16 / 16; ++ks) {
-            bf8 af[4], bfr[2];
-            const int oct = ks * 2 + (lane >> 5);
-#pragma unroll
-            for (int b = 0; b < 4; ++b) af[b] = *reinterpret_cast<const bf8*>(At + swz(wm * 128 + b * 32 + (lane & 31), oct));
-#pragma unroll
-            for (int b = 0; b < 2; ++b) bfr[b] = *reinterpret_cast<const bf8*>(Bt + swz(wn * 64 + b * 32 + (lane & 31), oct));
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+        for (int q = 0; q < 8; ++q) {
+            const int g = wave + 4 * q;                           // 0..15: A tile, 16..31: B tile
+            const int op = g >> 4, row = 2 * (g & 15) + lrow;
+            const int chunk = lpos ^ (4 * (row & 3));
+            src_off[q] = (uint32_t)(((int64_t)row * d_in + (op ? j0 - i0 : 0) + 8 * chunk) * 2);
+            dst_off[q] = (uint32_t)(op * TILE_BYTES + 2 * (g & 15) * ROWB);
         }
-        if (more) lstore(buf ^ 1);
+        const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds;
+        const char* xbase = reinterpret_cast<const char*>(X + t_begin * d_in + i0);
+        const int64_t step_bytes = (int64_t)BKS * d_in * 2;
+        auto issue = [&](int step) {
+            const char* base = xbase + (int64_t)step * step_bytes;
+            const uint32_t stage_lds = lds_base + (uint32_t)((step % NSTAGE) * 2 * TILE_BYTES);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (q < per_wave) {
+                    const uint32_t m0v = __builtin_amdgcn_readfirstlane(stage_lds + dst_off[q]);
+                    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(src_off[q]), "s"(base) : "m0", "memory");
+                }
+            }
+        };
+        // Software pipeline over half steps.  While the MFMAs of one 16-token half run, the fragments of the next half
+        // are read; the barrier sits between the two halves of a step: behind it the next step's tiles are visible
+        // (each wavefront has waited for its own loads) and the previous step's stage is free for new loads.
+        auto wait_loads = [&](int groups_left) {          // until at most `groups_left` steps' worth of this wavefront's loads are pending
+            if (diag) { if (groups_left >= 2) wait_vmem<8>(); else if (groups_left == 1) wait_vmem<4>(); else wait_vmem<0>(); }
+            else      { if (groups_left >= 2) wait_vmem<16>(); else if (groups_left == 1) wait_vmem<8>(); else wait_vmem<0>(); }
+        };
+        static_assert(NSTAGE == 4, "the wait counts below assume three steps in flight");
+        const int pro = n_steps < NSTAGE - 1 ? n_steps : NSTAGE - 1;
+        for (int s0 = 0; s0 < pro; ++s0) issue(s0);
+        wait_loads(pro - 1);
         __syncthreads();
-        buf ^= 1;
+        bf8 a0[4], b0[4], a1[4], b1[4];
+        load_frags(lds, diag ? lds : lds + TILE_BYTES, 0, a0, b0);
+        for (int step = 0; step + 1 < n_steps; ++step) {
+            const char* At = lds + (step % NSTAGE) * 2 * TILE_BYTES;
+            const char* Bt = diag ? At : At + TILE_BYTES;
+            load_frags(At, Bt, 1, a1, b1);
+            mfmas(a0, b0);
+            interleave();
+            const int in_flight = (n_steps - 1 - step < NSTAGE - 2) ? n_steps - 1 - step : NSTAGE - 2;   // steps step+1 .. already issued
+            wait_loads(in_flight - 1);
+            __syncthreads();
+            if (step + NSTAGE - 1 < n_steps) issue(step + NSTAGE - 1);       // into the stage of step-1, which nobody reads any more
+            const char* An = lds + ((step + 1) % NSTAGE) * 2 * TILE_BYTES;
+            load_frags(An, diag ? An : An + TILE_BYTES, 0, a0, b0);
+            mfmas(a1, b1);
+            interleave();
+        }
+        {       // last step: nothing left to fetch behind it
+            const char* At = lds + ((n_steps - 1) % NSTAGE) * 2 * TILE_BYTES;
+            load_frags(At, diag ? At : At + TILE_BYTES, 1, a1, b1);
+            mfmas(a0, b0);
+            mfmas(a1, b1);
+        }
+    } else {
+        // ---- edge tiles / ragged token range: through registers with zero fill, one stage, same layout
+        const int cpos = tid & 31, rgrp = tid >> 5;                 // 8 row groups of 4 token rows, 32 chunks per row
+        for (int step = 0; step < n_steps; ++step) {
+            const int64_t t0 = t_begin + (int64_t)step * BKS;
+            u4 r[2][4];
+#pragma unroll
+            for (int half = 0; half < 2; ++half)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int row = rgrp * 4 + q;
+                    const int64_t t = t0 + row, col = (half ? j0 : i0) + 8 * (cpos ^ (4 * q));
+                    r[half][q] = (u4){0u, 0u, 0u, 0u};
+                    if (!(half && diag) && t < t_end && col < d_in) r[half][q] = *reinterpret_cast<const u4*>(X + t * d_in + col);
+                }
+            __syncthreads();                 // previous step's reads are done
+#pragma unroll
+            for (int half = 0; half < 2; ++half)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (!(half && diag))
+                        *reinterpret_cast<u4*>(lds + half * TILE_BYTES + (rgrp * 4 + q) * ROWB + cpos * 16) = r[half][q];
+            __syncthreads();
+            compute(0);
+        }
     }
     // 32x32 result block: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
     float* dst = out + (int64_t)blockIdx.z * split_stride;
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t row = i0 + wm * 128 + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
-                const int64_t col = j0 + wn * 64 + b * 32 + (lane & 31);
+                const int64_t col = j0 + wn * 128 + b * 32 + (lane & 31);
                 if (row < d_in && col < d_in) dst[row * d_in + col] = acc[a][b][v];
             }
 }
@@ -339,9 +447,9 @@ int hessian_launch(const void* X, int x_dtype, int64_t n, int64_t d_in, float* H
     dim3 grid((unsigned)tiles, 1, (unsigned)splits);
     if (x_dtype == CDQ_BF16) {
         static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(hessian_bf16_kernel),
-                                                              hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILE_BYTES);
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize, HESS_LDS);
         if (attr_rc != hipSuccess) return CDQ_EHIP;
-        hipLaunchKernelGGL(hessian_bf16_kernel, grid, dim3(512), 4 * TILE_BYTES, st, (const uint16_t*)X, n, d_in, (int)n_t, per, parts, stride);
+        hipLaunchKernelGGL(hessian_bf16_kernel, grid, dim3(256), HESS_LDS, st, (const uint16_t*)X, n, d_in, (int)n_t, per, parts, stride);
     }
     else
         hipLaunchKernelGGL(hessian_f32_kernel, grid, dim3(256), 0, st, (const float*)X, n, d_in, (int)n_t, per, parts, stride);
