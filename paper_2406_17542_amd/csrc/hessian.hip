@@ -34,6 +34,38 @@ __device__ __forceinline__ void tile_from_linear(int lin, int n_t, int* I, int* 
     *J = i + rem;
 }
 
+// Tile order for large matrices: workgroups are handed to the 8 XCDs round-robin, and each XCD has its own L2, so
+// the 32 workgroups an XCD runs at a time should share operand column blocks.  Workgroup w belongs to XCD w % 8 and
+// is that XCD's (w / 8)-th; consecutive runs of 32 of them form a patch of 4 x 8 tiles (12 column blocks for 32
+// tiles instead of ~36 in row-major order).  Patches that lie wholly below the diagonal are not enumerated; tiles of
+// a patch below the diagonal or outside the matrix return at once.  `rot` rotates the patch-to-XCD assignment
+// (one value per token split) so that no XCD always gets the surplus patch.
+constexpr int PATCH_R = 4, PATCH_C = 8;
+
+__host__ __device__ inline int patch_row_first(int pi) { return (PATCH_R * pi) / PATCH_C; }     // first patch column reaching row block pi
+__host__ __device__ inline int patch_count(int n_t) {
+    const int PI = (n_t + PATCH_R - 1) / PATCH_R, PJ = (n_t + PATCH_C - 1) / PATCH_C;
+    int c = 0;
+    for (int pi = 0; pi < PI; ++pi) c += PJ - patch_row_first(pi);
+    return c;
+}
+__device__ __forceinline__ bool tile_from_patch(int w, int rot, int n_t, int* I, int* J) {
+    const int xcd = (w + rot) & 7, s = w >> 3;
+    int p = (s >> 5) * 8 + xcd;
+    const int pos = s & 31;
+    const int PI = (n_t + PATCH_R - 1) / PATCH_R, PJ = (n_t + PATCH_C - 1) / PATCH_C;
+    int pi = 0;
+    for (; pi < PI; ++pi) {
+        const int cnt = PJ - patch_row_first(pi);
+        if (p < cnt) break;
+        p -= cnt;
+    }
+    if (pi >= PI) return false;
+    *I = PATCH_R * pi + (pos >> 3);
+    *J = PATCH_C * (patch_row_first(pi) + p) + (pos & 7);
+    return *I < n_t && *J < n_t && *J >= *I;
+}
+
 // ------------------------------------------------------------------------------------------ bf16
 //
 // 256 x 256 tile of H per workgroup of 4 wavefronts (one per SIMD), each wavefront 128 x 128 =
@@ -93,10 +125,14 @@ __device__ __forceinline__ void wait_vmem() {          // until at most N of thi
 
 __global__ __launch_bounds__(256) void hessian_bf16_kernel(const uint16_t* __restrict__ X, int64_t n, int64_t d_in,
                                                            int n_t, int64_t tokens_per_split,
-                                                           float* __restrict__ out, int64_t split_stride) {
+                                                           float* __restrict__ out, int64_t split_stride, int patched) {
     extern __shared__ __attribute__((aligned(16))) char lds[];       // [NSTAGE][A tile | B tile]
     int I, J;
-    tile_from_linear(blockIdx.x, n_t, &I, &J);
+    if (patched) {
+        if (!tile_from_patch((int)blockIdx.x, (int)blockIdx.z, n_t, &I, &J)) return;
+    } else {
+        tile_from_linear(blockIdx.x, n_t, &I, &J);
+    }
     const bool diag = (I == J);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;           // 2 x 2 wavefronts, each 128 rows x 128 columns
@@ -449,7 +485,10 @@ int hessian_launch(const void* X, int x_dtype, int64_t n, int64_t d_in, float* H
         static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(hessian_bf16_kernel),
                                                               hipFuncAttributeMaxDynamicSharedMemorySize, HESS_LDS);
         if (attr_rc != hipSuccess) return CDQ_EHIP;
-        hipLaunchKernelGGL(hessian_bf16_kernel, grid, dim3(256), HESS_LDS, st, (const uint16_t*)X, n, d_in, (int)n_t, per, parts, stride);
+        const bool patched = n_t >= 24;                  // enough tiles for every XCD to fill whole patches
+        if (patched) grid.x = (unsigned)(8 * ((patch_count((int)n_t) + 7) / 8) * PATCH_R * PATCH_C);
+        hipLaunchKernelGGL(hessian_bf16_kernel, grid, dim3(256), HESS_LDS, st, (const uint16_t*)X, n, d_in, (int)n_t, per, parts, stride,
+                           patched ? 1 : 0);
     }
     else
         hipLaunchKernelGGL(hessian_f32_kernel, grid, dim3(256), 0, st, (const float*)X, n, d_in, (int)n_t, per, parts, stride);
