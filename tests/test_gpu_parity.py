@@ -87,6 +87,8 @@ def test_init_rtn_tiny_config(cdq, oracle):
 @pytest.mark.parametrize("x_dtype,n,d_in", [
     ("f32", 512, 128), ("f32", 300, 132), ("f32", 1, 4), ("f32", 1000, 260),
     ("bf16", 512, 128), ("bf16", 333, 136), ("bf16", 4096, 392), ("bf16", 7, 8), ("bf16", 2500, 1024),
+    # interior 256-wide tiles with 1, 2, 3, 4 and 5 steps of 32 tokens: every length of the load pipeline's start-up
+    ("bf16", 32, 256), ("bf16", 64, 512), ("bf16", 96, 256), ("bf16", 128, 512), ("bf16", 160, 256), ("bf16", 1056, 768),
 ])
 def test_hessian(cdq, oracle, x_dtype, n, d_in):
     X = inputs.make_x("outlier8x20", n, d_in, seed=n, x_dtype=x_dtype)
