@@ -164,13 +164,16 @@ int cdq_init_owc_cd(const float *H, const float *Wt, int64_t d_out, int64_t d_in
  *   Q [d_out][d_in] in/out; moves NULL or [d_out] int32 out; G_out NULL or [d_out][d_in] fp32:
  *   g = He of the final codes as maintained by the updates;
  *   trace NULL or [d_out][trace_cap][4] int32: iteration, block, r_i | r_k<<4, score bits.
- *   score_all 0: pairs that provably hold no improving move (both coordinates' |2 g| below
- *   (1 - |H_ik|/sqrt(H_ii H_kk) - 2^-10) H a) are not scored; 1: every pair is scored.  Same results.
+ *   flags bit 0 clear: pairs that provably hold no improving move (both coordinates' |2 g| below
+ *   (1 - |H_ik|/sqrt(H_ii H_kk) - 2^-10) H a) are not scored; set: every pair is scored.
+ *   flags bit 1 set: one column per workgroup also where the kernel that gives a workgroup
+ *   several columns applies (d_in % 8 == 0 and the columns' state fits LDS).  Same results for
+ *   every value of flags; the bits exist for tests and timing.
  * Needs d_in % 4 == 0, d_in <= 8192, 16-byte aligned H; workspace of CDQ_OP_BCD size (n = T).
  */
 int cdq_bcd(const float *H, const float *Wt, const float *scale, const float *zero, uint8_t *Q,
             int64_t d_out, int64_t d_in, int bits, int64_t group, int k, const int32_t *parts, int64_t T,
-            int32_t *moves, float *G_out, int32_t *trace, int64_t trace_cap, int score_all,
+            int32_t *moves, float *G_out, int32_t *trace, int64_t trace_cap, int flags,
             void *workspace, size_t workspace_bytes, void *stream);
 
 /*

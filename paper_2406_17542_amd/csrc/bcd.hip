@@ -1,6 +1,8 @@
 // Block coordinate descent with random blocks of two coordinates (paper Algorithm 2; Algorithm 5
-// for groups), weight-space form.  One workgroup owns a column for all T iterations; 2g, the codes,
-// the Hessian diagonal and u = |2g| / (H_ii a_i) sit in LDS.  The loss change of moving the pair
+// for groups), weight-space form.  Two kernels compute the same thing: bcd2_multi_kernel (further
+// down) gives a workgroup several columns that share each row of the pair table and is used where
+// their state fits in LDS; bcd2_kernel, described here, gives a workgroup one column for all T
+// iterations; 2g, the codes, the Hessian diagonal and u = |2g| / (H_ii a_i) sit in LDS.  The loss change of moving the pair
 // (i,k) to the levels (r_i, r_k) is
 //     delta_i = a_i (r_i - q_i),   s_i = delta_i * fma(delta_i, H_ii, 2 g_i)      (same for k)
 //     s(r_i, r_k) = fma(delta_i * delta_k, 2 H_ik, s_i + s_k).
@@ -17,6 +19,7 @@
 // The entries of the next iteration are loaded while the current one is processed.
 #include "cdq_internal.h"
 #include "wave_min.h"
+#include <type_traits>
 
 namespace cdq {
 namespace {
@@ -29,9 +32,10 @@ constexpr int BCD_PPT = 4;          // pairs per thread at most
 // and a nonzero step is at least one grid step a, so |2 g| |d| <= (|2 g| / a) d^2.  If
 // u_i = |2 g_i| / (H_ii a_i) <= 1 - rho - tau and the same for k, every move has
 // s >= tau (H_ii di^2 + H_kk dk^2) > 0 in exact arithmetic; the fp32 evaluation differs from that by
-// a few 1e-7 of the same magnitude, far inside tau = 2^-10.  thr = 1 - rho - tau per pair; -1 (never
-// dropped) when a diagonal entry is not positive.
-constexpr float kBcdTau = 1.0f / 1024.0f;
+// less than 1e-6 of the same magnitude (five roundings of 2^-24 on terms that sum to at most three times it),
+// far inside tau = 2^-14.  thr = 1 - rho - tau per pair; -1 (never dropped) when a diagonal entry is not
+// positive.  A larger tau only costs time: coordinates with u within tau of 1 keep all their pairs alive.
+constexpr float kBcdTau = 1.0f / 16384.0f;
 
 __global__ __launch_bounds__(256) void bcd_pair_gather_kernel(const float* __restrict__ H, const int32_t* __restrict__ parts,
                                                               const int32_t* __restrict__ bad, int64_t d_in, int64_t n_items,
@@ -287,6 +291,363 @@ __global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H,
     if (tid == 0 && moves_out != nullptr) moves_out[j] = moves;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Several columns per workgroup.  Near a coordinate-wise optimum almost every iteration is idle for a
+// column; what it costs is reading the iteration's row of the pair table, the test of every pair and a
+// barrier.  Here a workgroup of 512 threads owns CW columns and pays that once for all of them.
+//   The pair test.  With u = |2 g| / (H_ii a) per coordinate and rho = |H_ik| / sqrt(H_ii H_kk), a move
+//   (di, dk) of the pair changes the loss by at least x^2 (1 - u_i) + y^2 (1 - u_k) - 2 rho x y with
+//   x = |di| sqrt(H_ii), y = |dk| sqrt(H_kk), which is >= tau (x^2 + y^2) for all x, y when
+//   (1 - u_i - tau)(1 - u_k - tau) >= rho^2 and both factors are >= 0; tau = 2^-14 keeps fp32 rounding of the
+//   scores (below 1e-6 of the same magnitude) from turning such a pair into a move.  Both u <= 1 - rho - tau,
+//   the one-column kernel's test, implies this one, so fewer pairs are scored here.
+//   state in LDS: 2g [coordinate][column] fp32; v = 1 - u - tau in units of 2^-16 rounded DOWN,
+//   V [coordinate][column] u16, and its minimum over the columns, Vmin [coordinate]; H_ii; the codes, 4 bits a
+//   column in one word a coordinate; a ring of pair-table rows (i | k << 16, 2 H_ik, and rho^2 rounded
+//   UP to 16 bits) that direct global->LDS loads fill several iterations ahead.
+//   per pair: (vmin_i vmin_k) >> 16 >= R proves the bound for every column (all roundings are on the safe
+//   side, by more than fp32 rounding moves u or rho): four small LDS reads, a 24-bit multiply and a compare.
+//   Otherwise the two V rows say which columns go to the queue.
+//   queue (column, pair): up to BCDM_SPREAD entries 16 lanes share an entry's level pairs, up to the
+//   queue's size a thread takes an entry; beyond (far from an optimum) every thread scores its own pairs
+//   for every column.  Candidates go straight to the column's 64-bit key (score image, then block and
+//   levels) with an LDS minimum, so the result does not depend on the order.
+//   commit: the columns that found a move update 2g with two H rows, then V and Vmin.
+constexpr int BCDM_NT = 1024;
+constexpr int BCDM_QMAX = 512;      // queued entries (column | pair << 4), 4 bytes each
+constexpr int BCDM_SPREAD = 128;    // up to this many entries, 16 lanes share an entry's level pairs
+constexpr int BCDM_MAXI = 3;        // direct loads of 1 KiB a wavefront issues per pair-table row, at most
+
+__device__ __forceinline__ void bcdm_wait_vmem(int n) {       // at most n of this wavefront's vector-memory operations pending
+    switch (n) {
+        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        case 1: asm volatile("s_waitcnt vmcnt(1)" ::: "memory"); break;
+        case 2: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
+        case 3: asm volatile("s_waitcnt vmcnt(3)" ::: "memory"); break;
+        case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+        case 5: asm volatile("s_waitcnt vmcnt(5)" ::: "memory"); break;
+        case 6: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
+        case 7: asm volatile("s_waitcnt vmcnt(7)" ::: "memory"); break;
+        case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;      // waiting for more than needed is always safe
+    }
+}
+
+// v = 1 - u - tau in units of 2^-16 (tau is 4 of them), rounded DOWN by more than one unit; 0 when u is not a number below 0.99
+__device__ __forceinline__ uint32_t bcdm_v16(float g2, float h, float a) {
+    const float u = __fdiv_rn(fabsf(g2), h * a);
+    return (u >= 0.0f && u < 0.99f) ? 65530u - (uint32_t)(u * 65536.0f) : 0u;
+}
+
+// pair-table rows for the kernel above: ik [T][n_pairs] u32, R [T][n_pairs] u16 = rho^2 in units of 2^-16 rounded UP by more than
+// one unit (65535 = never skip)
+__global__ __launch_bounds__(256) void bcdm_pair_gather_kernel(const float* __restrict__ H, const int32_t* __restrict__ parts,
+                                                               const int32_t* __restrict__ bad, int64_t d_in, int64_t n_items,
+                                                               uint32_t* __restrict__ pair_ik, uint16_t* __restrict__ pair_thr,
+                                                               float* __restrict__ pair_h2) {
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;        // x = t * (d_in/2) + p
+    if (x >= n_items || *bad != 0) return;                            // indices are only followed once the check accepted them
+    const int32_t i = parts[2 * x], k = parts[2 * x + 1];
+    const float h2 = 2.0f * H[(int64_t)i * d_in + k];
+    const float hii = H[(int64_t)i * d_in + i], hkk = H[(int64_t)k * d_in + k];
+    uint32_t r16 = 65535u;
+    if (hii > 0.0f && hkk > 0.0f) {
+        const float rho = (0.5f * fabsf(h2) * __frsqrt_rn(hii)) * __frsqrt_rn(hkk);
+        const float r2 = rho * rho;
+        if (r2 < 0.99f) r16 = (uint32_t)(r2 * 65536.0f) + 2u;
+    }
+    pair_ik[x] = (uint32_t)i | ((uint32_t)k << 16);
+    pair_thr[x] = (uint16_t)r16;
+    pair_h2[x] = h2;
+}
+
+template <int BITS, int CW>
+__global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __restrict__ H, const float* __restrict__ hdiag,
+                                                             const float* __restrict__ G0, const float* __restrict__ scale,
+                                                             uint8_t* __restrict__ Q, const uint32_t* __restrict__ pair_ik,
+                                                             const uint16_t* __restrict__ pair_thr, const float* __restrict__ pair_h2,
+                                                             const int32_t* __restrict__ bad_parts,
+                                                             int d_out, int d_in, int group, int T, int nst, int score_all,
+                                                             int32_t* __restrict__ moves_out, float* __restrict__ G_out,
+                                                             int32_t* __restrict__ trace, int trace_cap) {
+    constexpr int L = 1 << BITS, NC = L * L;
+    constexpr int LPE = 16, CPL = NC / LPE;                                 // lanes per entry and level pairs per lane when an entry is shared
+    static_assert(NC % LPE == 0, "at least 2 bits");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_grp = d_in / group, n_pairs = d_in / 2;
+    // group of a coordinate without a division: exact for coordinates below 2^16 and groups below 2^13
+    const uint32_t grp_mul = (uint32_t)((0x100000000ull + (uint32_t)group - 1u) / (uint32_t)group);
+    auto grp = [&](int i) { return group == 1 ? i : (int)__umulhi((uint32_t)i, grp_mul); };
+    const int j0 = blockIdx.x * CW;
+    const int ncol = (d_out - j0 < CW) ? d_out - j0 : CW;
+    const int stage_bytes = 10 * n_pairs;                                   // ik (4 B a pair), 2 H_ik (4 B), thr16 (2 B)
+    float* g2 = reinterpret_cast<float*>(smem);                             // [d_in][CW]
+    uint16_t* V = reinterpret_cast<uint16_t*>(g2 + (size_t)d_in * CW);      // [d_in][CW]
+    float* hd = reinterpret_cast<float*>(V + (size_t)d_in * CW);            // [d_in]
+    using qpack_t = typename std::conditional<(CW <= 2), uint8_t, uint32_t>::type;
+    qpack_t* qpack = reinterpret_cast<qpack_t*>(hd + d_in);                 // [d_in] 4 bits a column
+    char* ring = reinterpret_cast<char*>(qpack + d_in);                     // [nst][stage_bytes]
+    int* queue = reinterpret_cast<int*>(ring + (size_t)nst * stage_bytes);  // [BCDM_QMAX] column | pair << 4
+    unsigned long long* colkey = reinterpret_cast<unsigned long long*>(queue + BCDM_QMAX);   // [2][CW]
+    float* a = reinterpret_cast<float*>(colkey + 2 * CW);                   // [CW][n_grp]
+    int* cnt = reinterpret_cast<int*>(a + CW * n_grp);                      // [4] ring of queue lengths
+    int* found = cnt + 4;                                                   // [2] set when a column offered a move; [2] spare
+    uint16_t* Vmin = reinterpret_cast<uint16_t*>(cnt + 8);                  // [d_in]
+
+    if (*bad_parts != 0) {                                                  // invalid partitions: leave the columns untouched
+        if (tid < ncol && moves_out != nullptr) moves_out[j0 + tid] = -1;
+        return;
+    }
+    for (int x = tid; x < CW * n_grp; x += BCDM_NT) {
+        const int c = x / n_grp;
+        a[x] = (c < ncol) ? scale[(int64_t)(j0 + c) * n_grp + x % n_grp] : 1.0f;
+    }
+    if (tid < 8) cnt[tid] = 0;
+    if (tid < 2 * CW) colkey[tid] = ~0ull;
+    for (int i = tid; i < d_in; i += BCDM_NT) hd[i] = hdiag[i];
+    __syncthreads();
+    for (int i = tid; i < d_in; i += BCDM_NT) {                             // a thread owns coordinate i in all columns
+        uint32_t qp = 0, vm = 65535u;
+        const float h = hd[i];
+        for (int c = 0; c < CW; ++c) {
+            const float g = (c < ncol) ? 2.0f * G0[(int64_t)(j0 + c) * d_in + i] : 0.0f;
+            const uint32_t qv = (c < ncol) ? Q[(int64_t)(j0 + c) * d_in + i] : 0u;
+            const uint32_t u = (c < ncol) ? bcdm_v16(g, h, a[c * n_grp + grp(i)]) : 65535u;
+            g2[i * CW + c] = g;
+            V[i * CW + c] = (uint16_t)u;
+            qp |= qv << (4 * c);
+            vm = vm < u ? vm : u;
+        }
+        qpack[i] = (qpack_t)qp;
+        Vmin[i] = (uint16_t)vm;
+    }
+
+    // ---- ring of pair-table rows: 16-byte chunk x of a stage comes from ik, 2 H_ik or thr16
+    const int ch_ik = n_pairs / 4, ch_h2 = n_pairs / 4, chunks = ch_ik + ch_h2 + n_pairs / 8;
+    const int n_instr = (chunks + 63) / 64;
+    const int my_instr = (n_instr > wave) ? (n_instr - wave + BCDM_NT / 64 - 1) / (BCDM_NT / 64) : 0;   // direct loads this wavefront issues per stage
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)ring;
+    // a wavefront issues at most BCDM_MAXI loads a stage (the host checks it): per lane the source of row 0 and the bytes
+    // from one row to the next are fixed, per wavefront the offset in the stage
+    const char* src0[BCDM_MAXI];
+    uint32_t row_step[BCDM_MAXI], lds_off[BCDM_MAXI];
+    bool on[BCDM_MAXI];
+#pragma unroll
+    for (int s2 = 0; s2 < BCDM_MAXI; ++s2) {
+        const int ii = wave + (BCDM_NT / 64) * s2, x = ii * 64 + lane;
+        on[s2] = ii < n_instr && x < chunks;
+        const int arr = (x < ch_ik) ? 0 : (x < ch_ik + ch_h2) ? 1 : 2;
+        const char* base = arr == 0 ? reinterpret_cast<const char*>(pair_ik) : arr == 1 ? reinterpret_cast<const char*>(pair_h2)
+                                                                                        : reinterpret_cast<const char*>(pair_thr);
+        src0[s2] = base + 16 * (int64_t)(arr == 0 ? x : arr == 1 ? x - ch_ik : x - ch_ik - ch_h2);
+        row_step[s2] = (uint32_t)n_pairs * (arr == 2 ? 2u : 4u);
+        lds_off[s2] = (uint32_t)(ii * 1024);
+    }
+    auto issue = [&](int t, int stage_idx) {
+        const uint32_t stage_lds = ring_lds + (uint32_t)(stage_idx * stage_bytes);
+#pragma unroll
+        for (int s2 = 0; s2 < BCDM_MAXI; ++s2) {
+            const char* src = src0[s2] + (uint64_t)row_step[s2] * (uint32_t)t;
+            const uint32_t m0v = __builtin_amdgcn_readfirstlane(stage_lds + lds_off[s2]);
+            if (on[s2])
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0v), "v"(src) : "m0", "memory");
+        }
+    };
+    const int pro = (T < nst - 1) ? T : nst - 1;
+    for (int t = 0; t < pro; ++t) issue(t, t);
+    bcdm_wait_vmem((pro - 1) * my_instr);                        // the first row has landed
+    __syncthreads();
+
+    int moves[CW];
+#pragma unroll
+    for (int c = 0; c < CW; ++c) moves[c] = 0;
+    const uint32_t valid_mask = (1u << ncol) - 1u;
+
+    int st_cur = 0, st_fill = nst - 1;                            // stage of iteration t; stage the next load goes to (that of t - 1)
+    const int steady_wait = (nst - 3) * my_instr;
+    for (int t = 0; t < T; ++t, st_cur = (st_cur + 1 == nst) ? 0 : st_cur + 1, st_fill = (st_fill + 1 == nst) ? 0 : st_fill + 1) {
+        const char* stage = ring + (size_t)st_cur * stage_bytes;
+        const uint32_t* s_ik = reinterpret_cast<const uint32_t*>(stage);
+        const float* s_h2 = reinterpret_cast<const float*>(stage + 4 * (size_t)n_pairs);
+        const uint16_t* s_thr = reinterpret_cast<const uint16_t*>(stage + 8 * (size_t)n_pairs);
+        int* my_cnt = cnt + (t & 3);
+        unsigned long long* key_t = colkey + (t & 1) * CW;
+        // level pair cidx = r_i * L + r_k of pair p for column c
+        auto score_one = [&](int c, int p, int i, int k, float hh, float ai, float ak, float gi, float gk, float hii, float hkk,
+                             int qi, int qk, int cidx, float& best_s, uint32_t& best_pay) {
+            const int ri = cidx >> BITS, rk = cidx & (L - 1);
+            const float di = ai * (float)(ri - qi), dk = ak * (float)(rk - qk);
+            const float si = di * fmaf(di, hii, gi), sk = dk * fmaf(dk, hkk, gk);
+            const float sc = fmaf(di * dk, hh, si + sk);
+            if (sc < best_s) { best_s = sc; best_pay = ((uint32_t)p << 8) | (uint32_t)(ri << 4) | (uint32_t)rk; }
+        };
+        // level pairs sub, sub + step, ... of pair p for column c in increasing order, folded into the running best
+        auto score_pair = [&](int c, int p, int sub, int step, float& best_s, uint32_t& best_pay) {
+            const uint32_t ik = s_ik[p];
+            const int i = (int)(ik & 0xffffu), k = (int)(ik >> 16);
+            const float hh = s_h2[p];
+            const float ai = a[c * n_grp + grp(i)], ak = a[c * n_grp + grp(k)];
+            const float gi = g2[i * CW + c], gk = g2[k * CW + c], hii = hd[i], hkk = hd[k];
+            const int qi = (int)((qpack[i] >> (4 * c)) & 15u), qk = (int)((qpack[k] >> (4 * c)) & 15u);
+            if (step == 1) {
+#pragma unroll
+                for (int cidx = 0; cidx < NC; ++cidx) score_one(c, p, i, k, hh, ai, ak, gi, gk, hii, hkk, qi, qk, cidx, best_s, best_pay);
+            } else {
+#pragma unroll
+                for (int m = 0; m < CPL; ++m) score_one(c, p, i, k, hh, ai, ak, gi, gk, hii, hkk, qi, qk, sub + m * LPE, best_s, best_pay);
+            }
+        };
+        auto offer = [&](int c, float best_s, uint32_t best_pay) {
+            if (best_s < 0.0f) {
+                const unsigned long long key = ((unsigned long long)order_bits(best_s) << 32) | best_pay;
+                if (key < key_t[c]) {
+                    found[t & 1] = 1;
+                    atomicMin(&key_t[c], key);
+                }
+            }
+        };
+
+        // ---- which (column, pair) need scoring
+        for (int p = tid; p < n_pairs; p += BCDM_NT) {
+            const uint32_t ik = s_ik[p];
+            const uint32_t thr = s_thr[p];
+            const int i = (int)(ik & 0xffffu), k = (int)(ik >> 16);
+            const uint32_t vi = Vmin[i], vk = Vmin[k];
+            if ((__umul24(vi, vk) >> 16) < thr || score_all) {
+                uint32_t mask = 0;
+#pragma unroll
+                for (int c = 0; c < CW; ++c) mask |= ((__umul24(V[i * CW + c], V[k * CW + c]) >> 16) < thr ? 1u : 0u) << c;
+                if (score_all) mask = ~0u;
+                mask &= valid_mask;
+                if (mask) {
+                    int pos = atomicAdd(my_cnt, __builtin_popcount(mask));
+                    while (mask) {
+                        const int c = __builtin_ctz(mask);
+                        mask &= mask - 1;
+                        if (pos < BCDM_QMAX) queue[pos] = c | (p << 4);
+                        ++pos;
+                    }
+                }
+            }
+        }
+        // the next iteration's row has landed when only the loads issued after it are pending (loads return in order);
+        // near the end fewer were issued and everything is waited for
+        if (t + nst - 1 <= T) bcdm_wait_vmem(steady_wait);
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                                         // the queue is complete, the next row visible, iteration t-1 over for everybody
+        if (t + nst - 1 < T) issue(t + nst - 1, st_fill);        // into the stage iteration t-1 read
+        if (tid == 0) { cnt[(t + 2) & 3] = 0; found[(t + 1) & 1] = 0; }
+        if (tid < CW) colkey[((t + 1) & 1) * CW + tid] = ~0ull;
+        const int n_q = *my_cnt;
+        if (n_q == 0) continue;                                  // an idle iteration costs one barrier
+
+        if (n_q <= BCDM_SPREAD) {
+            // ---- few: 16 lanes share an entry
+            for (int x = tid / LPE; x < n_q; x += BCDM_NT / LPE) {
+                const int e = queue[x];
+                float best_s = 0.0f;
+                uint32_t best_pay = 0xffffffffu;
+                score_pair(e & 15, e >> 4, tid % LPE, LPE, best_s, best_pay);
+                offer(e & 15, best_s, best_pay);
+            }
+        } else if (n_q <= BCDM_QMAX) {
+            // ---- more: an entry per thread
+            for (int x = tid; x < n_q; x += BCDM_NT) {
+                const int e = queue[x];
+                float best_s = 0.0f;
+                uint32_t best_pay = 0xffffffffu;
+                score_pair(e & 15, e >> 4, 0, 1, best_s, best_pay);
+                offer(e & 15, best_s, best_pay);
+            }
+        } else {
+            // ---- the queue overflowed: every thread scores its own pairs for every column
+            for (int c = 0; c < ncol; ++c) {
+                float best_s = 0.0f;
+                uint32_t best_pay = 0xffffffffu;
+                for (int p = tid; p < n_pairs; p += BCDM_NT) score_pair(c, p, 0, 1, best_s, best_pay);
+                const uint64_t key = wave_min_key(order_bits(best_s), best_pay);
+                if (lane == 0 && (uint32_t)(key >> 32) < kOrderedZero) {
+                    found[t & 1] = 1;
+                    atomicMin(&key_t[c], (unsigned long long)key);
+                }
+            }
+        }
+        __syncthreads();                                         // the columns' keys are final
+        if (found[t & 1] == 0) continue;                         // scored, no move: two barriers
+        // ---- commit: every thread derives the moves, then updates its own coordinates of 2g, V and Vmin
+        bool any = false;
+#pragma unroll
+        for (int c = 0; c < CW; ++c) {
+            const unsigned long long key = key_t[c];
+            if (c < ncol && (uint32_t)(key >> 32) < kOrderedZero) {
+                any = true;
+                const uint32_t pay = (uint32_t)key;
+                const int p = (int)(pay >> 8), ri = (int)((pay >> 4) & 15u), rk = (int)(pay & 15u);
+                const uint32_t ik = s_ik[p];
+                const int i = (int)(ik & 0xffffu), k = (int)(ik >> 16);
+                const float di2 = 2.0f * (a[c * n_grp + grp(i)] * (float)(ri - (int)((qpack[i] >> (4 * c)) & 15u)));
+                const float dk2 = 2.0f * (a[c * n_grp + grp(k)] * (float)(rk - (int)((qpack[k] >> (4 * c)) & 15u)));
+                const float* hi = H + (int64_t)i * d_in;
+                const float* hk = H + (int64_t)k * d_in;
+                for (int x = tid; x < d_in; x += BCDM_NT) {
+                    const float g = fmaf(dk2, hk[x], fmaf(di2, hi[x], g2[x * CW + c]));
+                    g2[x * CW + c] = g;
+                    V[x * CW + c] = (uint16_t)bcdm_v16(g, hd[x], a[c * n_grp + grp(x)]);
+                }
+            }
+        }
+        if (any)
+            for (int x = tid; x < d_in; x += BCDM_NT) {
+                uint32_t vm = 65535u;
+#pragma unroll
+                for (int c = 0; c < CW; ++c) { const uint32_t v = V[x * CW + c]; vm = vm < v ? vm : v; }
+                Vmin[x] = (uint16_t)vm;
+            }
+        __syncthreads();                                         // 2g, V, Vmin are updated and everybody has read the old codes
+        if (any) {
+#pragma unroll
+            for (int c = 0; c < CW; ++c) {
+                const unsigned long long key = key_t[c];
+                if (c < ncol && (uint32_t)(key >> 32) < kOrderedZero) {
+                    if (tid == 0) {
+                        const uint32_t pay = (uint32_t)key;
+                        const uint32_t ik = s_ik[pay >> 8];
+                        const int i = (int)(ik & 0xffffu), k = (int)(ik >> 16);
+                        qpack[i] = (qpack_t)((qpack[i] & ~(15u << (4 * c))) | (((pay >> 4) & 15u) << (4 * c)));
+                        qpack[k] = (qpack_t)((qpack[k] & ~(15u << (4 * c))) | ((pay & 15u) << (4 * c)));
+                        if (trace != nullptr && moves[c] < trace_cap) {
+                            int32_t* tr = trace + ((int64_t)(j0 + c) * trace_cap + moves[c]) * 4;
+                            tr[0] = t; tr[1] = (int32_t)(pay >> 8);
+                            tr[2] = (int32_t)(((pay >> 4) & 15u) | ((pay & 15u) << 4));
+                            tr[3] = (int32_t)~(uint32_t)(key >> 32);       // the ordered image of a negative score is ~bits
+                        }
+                    }
+                    ++moves[c];
+                }
+            }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int c = 0; c < ncol; ++c)
+        for (int i = tid; i < d_in; i += BCDM_NT) {
+            Q[(int64_t)(j0 + c) * d_in + i] = (uint8_t)((qpack[i] >> (4 * c)) & 15u);
+            if (G_out != nullptr) G_out[(int64_t)(j0 + c) * d_in + i] = 0.5f * g2[i * CW + c];
+        }
+    if (tid == 0 && moves_out != nullptr) {
+#pragma unroll
+        for (int c = 0; c < CW; ++c)
+            if (c < ncol) moves_out[j0 + c] = moves[c];
+    }
+}
+
+size_t bcdm_lds_bytes(int64_t d_in, int64_t group, int cw, int nst) {
+    const int64_t n_grp = d_in / group, n_pairs = d_in / 2;
+    return cdq_align_up((size_t)d_in * cw * 6 + (size_t)d_in * (cw <= 2 ? 7 : 10) + (size_t)nst * 10 * n_pairs + 4 * BCDM_QMAX +
+                        sizeof(unsigned long long) * 2 * cw + sizeof(float) * cw * n_grp + sizeof(int) * 8, 16);
+}
+
 size_t bcd_lds_bytes(int64_t d_in, int64_t group) {
     const int64_t n_grp = d_in / group;
     return cdq_align_up(sizeof(float) * 3 * d_in + 16 * BCD_FASTQ + sizeof(uint64_t) * 32 + sizeof(float) * 8 + sizeof(int) * 4 +
@@ -303,7 +664,8 @@ size_t bcd_workspace_bytes(int64_t d_out, int64_t d_in, int64_t T) {
 
 int bcd_launch(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out, int64_t d_in,
                int bits, int64_t group, const int32_t* parts, int64_t T, int32_t* moves, float* G_out, int32_t* trace,
-               int64_t trace_cap, bool score_all, void* ws, size_t ws_bytes, hipStream_t st) {
+               int64_t trace_cap, int flags, void* ws, size_t ws_bytes, hipStream_t st) {
+    const bool score_all = (flags & 1) != 0, single = (flags & 2) != 0;
     if (d_out == 0 || T == 0) {
         if (T == 0 && d_out > 0 && moves != nullptr) {
             hipLaunchKernelGGL(bcd_fill_i32_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, moves, d_out, 0);
@@ -333,9 +695,48 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
     rc = extract_diag_launch(H, d_in, hdiag, st);
     if (rc != CDQ_OK) return rc;
     const int64_t n_items = T * (d_in / 2);
-    hipLaunchKernelGGL(bcd_pair_gather_kernel, dim3((unsigned)((n_items + 255) / 256)), dim3(256), 0, st, H, parts,
-                       (const int32_t*)bad, d_in, n_items, pair_rec, pair_h2);
+    // several columns per workgroup where the columns' state and at least three pair-table rows fit in LDS
+    int cw = 0, nst = 0;
+    if (d_in % 16 == 0 && 5 * d_in / 16 <= BCDM_NT * BCDM_MAXI && !single)        // a row is 5 d_in / 16 chunks of 16 bytes
+        for (int c : {8, 4, 2}) {
+            const size_t fixed = bcdm_lds_bytes(d_in, group, c, 0);
+            if (fixed >= 160 * 1024) continue;
+            const int64_t fit = (int64_t)((160 * 1024 - fixed) / (10 * (size_t)(d_in / 2)));
+            if (fit < 3) continue;
+            cw = c;
+            nst = fit > 6 ? 6 : (int)fit;
+            break;
+        }
+    if (cw != 0) {
+        hipLaunchKernelGGL(bcdm_pair_gather_kernel, dim3((unsigned)((n_items + 255) / 256)), dim3(256), 0, st, H, parts,
+                           (const int32_t*)bad, d_in, n_items, (uint32_t*)pair_rec, (uint16_t*)((char*)pair_rec + 4 * n_items), pair_h2);
+    } else {
+        hipLaunchKernelGGL(bcd_pair_gather_kernel, dim3((unsigned)((n_items + 255) / 256)), dim3(256), 0, st, H, parts,
+                           (const int32_t*)bad, d_in, n_items, pair_rec, pair_h2);
+    }
     CDQ_LAUNCH_CHECK();
+    if (cw != 0) {
+        const size_t mlds = bcdm_lds_bytes(d_in, group, cw, nst);
+        const int tc = (int)(trace_cap > 0x7fffffffLL ? 0x7fffffffLL : trace_cap);
+        const dim3 grid((unsigned)((d_out + cw - 1) / cw));
+#define BCDM_CASE(B, C)                                                                                                          \
+    if (bits == B && cw == C) {                                                                                                  \
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(bcd2_multi_kernel<B, C>), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                (int)mlds) != hipSuccess)                                                                        \
+            return CDQ_EHIP;                                                                                                     \
+        hipLaunchKernelGGL((bcd2_multi_kernel<B, C>), grid, dim3(BCDM_NT), mlds, st, H, (const float*)hdiag, (const float*)G0,    \
+                           scale, Q, (const uint32_t*)pair_rec, (const uint16_t*)((char*)pair_rec + 4 * n_items),                \
+                           (const float*)pair_h2, (const int32_t*)bad, (int)d_out, (int)d_in,                                    \
+                           (int)group, (int)T, nst, score_all ? 1 : 0, moves, G_out, trace, tc);                                 \
+        CDQ_LAUNCH_CHECK();                                                                                                      \
+        return CDQ_OK;                                                                                                           \
+    }
+        BCDM_CASE(2, 8) BCDM_CASE(2, 4) BCDM_CASE(2, 2)
+        BCDM_CASE(3, 8) BCDM_CASE(3, 4) BCDM_CASE(3, 2)
+        BCDM_CASE(4, 8) BCDM_CASE(4, 4) BCDM_CASE(4, 2)
+#undef BCDM_CASE
+        return CDQ_EINVAL;
+    }
 #define BCD_CASE(B)                                                                                                              \
     case B:                                                                                                                      \
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(bcd2_kernel<B>), hipFuncAttributeMaxDynamicSharedMemorySize,       \

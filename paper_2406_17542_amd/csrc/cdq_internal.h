@@ -51,7 +51,7 @@ size_t owc_cd_workspace_bytes(int64_t d_out, int64_t d_in);
 size_t bcd_workspace_bytes(int64_t d_out, int64_t d_in, int64_t T);
 int bcd_launch(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out, int64_t d_in,
                int bits, int64_t group, const int32_t* parts, int64_t T, int32_t* moves, float* G_out, int32_t* trace,
-               int64_t trace_cap, bool score_all, void* ws, size_t ws_bytes, hipStream_t st);
+               int64_t trace_cap, int flags, void* ws, size_t ws_bytes, hipStream_t st);
 
 // ---- cyclic.hip
 size_t cyclic_workspace_bytes(int64_t d_out, int64_t d_in);

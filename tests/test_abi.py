@@ -85,11 +85,12 @@ def test_argument_checks_of_the_wider_entry_points(L):
     assert L.cdq_init_owc_cd(p, p, 4, 256, 3, 64, 50, 4, p, p, p, n, n, n, 0, 0, n, 0, n) == EWS         # tiled kernel needs G64
     assert L.cdq_init_owc_cd(p, p, 4, 65536, 3, 128, 50, 4, p, p, p, n, n, n, 0, 1, n, 0, n) == EUNSUP   # state does not fit LDS
     assert cdq.workspace_bytes(cdq.OP_INIT_OWC_CD, 0, 16, 256) >= 16 * 256 * 8
-    # cdq_bcd(H, Wt, scale, zero, Q, d_out, d_in, bits, group, k, parts, T, moves, G_out, trace, trace_cap, score_all, ws, ws_bytes, stream)
+    # cdq_bcd(H, Wt, scale, zero, Q, d_out, d_in, bits, group, k, parts, T, moves, G_out, trace, trace_cap, flags, ws, ws_bytes, stream)
     assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 0, p, 8, n, n, n, 0, 0, p, 1 << 30, n) == EINVAL     # k < 1
     assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 3, p, 8, n, n, n, 0, 0, p, 1 << 30, n) == EUNSUP     # only pairs are built
     assert L.cdq_bcd(p, p, p, p, p, 4, 255, 3, 255, 2, p, 8, n, n, n, 0, 0, p, 1 << 30, n) == EINVAL     # odd d_in
     assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 2, n, 8, n, n, n, 0, 0, p, 1 << 30, n) == EINVAL     # no partitions
+    assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 2, p, 8, n, n, n, 0, 4, p, 1 << 30, n) == EINVAL     # unknown flag bit
     assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 2, p, 8, n, n, n, 0, 0, n, 0, n) == EWS
     assert L.cdq_bcd(p, p, p, p, p, 4, 16384, 3, 16384, 2, p, 8, n, n, n, 0, 0, p, 1 << 40, n) == EUNSUP # more than 4 pairs per thread
     assert cdq.workspace_bytes(cdq.OP_BCD, 8, 4, 256) >= 4 * 256 * 4 + 8 * 128 * 12

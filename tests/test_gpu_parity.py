@@ -234,11 +234,12 @@ def bcd_moves_from_gpu(trace_j):
 @pytest.mark.parametrize("d_out,d_in,n,bits,group,T,start", [
     (24, 128, 400, 2, 128, 160, "random"), (16, 256, 700, 3, 64, 200, "random"), (10, 64, 300, 4, 16, 100, "random"),
     (12, 512, 1200, 3, 512, 300, "cd"), (9, 136, 400, 2, 8, 80, "random"), (6, 2048, 4096, 2, 128, 64, "rtn"),
-    (5, 4096, 6000, 3, 4096, 24, "rtn")])
-@pytest.mark.parametrize("score_all", [False, True])
-def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start, score_all):
+    (5, 4096, 6000, 3, 4096, 24, "rtn"), (6, 3072, 4000, 3, 128, 16, "rtn")])
+@pytest.mark.parametrize("score_all,single_column", [(False, False), (True, False), (False, True), (True, True)])
+def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start, score_all, single_column):
     """Same partitions on both sides: the trajectories (iteration, block, levels, score bits), the final codes, the
-    move counts and the maintained gradient are equal bit for bit."""
+    move counts and the maintained gradient are equal bit for bit, for the kernel that gives a workgroup several
+    columns and the one-column kernel, with and without the test that skips pairs."""
     X, Wt = rand_layer(31 + d_in + bits, d_in, d_out, n, corr=0.7)
     H32 = oracle.hessian(X).astype(np.float32)
     a, b, q_rtn = oracle.init_grid(Wt, bits, group)
@@ -251,7 +252,8 @@ def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start, score
     parts = inputs.make_partitions(T, d_in, seed=d_in + 1)
     ref = oracle.bcd(H32, Wt, a, b, q0, parts, bits, group, k=2, trace_cap=T)
     Q = dev(q0)
-    out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, bits, group, dev(parts), trace_cap=T, want_G=True, score_all=score_all)
+    out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, bits, group, dev(parts), trace_cap=T, want_G=True, score_all=score_all,
+                  single_column=single_column)
     moves = out["moves"].cpu().numpy()
     trace = out["trace"].cpu().numpy()
     assert ref["moves"].sum() > 0
