@@ -53,28 +53,35 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
     float g2[E], hd[E], cinv[E], a_c[NCH];
     uint32_t qpack[NCH];
 
+    // lanes past the end of the column load from its start and then zero what they loaded: no load sits in a divergent
+    // branch, so all of them are in flight together
+    float gl[E], hl[E];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int base = c * STRIDE + tid * VEC;
-        const bool valid = base < d_in;
-        float a = 1.0f;
-        uint32_t qp = 0;
-        if (valid) {
-            const int gi = (n_grp == 1) ? 0 : (group_shift >= 0 ? (base >> group_shift) : (base / group));
-            a = scale_j[gi];
-            if (VEC == 4) qp = *reinterpret_cast<const uint32_t*>(Qj + base);
-            else qp = Qj[base];
+        const int b = base < d_in ? base : 0;
+        const int gi = (n_grp == 1) ? 0 : (group_shift >= 0 ? (b >> group_shift) : (b / group));
+        a_c[c] = scale_j[gi];
+        if constexpr (VEC == 4) {
+            qpack[c] = *reinterpret_cast<const uint32_t*>(Qj + b);
+            const float4 g4 = *reinterpret_cast<const float4*>(G0j + b), h4 = *reinterpret_cast<const float4*>(hdiag + b);
+            gl[c * 4 + 0] = g4.x; gl[c * 4 + 1] = g4.y; gl[c * 4 + 2] = g4.z; gl[c * 4 + 3] = g4.w;
+            hl[c * 4 + 0] = h4.x; hl[c * 4 + 1] = h4.y; hl[c * 4 + 2] = h4.z; hl[c * 4 + 3] = h4.w;
+        } else {
+            qpack[c] = Qj[b];
+            gl[c] = G0j[b];
+            hl[c] = hdiag[b];
         }
-        a_c[c] = a;
-        qpack[c] = qp;
+    }
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const bool valid = c * STRIDE + tid * VEC < d_in;
+        if (!valid) { a_c[c] = 1.0f; qpack[c] = 0; }
+        const float a = a_c[c];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             const int e = c * VEC + v;
-            float g = 0.0f, h = 0.0f;
-            if (valid) {
-                g = G0j[base + v];
-                h = hdiag[base + v];
-            }
+            const float g = valid ? gl[e] : 0.0f, h = valid ? hl[e] : 0.0f;
             g2[e] = 2.0f * g;
             hd[e] = h;
             // reciprocal of the parabola's curvature; only steers which levels are scored
@@ -175,20 +182,32 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
 #pragma unroll
         for (int c = 0; c < NCH; ++c) qpack[c] += (c == cstar) ? inc : 0u;
 
+        // all loads of the row first (lanes past the end read the row's start and add nothing), so that the
+        // chunks' memory latencies overlap instead of following one another
+        if constexpr (VEC == 4) {
+            float4 hv[NCH];
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            const int base = c * STRIDE + tid * VEC;
-            if (base < d_in) {
-                if (VEC == 4) {
-                    const float4 hv = hrow4[base >> 2];
-                    g2[c * 4 + 0] = fmaf(delta2, hv.x, g2[c * 4 + 0]);
-                    g2[c * 4 + 1] = fmaf(delta2, hv.y, g2[c * 4 + 1]);
-                    g2[c * 4 + 2] = fmaf(delta2, hv.z, g2[c * 4 + 2]);
-                    g2[c * 4 + 3] = fmaf(delta2, hv.w, g2[c * 4 + 3]);
-                } else {
-                    g2[c] = fmaf(delta2, hrow[base], g2[c]);
-                }
+            for (int c = 0; c < NCH; ++c) {
+                const int base = c * STRIDE + tid * VEC;
+                hv[c] = hrow4[(base < d_in ? base : 0) >> 2];
             }
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const float m = (c * STRIDE + tid * VEC < d_in) ? delta2 : 0.0f;
+                g2[c * 4 + 0] = fmaf(m, hv[c].x, g2[c * 4 + 0]);
+                g2[c * 4 + 1] = fmaf(m, hv[c].y, g2[c * 4 + 1]);
+                g2[c * 4 + 2] = fmaf(m, hv[c].z, g2[c * 4 + 2]);
+                g2[c * 4 + 3] = fmaf(m, hv[c].w, g2[c * 4 + 3]);
+            }
+        } else {
+            float hv[NCH];
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int base = c * STRIDE + tid;
+                hv[c] = hrow[base < d_in ? base : 0];
+            }
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) g2[c] = fmaf((c * STRIDE + tid < d_in) ? delta2 : 0.0f, hv[c], g2[c]);
         }
         if (trace != nullptr && tid == 0 && moves < trace_cap) trace[j * trace_cap + moves] = (int32_t)(klo >> 1);
         last_hi = khi;
