@@ -410,9 +410,18 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
     for (int i = tid; i < d_in; i += BCDM_NT) {                             // a thread owns coordinate i in all columns
         uint32_t qp = 0, vm = 65535u;
         const float h = hd[i];
+        float gl[CW];
+        uint32_t ql[CW];
+#pragma unroll
+        for (int c = 0; c < CW; ++c) {                                      // columns past the end load column 0: every load is in flight at once
+            const int64_t col = j0 + (c < ncol ? c : 0);
+            gl[c] = G0[col * d_in + i];
+            ql[c] = Q[col * d_in + i];
+        }
+#pragma unroll
         for (int c = 0; c < CW; ++c) {
-            const float g = (c < ncol) ? 2.0f * G0[(int64_t)(j0 + c) * d_in + i] : 0.0f;
-            const uint32_t qv = (c < ncol) ? Q[(int64_t)(j0 + c) * d_in + i] : 0u;
+            const float g = (c < ncol) ? 2.0f * gl[c] : 0.0f;
+            const uint32_t qv = (c < ncol) ? ql[c] : 0u;
             const uint32_t u = (c < ncol) ? bcdm_v16(g, h, a[c * n_grp + grp(i)]) : 65535u;
             g2[i * CW + c] = g;
             V[i * CW + c] = (uint16_t)u;
