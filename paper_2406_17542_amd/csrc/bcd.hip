@@ -318,6 +318,9 @@ constexpr int BCDM_QMAX = 512;      // queued entries (column | pair << 4), 4 by
 constexpr int BCDM_SPREAD = 128;    // up to this many entries, 16 lanes share an entry's level pairs
 constexpr int BCDM_MAXI = 3;        // direct loads of 1 KiB a wavefront issues per pair-table row, at most
 
+// coordinates per thread the kernel is built for; more than the LDS can hold for that many columns (checked again by the host)
+constexpr int bcdm_xpt(int cw) { return (cw == 8 ? 3 : cw == 4 ? 4 : 5) * (1024 / BCDM_NT); }
+
 __device__ __forceinline__ void bcdm_wait_vmem(int n) {       // at most n of this wavefront's vector-memory operations pending
     switch (n) {
         case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
@@ -333,10 +336,11 @@ __device__ __forceinline__ void bcdm_wait_vmem(int n) {       // at most n of th
     }
 }
 
-// v = 1 - u - tau in units of 2^-16 (tau is 4 of them), rounded DOWN by more than one unit; 0 when u is not a number below 0.99
+// v = 1 - u - tau in units of 2^-16 (tau is 4 of them), rounded DOWN by more than one unit; 0 when u is not a number
+// below 1 - 10 units
 __device__ __forceinline__ uint32_t bcdm_v16(float g2, float h, float a) {
     const float u = __fdiv_rn(fabsf(g2), h * a);
-    return (u >= 0.0f && u < 0.99f) ? 65530u - (uint32_t)(u * 65536.0f) : 0u;
+    return (u >= 0.0f && u < 0.99985f) ? 65530u - (uint32_t)(u * 65536.0f) : 0u;
 }
 
 // pair-table rows for the kernel above: ik [T][n_pairs] u32, R [T][n_pairs] u16 = rho^2 in units of 2^-16 rounded UP by more than
@@ -371,6 +375,7 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
                                                              int32_t* __restrict__ moves_out, float* __restrict__ G_out,
                                                              int32_t* __restrict__ trace, int trace_cap) {
     constexpr int L = 1 << BITS, NC = L * L;
+    constexpr int XPT = bcdm_xpt(CW);                                       // coordinates a thread owns at most
     constexpr int LPE = 16, CPL = NC / LPE;                                 // lanes per entry and level pairs per lane when an entry is shared
     static_assert(NC % LPE == 0, "at least 2 bits");
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -393,7 +398,8 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
     float* a = reinterpret_cast<float*>(colkey + 2 * CW);                   // [CW][n_grp]
     int* cnt = reinterpret_cast<int*>(a + CW * n_grp);                      // [4] ring of queue lengths
     int* found = cnt + 4;                                                   // [2] set when a column offered a move; [2] spare
-    uint16_t* Vmin = reinterpret_cast<uint16_t*>(cnt + 8);                  // [d_in]
+    int* moves = cnt + 8;                                                   // [8] committed moves per column, written by thread 0
+    uint16_t* Vmin = reinterpret_cast<uint16_t*>(cnt + 16);                 // [d_in]
 
     if (*bad_parts != 0) {                                                  // invalid partitions: leave the columns untouched
         if (tid < ncol && moves_out != nullptr) moves_out[j0 + tid] = -1;
@@ -403,7 +409,7 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
         const int c = x / n_grp;
         a[x] = (c < ncol) ? scale[(int64_t)(j0 + c) * n_grp + x % n_grp] : 1.0f;
     }
-    if (tid < 8) cnt[tid] = 0;
+    if (tid < 16) cnt[tid] = 0;
     if (tid < 2 * CW) colkey[tid] = ~0ull;
     for (int i = tid; i < d_in; i += BCDM_NT) hd[i] = hdiag[i];
     __syncthreads();
@@ -468,9 +474,6 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
     bcdm_wait_vmem((pro - 1) * my_instr);                        // the first row has landed
     __syncthreads();
 
-    int moves[CW];
-#pragma unroll
-    for (int c = 0; c < CW; ++c) moves[c] = 0;
     const uint32_t valid_mask = (1u << ncol) - 1u;
 
     int st_cur = 0, st_fill = nst - 1;                            // stage of iteration t; stage the next load goes to (that of t - 1)
@@ -586,10 +589,9 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
         if (found[t & 1] == 0) continue;                         // scored, no move: two barriers
         // ---- commit: every thread derives the moves, then updates its own coordinates of 2g, V and Vmin
         bool any = false;
-#pragma unroll
-        for (int c = 0; c < CW; ++c) {
+        for (int c = 0; c < ncol; ++c) {                       // a loop, not unrolled: moves are rare and the code is long
             const unsigned long long key = key_t[c];
-            if (c < ncol && (uint32_t)(key >> 32) < kOrderedZero) {
+            if ((uint32_t)(key >> 32) < kOrderedZero) {
                 any = true;
                 const uint32_t pay = (uint32_t)key;
                 const int p = (int)(pay >> 8), ri = (int)((pay >> 4) & 15u), rk = (int)(pay & 15u);
@@ -599,13 +601,27 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
                 const float dk2 = 2.0f * (a[c * n_grp + grp(k)] * (float)(rk - (int)((qpack[k] >> (4 * c)) & 15u)));
                 const float* hi = H + (int64_t)i * d_in;
                 const float* hk = H + (int64_t)k * d_in;
-                for (int x = tid; x < d_in; x += BCDM_NT) {
-                    const float g = fmaf(dk2, hk[x], fmaf(di2, hi[x], g2[x * CW + c]));
-                    g2[x * CW + c] = g;
-                    V[x * CW + c] = (uint16_t)bcdm_v16(g, hd[x], a[c * n_grp + grp(x)]);
+                float hiv[XPT], hkv[XPT];                       // both rows' loads in flight together (d_in <= XPT * BCDM_NT here)
+#pragma unroll
+                for (int xx = 0; xx < XPT; ++xx) {
+                    const int x = tid + xx * BCDM_NT, xc = x < d_in ? x : 0;
+                    hiv[xx] = hi[xc];
+                    hkv[xx] = hk[xc];
+                }
+#pragma unroll
+                for (int xx = 0; xx < XPT; ++xx) {
+                    const int x = tid + xx * BCDM_NT;
+                    if (x < d_in) {
+                        const float g = fmaf(dk2, hkv[xx], fmaf(di2, hiv[xx], g2[x * CW + c]));
+                        g2[x * CW + c] = g;
+                        V[x * CW + c] = (uint16_t)bcdm_v16(g, hd[x], a[c * n_grp + grp(x)]);
+                    }
                 }
             }
         }
+        // every load of the commit has landed (a load whose result a thread did not use would otherwise count as
+        // pending at the loop head and make the compiler wait for vector memory, and with it for the ring's loads)
+        __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0) only
         if (any)
             for (int x = tid; x < d_in; x += BCDM_NT) {
                 uint32_t vm = 65535u;
@@ -614,12 +630,11 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
                 Vmin[x] = (uint16_t)vm;
             }
         __syncthreads();                                         // 2g, V, Vmin are updated and everybody has read the old codes
-        if (any) {
-#pragma unroll
-            for (int c = 0; c < CW; ++c) {
+        if (any && tid == 0) {
+            for (int c = 0; c < ncol; ++c) {
                 const unsigned long long key = key_t[c];
-                if (c < ncol && (uint32_t)(key >> 32) < kOrderedZero) {
-                    if (tid == 0) {
+                if ((uint32_t)(key >> 32) < kOrderedZero) {
+                    {
                         const uint32_t pay = (uint32_t)key;
                         const uint32_t ik = s_ik[pay >> 8];
                         const int i = (int)(ik & 0xffffu), k = (int)(ik >> 16);
@@ -654,7 +669,7 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
 size_t bcdm_lds_bytes(int64_t d_in, int64_t group, int cw, int nst) {
     const int64_t n_grp = d_in / group, n_pairs = d_in / 2;
     return cdq_align_up((size_t)d_in * cw * 6 + (size_t)d_in * (cw <= 2 ? 7 : 10) + (size_t)nst * 10 * n_pairs + 4 * BCDM_QMAX +
-                        sizeof(unsigned long long) * 2 * cw + sizeof(float) * cw * n_grp + sizeof(int) * 8, 16);
+                        sizeof(unsigned long long) * 2 * cw + sizeof(float) * cw * n_grp + sizeof(int) * 16, 16);
 }
 
 size_t bcd_lds_bytes(int64_t d_in, int64_t group) {
@@ -711,7 +726,7 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
             const size_t fixed = bcdm_lds_bytes(d_in, group, c, 0);
             if (fixed >= 160 * 1024) continue;
             const int64_t fit = (int64_t)((160 * 1024 - fixed) / (10 * (size_t)(d_in / 2)));
-            if (fit < 3) continue;
+            if (fit < 3 || d_in > (int64_t)bcdm_xpt(c) * BCDM_NT) continue;
             cw = c;
             nst = fit > 6 ? 6 : (int)fit;
             break;
