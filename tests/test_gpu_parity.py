@@ -268,6 +268,22 @@ def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start, score
     assert np.array_equal(out["G"].cpu().numpy(), ref["G"])
 
 
+@pytest.mark.parametrize("T", [1, 2, 3, 5, 7])
+def test_bcd_few_iterations(cdq, oracle, T):
+    """Fewer iterations than the kernel's ring of partition rows has stages (its start-up and drain paths)."""
+    X, Wt = rand_layer(77, 256, 11, 600, corr=0.5)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, _ = oracle.init_grid(Wt, 3, 256)
+    q0 = inputs.make_random_codes(11, 256, 3, seed=T)
+    parts = inputs.make_partitions(T, 256, seed=T)
+    ref = oracle.bcd(H32, Wt, a, b, q0, parts, 3, 256, k=2)
+    for single in (False, True):
+        Q = dev(q0)
+        out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, 256, dev(parts), single_column=single)
+        assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), single
+        assert np.array_equal(Q.cpu().numpy(), ref["Q"]), single
+
+
 def test_bcd_rejects_bad_partitions_and_block_sizes(cdq, oracle):
     X, Wt = rand_layer(5, 64, 4, 200)
     H32 = oracle.hessian(X).astype(np.float32)
