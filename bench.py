@@ -331,7 +331,11 @@ def main():
                     "frac_of_measured_mfma_only": (h_tflops_exec / achievable["mfma_bf16_only_TFLOPs"])
                     if cfg.x_dtype == "bf16" and "mfma_bf16_only_TFLOPs" in achievable else None},
         "fp64_gemm": {"gradient_init_tflops": 2.0 * cfg.d_out * cfg.d_in * cfg.d_in / (stages["cd_gradient_init"] * 1e-3) * 1e-12,
-                      "loss_tflops": 2.0 * cfg.d_out * cfg.d_in * cfg.d_in / (stages["loss"] * 1e-3) * 1e-12, "mfma_f64_peak_tflops": 78.6},
+                      # the loss multiplies only the 128-wide blocks of H on and above the diagonal (H is symmetric)
+                      "loss_tflops_executed": 2.0 * cfg.d_out * 128.0 * 128.0 * sum(range(1, (cfg.d_in + 127) // 128 + 1))
+                      / (stages["loss"] * 1e-3) * 1e-12,
+                      "loss_tflops_effective": 2.0 * cfg.d_out * cfg.d_in * cfg.d_in / (stages["loss"] * 1e-3) * 1e-12,
+                      "mfma_f64_peak_tflops": 78.6},
         "loss_final": loss_final,
         "achievable": achievable,
     }

@@ -120,7 +120,8 @@ int cdq_init_rtn(const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t
  * Needs group == d_in (one clipping strength per column), else CDQ_EUNSUPPORTED.
  *   scale, zero [d_out] out; Q [d_out][d_in] out; gamma_out NULL or [d_out] fp32;
  *   loss_out NULL or [d_out] fp64 (loss of the chosen grid).
- * Cost: n_gamma passes of the loss kernel (2 d_out d_in^2 fp64 FLOP each).
+ * Cost: n_gamma passes of the loss kernel (d_out d_in^2 fp64 FLOP each: H is taken to be symmetric
+ * and only its blocks on and above the diagonal are multiplied, see cdq_loss).
  */
 int cdq_init_owc(const float *H, const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t group,
                  int n_gamma, float *scale, float *zero, uint8_t *Q, float *gamma_out, double *loss_out,
@@ -254,6 +255,8 @@ int cdq_greedy_cd_stepwise(const float *H, const float *Wt, const float *scale, 
 /*
  * Layer loss of Eq. (1) from the codes: loss_per_col[j] = e_j^T H e_j, loss_total = sum_j
  * (= ||X (W - W_hat)||_F^2).  fp32 inputs, fp64 accumulation, fixed summation order.
+ * H is taken to be symmetric, as cdq_hessian writes it: only its 128 x 128 blocks on and above
+ * the diagonal are read, those above counted twice.
  *   loss_per_col  NULL or [d_out] fp64 out;  loss_total  NULL or one fp64 out (device).
  */
 int cdq_loss(const float *H, const float *Wt, const float *scale, const float *zero,

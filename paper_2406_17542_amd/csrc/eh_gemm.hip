@@ -1,7 +1,12 @@
 // C = E * H for all output columns, E = scale*Q + zero - Wt formed on the fly, fp32 data with
 // fp64 accumulation on the matrix cores (v_mfma_f64_16x16x4_f64).  Two epilogues:
 //   gradient: G[j][k] = (float) C[j][k]            -- Algorithm 1, "Compute gradient" (weight space)
-//   loss:     partial[j][tile] = sum_k C[j][k]*E[j][k] over the tile's columns -- Eq. (1) as e^T H e
+//   loss:     partial[j][item] = sum_k C[j][k]*E[j][k] over the item's columns -- Eq. (1) as e^T H e.
+//             H is symmetric, so only the blocks on and above its diagonal are multiplied: with 128-wide
+//             blocks, e^T H e = sum_cb ( 2 sum_{kb<cb} e[kb]^T H[kb,cb] e[cb] + e[cb]^T H[cb,cb] e[cb] ),
+//             half the matrix-core work.  A work item is (128 columns j) x (column block cb) x (a chunk
+//             of the contraction range [0, (cb+1)*128) that does not straddle the diagonal block's start);
+//             the doubling is exact in fp64.  Chunks make the items of a small layer equally long.
 // fp64 accumulation keeps the one rounding to fp32 reproducible: the result differs from a
 // sequential fp64 sum only when that sum lies within ~1e-16 relative of a rounding boundary.
 //
@@ -58,7 +63,8 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
                                                      const float* __restrict__ scale, const float* __restrict__ zero,
                                                      const uint8_t* __restrict__ Q, int64_t d_out, int64_t d_in,
                                                      int64_t group, float* __restrict__ G,
-                                                     double* __restrict__ partial, int n_tiles, double* __restrict__ G64) {
+                                                     double* __restrict__ partial, int n_items, int chunk_blocks,
+                                                     double* __restrict__ G64) {
     // two stages of As[k][m] = E[m0+m][k0+k] and Bs[k][n] = H[k0+k][n0+n]: the next step's tiles are written
     // while the current ones are multiplied, one barrier per step
     extern __shared__ __attribute__((aligned(16))) char eh_smem[];
@@ -68,8 +74,29 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
-    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    // loss: consecutive workgroups take the same item for consecutive column tiles (they share the H blocks, and the
+    // longest items of all column tiles start first); gradient: x = column block of H, y = column tile
+    const int64_t m0 = (int64_t)(LOSS ? blockIdx.x : blockIdx.y) * BM;
     const int64_t n_grp = d_in / group;
+    // gradient: item = column block, whole contraction range.  loss: decode (column block, chunk) from the item index;
+    // column blocks are laid out from the last (longest range) to the first
+    int64_t n0 = (int64_t)blockIdx.x * BN, k_begin = 0, k_end = d_in;
+    bool has_diag = false;
+    if (LOSS) {
+        const int n_cb = (int)((d_in + BN - 1) / BN);
+        int item = (int)blockIdx.y, cb = n_cb - 1;
+        while (true) {
+            const int items_cb = (cb + chunk_blocks) / chunk_blocks;        // ceil((cb + 1) / chunk_blocks)
+            if (item < items_cb) break;
+            item -= items_cb;
+            --cb;
+        }
+        n0 = (int64_t)cb * BN;
+        k_begin = (int64_t)item * chunk_blocks * BN;
+        k_end = k_begin + (int64_t)chunk_blocks * BN;
+        if (k_end >= n0 + BN) { k_end = n0 + BN; has_diag = true; }
+        if (k_end > d_in) k_end = d_in;
+    }
 
     d4 acc[2][2];
 #pragma unroll
@@ -148,13 +175,19 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
             *reinterpret_cast<float4*>(&Bs[st][32 * p + b_row][b_col]) = make_float4(rb[p][0], rb[p][1], rb[p][2], rb[p][3]);
         }
     };
-    load_tiles(0);
+    load_tiles(k_begin);
     store_tiles(0);
     __syncthreads();
     int st = 0;
-    for (int64_t k0 = 0; k0 < d_in; k0 += BK) {
-        const bool more = k0 + BK < d_in;
+    for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+        const bool more = k0 + BK < k_end;
         if (more) load_tiles(k0 + BK);
+        if (LOSS && has_diag && k0 == n0 && k0 > k_begin) {      // what came from above the diagonal block counts twice
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = acc[i][j] * 2.0;
+        }
 #pragma unroll
         for (int ks = 0; ks < BK; ks += 4) {
             double a[2], b[2];
@@ -214,24 +247,40 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
                 }
                 // sum over the 16 lanes that share this row (fixed butterfly order)
                 for (int o = 8; o; o >>= 1) s += __shfl_xor(s, o);
-                if (c_in == 0) red[wn][lrow] = s;
+                if (c_in == 0) red[wn][lrow] = has_diag ? s : 2.0 * s;
             }
         __syncthreads();
         if (tid < BM) {
             const int64_t row = m0 + tid;
-            if (row < d_out) partial[row * n_tiles + blockIdx.x] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+            if (row < d_out) partial[row * n_items + blockIdx.y] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
         }
     }
 }
 
-// loss_per_col[j] = sum over tiles in ascending order; optional total over columns by one workgroup
-__global__ __launch_bounds__(256) void loss_rows_kernel(const double* __restrict__ partial, int64_t d_out, int n_tiles,
+// loss_per_col[j] = sum over the work items in index order; optional total over columns by one workgroup
+__global__ __launch_bounds__(256) void loss_rows_kernel(const double* __restrict__ partial, int64_t d_out, int n_items,
                                                         double* __restrict__ row_loss) {
     const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= d_out) return;
     double s = 0.0;
-    for (int t = 0; t < n_tiles; ++t) s += partial[j * n_tiles + t];
+    for (int t = 0; t < n_items; ++t) s += partial[j * n_items + t];
     row_loss[j] = s;
+}
+
+// Work items of the loss per 128 columns j: the contraction range of column block cb, (cb+1) blocks, in chunks of
+// `chunk` blocks.  Large layers take whole ranges (chunk = number of blocks); small ones are cut until there are
+// enough items of equal length to fill the chip a few times over.
+void loss_items(int64_t d_out, int64_t d_in, int* chunk, int64_t* n_items) {
+    const int64_t n_cb = (d_in + BN - 1) / BN, gy = (d_out + BM - 1) / BM;
+    auto count = [&](int64_t ch) {
+        int64_t n = 0;
+        for (int64_t cb = 0; cb < n_cb; ++cb) n += (cb + ch) / ch;
+        return n;
+    };
+    int64_t ch = n_cb > 0 ? n_cb : 1;
+    while (ch > 2 && count(ch) * gy < 4 * 256) ch = (ch + 1) / 2;
+    *chunk = (int)ch;
+    *n_items = count(ch);
 }
 
 __global__ __launch_bounds__(1024) void loss_total_kernel(const double* __restrict__ row_loss, int64_t d_out,
@@ -262,8 +311,10 @@ bool vec4_ok(const float* H, const float* Wt, const uint8_t* Q, int64_t d_in, in
 }  // namespace
 
 size_t loss_workspace_bytes(int64_t d_out, int64_t d_in) {
-    const int64_t n_tiles = (d_in + BN - 1) / BN;
-    return cdq_align_up((size_t)d_out * n_tiles * sizeof(double), 256) + cdq_align_up((size_t)d_out * sizeof(double), 256);
+    int chunk;
+    int64_t n_items;
+    loss_items(d_out, d_in, &chunk, &n_items);
+    return cdq_align_up((size_t)d_out * n_items * sizeof(double), 256) + cdq_align_up((size_t)d_out * sizeof(double), 256);
 }
 
 int gradient_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
@@ -274,10 +325,10 @@ int gradient_launch(const float* H, const float* Wt, const float* scale, const f
     if (!eh_allow_lds<false, true>() || !eh_allow_lds<false, false>()) return CDQ_EHIP;
     if (vec4_ok(H, Wt, Q, d_in, group))
         hipLaunchKernelGGL((eh_gemm_kernel<false, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, G, (double*)nullptr, (int)gx, G64);
+                           d_out, d_in, group, G, (double*)nullptr, (int)gx, 0, G64);
     else
         hipLaunchKernelGGL((eh_gemm_kernel<false, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, G, (double*)nullptr, (int)gx, G64);
+                           d_out, d_in, group, G, (double*)nullptr, (int)gx, 0, G64);
     CDQ_LAUNCH_CHECK();
     return CDQ_OK;
 }
@@ -293,18 +344,21 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
         return CDQ_OK;
     }
     if (ws == nullptr || ws_bytes < loss_workspace_bytes(d_out, d_in) || ((uintptr_t)ws & 255)) return CDQ_EWORKSPACE;
-    const int64_t gx = (d_in + BN - 1) / BN, gy = (d_out + BM - 1) / BM;
-    if (gy > 65535) return CDQ_EUNSUPPORTED;
+    const int64_t gy = (d_out + BM - 1) / BM;
+    int chunk;
+    int64_t gx;
+    loss_items(d_out, d_in, &chunk, &gx);
+    if (gx > 65535 || gy > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
     double* partial = (double*)ws;
     double* rows_ws = (double*)((char*)ws + cdq_align_up((size_t)d_out * gx * sizeof(double), 256));
     double* rows = loss_per_col ? loss_per_col : rows_ws;
     if (!eh_allow_lds<true, true>() || !eh_allow_lds<true, false>()) return CDQ_EHIP;
     if (vec4_ok(H, Wt, Q, d_in, group))
-        hipLaunchKernelGGL((eh_gemm_kernel<true, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, (float*)nullptr, partial, (int)gx, (double*)nullptr);
+        hipLaunchKernelGGL((eh_gemm_kernel<true, true>), dim3((unsigned)gy, (unsigned)gx), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, (float*)nullptr, partial, (int)gx, chunk, (double*)nullptr);
     else
-        hipLaunchKernelGGL((eh_gemm_kernel<true, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, (float*)nullptr, partial, (int)gx, (double*)nullptr);
+        hipLaunchKernelGGL((eh_gemm_kernel<true, false>), dim3((unsigned)gy, (unsigned)gx), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, (float*)nullptr, partial, (int)gx, chunk, (double*)nullptr);
     CDQ_LAUNCH_CHECK();
     hipLaunchKernelGGL(loss_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, partial, d_out, (int)gx, rows);
     CDQ_LAUNCH_CHECK();

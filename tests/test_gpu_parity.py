@@ -307,7 +307,8 @@ def test_bcd_rejects_bad_partitions_and_block_sizes(cdq, oracle):
 
 # ----------------------------------------------------------------------------- gradient, loss
 
-@pytest.mark.parametrize("d_out,d_in,n,bits,group", [(64, 128, 512, 4, 128), (37, 200, 600, 3, 40), (130, 264, 800, 2, 8), (3, 7, 40, 3, 7)])
+@pytest.mark.parametrize("d_out,d_in,n,bits,group", [(64, 128, 512, 4, 128), (37, 200, 600, 3, 40), (130, 264, 800, 2, 8), (3, 7, 40, 3, 7),
+                                                     (70, 1100, 1500, 3, 1100), (260, 640, 900, 4, 128)])
 def test_gradient_and_loss(cdq, oracle, d_out, d_in, n, bits, group):
     X, Wt = rand_layer(d_in, d_in, d_out, n)
     H32 = oracle.hessian(X).astype(np.float32)
