@@ -1,7 +1,7 @@
 // C = E * H for all output columns, E = scale*Q + zero - Wt formed on the fly, fp32 data with
 // fp64 accumulation on the matrix cores (v_mfma_f64_16x16x4_f64).  Two epilogues:
 //   gradient: G[j][k] = (float) C[j][k]            -- Algorithm 1, "Compute gradient" (weight space)
-//   loss:     partial[j][item] = sum_k C[j][k]*E[j][k] over the item's columns -- Eq. (1) as e^T H e.
+//   loss:     partial[item][j] = sum_k C[j][k]*E[j][k] over the item's columns -- Eq. (1) as e^T H e.
 //             H is symmetric, so only the blocks on and above its diagonal are multiplied: with 128-wide
 //             blocks, e^T H e = sum_cb ( 2 sum_{kb<cb} e[kb]^T H[kb,cb] e[cb] + e[cb]^T H[cb,cb] e[cb] ),
 //             half the matrix-core work.  A work item is (128 columns j) x (column block cb) x (a chunk
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
         __syncthreads();
         if (tid < BM) {
             const int64_t row = m0 + tid;
-            if (row < d_out) partial[row * n_items + blockIdx.y] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+            if (row < d_out) partial[(int64_t)blockIdx.y * d_out + row] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
         }
     }
 }
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void loss_rows_kernel(const double* __restrict
     const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= d_out) return;
     double s = 0.0;
-    for (int t = 0; t < n_items; ++t) s += partial[j * n_items + t];
+    for (int t = 0; t < n_items; ++t) s += partial[(int64_t)t * d_out + j];       // [item][column]: coalesced
     row_loss[j] = s;
 }
 
