@@ -51,7 +51,8 @@ extern "C" {
 #define CDQ_OP_BCD       5   /* n = T, the number of iterations */
 #define CDQ_OP_CYCLIC_CD 6
 
-#define CDQ_MAX_D_IN 32768      /* largest d_in the register-resident CD kernel covers */
+#define CDQ_MAX_D_IN 36864      /* largest d_in the register-resident CD kernel covers (above 32768 only
+                                   with d_in and group multiples of 4 and 16-byte aligned H) */
 
 /* Per-column outcome of cdq_greedy_cd. */
 typedef struct {
@@ -64,7 +65,9 @@ typedef struct {
 /* Optional controls for cdq_greedy_cd_ex; zero-initialise for defaults. */
 typedef struct {
     int32_t  waves_per_column;  /* 0 = choose; else 1,2,4,8,16 wavefronts cooperating on a column */
-    int32_t  elems_per_lane;    /* 0 = choose; else 4,8,16,32 coordinates held per lane */
+    int32_t  elems_per_lane;    /* 0 = choose; else 4,8,16,32 coordinates held per lane; 36 (with 16
+                                   wavefronts) is the kernel that keeps the Hessian diagonal in LDS, the one
+                                   chosen for d_in above 32768 */
     int32_t  exact_scorer_only; /* 0 = nearest-level scorer with the two-level scorer as arbiter
                                    (default); 1 = two-level scorer on every iteration.  Both
                                    select the same moves; 1 exists for testing and timing. */

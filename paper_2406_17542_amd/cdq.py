@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_PKG, "libcdq.so")
 
 CDQ_F32, CDQ_BF16 = 0, 1
 OP_HESSIAN, OP_GREEDY_CD, OP_LOSS, OP_INIT_OWC, OP_INIT_OWC_CD, OP_BCD, OP_CYCLIC_CD = 0, 1, 2, 3, 4, 5, 6
-MAX_D_IN = 32768
+MAX_D_IN = 36864
 
 _lib = None
 

@@ -32,7 +32,16 @@ namespace {
 
 constexpr float kHalfWindow = 1.0f / 512.0f;     // |frac(rf) - 1/2| below this: neighbouring levels may tie
 
-template <int W, int E, int VEC>
+// reciprocal of the parabola's curvature 2 a H_ii; only steers which levels are scored
+__device__ __forceinline__ float curvature_inv(float h, float a) {
+    return (h > 0.0f) ? fminf(__frcp_rn(2.0f * a * h), 3.0e38f) : 0.0f;
+}
+
+// LDSH: the Hessian diagonal lives in LDS (each lane reads back only what it wrote, so no barrier is involved) and
+// the curvature reciprocal is recomputed per use -- the same operations on the same values, hence the same numbers.
+// It frees 2E registers per lane and is what lets a team of 16 wavefronts cover d_in up to 36864 (the diagonal of a
+// longer column would not fit the 160 KiB of LDS).
+template <int W, int E, int VEC, bool LDSH>
 __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
     const float* __restrict__ H, const float* __restrict__ hdiag, const float* __restrict__ G0,
     const float* __restrict__ scale, uint8_t* __restrict__ Q, int d_in, int bits, int group, int group_shift,
@@ -41,6 +50,7 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
     constexpr int NCH = E / VEC;              // chunks of VEC consecutive coordinates per lane
     constexpr int STRIDE = 64 * W * VEC;      // coordinates covered by the team per chunk
     __shared__ unsigned long long slots[2][16];
+    extern __shared__ __attribute__((aligned(16))) float hd_lds[];     // LDSH: [NCH][64 W][VEC]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -50,7 +60,7 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
     const float* G0j = G0 + j * (int64_t)d_in;
     const float top = (float)((1 << bits) - 1);
 
-    float g2[E], hd[E], cinv[E], a_c[NCH];
+    float g2[E], hd[LDSH ? 1 : E], cinv[LDSH ? 1 : E], a_c[NCH];
     uint32_t qpack[NCH];
 
     // lanes past the end of the column load from its start and then zero what they loaded: no load sits in a divergent
@@ -83,13 +93,27 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
             const int e = c * VEC + v;
             const float g = valid ? gl[e] : 0.0f, h = valid ? hl[e] : 0.0f;
             g2[e] = 2.0f * g;
-            hd[e] = h;
-            // reciprocal of the parabola's curvature; only steers which levels are scored
-            float ci = 0.0f;
-            if (h > 0.0f) ci = fminf(__frcp_rn(2.0f * a * h), 3.0e38f);
-            cinv[e] = ci;
+            if constexpr (LDSH) {
+                hd_lds[(c * 64 * W + tid) * VEC + v] = h;
+            } else {
+                hd[e] = h;
+                cinv[e] = curvature_inv(h, a);
+            }
         }
     }
+    // Hessian diagonal and curvature reciprocal of the lane's chunk c
+    auto diag_of = [&](int c, float (&h)[VEC], float (&ci)[VEC]) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            if constexpr (LDSH) {
+                h[v] = hd_lds[(c * 64 * W + tid) * VEC + v];
+                ci[v] = curvature_inv(h[v], a_c[c]);
+            } else {
+                h[v] = hd[c * VEC + v];
+                ci[v] = cinv[c * VEC + v];
+            }
+        }
+    };
 
     int moves = 0, converged = 0, n_reduce = 0;
     uint32_t last_hi = kOrderedZero;
@@ -116,15 +140,17 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const float a = a_c[c];
+            float hc[VEC], cc[VEC];
+            diag_of(c, hc, cc);
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 const int e = c * VEC + v;
                 const float qf = (float)((qpack[c] >> (8 * v)) & 0xffu);
-                const float rf = fmaf(-g2[e], cinv[e], qf);
+                const float rf = fmaf(-g2[e], cc[v], qf);
                 const float rn = __builtin_amdgcn_fmed3f(rintf(rf), 0.0f, top);
                 const float u = rn - qf;
                 const float d = a * u;
-                const float s = d * fmaf(d, hd[e], g2[e]);
+                const float s = d * fmaf(d, hc[v], g2[e]);
                 if (s < bs) { bs = s; bu = u; brf = rf; be = e; }
             }
         }
@@ -139,17 +165,19 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const float a = a_c[c];
+            float hc[VEC], cc[VEC];
+            diag_of(c, hc, cc);
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 const int e = c * VEC + v;
                 const float qf = (float)((qpack[c] >> (8 * v)) & 0xffu);
-                const float rf = __builtin_amdgcn_fmed3f(fmaf(-g2[e], cinv[e], qf), 0.0f, top);
+                const float rf = __builtin_amdgcn_fmed3f(fmaf(-g2[e], cc[v], qf), 0.0f, top);
                 const float r0 = floorf(rf), r1 = ceilf(rf);
                 float u0 = r0 - qf;
                 const float u1 = r1 - qf;
                 const float d0 = a * u0, d1 = a * u1;
-                float s0 = d0 * fmaf(d0, hd[e], g2[e]);
-                const float s1 = d1 * fmaf(d1, hd[e], g2[e]);
+                float s0 = d0 * fmaf(d0, hc[v], g2[e]);
+                const float s1 = d1 * fmaf(d1, hc[v], g2[e]);
                 if (s1 < s0) { s0 = s1; u0 = u1; }      // equal scores keep the lower level
                 if (s0 < bs) { bs = s0; bu = u0; be = e; }
             }
@@ -185,19 +213,29 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
         // all loads of the row first (lanes past the end read the row's start and add nothing), so that the
         // chunks' memory latencies overlap instead of following one another
         if constexpr (VEC == 4) {
-            float4 hv[NCH];
+            constexpr int BATCH = LDSH ? 3 : NCH;        // chunks whose loads are in flight together (registers)
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const int base = c * STRIDE + tid * VEC;
-                hv[c] = hrow4[(base < d_in ? base : 0) >> 2];
-            }
+            for (int c0 = 0; c0 < NCH; c0 += BATCH) {
+                float4 hv[BATCH];
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const float m = (c * STRIDE + tid * VEC < d_in) ? delta2 : 0.0f;
-                g2[c * 4 + 0] = fmaf(m, hv[c].x, g2[c * 4 + 0]);
-                g2[c * 4 + 1] = fmaf(m, hv[c].y, g2[c * 4 + 1]);
-                g2[c * 4 + 2] = fmaf(m, hv[c].z, g2[c * 4 + 2]);
-                g2[c * 4 + 3] = fmaf(m, hv[c].w, g2[c * 4 + 3]);
+                for (int cb = 0; cb < BATCH; ++cb) {
+                    const int c = c0 + cb;
+                    if (c < NCH) {
+                        const int base = c * STRIDE + tid * VEC;
+                        hv[cb] = hrow4[(base < d_in ? base : 0) >> 2];
+                    }
+                }
+#pragma unroll
+                for (int cb = 0; cb < BATCH; ++cb) {
+                    const int c = c0 + cb;
+                    if (c < NCH) {
+                        const float m = (c * STRIDE + tid * VEC < d_in) ? delta2 : 0.0f;
+                        g2[c * 4 + 0] = fmaf(m, hv[cb].x, g2[c * 4 + 0]);
+                        g2[c * 4 + 1] = fmaf(m, hv[cb].y, g2[c * 4 + 1]);
+                        g2[c * 4 + 2] = fmaf(m, hv[cb].z, g2[c * 4 + 2]);
+                        g2[c * 4 + 3] = fmaf(m, hv[cb].w, g2[c * 4 + 3]);
+                    }
+                }
             }
         } else {
             float hv[NCH];
@@ -242,11 +280,17 @@ __global__ __launch_bounds__(256) void extract_diag_kernel(const float* __restri
     if (i < d_in) hdiag[i] = H[i * d_in + i];
 }
 
-template <int W, int E, int VEC>
+template <int W, int E, int VEC, bool LDSH = false>
 int launch_one(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q, int64_t d_out,
                int d_in, int bits, int group, int group_shift, int n_grp, int T, int exact_only, cdq_col_stats* stats,
                int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
-    hipLaunchKernelGGL((cd_fused_kernel<W, E, VEC>), dim3((unsigned)d_out), dim3(64 * W), 0, st, H, hdiag, G0, scale, Q, d_in,
+    const size_t lds = LDSH ? sizeof(float) * 64 * W * E : 0;
+    if (LDSH) {
+        static const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(cd_fused_kernel<W, E, VEC, LDSH>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (rc != hipSuccess) return CDQ_EHIP;
+    }
+    hipLaunchKernelGGL((cd_fused_kernel<W, E, VEC, LDSH>), dim3((unsigned)d_out), dim3(64 * W), lds, st, H, hdiag, G0, scale, Q, d_in,
                        bits, group, group_shift, n_grp, T, exact_only, stats, trace, trace_cap, G_out);
     CDQ_LAUNCH_CHECK();
     return CDQ_OK;
@@ -278,9 +322,13 @@ int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int*
     if (w > 16) {
         e = 32;
         w = team(e);
-        if (w > 16) return CDQ_EUNSUPPORTED;
+        if (w > 16) {                          // beyond 32768: 36 per lane with the Hessian diagonal in LDS (16-byte chunks only)
+            e = 36;
+            w = 16;
+            if (v != 4 || d_in > (int64_t)64 * w * e) return CDQ_EUNSUPPORTED;
+        }
     }
-    while (e > 4 && d_out * w < 2048 && team(e / 2) <= 8) {
+    while (e > 4 && e <= 32 && d_out * w < 2048 && team(e / 2) <= 8) {
         e /= 2;
         w = team(e);
     }
@@ -316,6 +364,9 @@ int cd_launch(const float* H, const float* hdiag, const float* G0, const float* 
     CDQ_CD_CASE(4, 4) CDQ_CD_CASE(4, 8) CDQ_CD_CASE(4, 16) CDQ_CD_CASE(4, 32)
     CDQ_CD_CASE(8, 4) CDQ_CD_CASE(8, 8) CDQ_CD_CASE(8, 16) CDQ_CD_CASE(8, 32)
     CDQ_CD_CASE(16, 4) CDQ_CD_CASE(16, 8) CDQ_CD_CASE(16, 16) CDQ_CD_CASE(16, 32)
+    if (waves == 16 && elems == 36 && vec == 4)
+        return launch_one<16, 36, 4, true>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, exact_only, stats, trace,
+                                           trace_cap, G_out, st);
     return CDQ_EINVAL;
 }
 

@@ -138,8 +138,8 @@ def main():
     rows = []
     for name in args.layers.split(","):
         d_in, d_out = (d_model, d_ff) if name == "ffn1" else (d_ff, d_model)
-        if d_in > 32768:
-            rows.append({"layer": name, "d_in": d_in, "d_out": d_out, "skipped": "d_in above the fused loop's 32768 limit"})
+        if d_in > cdq.MAX_D_IN:
+            rows.append({"layer": name, "d_in": d_in, "d_out": d_out, "skipped": f"d_in above the fused loop's limit of {cdq.MAX_D_IN}"})
             print(json.dumps(rows[-1]), flush=True)
             continue
         Wt = torch.from_numpy(inputs.make_wt(d_out, d_in, seed=1)).cuda()

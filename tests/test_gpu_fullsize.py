@@ -254,3 +254,35 @@ def test_attn_proj_bcd_after_cd(cdq, oracle):
     say(f"  codes equal on {eq.mean():.6f} of sampled entries")
     assert eq.all()
     assert np.array_equal(moves[cols], ref["moves"])
+
+
+def test_widest_layer_36864_columns_against_the_oracle(cdq, oracle):
+    """d_in = 36864 (the FFN2 width of the largest model in the paper's runtime table) is above what the
+    registers alone can hold: the fused loop keeps the Hessian diagonal in LDS there.  A few columns, the
+    default launch shape, RTN start; the oracle reruns them from the GPU's fp32 H: codes, move counts and the
+    per-column loss must match."""
+    d_in, d_out, n, bits, T = 36864, 6, 2048, 3, 96
+    say(f"generating X [{n}x{d_in}] on the GPU and Wt [{d_out}x{d_in}]")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    Xd = (torch.randn((n, d_in), generator=g, device="cuda") * torch.exp(0.5 * torch.randn(d_in, generator=g, device="cuda"))).to(torch.bfloat16)
+    Wt = inputs.make_wt(d_out, d_in, seed=5)
+    say("hessian on the GPU")
+    Hd = cdq.hessian(Xd)
+    del Xd
+    Wd = torch.from_numpy(Wt).cuda()
+    scale, zero, Q = cdq.init_rtn(Wd, bits, d_in)
+    q0 = Q.cpu().numpy().copy()
+    say(f"greedy CD on the GPU, T={T}")
+    out = cdq.greedy_cd(Hd, Wd, scale, zero, Q, bits, d_in, T)
+    st = out["stats"].cpu().numpy()
+    per = cdq.loss(Hd, Wd, scale, zero, Q, d_in)[0].cpu().numpy()
+    say(f"  moves per column {st[:, 0].tolist()}")
+    assert (st[:, 0] > 0).all() and (st[:, 0] <= T).all()
+    say("copying H to the host for the oracle")
+    H32 = Hd.cpu().numpy()
+    a, b = scale.cpu().numpy(), zero.cpu().numpy()
+    ref = oracle.greedy_cd(H32, Wt, a, b, q0, bits, d_in, T)
+    assert np.array_equal(Q.cpu().numpy(), ref["Q"])
+    assert np.array_equal(st[:, 0], ref["moves"])
+    np.testing.assert_allclose(per, oracle.loss(H32, Wt, ref["Q"], a, b, d_in), rtol=1e-6)

@@ -410,6 +410,9 @@ CD_CASES = [
     (12, 2048, 2600, 3, 2048, 600, True, 8, 4),
     (12, 2048, 2600, 2, 128, 600, False, 16, 4),
     (6, 4096, 4500, 4, 4096, 300, True, 2, 32),
+    (6, 4096, 4500, 3, 4096, 300, True, 16, 36),     # the kernel with the Hessian diagonal in LDS (d_in above 32768)
+    (7, 2048, 2600, 2, 128, 500, False, 16, 36),
+    (3, 1032, 1500, 4, 8, 300, True, 16, 36),
     (5, 64, 256, 3, 64, 0, True, 0, 0),              # T = 0: nothing changes
     (5, 64, 256, 3, 64, 3, True, 0, 0),              # tiny budget: stops after 3 moves
     (1, 8, 64, 2, 8, 50, True, 0, 0),
