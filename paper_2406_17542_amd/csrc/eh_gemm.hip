@@ -63,7 +63,7 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
                                                      const float* __restrict__ scale, const float* __restrict__ zero,
                                                      const uint8_t* __restrict__ Q, int64_t d_out, int64_t d_in,
                                                      int64_t group, float* __restrict__ G,
-                                                     double* __restrict__ partial, int n_items, int chunk_blocks,
+                                                     double* __restrict__ partial, int chunk_blocks,
                                                      double* __restrict__ G64) {
     // two stages of As[k][m] = E[m0+m][k0+k] and Bs[k][n] = H[k0+k][n0+n]: the next step's tiles are written
     // while the current ones are multiplied, one barrier per step
@@ -325,10 +325,10 @@ int gradient_launch(const float* H, const float* Wt, const float* scale, const f
     if (!eh_allow_lds<false, true>() || !eh_allow_lds<false, false>()) return CDQ_EHIP;
     if (vec4_ok(H, Wt, Q, d_in, group))
         hipLaunchKernelGGL((eh_gemm_kernel<false, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, G, (double*)nullptr, (int)gx, 0, G64);
+                           d_out, d_in, group, G, (double*)nullptr, 0, G64);
     else
         hipLaunchKernelGGL((eh_gemm_kernel<false, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, G, (double*)nullptr, (int)gx, 0, G64);
+                           d_out, d_in, group, G, (double*)nullptr, 0, G64);
     CDQ_LAUNCH_CHECK();
     return CDQ_OK;
 }
@@ -355,10 +355,10 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
     if (!eh_allow_lds<true, true>() || !eh_allow_lds<true, false>()) return CDQ_EHIP;
     if (vec4_ok(H, Wt, Q, d_in, group))
         hipLaunchKernelGGL((eh_gemm_kernel<true, true>), dim3((unsigned)gy, (unsigned)gx), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, (float*)nullptr, partial, (int)gx, chunk, (double*)nullptr);
+                           d_out, d_in, group, (float*)nullptr, partial, chunk, (double*)nullptr);
     else
         hipLaunchKernelGGL((eh_gemm_kernel<true, false>), dim3((unsigned)gy, (unsigned)gx), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, (float*)nullptr, partial, (int)gx, chunk, (double*)nullptr);
+                           d_out, d_in, group, (float*)nullptr, partial, chunk, (double*)nullptr);
     CDQ_LAUNCH_CHECK();
     hipLaunchKernelGGL(loss_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, partial, d_out, (int)gx, rows);
     CDQ_LAUNCH_CHECK();
