@@ -263,7 +263,15 @@ __global__ __launch_bounds__(256) void loss_rows_kernel(const double* __restrict
     const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= d_out) return;
     double s = 0.0;
-    for (int t = 0; t < n_items; ++t) s += partial[(int64_t)t * d_out + j];       // [item][column]: coalesced
+    int t = 0;
+    for (; t + 8 <= n_items; t += 8) {                                             // [item][column]: coalesced; eight loads in flight,
+        double v[8];                                                               // added in index order
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(t + u) * d_out + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; t < n_items; ++t) s += partial[(int64_t)t * d_out + j];
     row_loss[j] = s;
 }
 
