@@ -396,7 +396,15 @@ __global__ __launch_bounds__(256) void hessian_finalize_kernel(const float* part
         if (row < d_in && col < d_in) {
             // in diagonal blocks take the entry on or above the diagonal for both positions
             const int64_t rr = (I == J && row > col) ? col : row, cc = (I == J && row > col) ? row : col;
-            for (int z = 0; z < splits; ++z) v += parts[z * split_stride + rr * d_in + cc];
+            const float* src = parts + rr * d_in + cc;
+            for (int z0 = 0; z0 < splits; z0 += 8) {           // eight splits' loads in flight, added in ascending order
+                float pv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) pv[u] = src[(int64_t)(z0 + u < splits ? z0 + u : z0) * split_stride];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (z0 + u < splits) v += pv[u];
+            }
             if (accumulate) v += H[rr * d_in + cc];
         }
         tile[r][tx] = v;
