@@ -311,6 +311,9 @@ def main():
                     "algorithmic_bytes_per_launch": cd_bytes, "avg_launch_ms": stages["cd_loop"]}
         if "h_row_gather_GBps" in achievable:
             roofline["frac_of_achievable_gather"] = cd_gbs / achievable["h_row_gather_GBps"]
+        if 4 * cfg.d_in * cfg.d_in <= 256 * 2 ** 20:
+            # the rows of an H that fits the 256 MiB Infinity Cache are not served by HBM: achieved may exceed the HBM peak
+            roofline["note"] = "H is cache-resident: rows come from L2 / Infinity Cache, see frac_of_achievable_gather"
     else:
         roofline = {"kernel": "hessian_kernel", "bound": "mfma", "achieved": h_tflops_exec, "peak": mfma_peak, "unit": "TFLOP/s",
                     "frac": h_tflops_exec / mfma_peak, "traffic": load_traffic("hessian_kernel", f"{cfg.name}:{args.mode}"),
