@@ -343,6 +343,10 @@ __device__ __forceinline__ uint32_t bcdm_v16(float g2, float h, float a) {
     return (u >= 0.0f && u < 0.99985f) ? 65530u - (uint32_t)(u * 65536.0f) : 0u;
 }
 
+// (v_i v_k) >> 16 for two 16-bit margins.  __umul24 returns a signed int: without the cast the shift would smear the sign
+// of a product of 2^31 or more over the result, and the pair would pass the test whatever its rho.
+__device__ __forceinline__ uint32_t bcdm_margin(uint32_t vi, uint32_t vk) { return (uint32_t)__umul24(vi, vk) >> 16; }
+
 // pair-table rows for the kernel above: ik [T][n_pairs] u32, R [T][n_pairs] u16 = rho^2 in units of 2^-16 rounded UP by more than
 // one unit (65535 = never skip)
 __global__ __launch_bounds__(256) void bcdm_pair_gather_kernel(const float* __restrict__ H, const int32_t* __restrict__ parts,
@@ -526,10 +530,10 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
             const uint32_t thr = s_thr[p];
             const int i = (int)(ik & 0xffffu), k = (int)(ik >> 16);
             const uint32_t vi = Vmin[i], vk = Vmin[k];
-            if ((__umul24(vi, vk) >> 16) < thr || score_all) {
+            if (bcdm_margin(vi, vk) < thr || score_all) {
                 uint32_t mask = 0;
 #pragma unroll
-                for (int c = 0; c < CW; ++c) mask |= ((__umul24(V[i * CW + c], V[k * CW + c]) >> 16) < thr ? 1u : 0u) << c;
+                for (int c = 0; c < CW; ++c) mask |= (bcdm_margin(V[i * CW + c], V[k * CW + c]) < thr ? 1u : 0u) << c;
                 if (score_all) mask = ~0u;
                 mask &= valid_mask;
                 if (mask) {

@@ -284,6 +284,27 @@ def test_bcd_few_iterations(cdq, oracle, T):
         assert np.array_equal(Q.cpu().numpy(), ref["Q"]), single
 
 
+@pytest.mark.parametrize("d_out,d_in,n,bits,T", [(4, 1360, 2313, 4, 45), (9, 336, 700, 4, 60), (5, 512, 900, 3, 50)])
+def test_bcd_strongly_correlated_pairs(cdq, oracle, d_out, d_in, n, bits, T):
+    """Channels of very different scale plus a common component give pairs with |H_ik| close to sqrt(H_ii H_kk); from the
+    RTN start such pairs have improving moves while both coordinates are far from a single-coordinate move, the corner
+    of the skip test where the product of the two 16-bit margins exceeds 2^31 (found by a randomised sweep)."""
+    r = np.random.default_rng(d_in)
+    X = r.standard_normal((n, d_in)).astype(np.float32) * np.exp(0.5 * r.standard_normal(d_in)).astype(np.float32)
+    X += r.standard_normal((n, 1)).astype(np.float32)
+    Wt = (r.standard_normal((d_out, d_in)) / np.sqrt(d_in)).astype(np.float32)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q0 = oracle.init_grid(Wt, bits, d_in)
+    parts = inputs.make_partitions(T, d_in, seed=d_in)
+    ref = oracle.bcd(H32, Wt, a, b, q0, parts, bits, d_in, k=2)
+    for single in (False, True):
+        Q = dev(q0.copy())
+        out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, bits, d_in, dev(parts), single_column=single, want_G=True)
+        assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), single
+        assert np.array_equal(Q.cpu().numpy(), ref["Q"]), single
+        assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), single
+
+
 def test_bcd_rejects_bad_partitions_and_block_sizes(cdq, oracle):
     X, Wt = rand_layer(5, 64, 4, 200)
     H32 = oracle.hessian(X).astype(np.float32)
