@@ -667,3 +667,69 @@ def test_cyclic_cd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start)
     assert np.array_equal(out["G"].cpu().numpy(), ref["G"])
     if d_in == 128:
         assert ref["converged"].any(), "ten epochs on the uncorrelated case should reach a coordinate-wise optimum"
+
+
+# ----------------------------------------------------------------------------- randomised shapes
+
+def scaled_layer(seed, d_in, d_out, n, corr):
+    """Channels of very different scale plus a common component: strongly correlated pairs, large and small H_ii."""
+    r = np.random.default_rng(seed)
+    X = r.standard_normal((n, d_in)).astype(np.float32) * np.exp(0.5 * r.standard_normal(d_in)).astype(np.float32)
+    if corr:
+        X += (corr * r.standard_normal((n, 1))).astype(np.float32)
+    Wt = (r.standard_normal((d_out, d_in)) / np.sqrt(d_in)).astype(np.float32)
+    return X, Wt
+
+
+@pytest.mark.parametrize("seed,big", [(1, False), (2, False), (3, True)])
+def test_random_shapes_against_the_oracle(cdq, oracle, seed, big):
+    """A seeded sweep over shapes nobody picked by hand (widths, group sizes, column counts, budgets, starts): greedy CD,
+    block CD (both kernels, with and without the pair test), cyclic CD, loss and gradient against the oracle, exactly."""
+    rng = np.random.default_rng(seed)
+    for case in range(45 if big else 120):
+        bits = int(rng.choice([2, 3, 4]))
+        kind = str(rng.choice(["cd", "cd", "bcd", "bcd", "cyclic", "loss"]))
+        d_in = int(rng.integers(2, 90)) * int(rng.choice([16, 32, 48] if big else [4, 8, 16, 16]))
+        divs = [g for g in range(1, d_in + 1) if d_in % g == 0]
+        group = int(rng.choice(divs[len(divs) // 2:]))
+        d_out = int(rng.integers(1, 40))
+        n = int(rng.integers(d_in, 3 * d_in + 8))
+        corr = float(rng.choice([0.0, 0.5, 1.0]))
+        X, Wt = scaled_layer(1000 * seed + case, d_in, d_out, n, corr)
+        H32 = oracle.hessian(X).astype(np.float32)
+        a, b, q_rtn = oracle.init_grid(Wt, bits, group)
+        q0 = q_rtn if rng.random() < 0.5 else inputs.make_random_codes(d_out, d_in, bits, seed=case)
+        tag = f"case {case}: {kind} d_out={d_out} d_in={d_in} n={n} bits={bits} group={group} corr={corr}"
+        Hd, Wd, ad, bd = dev(H32), dev(Wt), dev(a), dev(b)
+        if kind == "cd":
+            T = int(rng.integers(1, 2 * d_in))
+            ref = oracle.greedy_cd(H32, Wt, a, b, q0, bits, group, T)
+            Q = dev(q0.copy())
+            out = cdq.greedy_cd(Hd, Wd, ad, bd, Q, bits, group, T)
+            assert np.array_equal(Q.cpu().numpy(), ref["Q"]), tag
+            assert np.array_equal(out["stats"].cpu().numpy()[:, 0], ref["moves"]), tag
+        elif kind == "bcd":
+            T = int(rng.integers(1, 60))
+            parts = inputs.make_partitions(T, d_in, seed=case)
+            ref = oracle.bcd(H32, Wt, a, b, q0, parts, bits, group, k=2)
+            for single in (False, True):
+                for score_all in (False, True):
+                    Q = dev(q0.copy())
+                    out = cdq.bcd(Hd, Wd, ad, bd, Q, bits, group, dev(parts), single_column=single, score_all=score_all, want_G=True)
+                    assert np.array_equal(Q.cpu().numpy(), ref["Q"]), (tag, single, score_all)
+                    assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), (tag, single, score_all)
+                    assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), (tag, single, score_all)
+        elif kind == "cyclic":
+            T = int(rng.integers(1, 3 * d_in))
+            ref = oracle.cyclic_cd(H32, Wt, a, b, q0, bits, group, T)
+            Q = dev(q0.copy())
+            cdq.cyclic_cd(Hd, Wd, ad, bd, Q, bits, group, T)
+            assert np.array_equal(Q.cpu().numpy(), ref["Q"]), tag
+        else:
+            E = oracle.residual(Wt, q0, a, b, group)
+            E64 = E.astype(np.float64)
+            ref = np.einsum("ji,ji->j", E64 @ H32.astype(np.float64), E64)
+            per = cdq.loss(Hd, Wd, ad, bd, dev(q0), group)[0].cpu().numpy()
+            np.testing.assert_allclose(per, ref, rtol=1e-11, err_msg=tag)
+            G = cdq.gradient(Hd, Wd, ad, bd, dev(q0), group).cpu().numpy()
+            assert (G != oracle.gradient(H32, E)).mean() <= 1e-5, tag
