@@ -56,16 +56,16 @@ __global__ void bcd_fill_i32_kernel(int32_t* __restrict__ p, int64_t n, int32_t 
     if (x < n) p[x] = v;
 }
 
-// every entry of parts in range, every row a permutation (each value hit exactly once)
+// every entry of parts in range, every row a permutation (each value hit exactly once): one bit per value in LDS
 __global__ __launch_bounds__(256) void bcd_check_parts_kernel(const int32_t* __restrict__ parts, int d_in, int32_t* __restrict__ bad) {
-    extern __shared__ int32_t seen[];
+    extern __shared__ uint32_t seen[];
     const int32_t* row = parts + (int64_t)blockIdx.x * d_in;
-    for (int c = threadIdx.x; c < d_in; c += 256) seen[c] = 0;
+    for (int c = threadIdx.x; c < (d_in + 31) / 32; c += 256) seen[c] = 0;
     __syncthreads();
     for (int c = threadIdx.x; c < d_in; c += 256) {
         const int32_t v = row[c];
         if (v < 0 || v >= d_in) atomicAdd(bad, 1);
-        else if (atomicAdd(&seen[v], 1) != 0) atomicAdd(bad, 1);
+        else if (atomicOr(&seen[v >> 5], 1u << (v & 31)) & (1u << (v & 31))) atomicAdd(bad, 1);
     }
 }
 
@@ -676,6 +676,150 @@ size_t bcdm_lds_bytes(int64_t d_in, int64_t group, int cw, int nst) {
                         sizeof(unsigned long long) * 2 * cw + sizeof(float) * cw * n_grp + sizeof(int) * 16, 16);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Wide layers (d_in above what the kernels above hold: up to 40896).  One 1024-thread workgroup per column; LDS holds
+// only 2g.  Everything else a pair needs comes with its table entry -- i | k << 16, thr, 2 H_ik, H_ii, H_kk, 20 bytes --
+// and the codes stay in global memory (read for the pairs that are scored and at a commit).  The pair test is the
+// one-column kernel's, as a product: |2 g_i| <= thr H_ii a_i (the rounding of the product is 2^-23, tau is 2^-14).
+// A thread scores its surviving pairs itself, all level pairs in (r_i, r_k) order.  Per iteration: one barrier when nothing
+// moves, three when the column commits.  The kernel streams the whole table once per column: it is bound by that.
+constexpr int BCDW_NT = 1024;
+constexpr int BCDW_UNR = 4;          // table entries whose loads are in flight together, per thread
+
+__global__ __launch_bounds__(256) void bcdw_pair_gather_kernel(const float* __restrict__ H, const int32_t* __restrict__ parts,
+                                                               const int32_t* __restrict__ bad, int64_t d_in, int64_t n_items,
+                                                               uint32_t* __restrict__ t_ik, float* __restrict__ t_thr,
+                                                               float* __restrict__ t_h2, float* __restrict__ t_hi, float* __restrict__ t_hk) {
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;        // x = t * (d_in/2) + p
+    if (x >= n_items || *bad != 0) return;
+    const int32_t i = parts[2 * x], k = parts[2 * x + 1];
+    const float h2 = 2.0f * H[(int64_t)i * d_in + k];
+    const float hii = H[(int64_t)i * d_in + i], hkk = H[(int64_t)k * d_in + k];
+    float thr = -1.0f;
+    if (hii > 0.0f && hkk > 0.0f) thr = 1.0f - (0.5f * fabsf(h2) * __frsqrt_rn(hii)) * __frsqrt_rn(hkk) - kBcdTau;
+    t_ik[x] = (uint32_t)i | ((uint32_t)k << 16);
+    t_thr[x] = thr;
+    t_h2[x] = h2;
+    t_hi[x] = hii;
+    t_hk[x] = hkk;
+}
+
+template <int BITS>
+__global__ __launch_bounds__(BCDW_NT) void bcd2_wide_kernel(const float* __restrict__ H, const float* __restrict__ G0,
+                                                            const float* __restrict__ scale, uint8_t* Q,
+                                                            const uint32_t* __restrict__ t_ik, const float* __restrict__ t_thr,
+                                                            const float* __restrict__ t_h2, const float* __restrict__ t_hi,
+                                                            const float* __restrict__ t_hk, const int32_t* __restrict__ bad_parts,
+                                                            int d_in, int group, int T, int score_all,
+                                                            int32_t* __restrict__ moves_out, float* __restrict__ G_out,
+                                                            int32_t* __restrict__ trace, int trace_cap) {
+    constexpr int L = 1 << BITS;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ unsigned long long slots[2][BCDW_NT / 64];
+    float* g2 = reinterpret_cast<float*>(smem);                   // [d_in] 2 g
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_grp = d_in / group, n_pairs = d_in / 2;
+    const int64_t j = blockIdx.x;
+    const float* scale_j = scale + j * n_grp;
+    uint8_t* Qj = Q + j * (int64_t)d_in;                          // read and written by this workgroup only
+    if (*bad_parts != 0) {
+        if (tid == 0 && moves_out != nullptr) moves_out[j] = -1;
+        return;
+    }
+    for (int c = tid; c < d_in; c += BCDW_NT) g2[c] = 2.0f * G0[j * (int64_t)d_in + c];
+    __syncthreads();
+    const uint32_t grp_mul = (uint32_t)((0x100000000ull + (uint32_t)group - 1u) / (uint32_t)group);   // exact below 2^16 (group > 1)
+    auto a_of = [&](int i) { return scale_j[n_grp == 1 ? 0 : (group == 1 ? i : (int)__umulhi((uint32_t)i, grp_mul))]; };
+
+    int moves = 0;
+    for (int t = 0; t < T; ++t) {
+        const int64_t row = (int64_t)t * n_pairs;
+        float best_s = 0.0f;
+        uint32_t best_pay = 0xffffffffu;
+        for (int p0 = tid; p0 < n_pairs; p0 += BCDW_NT * BCDW_UNR) {
+            uint32_t ik[BCDW_UNR];
+            float thr[BCDW_UNR], h2[BCDW_UNR], hi[BCDW_UNR], hk[BCDW_UNR];
+#pragma unroll
+            for (int u = 0; u < BCDW_UNR; ++u) {                  // entries past the end reload the thread's first one
+                const int p = p0 + u * BCDW_NT;
+                const int64_t x = row + (p < n_pairs ? p : p0);
+                ik[u] = t_ik[x]; thr[u] = t_thr[x]; h2[u] = t_h2[x]; hi[u] = t_hi[x]; hk[u] = t_hk[x];
+            }
+#pragma unroll
+            for (int u = 0; u < BCDW_UNR; ++u) {
+                const int p = p0 + u * BCDW_NT;
+                if (p >= n_pairs) continue;
+                const int i = (int)(ik[u] & 0xffffu), k = (int)(ik[u] >> 16);
+                const float ai = a_of(i), ak = a_of(k), gi = g2[i], gk = g2[k];
+                const bool quiet = (fabsf(gi) <= thr[u] * (hi[u] * ai)) & (fabsf(gk) <= thr[u] * (hk[u] * ak));   // thr < 0 or a NaN: not quiet
+                if (quiet && !score_all) continue;
+                const int qi = Qj[i], qk = Qj[k];
+                float dk[L], sk[L];
+#pragma unroll
+                for (int rr = 0; rr < L; ++rr) {
+                    dk[rr] = ak * (float)(rr - qk);
+                    sk[rr] = dk[rr] * fmaf(dk[rr], hk[u], gk);
+                }
+#pragma unroll
+                for (int ri = 0; ri < L; ++ri) {
+                    const float di = ai * (float)(ri - qi);
+                    const float si = di * fmaf(di, hi[u], gi);
+#pragma unroll
+                    for (int rk = 0; rk < L; ++rk) {
+                        const float sc = fmaf(di * dk[rk], h2[u], si + sk[rk]);
+                        if (sc < best_s) { best_s = sc; best_pay = ((uint32_t)p << 8) | (uint32_t)(ri << 4) | (uint32_t)rk; }
+                    }
+                }
+            }
+        }
+        uint64_t key = wave_min_key(order_bits(best_s), best_pay);
+        if (lane == 0) slots[t & 1][wave] = key;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < BCDW_NT / 64; ++w) key = umin64(key, (uint64_t)slots[t & 1][w]);
+        if ((uint32_t)(key >> 32) >= kOrderedZero) continue;          // no pair lowers the loss under this partition
+        // ---- commit
+        const uint32_t pay = (uint32_t)key;
+        const int p = (int)(pay >> 8), ri = (int)((pay >> 4) & 15u), rk = (int)(pay & 15u);
+        const uint32_t ikw = t_ik[row + p];
+        const int i = (int)(ikw & 0xffffu), k = (int)(ikw >> 16);
+        const float di2 = 2.0f * (a_of(i) * (float)(ri - (int)Qj[i])), dk2 = 2.0f * (a_of(k) * (float)(rk - (int)Qj[k]));
+        __syncthreads();                                               // everybody has read the old codes
+        if (tid == 0) {
+            Qj[i] = (uint8_t)ri;
+            Qj[k] = (uint8_t)rk;
+            if (trace != nullptr && moves < trace_cap) {
+                int32_t* tr = trace + (j * trace_cap + moves) * 4;
+                tr[0] = t; tr[1] = p; tr[2] = ri | (rk << 4);
+                tr[3] = (int32_t)~(uint32_t)(key >> 32);               // the ordered image of a negative score is ~bits
+            }
+            __threadfence_block();
+        }
+        const float* hrow_i = H + (int64_t)i * d_in;
+        const float* hrow_k = H + (int64_t)k * d_in;
+        for (int x0 = tid; x0 < d_in; x0 += BCDW_NT * BCDW_UNR) {
+            float vi[BCDW_UNR], vk[BCDW_UNR];
+#pragma unroll
+            for (int u = 0; u < BCDW_UNR; ++u) {
+                const int x = x0 + u * BCDW_NT, xc = x < d_in ? x : x0;
+                vi[u] = hrow_i[xc];
+                vk[u] = hrow_k[xc];
+            }
+#pragma unroll
+            for (int u = 0; u < BCDW_UNR; ++u) {
+                const int x = x0 + u * BCDW_NT;
+                if (x < d_in) g2[x] = fmaf(dk2, vk[u], fmaf(di2, vi[u], g2[x]));
+            }
+        }
+        ++moves;
+        __syncthreads();                                               // 2g and the codes are updated
+    }
+    __syncthreads();
+    if (G_out != nullptr)
+        for (int c = tid; c < d_in; c += BCDW_NT) G_out[j * (int64_t)d_in + c] = 0.5f * g2[c];
+    if (tid == 0 && moves_out != nullptr) moves_out[j] = moves;
+}
+
 size_t bcd_lds_bytes(int64_t d_in, int64_t group) {
     const int64_t n_grp = d_in / group;
     return cdq_align_up(sizeof(float) * 3 * d_in + 16 * BCD_FASTQ + sizeof(uint64_t) * 32 + sizeof(float) * 8 + sizeof(int) * 4 +
@@ -684,10 +828,11 @@ size_t bcd_lds_bytes(int64_t d_in, int64_t group) {
 
 }  // namespace
 
-// workspace: G0 [d_out][d_in] fp32 | hdiag [d_in] | pair_rec [T][d_in/2] int2 | pair_h2 [T][d_in/2] | flag
+// workspace: G0 [d_out][d_in] fp32 | hdiag [d_in] | pair table, 20 bytes per (iteration, pair) | flag.
+// The one- and several-column kernels use 12 of the 20 bytes (pair_rec int2 + pair_h2, or ik + R16 + pair_h2).
 size_t bcd_workspace_bytes(int64_t d_out, int64_t d_in, int64_t T) {
     return cdq_align_up((size_t)d_out * d_in * sizeof(float), 256) + cdq_align_up((size_t)d_in * sizeof(float), 256) +
-           cdq_align_up((size_t)T * (d_in / 2) * sizeof(int2), 256) + cdq_align_up((size_t)T * (d_in / 2) * sizeof(float), 256) + 256;
+           cdq_align_up((size_t)T * (d_in / 2) * 20, 256) + 256;
 }
 
 int bcd_launch(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out, int64_t d_in,
@@ -705,24 +850,54 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
     int nt = 256;
     while ((int64_t)nt * BCD_PPT < d_in / 2) nt *= 2;
     const size_t lds = bcd_lds_bytes(d_in, group);
-    if (nt > 1024 || lds > 160 * 1024 || d_in % 4 != 0 || ((uintptr_t)H & 15) || d_in >= (1 << 24) || T > 0x7fffffffLL || d_out > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
+    // one column per workgroup with its state in LDS; failing that, the wide-layer kernel (2g only in LDS, any alignment)
+    const bool single_ok = nt <= 1024 && lds <= 160 * 1024 && d_in % 4 == 0 && ((uintptr_t)H & 15) == 0;
+    const size_t wide_lds = sizeof(float) * (size_t)d_in;
+    const bool wide_ok = d_in < 65536 && wide_lds + 512 <= 160 * 1024;
+    if ((!single_ok && !wide_ok) || T > 0x7fffffffLL || d_out > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
     if (ws == nullptr || ((uintptr_t)ws & 255) || ws_bytes < bcd_workspace_bytes(d_out, d_in, T)) return CDQ_EWORKSPACE;
+    const int64_t n_items = T * (d_in / 2);
     char* wp = (char*)ws;
     float* G0 = (float*)wp;           wp += cdq_align_up((size_t)d_out * d_in * sizeof(float), 256);
     float* hdiag = (float*)wp;        wp += cdq_align_up((size_t)d_in * sizeof(float), 256);
-    int2* pair_rec = (int2*)wp;       wp += cdq_align_up((size_t)T * (d_in / 2) * sizeof(int2), 256);
-    float* pair_h2 = (float*)wp;      wp += cdq_align_up((size_t)T * (d_in / 2) * sizeof(float), 256);
+    char* table = wp;                 wp += cdq_align_up((size_t)n_items * 20, 256);
+    int2* pair_rec = (int2*)table;                                       // [n_items] 8 bytes each, then
+    float* pair_h2 = (float*)(table + 8 * (size_t)n_items);              // [n_items]
     int32_t* bad = (int32_t*)wp;
 
     hipLaunchKernelGGL(bcd_fill_i32_kernel, dim3(1), dim3(64), 0, st, bad, (int64_t)1, 0);
     CDQ_LAUNCH_CHECK();
-    hipLaunchKernelGGL(bcd_check_parts_kernel, dim3((unsigned)T), dim3(256), sizeof(int32_t) * (size_t)d_in, st, parts, (int)d_in, bad);
+    hipLaunchKernelGGL(bcd_check_parts_kernel, dim3((unsigned)T), dim3(256), sizeof(uint32_t) * (size_t)((d_in + 31) / 32), st, parts, (int)d_in, bad);
     CDQ_LAUNCH_CHECK();
     int rc = gradient_launch(H, Wt, scale, zero, Q, d_out, d_in, group, G0, st);
     if (rc != CDQ_OK) return rc;
     rc = extract_diag_launch(H, d_in, hdiag, st);
     if (rc != CDQ_OK) return rc;
-    const int64_t n_items = T * (d_in / 2);
+    if (!single_ok) {
+        uint32_t* t_ik = (uint32_t*)table;
+        float* t_thr = (float*)(table + 4 * (size_t)n_items);
+        float* t_h2 = (float*)(table + 8 * (size_t)n_items);
+        float* t_hi = (float*)(table + 12 * (size_t)n_items);
+        float* t_hk = (float*)(table + 16 * (size_t)n_items);
+        hipLaunchKernelGGL(bcdw_pair_gather_kernel, dim3((unsigned)((n_items + 255) / 256)), dim3(256), 0, st, H, parts,
+                           (const int32_t*)bad, d_in, n_items, t_ik, t_thr, t_h2, t_hi, t_hk);
+        CDQ_LAUNCH_CHECK();
+        const int tc = (int)(trace_cap > 0x7fffffffLL ? 0x7fffffffLL : trace_cap);
+#define BCDW_CASE(B)                                                                                                             \
+    if (bits == B) {                                                                                                             \
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(bcd2_wide_kernel<B>), hipFuncAttributeMaxDynamicSharedMemorySize,  \
+                                (int)wide_lds) != hipSuccess)                                                                    \
+            return CDQ_EHIP;                                                                                                     \
+        hipLaunchKernelGGL((bcd2_wide_kernel<B>), dim3((unsigned)d_out), dim3(BCDW_NT), wide_lds, st, H, (const float*)G0, scale, Q, \
+                           (const uint32_t*)t_ik, (const float*)t_thr, (const float*)t_h2, (const float*)t_hi, (const float*)t_hk, \
+                           (const int32_t*)bad, (int)d_in, (int)group, (int)T, score_all ? 1 : 0, moves, G_out, trace, tc);      \
+        CDQ_LAUNCH_CHECK();                                                                                                      \
+        return CDQ_OK;                                                                                                           \
+    }
+        BCDW_CASE(2) BCDW_CASE(3) BCDW_CASE(4)
+#undef BCDW_CASE
+        return CDQ_EINVAL;
+    }
     // several columns per workgroup where the columns' state and at least three pair-table rows fit in LDS
     int cw = 0, nst = 0;
     if (d_in % 16 == 0 && 5 * d_in / 16 <= BCDM_NT * BCDM_MAXI && !single)        // a row is 5 d_in / 16 chunks of 16 bytes

@@ -286,3 +286,35 @@ def test_widest_layer_36864_columns_against_the_oracle(cdq, oracle):
     assert np.array_equal(Q.cpu().numpy(), ref["Q"])
     assert np.array_equal(st[:, 0], ref["moves"])
     np.testing.assert_allclose(per, oracle.loss(H32, Wt, ref["Q"], a, b, d_in), rtol=1e-6)
+
+
+def test_wide_layer_bcd_against_the_oracle(cdq, oracle):
+    """Block CD at d_in = 14336 (an FFN2 width): beyond what the kernels with their state in LDS hold, so the wide-layer
+    kernel runs -- 2g in LDS, 20-byte table entries, codes in global memory.  A few columns from greedy CD's result, as
+    the paper starts it; the oracle reruns them from the GPU's fp32 H."""
+    d_in, d_out, n, bits, T = 14336, 4, 2048, 3, 48
+    say(f"generating X [{n}x{d_in}] on the GPU and Wt [{d_out}x{d_in}]")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(13)
+    Xd = (torch.randn((n, d_in), generator=g, device="cuda") * torch.exp(0.5 * torch.randn(d_in, generator=g, device="cuda"))
+          + torch.randn((n, 1), generator=g, device="cuda")).to(torch.bfloat16)
+    Wt = inputs.make_wt(d_out, d_in, seed=6)
+    Hd = cdq.hessian(Xd)
+    del Xd
+    Wd = torch.from_numpy(Wt).cuda()
+    scale, zero, Q = cdq.init_rtn(Wd, bits, d_in)
+    cdq.greedy_cd(Hd, Wd, scale, zero, Q, bits, d_in, 4000)
+    q_cd = Q.cpu().numpy().copy()
+    parts = inputs.make_partitions(T, d_in, seed=3)
+    say(f"BCD on the GPU, T={T}")
+    out = cdq.bcd(Hd, Wd, scale, zero, Q, bits, d_in, torch.from_numpy(parts).cuda(), want_G=True)
+    moves = out["moves"].cpu().numpy()
+    say(f"  block moves per column {moves.tolist()}")
+    say("copying H to the host for the oracle")
+    H32 = Hd.cpu().numpy()
+    a, b = scale.cpu().numpy(), zero.cpu().numpy()
+    ref = oracle.bcd(H32, Wt, a, b, q_cd, parts, bits, d_in, k=2)
+    assert moves.sum() > 0
+    assert np.array_equal(moves, ref["moves"])
+    assert np.array_equal(Q.cpu().numpy(), ref["Q"])
+    assert np.array_equal(out["G"].cpu().numpy(), ref["G"])

@@ -234,7 +234,9 @@ def bcd_moves_from_gpu(trace_j):
 @pytest.mark.parametrize("d_out,d_in,n,bits,group,T,start", [
     (24, 128, 400, 2, 128, 160, "random"), (16, 256, 700, 3, 64, 200, "random"), (10, 64, 300, 4, 16, 100, "random"),
     (12, 512, 1200, 3, 512, 300, "cd"), (9, 136, 400, 2, 8, 80, "random"), (6, 2048, 4096, 2, 128, 64, "rtn"),
-    (5, 4096, 6000, 3, 4096, 24, "rtn"), (6, 3072, 4000, 3, 128, 16, "rtn")])
+    (5, 4096, 6000, 3, 4096, 24, "rtn"), (6, 3072, 4000, 3, 128, 16, "rtn"),
+    # d_in not a multiple of 4: the wide-layer kernel (2g only in LDS, table entries with the diagonal)
+    (7, 130, 400, 3, 26, 60, "random"), (5, 1002, 1500, 4, 1002, 40, "rtn"), (3, 6, 40, 2, 6, 10, "random"), (4, 2050, 2600, 2, 410, 30, "cd")])
 @pytest.mark.parametrize("score_all,single_column", [(False, False), (True, False), (False, True), (True, True)])
 def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start, score_all, single_column):
     """Same partitions on both sides: the trajectories (iteration, block, levels, score bits), the final codes, the
@@ -689,7 +691,7 @@ def test_random_shapes_against_the_oracle(cdq, oracle, seed, big):
     for case in range(45 if big else 120):
         bits = int(rng.choice([2, 3, 4]))
         kind = str(rng.choice(["cd", "cd", "bcd", "bcd", "cyclic", "loss"]))
-        d_in = int(rng.integers(2, 90)) * int(rng.choice([16, 32, 48] if big else [4, 8, 16, 16]))
+        d_in = int(rng.integers(2, 90)) * int(rng.choice([16, 32, 48] if big else [2, 4, 8, 16, 16]))
         divs = [g for g in range(1, d_in + 1) if d_in % g == 0]
         group = int(rng.choice(divs[len(divs) // 2:]))
         d_out = int(rng.integers(1, 40))
