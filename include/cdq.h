@@ -173,7 +173,7 @@ int cdq_init_owc_cd(const float *H, const float *Wt, int64_t d_out, int64_t d_in
  *   flags bit 1 set: one column per workgroup also where the kernel that gives a workgroup
  *   several columns applies (d_in % 8 == 0 and the columns' state fits LDS).  Same results for
  *   every value of flags; the bits exist for tests and timing.
- * d_in even, at most 40896.  Three kernels give the same results: several columns per workgroup
+ * d_in even, at most 38400.  Three kernels give the same results: several columns per workgroup
  * (d_in % 16 == 0 and the columns' state fits LDS, d_in up to about 4700), one column per workgroup
  * with its state in LDS (d_in <= 8192, d_in % 4 == 0, 16-byte aligned H), and for wider or
  * differently aligned layers one column per workgroup with only the gradient in LDS, which streams

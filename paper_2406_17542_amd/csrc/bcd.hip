@@ -71,6 +71,13 @@ __global__ __launch_bounds__(256) void bcd_check_parts_kernel(const int32_t* __r
 
 constexpr int BCD_FASTQ = 16;       // survivors up to this many are scored with the lanes spread over the level pairs
 
+// A coordinate at an end of its grid whose gradient asks for a step past that end cannot lower the loss on its own: every
+// move it still has, delta = a (r - q), satisfies delta * 2g >= 0, so delta (delta H_ii + 2g) >= delta^2 H_ii, and the pair
+// bound holds with u = 0 for it.  (A non-positive step size says nothing about directions: then the plain u is used.)
+__device__ __forceinline__ bool bcd_blocked(float g2, float a, int q, int top) {
+    return (a > 0.0f) & (((g2 > 0.0f) & (q == 0)) | ((g2 < 0.0f) & (q == top)));
+}
+
 template <int BITS>
 __global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H, const float* __restrict__ hdiag,
                                                     const float* __restrict__ G0, const float* __restrict__ scale,
@@ -106,8 +113,10 @@ __global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H,
         const float g = 2.0f * G0[j * (int64_t)d_in + c], h = hdiag[c];
         g2[c] = g;
         hd[c] = h;
-        u[c] = __fdiv_rn(fabsf(g), h * a[c / group]);
-        q[c] = Q[j * (int64_t)d_in + c];
+        const uint8_t qc = Q[j * (int64_t)d_in + c];
+        const float ac = a[c / group];
+        u[c] = bcd_blocked(g, ac, qc, L - 1) ? 0.0f : __fdiv_rn(fabsf(g), h * ac);
+        q[c] = qc;
     }
 
     // entries of the next iteration are in flight while the current one is processed
@@ -274,11 +283,13 @@ __global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H,
             g.z = fmaf(tdk, y.z, fmaf(tdi, x.z, g.z));
             g.w = fmaf(tdk, y.w, fmaf(tdi, x.w, g.w));
             *reinterpret_cast<float4*>(g2 + c) = g;
+            const uchar4 qv = *reinterpret_cast<const uchar4*>(q + c);              // the codes after this move
+            const float a0 = a[c / group], a1 = a[(c + 1) / group], a2 = a[(c + 2) / group], a3 = a[(c + 3) / group];
             float4 un;
-            un.x = __fdiv_rn(fabsf(g.x), h.x * a[c / group]);
-            un.y = __fdiv_rn(fabsf(g.y), h.y * a[(c + 1) / group]);
-            un.z = __fdiv_rn(fabsf(g.z), h.z * a[(c + 2) / group]);
-            un.w = __fdiv_rn(fabsf(g.w), h.w * a[(c + 3) / group]);
+            un.x = bcd_blocked(g.x, a0, qv.x, L - 1) ? 0.0f : __fdiv_rn(fabsf(g.x), h.x * a0);
+            un.y = bcd_blocked(g.y, a1, qv.y, L - 1) ? 0.0f : __fdiv_rn(fabsf(g.y), h.y * a1);
+            un.z = bcd_blocked(g.z, a2, qv.z, L - 1) ? 0.0f : __fdiv_rn(fabsf(g.z), h.z * a2);
+            un.w = bcd_blocked(g.w, a3, qv.w, L - 1) ? 0.0f : __fdiv_rn(fabsf(g.w), h.w * a3);
             *reinterpret_cast<float4*>(u + c) = un;
         }
         __syncthreads();
@@ -338,8 +349,8 @@ __device__ __forceinline__ void bcdm_wait_vmem(int n) {       // at most n of th
 
 // v = 1 - u - tau in units of 2^-16 (tau is 4 of them), rounded DOWN by more than one unit; 0 when u is not a number
 // below 1 - 10 units
-__device__ __forceinline__ uint32_t bcdm_v16(float g2, float h, float a) {
-    const float u = __fdiv_rn(fabsf(g2), h * a);
+__device__ __forceinline__ uint32_t bcdm_v16(float g2, float h, float a, int q, int top) {
+    const float u = bcd_blocked(g2, a, q, top) ? 0.0f : __fdiv_rn(fabsf(g2), h * a);
     return (u >= 0.0f && u < 0.99985f) ? 65530u - (uint32_t)(u * 65536.0f) : 0u;
 }
 
@@ -432,7 +443,7 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
         for (int c = 0; c < CW; ++c) {
             const float g = (c < ncol) ? 2.0f * gl[c] : 0.0f;
             const uint32_t qv = (c < ncol) ? ql[c] : 0u;
-            const uint32_t u = (c < ncol) ? bcdm_v16(g, h, a[c * n_grp + grp(i)]) : 65535u;
+            const uint32_t u = (c < ncol) ? bcdm_v16(g, h, a[c * n_grp + grp(i)], (int)qv, L - 1) : 65535u;
             g2[i * CW + c] = g;
             V[i * CW + c] = (uint16_t)u;
             qp |= qv << (4 * c);
@@ -618,7 +629,8 @@ __global__ __launch_bounds__(BCDM_NT) void bcd2_multi_kernel(const float* __rest
                     if (x < d_in) {
                         const float g = fmaf(dk2, hkv[xx], fmaf(di2, hiv[xx], g2[x * CW + c]));
                         g2[x * CW + c] = g;
-                        V[x * CW + c] = (uint16_t)bcdm_v16(g, hd[x], a[c * n_grp + grp(x)]);
+                        const int qx = x == i ? ri : x == k ? rk : (int)((qpack[x] >> (4 * c)) & 15u);   // the codes after this move
+                        V[x * CW + c] = (uint16_t)bcdm_v16(g, hd[x], a[c * n_grp + grp(x)], qx, L - 1);
                     }
                 }
             }
@@ -677,10 +689,11 @@ size_t bcdm_lds_bytes(int64_t d_in, int64_t group, int cw, int nst) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Wide layers (d_in above what the kernels above hold: up to 40896).  One 1024-thread workgroup per column; LDS holds
-// only 2g.  Everything else a pair needs comes with its table entry -- i | k << 16, thr, 2 H_ik, H_ii, H_kk, 20 bytes --
+// Wide layers (d_in above what the kernels above hold: up to 38400).  One 1024-thread workgroup per column; LDS holds
+// only 2g and two bits a coordinate that say whether its code is at an end of the grid.  Everything else a pair needs comes with its table entry -- i | k << 16, rho^2, 2 H_ik, H_ii, H_kk, 20 bytes --
 // and the codes stay in global memory (read for the pairs that are scored and at a commit).  The pair test is the
-// one-column kernel's, as a product: |2 g_i| <= thr H_ii a_i (the rounding of the product is 2^-23, tau is 2^-14).
+// product form (1 - u_i - tau)(1 - u_k - tau) >= rho^2 of the several-column kernel, in fp32 and without divisions;
+// thr in the table is rho^2 here.
 // A thread scores its surviving pairs itself, all level pairs in (r_i, r_k) order.  Per iteration: one barrier when nothing
 // moves, three when the column commits.  The kernel streams the whole table once per column: it is bound by that.
 constexpr int BCDW_NT = 1024;
@@ -695,10 +708,13 @@ __global__ __launch_bounds__(256) void bcdw_pair_gather_kernel(const float* __re
     const int32_t i = parts[2 * x], k = parts[2 * x + 1];
     const float h2 = 2.0f * H[(int64_t)i * d_in + k];
     const float hii = H[(int64_t)i * d_in + i], hkk = H[(int64_t)k * d_in + k];
-    float thr = -1.0f;
-    if (hii > 0.0f && hkk > 0.0f) thr = 1.0f - (0.5f * fabsf(h2) * __frsqrt_rn(hii)) * __frsqrt_rn(hkk) - kBcdTau;
+    float r2 = INFINITY;                                              // rho^2; infinite (never skip) when a diagonal entry is not positive
+    if (hii > 0.0f && hkk > 0.0f) {
+        const float rho = (0.5f * fabsf(h2) * __frsqrt_rn(hii)) * __frsqrt_rn(hkk);
+        r2 = rho * rho;
+    }
     t_ik[x] = (uint32_t)i | ((uint32_t)k << 16);
-    t_thr[x] = thr;
+    t_thr[x] = r2;
     t_h2[x] = h2;
     t_hi[x] = hii;
     t_hk[x] = hkk;
@@ -726,7 +742,15 @@ __global__ __launch_bounds__(BCDW_NT) void bcd2_wide_kernel(const float* __restr
         if (tid == 0 && moves_out != nullptr) moves_out[j] = -1;
         return;
     }
-    for (int c = tid; c < d_in; c += BCDW_NT) g2[c] = 2.0f * G0[j * (int64_t)d_in + c];
+    uint32_t* edge = reinterpret_cast<uint32_t*>(g2 + d_in);      // [ceil(d_in / 16)] two bits a coordinate: code 0, code L - 1
+    for (int c = tid; c < (d_in + 15) / 16; c += BCDW_NT) edge[c] = 0u;
+    __syncthreads();
+    for (int c = tid; c < d_in; c += BCDW_NT) {
+        g2[c] = 2.0f * G0[j * (int64_t)d_in + c];
+        const int qc = Qj[c];
+        const uint32_t e = (qc == 0 ? 1u : 0u) | (qc == L - 1 ? 2u : 0u);
+        if (e) atomicOr(&edge[c >> 4], e << (2 * (c & 15)));
+    }
     __syncthreads();
     const uint32_t grp_mul = (uint32_t)((0x100000000ull + (uint32_t)group - 1u) / (uint32_t)group);   // exact below 2^16 (group > 1)
     auto a_of = [&](int i) { return scale_j[n_grp == 1 ? 0 : (group == 1 ? i : (int)__umulhi((uint32_t)i, grp_mul))]; };
@@ -751,7 +775,15 @@ __global__ __launch_bounds__(BCDW_NT) void bcd2_wide_kernel(const float* __restr
                 if (p >= n_pairs) continue;
                 const int i = (int)(ik[u] & 0xffffu), k = (int)(ik[u] >> 16);
                 const float ai = a_of(i), ak = a_of(k), gi = g2[i], gk = g2[k];
-                const bool quiet = (fabsf(gi) <= thr[u] * (hi[u] * ai)) & (fabsf(gk) <= thr[u] * (hk[u] * ak));   // thr < 0 or a NaN: not quiet
+                // (1 - u_i - tau)(1 - u_k - tau) >= rho^2 with both factors >= 0, multiplied through by H_ii a_i H_kk a_k;
+                // the roundings of these products (a few 2^-24) are far inside tau; an infinite or NaN side is not quiet
+                // a coordinate held at the end of its grid that 2g points past counts with u = 0
+                const uint32_t ei = edge[i >> 4] >> (2 * (i & 15)), ek = edge[k >> 4] >> (2 * (k & 15));
+                const bool bi = (ai > 0.0f) & ((ei & (gi > 0.0f ? 1u : gi < 0.0f ? 2u : 0u)) != 0u);       // a NaN is never held
+                const bool bk = (ak > 0.0f) & ((ek & (gk > 0.0f ? 1u : gk < 0.0f ? 2u : 0u)) != 0u);
+                const float wi = hi[u] * ai, wk = hk[u] * ak;
+                const float mi = fmaf(wi, 1.0f - kBcdTau, bi ? 0.0f : -fabsf(gi)), mk = fmaf(wk, 1.0f - kBcdTau, bk ? 0.0f : -fabsf(gk));
+                const bool quiet = (mi >= 0.0f) & (mk >= 0.0f) & (mi * mk >= (thr[u] * wi) * wk);
                 if (quiet && !score_all) continue;
                 const int qi = Qj[i], qk = Qj[k];
                 float dk[L], sk[L];
@@ -788,6 +820,8 @@ __global__ __launch_bounds__(BCDW_NT) void bcd2_wide_kernel(const float* __restr
         if (tid == 0) {
             Qj[i] = (uint8_t)ri;
             Qj[k] = (uint8_t)rk;
+            edge[i >> 4] = (edge[i >> 4] & ~(3u << (2 * (i & 15)))) | (((ri == 0 ? 1u : 0u) | (ri == L - 1 ? 2u : 0u)) << (2 * (i & 15)));
+            edge[k >> 4] = (edge[k >> 4] & ~(3u << (2 * (k & 15)))) | (((rk == 0 ? 1u : 0u) | (rk == L - 1 ? 2u : 0u)) << (2 * (k & 15)));
             if (trace != nullptr && moves < trace_cap) {
                 int32_t* tr = trace + (j * trace_cap + moves) * 4;
                 tr[0] = t; tr[1] = p; tr[2] = ri | (rk << 4);
@@ -852,7 +886,7 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
     const size_t lds = bcd_lds_bytes(d_in, group);
     // one column per workgroup with its state in LDS; failing that, the wide-layer kernel (2g only in LDS, any alignment)
     const bool single_ok = nt <= 1024 && lds <= 160 * 1024 && d_in % 4 == 0 && ((uintptr_t)H & 15) == 0;
-    const size_t wide_lds = sizeof(float) * (size_t)d_in;
+    const size_t wide_lds = sizeof(float) * (size_t)d_in + sizeof(uint32_t) * (size_t)((d_in + 15) / 16);
     const bool wide_ok = d_in < 65536 && wide_lds + 512 <= 160 * 1024;
     if ((!single_ok && !wide_ok) || T > 0x7fffffffLL || d_out > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
     if (ws == nullptr || ((uintptr_t)ws & 255) || ws_bytes < bcd_workspace_bytes(d_out, d_in, T)) return CDQ_EWORKSPACE;

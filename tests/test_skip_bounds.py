@@ -131,3 +131,50 @@ def test_margin_tau_covers_the_rounding_of_the_scores():
                 y2 = (float(a_k) * (rk - q_k)) ** 2 * float(h_kk)
                 worst = min(worst, s[ri, rk] / (x2 + y2))
     assert worst >= 0.5 * float(TAU)
+
+
+def test_division_free_product_form_never_skips_an_improving_pair():
+    """Wide-layer kernel: the product form in fp32 without divisions, (w_i (1-tau) - |2g_i|)(w_k (1-tau) - |2g_k|) >=
+    rho^2 w_i w_k with w = H a and both factors >= 0.  A skipped pair must have no negative fp32 score."""
+    rng = np.random.default_rng(4)
+    skipped = 0
+    for n in range(8000):
+        lv, a_i, a_k, q_i, q_k, g2_i, g2_k, h_ii, h_kk, h2 = random_case(rng, near_optimum=n % 2 == 0)
+        rho = rho_of(h2, h_ii, h_kk)
+        r2 = f32(rho * rho)
+        wi, wk = f32(h_ii * a_i), f32(h_kk * a_k)
+        one_tau = f32(f32(1.0) - TAU)
+        mi = f32(np.float64(wi) * np.float64(one_tau) - np.float64(abs(g2_i)))
+        mk = f32(np.float64(wk) * np.float64(one_tau) - np.float64(abs(g2_k)))
+        if mi >= 0 and mk >= 0 and f32(mi * mk) >= f32(f32(r2 * wi) * wk):
+            skipped += 1
+            assert pair_scores(a_i, a_k, q_i, q_k, g2_i, g2_k, h_ii, h_kk, h2, lv).min() >= 0.0
+    assert skipped > 700
+
+
+def test_a_coordinate_held_at_the_end_of_its_grid_counts_with_u_zero():
+    """All three kernels: a coordinate whose code is 0 (or the top level) while 2g asks for a step further down
+    (up) has only moves with delta * 2g >= 0; the bound then holds with u = 0 for it.  Pairs skipped with that
+    substitution, and not without it, must still have no negative fp32 score."""
+    rng = np.random.default_rng(5)
+    extra = 0
+    for n in range(12000):
+        lv, a_i, a_k, q_i, q_k, g2_i, g2_k, h_ii, h_kk, h2 = random_case(rng, near_optimum=n % 4 != 0)
+        q_i = int(rng.choice([0, lv - 1]))
+        if n % 3 == 0:
+            q_k = int(rng.choice([0, lv - 1]))
+        if n % 2 == 0:                                  # strong outward gradients: the plain test would never skip these
+            g2_i = f32(g2_i * f32(rng.uniform(1.0, 30.0)))
+
+        def u_eff(g2, h, a, q):
+            held = a > 0 and ((g2 > 0 and q == 0) or (g2 < 0 and q == lv - 1))
+            return np.float64(0.0) if held else np.float64(u_of(g2, h, a))
+
+        rho = np.float64(rho_of(h2, h_ii, h_kk))
+        fi, fk = 1.0 - u_eff(g2_i, h_ii, a_i, q_i) - float(TAU), 1.0 - u_eff(g2_k, h_kk, a_k, q_k) - float(TAU)
+        pi, pk = 1.0 - np.float64(u_of(g2_i, h_ii, a_i)) - float(TAU), 1.0 - np.float64(u_of(g2_k, h_kk, a_k)) - float(TAU)
+        if fi >= 0 and fk >= 0 and fi * fk >= rho * rho * (1.0 + 1e-4):
+            if not (pi >= 0 and pk >= 0 and pi * pk >= rho * rho):
+                extra += 1
+            assert pair_scores(a_i, a_k, q_i, q_k, g2_i, g2_k, h_ii, h_kk, h2, lv).min() >= 0.0
+    assert extra > 1000
