@@ -307,6 +307,31 @@ def test_bcd_strongly_correlated_pairs(cdq, oracle, d_out, d_in, n, bits, T):
         assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), single
 
 
+@pytest.mark.parametrize("d_out,d_in,n,bits,T", [(24, 512, 900, 3, 160), (10, 2048, 2600, 3, 48), (6, 1002, 1500, 3, 90), (7, 640, 900, 4, 60)])
+def test_bcd_on_a_clipping_grid(cdq, oracle, d_out, d_in, n, bits, T):
+    """A grid that covers half of each column's range (what a clipping initialisation gives) leaves many codes at an end
+    of the grid with gradients that point past it.  The kernels' pair test counts such coordinates as unable to move on
+    their own; trajectories from greedy CD's result on that grid must stay those of the oracle, which has no such test."""
+    X, Wt = rand_layer(900 + d_in, d_in, d_out, n, corr=0.6)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, _ = oracle.init_grid(Wt, bits, d_in)
+    top = (1 << bits) - 1
+    a2 = (np.float32(0.5) * a).astype(np.float32)
+    b2 = (b + np.float32(0.25 * top) * a).astype(np.float32)
+    q0 = np.clip(np.rint((Wt - b2) / a2), 0, top).astype(np.uint8)
+    assert ((q0 == 0) | (q0 == top)).mean() > 0.12
+    q_cd = oracle.greedy_cd(H32, Wt, a2, b2, q0, bits, d_in, d_in)["Q"]
+    parts = inputs.make_partitions(T, d_in, seed=d_in + 5)
+    ref = oracle.bcd(H32, Wt, a2, b2, q_cd, parts, bits, d_in, k=2)
+    assert ref["moves"].sum() > 0
+    for single in (False, True):
+        Q = dev(q_cd.copy())
+        out = cdq.bcd(dev(H32), dev(Wt), dev(a2), dev(b2), Q, bits, d_in, dev(parts), single_column=single, want_G=True)
+        assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), single
+        assert np.array_equal(Q.cpu().numpy(), ref["Q"]), single
+        assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), single
+
+
 def test_bcd_rejects_bad_partitions_and_block_sizes(cdq, oracle):
     X, Wt = rand_layer(5, 64, 4, 200)
     H32 = oracle.hessian(X).astype(np.float32)
