@@ -171,14 +171,15 @@ int cdq_init_owc_cd(const float *H, const float *Wt, int64_t d_out, int64_t d_in
  *   flags bit 0 clear: pairs that provably hold no improving move (both coordinates' |2 g| below
  *   (1 - |H_ik|/sqrt(H_ii H_kk) - 2^-10) H a) are not scored; set: every pair is scored.
  *   flags bit 1 set: one column per workgroup also where the kernel that gives a workgroup
- *   several columns applies (d_in % 8 == 0 and the columns' state fits LDS).  Same results for
- *   every value of flags; the bits exist for tests and timing.
- * d_in even, at most 38400.  Three kernels give the same results: several columns per workgroup
- * (d_in % 16 == 0 and the columns' state fits LDS, d_in up to about 4700), one column per workgroup
- * with its state in LDS (d_in <= 8192, d_in % 4 == 0, 16-byte aligned H), and for wider or
- * differently aligned layers one column per workgroup with only the gradient in LDS, which streams
- * a 20-byte table entry per pair and iteration from memory.  Workspace of CDQ_OP_BCD size (n = T):
- * d_out*d_in*4 + T*(d_in/2)*20 bytes and change.
+ *   several columns applies (d_in % 8 == 0 and the columns' state fits LDS).
+ *   flags bit 2 set: the wide-layer kernel whatever d_in.  Same results for every value of flags;
+ *   the bits exist for tests and timing.
+ * d_in even, at most 65534.  Three kernels give the same results: several columns per workgroup
+ * with their state in LDS (d_in % 16 == 0, d_in up to about 4700), one column per workgroup with
+ * its state in LDS (d_in <= 8192, d_in % 4 == 0, 16-byte aligned H), and for wider or differently
+ * aligned layers up to eight columns per workgroup with only the pair test's 16-bit margins in LDS
+ * and everything else in global memory.  Workspace of CDQ_OP_BCD size (n = T):
+ * d_out*d_in*6 + T*(d_in/2)*12 bytes and change.
  */
 int cdq_bcd(const float *H, const float *Wt, const float *scale, const float *zero, uint8_t *Q,
             int64_t d_out, int64_t d_in, int bits, int64_t group, int k, const int32_t *parts, int64_t T,

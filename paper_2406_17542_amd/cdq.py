@@ -179,9 +179,9 @@ def init_owc_cd(H, Wt, bits: int, group: int, n_gamma: int = 50, T: int | None =
 
 
 def bcd(H, Wt, scale, zero, Q, bits: int, group: int, parts: torch.Tensor, k: int = 2, trace_cap: int = 0, want_G: bool = False,
-        score_all: bool = False, single_column: bool = False, workspace: torch.Tensor | None = None):
+        score_all: bool = False, single_column: bool = False, wide: bool = False, workspace: torch.Tensor | None = None):
     """Block coordinate descent with random blocks (Algorithm 2/5); Q is updated in place.  parts [T][d_in] int32 on
-    the GPU.  score_all / single_column set bits 0 / 1 of the entry point's flags (same results, for tests and timing).
+    the GPU.  score_all / single_column / wide set bits 0 / 1 / 2 of the entry point's flags (same results, for tests and timing).
     Returns a dict: moves[, trace [d_out][trace_cap][4]][, G]."""
     d_out, d_in = Wt.shape
     T = int(parts.shape[0])
@@ -198,7 +198,7 @@ def bcd(H, Wt, scale, zero, Q, bits: int, group: int, parts: torch.Tensor, k: in
         g = out["G"].data_ptr()
     _check(lib().cdq_bcd(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), _dev(scale, torch.float32, "scale"),
                          _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, bits, group, k,
-                         parts.data_ptr() if T else None, T, out["moves"].data_ptr(), g, tr, trace_cap, int(score_all) | (2 if single_column else 0),
+                         parts.data_ptr() if T else None, T, out["moves"].data_ptr(), g, tr, trace_cap, int(score_all) | (2 if single_column else 0) | (4 if wide else 0),
                          ws.data_ptr(), ws.numel(), _stream()), "cdq_bcd")
     return out
 

@@ -689,170 +689,296 @@ size_t bcdm_lds_bytes(int64_t d_in, int64_t group, int cw, int nst) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Wide layers (d_in above what the kernels above hold: up to 38400).  One 1024-thread workgroup per column; LDS holds
-// only 2g and two bits a coordinate that say whether its code is at an end of the grid.  Everything else a pair needs comes with its table entry -- i | k << 16, rho^2, 2 H_ik, H_ii, H_kk, 20 bytes --
-// and the codes stay in global memory (read for the pairs that are scored and at a commit).  The pair test is the
-// product form (1 - u_i - tau)(1 - u_k - tau) >= rho^2 of the several-column kernel, in fp32 and without divisions;
-// thr in the table is rho^2 here.
-// A thread scores its surviving pairs itself, all level pairs in (r_i, r_k) order.  Per iteration: one barrier when nothing
-// moves, three when the column commits.  The kernel streams the whole table once per column: it is bound by that.
+// Wide layers (d_in above what the kernels above hold, up to 65534; any alignment).  A 1024-thread workgroup owns
+// CW in {8, 4, 2, 1} columns.  What bounds an idle iteration here is the two scattered LDS reads per pair of the test,
+// so LDS holds only what that test reads for all the columns at once -- the minimum over the columns of v = 1 - u - tau,
+// 16 bits a coordinate -- and one pass over the pairs serves CW columns.  Everything else stays in global memory: the
+// per-column v (rows of CW values, read for the few pairs that fail the test on the minimum), 2g (the workspace's
+// gradient rows, doubled in place), H_ii, the step sizes and the codes; from a coordinate-wise optimum few pairs are
+// scored and fewer commit, so those reads are rare.  The pair table is the several-column kernel's (i | k << 16, rho^2
+// in 16 bits rounded up, 2 H_ik) and so is the test, (vmin_i vmin_k) >> 16 >= R; a thread reads 6 bytes of table per
+// pair, one batch of entries ahead of the one it tests.
+// Per iteration: test -> queue of (column, pair) -> barrier -> (if any) score the queue, 16 lanes an entry, candidates
+// to the column's 64-bit key by an LDS minimum -> barrier -> (if a column found a move) commit.
 constexpr int BCDW_NT = 1024;
-constexpr int BCDW_UNR = 4;          // table entries whose loads are in flight together, per thread
+constexpr int BCDW_UNR = 8;          // table entries whose loads are in flight together, per thread
+constexpr int BCDW_QMAX = 512;
+constexpr int BCDW_SPREAD = 128;
+constexpr int BCDW_CUNR = 6;         // coordinates per thread whose loads are in flight together at a commit
 
-__global__ __launch_bounds__(256) void bcdw_pair_gather_kernel(const float* __restrict__ H, const int32_t* __restrict__ parts,
-                                                               const int32_t* __restrict__ bad, int64_t d_in, int64_t n_items,
-                                                               uint32_t* __restrict__ t_ik, float* __restrict__ t_thr,
-                                                               float* __restrict__ t_h2, float* __restrict__ t_hi, float* __restrict__ t_hk) {
-    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;        // x = t * (d_in/2) + p
-    if (x >= n_items || *bad != 0) return;
-    const int32_t i = parts[2 * x], k = parts[2 * x + 1];
-    const float h2 = 2.0f * H[(int64_t)i * d_in + k];
-    const float hii = H[(int64_t)i * d_in + i], hkk = H[(int64_t)k * d_in + k];
-    float r2 = INFINITY;                                              // rho^2; infinite (never skip) when a diagonal entry is not positive
-    if (hii > 0.0f && hkk > 0.0f) {
-        const float rho = (0.5f * fabsf(h2) * __frsqrt_rn(hii)) * __frsqrt_rn(hkk);
-        r2 = rho * rho;
+// the CW 16-bit margins of one coordinate, one load
+template <int CW>
+__device__ __forceinline__ void bcdw_load_row(const uint16_t* p, uint32_t (&v)[CW]) {
+    if constexpr (CW == 8) {
+        const uint4 w = *reinterpret_cast<const uint4*>(p);
+        v[0] = w.x & 0xffffu; v[1] = w.x >> 16; v[2] = w.y & 0xffffu; v[3] = w.y >> 16;
+        v[4] = w.z & 0xffffu; v[5] = w.z >> 16; v[6] = w.w & 0xffffu; v[7] = w.w >> 16;
+    } else if constexpr (CW == 4) {
+        const uint2 w = *reinterpret_cast<const uint2*>(p);
+        v[0] = w.x & 0xffffu; v[1] = w.x >> 16; v[2] = w.y & 0xffffu; v[3] = w.y >> 16;
+    } else if constexpr (CW == 2) {
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(p);
+        v[0] = w & 0xffffu; v[1] = w >> 16;
+    } else {
+        v[0] = *p;
     }
-    t_ik[x] = (uint32_t)i | ((uint32_t)k << 16);
-    t_thr[x] = r2;
-    t_h2[x] = h2;
-    t_hi[x] = hii;
-    t_hk[x] = hkk;
 }
 
-template <int BITS>
-__global__ __launch_bounds__(BCDW_NT) void bcd2_wide_kernel(const float* __restrict__ H, const float* __restrict__ G0,
-                                                            const float* __restrict__ scale, uint8_t* Q,
-                                                            const uint32_t* __restrict__ t_ik, const float* __restrict__ t_thr,
-                                                            const float* __restrict__ t_h2, const float* __restrict__ t_hi,
-                                                            const float* __restrict__ t_hk, const int32_t* __restrict__ bad_parts,
-                                                            int d_in, int group, int T, int score_all,
+template <int BITS, int CW>
+__global__ __launch_bounds__(BCDW_NT) void bcd2_wide_kernel(const float* __restrict__ H, const float* __restrict__ hdiag, float* G2,
+                                                            uint16_t* Vg_all, const float* __restrict__ scale, uint8_t* Q,
+                                                            const uint32_t* __restrict__ pair_ik, const uint16_t* __restrict__ pair_thr,
+                                                            const float* __restrict__ pair_h2, const int32_t* __restrict__ bad_parts,
+                                                            int d_out, int d_in, int group, int T, int score_all,
                                                             int32_t* __restrict__ moves_out, float* __restrict__ G_out,
                                                             int32_t* __restrict__ trace, int trace_cap) {
-    constexpr int L = 1 << BITS;
+    constexpr int L = 1 << BITS, NC = L * L;
+    constexpr int LPE = 16, CPL = NC / LPE;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    __shared__ unsigned long long slots[2][BCDW_NT / 64];
-    float* g2 = reinterpret_cast<float*>(smem);                   // [d_in] 2 g
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ unsigned long long colkey[3][CW];                  // per iteration mod 3: the columns' best (score image, pair, levels)
+    __shared__ int cnt[4];                                        // ring of queue lengths
+    __shared__ int found[3];                                      // per iteration mod 3: some column offered a move
+    __shared__ int moves[CW];
+    __shared__ int queue[BCDW_QMAX];                              // column | pair << 4
+    __shared__ uint32_t queue_ik[BCDW_QMAX];                      // the pair's i | k << 16
+    uint16_t* Vmin = reinterpret_cast<uint16_t*>(smem);           // [d_in] min over the columns of v
+    uint16_t* V = Vg_all + (size_t)blockIdx.x * d_in * CW;        // [d_in][CW] in global memory, this workgroup's alone
+    const int tid = threadIdx.x, lane = tid & 63;
     const int n_grp = d_in / group, n_pairs = d_in / 2;
-    const int64_t j = blockIdx.x;
-    const float* scale_j = scale + j * n_grp;
-    uint8_t* Qj = Q + j * (int64_t)d_in;                          // read and written by this workgroup only
-    if (*bad_parts != 0) {
-        if (tid == 0 && moves_out != nullptr) moves_out[j] = -1;
+    const uint32_t grp_mul = (uint32_t)((0x100000000ull + (uint32_t)group - 1u) / (uint32_t)group);   // exact below 2^16 (group > 1)
+    auto grp = [&](int i) { return n_grp == 1 ? 0 : (group == 1 ? i : (int)__umulhi((uint32_t)i, grp_mul)); };
+    const int j0 = blockIdx.x * CW;
+    const int ncol = (d_out - j0 < CW) ? d_out - j0 : CW;
+    if (*bad_parts != 0) {                                        // invalid partitions: leave the columns untouched
+        if (tid < ncol && moves_out != nullptr) moves_out[j0 + tid] = -1;
         return;
     }
-    uint32_t* edge = reinterpret_cast<uint32_t*>(g2 + d_in);      // [ceil(d_in / 16)] two bits a coordinate: code 0, code L - 1
-    for (int c = tid; c < (d_in + 15) / 16; c += BCDW_NT) edge[c] = 0u;
-    __syncthreads();
-    for (int c = tid; c < d_in; c += BCDW_NT) {
-        g2[c] = 2.0f * G0[j * (int64_t)d_in + c];
-        const int qc = Qj[c];
-        const uint32_t e = (qc == 0 ? 1u : 0u) | (qc == L - 1 ? 2u : 0u);
-        if (e) atomicOr(&edge[c >> 4], e << (2 * (c & 15)));
+    if (tid < 3 * CW) (&colkey[0][0])[tid] = ~0ull;
+    if (tid < 4) cnt[tid] = 0;
+    if (tid < 3) found[tid] = 0;
+    if (tid < CW) moves[tid] = 0;
+    for (int i = tid; i < d_in; i += BCDW_NT) {                   // a thread owns coordinate i in all columns
+        const float h = hdiag[i];
+        uint32_t vm = 65535u;
+#pragma unroll
+        for (int c = 0; c < CW; ++c) {
+            uint32_t v = 65535u;                                  // columns past the end never fail the test
+            if (c < ncol) {
+                const int64_t at = (int64_t)(j0 + c) * d_in + i;
+                const float g = 2.0f * G2[at];
+                G2[at] = g;                                       // from here on the row holds 2g
+                v = bcdm_v16(g, h, scale[(int64_t)(j0 + c) * n_grp + grp(i)], (int)Q[at], L - 1);
+            }
+            if (CW > 1) V[(size_t)i * CW + c] = (uint16_t)v;
+            vm = vm < v ? vm : v;
+        }
+        Vmin[i] = (uint16_t)vm;
     }
     __syncthreads();
-    const uint32_t grp_mul = (uint32_t)((0x100000000ull + (uint32_t)group - 1u) / (uint32_t)group);   // exact below 2^16 (group > 1)
-    auto a_of = [&](int i) { return scale_j[n_grp == 1 ? 0 : (group == 1 ? i : (int)__umulhi((uint32_t)i, grp_mul))]; };
 
-    int moves = 0;
+    const uint32_t valid_mask = (1u << ncol) - 1u;
+    // table entries travel through registers one batch ahead: the next batch of this iteration, or the first of the next one,
+    // is requested before the current batch is tested, so an idle iteration does not wait for memory after its barrier
+    uint32_t nik[BCDW_UNR], nthr[BCDW_UNR];
+    auto fetch = [&](int tt, int p0) {
+        const uint32_t* f_ik = pair_ik + (int64_t)tt * n_pairs;
+        const uint16_t* f_thr = pair_thr + (int64_t)tt * n_pairs;
+#pragma unroll
+        for (int u = 0; u < BCDW_UNR; ++u) {                      // entries past the end reload the batch's first one
+            const int p = p0 + u * BCDW_NT, pc = p < n_pairs ? p : p0;
+            nik[u] = f_ik[pc];
+            nthr[u] = f_thr[pc];
+        }
+    };
+    if (tid < n_pairs) fetch(0, tid);
     for (int t = 0; t < T; ++t) {
         const int64_t row = (int64_t)t * n_pairs;
-        float best_s = 0.0f;
-        uint32_t best_pay = 0xffffffffu;
-        for (int p0 = tid; p0 < n_pairs; p0 += BCDW_NT * BCDW_UNR) {
-            uint32_t ik[BCDW_UNR];
-            float thr[BCDW_UNR], h2[BCDW_UNR], hi[BCDW_UNR], hk[BCDW_UNR];
+        const uint32_t* r_ik = pair_ik + row;
+        const float* r_h2 = pair_h2 + row;
+        int* my_cnt = cnt + (t & 3);
+        unsigned long long* key_t = colkey[t % 3];
+        int* found_t = found + t % 3;
+        // level pairs sub, sub + step, ... of pair p for column c in increasing order (r_i major), folded into the running best
+        auto score_pair = [&](int c, int p, uint32_t ik, int sub, int step, float& best_s, uint32_t& best_pay) {
+            const int i = (int)(ik & 0xffffu), k = (int)(ik >> 16);
+            const int64_t col = j0 + c;
+            const float hh = r_h2[p];
+            const float ai = scale[col * n_grp + grp(i)], ak = scale[col * n_grp + grp(k)];
+            const float gi = G2[col * d_in + i], gk = G2[col * d_in + k], hii = hdiag[i], hkk = hdiag[k];
+            const int qi = Q[col * d_in + i], qk = Q[col * d_in + k];
+            auto one = [&](int cidx) {
+                const int ri = cidx >> BITS, rk = cidx & (L - 1);
+                const float di = ai * (float)(ri - qi), dk = ak * (float)(rk - qk);
+                const float si = di * fmaf(di, hii, gi), sk = dk * fmaf(dk, hkk, gk);
+                const float sc = fmaf(di * dk, hh, si + sk);
+                if (sc < best_s) { best_s = sc; best_pay = ((uint32_t)p << 8) | (uint32_t)(ri << 4) | (uint32_t)rk; }
+            };
+            if (step == 1) {
 #pragma unroll
-            for (int u = 0; u < BCDW_UNR; ++u) {                  // entries past the end reload the thread's first one
-                const int p = p0 + u * BCDW_NT;
-                const int64_t x = row + (p < n_pairs ? p : p0);
-                ik[u] = t_ik[x]; thr[u] = t_thr[x]; h2[u] = t_h2[x]; hi[u] = t_hi[x]; hk[u] = t_hk[x];
+                for (int m = 0; m < NC; ++m) one(m);
+            } else {
+#pragma unroll
+                for (int m = 0; m < CPL; ++m) one(sub + m * LPE);
             }
+        };
+        auto offer = [&](int c, float best_s, uint32_t best_pay) {
+            if (best_s < 0.0f) {
+                const unsigned long long key = ((unsigned long long)order_bits(best_s) << 32) | best_pay;
+                *found_t = 1;
+                atomicMin(&key_t[c], key);
+            }
+        };
+
+        // ---- which (column, pair) need scoring
+        for (int p0 = tid; p0 < n_pairs; p0 += BCDW_NT * BCDW_UNR) {
+            uint32_t ik[BCDW_UNR], thr[BCDW_UNR];
+#pragma unroll
+            for (int u = 0; u < BCDW_UNR; ++u) { ik[u] = nik[u]; thr[u] = nthr[u]; }
+            if (p0 + BCDW_NT * BCDW_UNR < n_pairs) fetch(t, p0 + BCDW_NT * BCDW_UNR);
+            else if (t + 1 < T) fetch(t + 1, tid);
 #pragma unroll
             for (int u = 0; u < BCDW_UNR; ++u) {
                 const int p = p0 + u * BCDW_NT;
-                if (p >= n_pairs) continue;
                 const int i = (int)(ik[u] & 0xffffu), k = (int)(ik[u] >> 16);
-                const float ai = a_of(i), ak = a_of(k), gi = g2[i], gk = g2[k];
-                // (1 - u_i - tau)(1 - u_k - tau) >= rho^2 with both factors >= 0, multiplied through by H_ii a_i H_kk a_k;
-                // the roundings of these products (a few 2^-24) are far inside tau; an infinite or NaN side is not quiet
-                // a coordinate held at the end of its grid that 2g points past counts with u = 0
-                const uint32_t ei = edge[i >> 4] >> (2 * (i & 15)), ek = edge[k >> 4] >> (2 * (k & 15));
-                const bool bi = (ai > 0.0f) & ((ei & (gi > 0.0f ? 1u : gi < 0.0f ? 2u : 0u)) != 0u);       // a NaN is never held
-                const bool bk = (ak > 0.0f) & ((ek & (gk > 0.0f ? 1u : gk < 0.0f ? 2u : 0u)) != 0u);
-                const float wi = hi[u] * ai, wk = hk[u] * ak;
-                const float mi = fmaf(wi, 1.0f - kBcdTau, bi ? 0.0f : -fabsf(gi)), mk = fmaf(wk, 1.0f - kBcdTau, bk ? 0.0f : -fabsf(gk));
-                const bool quiet = (mi >= 0.0f) & (mk >= 0.0f) & (mi * mk >= (thr[u] * wi) * wk);
-                if (quiet && !score_all) continue;
-                const int qi = Qj[i], qk = Qj[k];
-                float dk[L], sk[L];
+                const uint32_t vi = Vmin[i], vk = Vmin[k];
+                if (p < n_pairs && (bcdm_margin(vi, vk) < thr[u] || score_all)) {
+                    uint32_t mask = 1u;
+                    if (CW > 1) {                                 // which columns: their own margins, two rows from global memory
+                        uint32_t ri[CW], rk[CW];
+                        bcdw_load_row<CW>(V + (size_t)i * CW, ri);
+                        bcdw_load_row<CW>(V + (size_t)k * CW, rk);
+                        mask = 0u;
 #pragma unroll
-                for (int rr = 0; rr < L; ++rr) {
-                    dk[rr] = ak * (float)(rr - qk);
-                    sk[rr] = dk[rr] * fmaf(dk[rr], hk[u], gk);
-                }
-#pragma unroll
-                for (int ri = 0; ri < L; ++ri) {
-                    const float di = ai * (float)(ri - qi);
-                    const float si = di * fmaf(di, hi[u], gi);
-#pragma unroll
-                    for (int rk = 0; rk < L; ++rk) {
-                        const float sc = fmaf(di * dk[rk], h2[u], si + sk[rk]);
-                        if (sc < best_s) { best_s = sc; best_pay = ((uint32_t)p << 8) | (uint32_t)(ri << 4) | (uint32_t)rk; }
+                        for (int c = 0; c < CW; ++c) mask |= (bcdm_margin(ri[c], rk[c]) < thr[u] ? 1u : 0u) << c;
+                    }
+                    if (score_all) mask = ~0u;
+                    mask &= valid_mask;
+                    if (mask) {
+                        int pos = atomicAdd(my_cnt, __builtin_popcount(mask));
+                        while (mask) {
+                            const int c = __builtin_ctz(mask);
+                            mask &= mask - 1;
+                            if (pos < BCDW_QMAX) { queue[pos] = c | (p << 4); queue_ik[pos] = ik[u]; }
+                            ++pos;
+                        }
                     }
                 }
             }
         }
-        uint64_t key = wave_min_key(order_bits(best_s), best_pay);
-        if (lane == 0) slots[t & 1][wave] = key;
-        __syncthreads();
-#pragma unroll
-        for (int w = 0; w < BCDW_NT / 64; ++w) key = umin64(key, (uint64_t)slots[t & 1][w]);
-        if ((uint32_t)(key >> 32) >= kOrderedZero) continue;          // no pair lowers the loss under this partition
-        // ---- commit
-        const uint32_t pay = (uint32_t)key;
-        const int p = (int)(pay >> 8), ri = (int)((pay >> 4) & 15u), rk = (int)(pay & 15u);
-        const uint32_t ikw = t_ik[row + p];
-        const int i = (int)(ikw & 0xffffu), k = (int)(ikw >> 16);
-        const float di2 = 2.0f * (a_of(i) * (float)(ri - (int)Qj[i])), dk2 = 2.0f * (a_of(k) * (float)(rk - (int)Qj[k]));
-        __syncthreads();                                               // everybody has read the old codes
-        if (tid == 0) {
-            Qj[i] = (uint8_t)ri;
-            Qj[k] = (uint8_t)rk;
-            edge[i >> 4] = (edge[i >> 4] & ~(3u << (2 * (i & 15)))) | (((ri == 0 ? 1u : 0u) | (ri == L - 1 ? 2u : 0u)) << (2 * (i & 15)));
-            edge[k >> 4] = (edge[k >> 4] & ~(3u << (2 * (k & 15)))) | (((rk == 0 ? 1u : 0u) | (rk == L - 1 ? 2u : 0u)) << (2 * (k & 15)));
-            if (trace != nullptr && moves < trace_cap) {
-                int32_t* tr = trace + (j * trace_cap + moves) * 4;
-                tr[0] = t; tr[1] = p; tr[2] = ri | (rk << 4);
-                tr[3] = (int32_t)~(uint32_t)(key >> 32);               // the ordered image of a negative score is ~bits
+        __syncthreads();                                         // the queue is complete; iteration t-1 is over for everybody
+        if (tid == 0) { cnt[(t + 2) & 3] = 0; found[(t + 2) % 3] = 0; }
+        if (tid < CW) colkey[(t + 2) % 3][tid] = ~0ull;
+        const int n_q = *my_cnt;
+        if (n_q == 0) continue;                                  // an idle iteration costs one barrier
+
+        if (n_q <= BCDW_SPREAD) {
+            for (int x = tid / LPE; x < n_q; x += BCDW_NT / LPE) {                  // few: 16 lanes share an entry
+                const int e = queue[x];
+                float best_s = 0.0f;
+                uint32_t best_pay = 0xffffffffu;
+                score_pair(e & 15, e >> 4, queue_ik[x], tid % LPE, LPE, best_s, best_pay);
+                offer(e & 15, best_s, best_pay);
             }
-            __threadfence_block();
-        }
-        const float* hrow_i = H + (int64_t)i * d_in;
-        const float* hrow_k = H + (int64_t)k * d_in;
-        for (int x0 = tid; x0 < d_in; x0 += BCDW_NT * BCDW_UNR) {
-            float vi[BCDW_UNR], vk[BCDW_UNR];
-#pragma unroll
-            for (int u = 0; u < BCDW_UNR; ++u) {
-                const int x = x0 + u * BCDW_NT, xc = x < d_in ? x : x0;
-                vi[u] = hrow_i[xc];
-                vk[u] = hrow_k[xc];
+        } else if (n_q <= BCDW_QMAX) {
+            for (int x = tid; x < n_q; x += BCDW_NT) {                              // more: an entry per thread
+                const int e = queue[x];
+                float best_s = 0.0f;
+                uint32_t best_pay = 0xffffffffu;
+                score_pair(e & 15, e >> 4, queue_ik[x], 0, 1, best_s, best_pay);
+                offer(e & 15, best_s, best_pay);
             }
-#pragma unroll
-            for (int u = 0; u < BCDW_UNR; ++u) {
-                const int x = x0 + u * BCDW_NT;
-                if (x < d_in) g2[x] = fmaf(dk2, vk[u], fmaf(di2, vi[u], g2[x]));
+        } else {
+            for (int c = 0; c < ncol; ++c) {                                        // the queue overflowed: everything, column by column
+                float best_s = 0.0f;
+                uint32_t best_pay = 0xffffffffu;
+                for (int p = tid; p < n_pairs; p += BCDW_NT) score_pair(c, p, r_ik[p], 0, 1, best_s, best_pay);
+                const uint64_t key = wave_min_key(order_bits(best_s), best_pay);
+                if (lane == 0 && (uint32_t)(key >> 32) < kOrderedZero) {
+                    *found_t = 1;
+                    atomicMin(&key_t[c], (unsigned long long)key);
+                }
             }
         }
-        ++moves;
-        __syncthreads();                                               // 2g and the codes are updated
+        __syncthreads();                                         // the columns' keys are final
+        if (*found_t == 0) continue;                             // scored, no move: two barriers
+        // ---- commit: every thread derives the moves, then updates its own coordinates of 2g, V and Vmin for the moving
+        // columns, one after the other
+        for (int c = 0; c < ncol; ++c) {
+            const unsigned long long key = key_t[c];
+            if ((uint32_t)(key >> 32) >= kOrderedZero) continue;
+            const uint32_t pay = (uint32_t)key;
+            const int p = (int)(pay >> 8), ri = (int)((pay >> 4) & 15u), rk = (int)(pay & 15u);
+            const uint32_t ik = r_ik[p];
+            const int i = (int)(ik & 0xffffu), k = (int)(ik >> 16);
+            const int64_t col = j0 + c;
+            float* g2c = G2 + col * d_in;
+            const uint8_t* qc = Q + col * d_in;
+            const float* ac = scale + col * n_grp;
+            const float di2 = 2.0f * (ac[grp(i)] * (float)(ri - (int)qc[i])), dk2 = 2.0f * (ac[grp(k)] * (float)(rk - (int)qc[k]));
+            const float* hi = H + (int64_t)i * d_in;
+            const float* hk = H + (int64_t)k * d_in;
+            for (int x0 = tid; x0 < d_in; x0 += BCDW_NT * BCDW_CUNR) {
+                float vi[BCDW_CUNR], vk[BCDW_CUNR], gv[BCDW_CUNR], hv[BCDW_CUNR], av[BCDW_CUNR];
+                int qv[BCDW_CUNR];
+                uint32_t rows[BCDW_CUNR][CW];
+#pragma unroll
+                for (int u = 0; u < BCDW_CUNR; ++u) {             // all loads of a batch of coordinates in flight together
+                    const int x = x0 + u * BCDW_NT, xc = x < d_in ? x : x0;
+                    vi[u] = hi[xc]; vk[u] = hk[xc]; gv[u] = g2c[xc]; hv[u] = hdiag[xc]; av[u] = ac[grp(xc)]; qv[u] = qc[xc];
+                    if (CW > 1) bcdw_load_row<CW>(V + (size_t)xc * CW, rows[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < BCDW_CUNR; ++u) {
+                    const int x = x0 + u * BCDW_NT;
+                    if (x < d_in) {
+                        const float g = fmaf(dk2, vk[u], fmaf(di2, vi[u], gv[u]));
+                        g2c[x] = g;
+                        const int qx = x == i ? ri : x == k ? rk : qv[u];                   // the codes after this move
+                        const uint32_t v = bcdm_v16(g, hv[u], av[u], qx, L - 1);
+                        uint32_t vm = v;
+                        if (CW > 1) {                             // the row with this column replaced: the new minimum
+                            V[(size_t)x * CW + c] = (uint16_t)v;
+#pragma unroll
+                            for (int c2 = 0; c2 < CW; ++c2) {
+                                const uint32_t o = c2 == c ? v : rows[u][c2];
+                                vm = vm < o ? vm : o;
+                            }
+                        }
+                        Vmin[x] = (uint16_t)vm;
+                    }
+                }
+            }
+            __syncthreads();                                     // (the same keys for every thread: a uniform barrier) this column's
+        }                                                        // margins are written before another column's pass reads the rows,
+        if (tid == 0) {                                          // and everybody has read the old codes
+            for (int c = 0; c < ncol; ++c) {
+                const unsigned long long key = key_t[c];
+                if ((uint32_t)(key >> 32) >= kOrderedZero) continue;
+                const uint32_t pay = (uint32_t)key;
+                const uint32_t ik = r_ik[pay >> 8];
+                uint8_t* qc = Q + (int64_t)(j0 + c) * d_in;
+                qc[ik & 0xffffu] = (uint8_t)((pay >> 4) & 15u);
+                qc[ik >> 16] = (uint8_t)(pay & 15u);
+                if (trace != nullptr && moves[c] < trace_cap) {
+                    int32_t* tr = trace + ((int64_t)(j0 + c) * trace_cap + moves[c]) * 4;
+                    tr[0] = t; tr[1] = (int32_t)(pay >> 8);
+                    tr[2] = (int32_t)(((pay >> 4) & 15u) | ((pay & 15u) << 4));
+                    tr[3] = (int32_t)~(uint32_t)(key >> 32);               // the ordered image of a negative score is ~bits
+                }
+                ++moves[c];
+            }
+        }
+        __syncthreads();                                         // 2g, V, Vmin and the codes are updated
     }
     __syncthreads();
-    if (G_out != nullptr)
-        for (int c = tid; c < d_in; c += BCDW_NT) G_out[j * (int64_t)d_in + c] = 0.5f * g2[c];
-    if (tid == 0 && moves_out != nullptr) moves_out[j] = moves;
+    for (int c = 0; c < ncol; ++c) {
+        if (G_out != nullptr)
+            for (int i = tid; i < d_in; i += BCDW_NT) G_out[(int64_t)(j0 + c) * d_in + i] = 0.5f * G2[(int64_t)(j0 + c) * d_in + i];
+        if (tid == 0 && moves_out != nullptr) moves_out[j0 + c] = moves[c];
+    }
 }
+
+size_t bcdw_lds_bytes(int64_t d_in) { return cdq_align_up((size_t)d_in * 2, 16); }
 
 size_t bcd_lds_bytes(int64_t d_in, int64_t group) {
     const int64_t n_grp = d_in / group;
@@ -862,17 +988,19 @@ size_t bcd_lds_bytes(int64_t d_in, int64_t group) {
 
 }  // namespace
 
-// workspace: G0 [d_out][d_in] fp32 | hdiag [d_in] | pair table, 20 bytes per (iteration, pair) | flag.
-// The one- and several-column kernels use 12 of the 20 bytes (pair_rec int2 + pair_h2, or ik + R16 + pair_h2).
+// workspace: G0 [d_out][d_in] fp32 | hdiag [d_in] | pair table, 12 bytes per (iteration, pair) | flag |
+// the wide-layer kernel's 16-bit margins, [d_out rounded up to 8][d_in].
+// (pair_rec int2 + pair_h2 for the one-column kernel, ik + R16 + 2 spare + pair_h2 for the others)
 size_t bcd_workspace_bytes(int64_t d_out, int64_t d_in, int64_t T) {
     return cdq_align_up((size_t)d_out * d_in * sizeof(float), 256) + cdq_align_up((size_t)d_in * sizeof(float), 256) +
-           cdq_align_up((size_t)T * (d_in / 2) * 20, 256) + 256;
+           cdq_align_up((size_t)T * (d_in / 2) * 12, 256) + 256 +
+           cdq_align_up((size_t)(d_out + 7) / 8 * 8 * d_in * sizeof(uint16_t), 256);
 }
 
 int bcd_launch(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out, int64_t d_in,
                int bits, int64_t group, const int32_t* parts, int64_t T, int32_t* moves, float* G_out, int32_t* trace,
                int64_t trace_cap, int flags, void* ws, size_t ws_bytes, hipStream_t st) {
-    const bool score_all = (flags & 1) != 0, single = (flags & 2) != 0;
+    const bool score_all = (flags & 1) != 0, single = (flags & 2) != 0, wide = (flags & 4) != 0;
     if (d_out == 0 || T == 0) {
         if (T == 0 && d_out > 0 && moves != nullptr) {
             hipLaunchKernelGGL(bcd_fill_i32_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, moves, d_out, 0);
@@ -884,20 +1012,23 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
     int nt = 256;
     while ((int64_t)nt * BCD_PPT < d_in / 2) nt *= 2;
     const size_t lds = bcd_lds_bytes(d_in, group);
-    // one column per workgroup with its state in LDS; failing that, the wide-layer kernel (2g only in LDS, any alignment)
+    // one column per workgroup with its state in LDS; failing that, the wide-layer kernel (any alignment)
     const bool single_ok = nt <= 1024 && lds <= 160 * 1024 && d_in % 4 == 0 && ((uintptr_t)H & 15) == 0;
-    const size_t wide_lds = sizeof(float) * (size_t)d_in + sizeof(uint32_t) * (size_t)((d_in + 15) / 16);
-    const bool wide_ok = d_in < 65536 && wide_lds + 512 <= 160 * 1024;
+    int wcw = 0;                                                  // columns per workgroup of the wide-layer kernel
+    if (d_in < 65536 && bcdw_lds_bytes(d_in) + 4096 <= 160 * 1024) wcw = 8;
+    while (wcw > 1 && (d_out + wcw - 1) / wcw < 256) wcw /= 2;   // rather more workgroups than CUs
+    const bool wide_ok = wcw != 0;
     if ((!single_ok && !wide_ok) || T > 0x7fffffffLL || d_out > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
     if (ws == nullptr || ((uintptr_t)ws & 255) || ws_bytes < bcd_workspace_bytes(d_out, d_in, T)) return CDQ_EWORKSPACE;
     const int64_t n_items = T * (d_in / 2);
     char* wp = (char*)ws;
     float* G0 = (float*)wp;           wp += cdq_align_up((size_t)d_out * d_in * sizeof(float), 256);
     float* hdiag = (float*)wp;        wp += cdq_align_up((size_t)d_in * sizeof(float), 256);
-    char* table = wp;                 wp += cdq_align_up((size_t)n_items * 20, 256);
+    char* table = wp;                 wp += cdq_align_up((size_t)n_items * 12, 256);
     int2* pair_rec = (int2*)table;                                       // [n_items] 8 bytes each, then
     float* pair_h2 = (float*)(table + 8 * (size_t)n_items);              // [n_items]
-    int32_t* bad = (int32_t*)wp;
+    int32_t* bad = (int32_t*)wp;       wp += 256;
+    uint16_t* Vg = (uint16_t*)wp;
 
     hipLaunchKernelGGL(bcd_fill_i32_kernel, dim3(1), dim3(64), 0, st, bad, (int64_t)1, 0);
     CDQ_LAUNCH_CHECK();
@@ -907,31 +1038,6 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
     if (rc != CDQ_OK) return rc;
     rc = extract_diag_launch(H, d_in, hdiag, st);
     if (rc != CDQ_OK) return rc;
-    if (!single_ok) {
-        uint32_t* t_ik = (uint32_t*)table;
-        float* t_thr = (float*)(table + 4 * (size_t)n_items);
-        float* t_h2 = (float*)(table + 8 * (size_t)n_items);
-        float* t_hi = (float*)(table + 12 * (size_t)n_items);
-        float* t_hk = (float*)(table + 16 * (size_t)n_items);
-        hipLaunchKernelGGL(bcdw_pair_gather_kernel, dim3((unsigned)((n_items + 255) / 256)), dim3(256), 0, st, H, parts,
-                           (const int32_t*)bad, d_in, n_items, t_ik, t_thr, t_h2, t_hi, t_hk);
-        CDQ_LAUNCH_CHECK();
-        const int tc = (int)(trace_cap > 0x7fffffffLL ? 0x7fffffffLL : trace_cap);
-#define BCDW_CASE(B)                                                                                                             \
-    if (bits == B) {                                                                                                             \
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(bcd2_wide_kernel<B>), hipFuncAttributeMaxDynamicSharedMemorySize,  \
-                                (int)wide_lds) != hipSuccess)                                                                    \
-            return CDQ_EHIP;                                                                                                     \
-        hipLaunchKernelGGL((bcd2_wide_kernel<B>), dim3((unsigned)d_out), dim3(BCDW_NT), wide_lds, st, H, (const float*)G0, scale, Q, \
-                           (const uint32_t*)t_ik, (const float*)t_thr, (const float*)t_h2, (const float*)t_hi, (const float*)t_hk, \
-                           (const int32_t*)bad, (int)d_in, (int)group, (int)T, score_all ? 1 : 0, moves, G_out, trace, tc);      \
-        CDQ_LAUNCH_CHECK();                                                                                                      \
-        return CDQ_OK;                                                                                                           \
-    }
-        BCDW_CASE(2) BCDW_CASE(3) BCDW_CASE(4)
-#undef BCDW_CASE
-        return CDQ_EINVAL;
-    }
     // several columns per workgroup where the columns' state and at least three pair-table rows fit in LDS
     int cw = 0, nst = 0;
     if (d_in % 16 == 0 && 5 * d_in / 16 <= BCDM_NT * BCDM_MAXI && !single)        // a row is 5 d_in / 16 chunks of 16 bytes
@@ -944,6 +1050,35 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
             nst = fit > 6 ? 6 : (int)fit;
             break;
         }
+    // the wide-layer kernel where nothing else applies, and where it shares a pass over the pairs among more columns than
+    // the kernels with the columns' state in LDS would (measured, d_in = 4608: 2 columns 363 ms, 8 columns here 205 ms)
+    const bool use_wide = !single_ok || (wide && wide_ok) || (!single && cw < 4 && wcw >= 4);
+    if (use_wide) {
+        uint32_t* t_ik = (uint32_t*)table;
+        uint16_t* t_thr = (uint16_t*)(table + 4 * (size_t)n_items);
+        hipLaunchKernelGGL(bcdm_pair_gather_kernel, dim3((unsigned)((n_items + 255) / 256)), dim3(256), 0, st, H, parts,
+                           (const int32_t*)bad, d_in, n_items, t_ik, t_thr, pair_h2);
+        CDQ_LAUNCH_CHECK();
+        const int tc = (int)(trace_cap > 0x7fffffffLL ? 0x7fffffffLL : trace_cap);
+        const size_t wlds = bcdw_lds_bytes(d_in);
+        const dim3 grid((unsigned)((d_out + wcw - 1) / wcw));
+#define BCDW_CASE(B, C)                                                                                                          \
+    if (bits == B && wcw == C) {                                                                                                 \
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(bcd2_wide_kernel<B, C>), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                (int)wlds) != hipSuccess)                                                                        \
+            return CDQ_EHIP;                                                                                                     \
+        hipLaunchKernelGGL((bcd2_wide_kernel<B, C>), grid, dim3(BCDW_NT), wlds, st, H, (const float*)hdiag, G0, Vg, scale, Q,    \
+                           (const uint32_t*)t_ik, (const uint16_t*)t_thr, (const float*)pair_h2, (const int32_t*)bad, (int)d_out, \
+                           (int)d_in, (int)group, (int)T, score_all ? 1 : 0, moves, G_out, trace, tc);                           \
+        CDQ_LAUNCH_CHECK();                                                                                                      \
+        return CDQ_OK;                                                                                                           \
+    }
+        BCDW_CASE(2, 8) BCDW_CASE(2, 4) BCDW_CASE(2, 2) BCDW_CASE(2, 1)
+        BCDW_CASE(3, 8) BCDW_CASE(3, 4) BCDW_CASE(3, 2) BCDW_CASE(3, 1)
+        BCDW_CASE(4, 8) BCDW_CASE(4, 4) BCDW_CASE(4, 2) BCDW_CASE(4, 1)
+#undef BCDW_CASE
+        return CDQ_EINVAL;
+    }
     if (cw != 0) {
         hipLaunchKernelGGL(bcdm_pair_gather_kernel, dim3((unsigned)((n_items + 255) / 256)), dim3(256), 0, st, H, parts,
                            (const int32_t*)bad, d_in, n_items, (uint32_t*)pair_rec, (uint16_t*)((char*)pair_rec + 4 * n_items), pair_h2);

@@ -89,7 +89,7 @@ int cdq_init_owc_cd(const float* H, const float* Wt, int64_t d_out, int64_t d_in
 int cdq_bcd(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out, int64_t d_in,
             int bits, int64_t group, int k, const int32_t* parts, int64_t T, int32_t* moves, float* G_out, int32_t* trace,
             int64_t trace_cap, int flags, void* workspace, size_t workspace_bytes, void* stream) {
-    if (bad_bits(bits) || bad_layer(d_out, d_in, group) || T < 0 || k < 1 || (flags & ~3) != 0) return CDQ_EINVAL;
+    if (bad_bits(bits) || bad_layer(d_out, d_in, group) || T < 0 || k < 1 || (flags & ~7) != 0) return CDQ_EINVAL;
     if (trace != nullptr && trace_cap <= 0) return CDQ_EINVAL;
     if (k != 2) return CDQ_EUNSUPPORTED;              // k = 1 is cdq_greedy_cd; larger blocks are not built
     if (d_in % 2 != 0) return CDQ_EINVAL;

@@ -144,7 +144,7 @@ def main():
             continue
         Wt = torch.from_numpy(inputs.make_wt(d_out, d_in, seed=1)).cuda()
         parts = None
-        if args.bcd and d_in <= 38400:
+        if args.bcd and d_in <= 65534:
             parts = torch.from_numpy(inputs.make_partitions(d_in, d_in, seed=2)).cuda()
         r = quantize_layer(synthetic_chunks(args.tokens, d_in, args.chunk, seed=3), Wt, args.bits, d_in, T=d_in // args.t_div,
                            init=args.init, lambda_rel=args.lambda_rel, bcd_parts=parts)

@@ -90,7 +90,7 @@ def test_argument_checks_of_the_wider_entry_points(L):
     assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 3, p, 8, n, n, n, 0, 0, p, 1 << 30, n) == EUNSUP     # only pairs are built
     assert L.cdq_bcd(p, p, p, p, p, 4, 255, 3, 255, 2, p, 8, n, n, n, 0, 0, p, 1 << 30, n) == EINVAL     # odd d_in
     assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 2, n, 8, n, n, n, 0, 0, p, 1 << 30, n) == EINVAL     # no partitions
-    assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 2, p, 8, n, n, n, 0, 4, p, 1 << 30, n) == EINVAL     # unknown flag bit
+    assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 2, p, 8, n, n, n, 0, 8, p, 1 << 30, n) == EINVAL     # unknown flag bit
     assert L.cdq_bcd(p, p, p, p, p, 4, 256, 3, 256, 2, p, 8, n, n, n, 0, 0, n, 0, n) == EWS
     assert L.cdq_bcd(p, p, p, p, p, 4, 65536, 3, 65536, 2, p, 8, n, n, n, 0, 0, p, 1 << 40, n) == EUNSUP # wider than the wide-layer kernel holds
     assert cdq.workspace_bytes(cdq.OP_BCD, 8, 4, 256) >= 4 * 256 * 4 + 8 * 128 * 12

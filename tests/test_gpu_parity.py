@@ -227,6 +227,9 @@ def test_init_owc_cd_rejects_oversized_state(cdq):
 
 # ----------------------------------------------------------------------------- BCD (Algorithm 2 / 5), k = 2
 
+BCD_KERNELS = {"auto": {}, "single": {"single_column": True}, "wide": {"wide": True}}   # flags of cdq_bcd: the same results
+
+
 def bcd_moves_from_gpu(trace_j):
     return [(int(t), int(b), int(r), np.int32(s).view(np.float32)) for t, b, r, s in trace_j if t >= 0]
 
@@ -235,13 +238,14 @@ def bcd_moves_from_gpu(trace_j):
     (24, 128, 400, 2, 128, 160, "random"), (16, 256, 700, 3, 64, 200, "random"), (10, 64, 300, 4, 16, 100, "random"),
     (12, 512, 1200, 3, 512, 300, "cd"), (9, 136, 400, 2, 8, 80, "random"), (6, 2048, 4096, 2, 128, 64, "rtn"),
     (5, 4096, 6000, 3, 4096, 24, "rtn"), (6, 3072, 4000, 3, 128, 16, "rtn"),
-    # d_in not a multiple of 4: the wide-layer kernel (2g only in LDS, table entries with the diagonal)
+    # d_in not a multiple of 4: the wide-layer kernel whatever the flags
     (7, 130, 400, 3, 26, 60, "random"), (5, 1002, 1500, 4, 1002, 40, "rtn"), (3, 6, 40, 2, 6, 10, "random"), (4, 2050, 2600, 2, 410, 30, "cd")])
-@pytest.mark.parametrize("score_all,single_column", [(False, False), (True, False), (False, True), (True, True)])
-def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start, score_all, single_column):
+@pytest.mark.parametrize("score_all,kernel", [(False, "auto"), (True, "auto"), (False, "single"), (True, "single"), (False, "wide"),
+                                              (True, "wide")])
+def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start, score_all, kernel):
     """Same partitions on both sides: the trajectories (iteration, block, levels, score bits), the final codes, the
     move counts and the maintained gradient are equal bit for bit, for the kernel that gives a workgroup several
-    columns and the one-column kernel, with and without the test that skips pairs."""
+    columns, the one-column kernel and the wide-layer kernel, with and without the test that skips pairs."""
     X, Wt = rand_layer(31 + d_in + bits, d_in, d_out, n, corr=0.7)
     H32 = oracle.hessian(X).astype(np.float32)
     a, b, q_rtn = oracle.init_grid(Wt, bits, group)
@@ -255,7 +259,7 @@ def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start, score
     ref = oracle.bcd(H32, Wt, a, b, q0, parts, bits, group, k=2, trace_cap=T)
     Q = dev(q0)
     out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, bits, group, dev(parts), trace_cap=T, want_G=True, score_all=score_all,
-                  single_column=single_column)
+                  **BCD_KERNELS[kernel])
     moves = out["moves"].cpu().numpy()
     trace = out["trace"].cpu().numpy()
     assert ref["moves"].sum() > 0
@@ -279,11 +283,11 @@ def test_bcd_few_iterations(cdq, oracle, T):
     q0 = inputs.make_random_codes(11, 256, 3, seed=T)
     parts = inputs.make_partitions(T, 256, seed=T)
     ref = oracle.bcd(H32, Wt, a, b, q0, parts, 3, 256, k=2)
-    for single in (False, True):
+    for kernel, kw in BCD_KERNELS.items():
         Q = dev(q0)
-        out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, 256, dev(parts), single_column=single)
-        assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), single
-        assert np.array_equal(Q.cpu().numpy(), ref["Q"]), single
+        out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, 256, dev(parts), **kw)
+        assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), kernel
+        assert np.array_equal(Q.cpu().numpy(), ref["Q"]), kernel
 
 
 @pytest.mark.parametrize("d_out,d_in,n,bits,T", [(4, 1360, 2313, 4, 45), (9, 336, 700, 4, 60), (5, 512, 900, 3, 50)])
@@ -299,12 +303,12 @@ def test_bcd_strongly_correlated_pairs(cdq, oracle, d_out, d_in, n, bits, T):
     a, b, q0 = oracle.init_grid(Wt, bits, d_in)
     parts = inputs.make_partitions(T, d_in, seed=d_in)
     ref = oracle.bcd(H32, Wt, a, b, q0, parts, bits, d_in, k=2)
-    for single in (False, True):
+    for kernel, kw in BCD_KERNELS.items():
         Q = dev(q0.copy())
-        out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, bits, d_in, dev(parts), single_column=single, want_G=True)
-        assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), single
-        assert np.array_equal(Q.cpu().numpy(), ref["Q"]), single
-        assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), single
+        out = cdq.bcd(dev(H32), dev(Wt), dev(a), dev(b), Q, bits, d_in, dev(parts), want_G=True, **kw)
+        assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), kernel
+        assert np.array_equal(Q.cpu().numpy(), ref["Q"]), kernel
+        assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), kernel
 
 
 @pytest.mark.parametrize("d_out,d_in,n,bits,T", [(24, 512, 900, 3, 160), (10, 2048, 2600, 3, 48), (6, 1002, 1500, 3, 90), (7, 640, 900, 4, 60)])
@@ -324,12 +328,12 @@ def test_bcd_on_a_clipping_grid(cdq, oracle, d_out, d_in, n, bits, T):
     parts = inputs.make_partitions(T, d_in, seed=d_in + 5)
     ref = oracle.bcd(H32, Wt, a2, b2, q_cd, parts, bits, d_in, k=2)
     assert ref["moves"].sum() > 0
-    for single in (False, True):
+    for kernel, kw in BCD_KERNELS.items():
         Q = dev(q_cd.copy())
-        out = cdq.bcd(dev(H32), dev(Wt), dev(a2), dev(b2), Q, bits, d_in, dev(parts), single_column=single, want_G=True)
-        assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), single
-        assert np.array_equal(Q.cpu().numpy(), ref["Q"]), single
-        assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), single
+        out = cdq.bcd(dev(H32), dev(Wt), dev(a2), dev(b2), Q, bits, d_in, dev(parts), want_G=True, **kw)
+        assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), kernel
+        assert np.array_equal(Q.cpu().numpy(), ref["Q"]), kernel
+        assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), kernel
 
 
 def test_bcd_rejects_bad_partitions_and_block_sizes(cdq, oracle):
@@ -739,13 +743,13 @@ def test_random_shapes_against_the_oracle(cdq, oracle, seed, big):
             T = int(rng.integers(1, 60))
             parts = inputs.make_partitions(T, d_in, seed=case)
             ref = oracle.bcd(H32, Wt, a, b, q0, parts, bits, group, k=2)
-            for single in (False, True):
+            for kernel, kw in BCD_KERNELS.items():
                 for score_all in (False, True):
                     Q = dev(q0.copy())
-                    out = cdq.bcd(Hd, Wd, ad, bd, Q, bits, group, dev(parts), single_column=single, score_all=score_all, want_G=True)
-                    assert np.array_equal(Q.cpu().numpy(), ref["Q"]), (tag, single, score_all)
-                    assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), (tag, single, score_all)
-                    assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), (tag, single, score_all)
+                    out = cdq.bcd(Hd, Wd, ad, bd, Q, bits, group, dev(parts), score_all=score_all, want_G=True, **kw)
+                    assert np.array_equal(Q.cpu().numpy(), ref["Q"]), (tag, kernel, score_all)
+                    assert np.array_equal(out["moves"].cpu().numpy(), ref["moves"]), (tag, kernel, score_all)
+                    assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), (tag, kernel, score_all)
         elif kind == "cyclic":
             T = int(rng.integers(1, 3 * d_in))
             ref = oracle.cyclic_cd(H32, Wt, a, b, q0, bits, group, T)
