@@ -168,11 +168,14 @@ int cdq_init_owc_cd(const float *H, const float *Wt, int64_t d_out, int64_t d_in
  *   Q [d_out][d_in] in/out; moves NULL or [d_out] int32 out; G_out NULL or [d_out][d_in] fp32:
  *   g = He of the final codes as maintained by the updates;
  *   trace NULL or [d_out][trace_cap][4] int32: iteration, block, r_i | r_k<<4, score bits.
- *   flags bit 0 clear: pairs that provably hold no improving move (both coordinates' |2 g| below
- *   (1 - |H_ik|/sqrt(H_ii H_kk) - 2^-10) H a) are not scored; set: every pair is scored.
+ *   flags bit 0 clear: pairs that provably hold no improving move are not scored (with
+ *   u = |2 g| / (H_ii a), or 0 for a code at the end of its grid that g points past, and
+ *   rho = |H_ik| / sqrt(H_ii H_kk): (1 - u_i - 2^-14)(1 - u_k - 2^-14) >= rho^2, both factors >= 0);
+ *   set: every pair is scored.
  *   flags bit 1 set: one column per workgroup also where the kernel that gives a workgroup
  *   several columns applies (d_in % 8 == 0 and the columns' state fits LDS).
- *   flags bit 2 set: the wide-layer kernel whatever d_in.  Same results for every value of flags;
+ *   flags bit 2 set: the wide-layer kernel with 8 columns per workgroup whatever the shape.  Same
+ *   results for every value of flags;
  *   the bits exist for tests and timing.
  * d_in even, at most 65534.  Three kernels give the same results: several columns per workgroup
  * with their state in LDS (d_in % 16 == 0, d_in up to about 4700), one column per workgroup with

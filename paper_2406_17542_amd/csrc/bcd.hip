@@ -305,7 +305,7 @@ __global__ __launch_bounds__(1024) void bcd2_kernel(const float* __restrict__ H,
 // ------------------------------------------------------------------------------------------------
 // Several columns per workgroup.  Near a coordinate-wise optimum almost every iteration is idle for a
 // column; what it costs is reading the iteration's row of the pair table, the test of every pair and a
-// barrier.  Here a workgroup of 512 threads owns CW columns and pays that once for all of them.
+// barrier.  Here a workgroup of 1024 threads owns CW columns and pays that once for all of them.
 //   The pair test.  With u = |2 g| / (H_ii a) per coordinate and rho = |H_ik| / sqrt(H_ii H_kk), a move
 //   (di, dk) of the pair changes the loss by at least x^2 (1 - u_i) + y^2 (1 - u_k) - 2 rho x y with
 //   x = |di| sqrt(H_ii), y = |dk| sqrt(H_kk), which is >= tau (x^2 + y^2) for all x, y when
@@ -1016,7 +1016,7 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
     const bool single_ok = nt <= 1024 && lds <= 160 * 1024 && d_in % 4 == 0 && ((uintptr_t)H & 15) == 0;
     int wcw = 0;                                                  // columns per workgroup of the wide-layer kernel
     if (d_in < 65536 && bcdw_lds_bytes(d_in) + 4096 <= 160 * 1024) wcw = 8;
-    while (wcw > 1 && (d_out + wcw - 1) / wcw < 256) wcw /= 2;   // rather more workgroups than CUs
+    while (!wide && wcw > 1 && (d_out + wcw - 1) / wcw < 256) wcw /= 2;   // rather more workgroups than CUs (the flag keeps 8)
     const bool wide_ok = wcw != 0;
     if ((!single_ok && !wide_ok) || T > 0x7fffffffLL || d_out > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
     if (ws == nullptr || ((uintptr_t)ws & 255) || ws_bytes < bcd_workspace_bytes(d_out, d_in, T)) return CDQ_EWORKSPACE;

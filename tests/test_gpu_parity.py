@@ -239,7 +239,9 @@ def bcd_moves_from_gpu(trace_j):
     (12, 512, 1200, 3, 512, 300, "cd"), (9, 136, 400, 2, 8, 80, "random"), (6, 2048, 4096, 2, 128, 64, "rtn"),
     (5, 4096, 6000, 3, 4096, 24, "rtn"), (6, 3072, 4000, 3, 128, 16, "rtn"),
     # d_in not a multiple of 4: the wide-layer kernel whatever the flags
-    (7, 130, 400, 3, 26, 60, "random"), (5, 1002, 1500, 4, 1002, 40, "rtn"), (3, 6, 40, 2, 6, 10, "random"), (4, 2050, 2600, 2, 410, 30, "cd")])
+    (7, 130, 400, 3, 26, 60, "random"), (5, 1002, 1500, 4, 1002, 40, "rtn"), (3, 6, 40, 2, 6, 10, "random"), (4, 2050, 2600, 2, 410, 30, "cd"),
+    # ... with 4 and with 2 columns per workgroup (what it picks for this many columns), last workgroup not full
+    (1501, 130, 400, 3, 130, 24, "rtn"), (701, 66, 300, 2, 22, 20, "random")])
 @pytest.mark.parametrize("score_all,kernel", [(False, "auto"), (True, "auto"), (False, "single"), (True, "single"), (False, "wide"),
                                               (True, "wide")])
 def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start, score_all, kernel):
