@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libcdq.so")
 
-SOURCES = ["cdq_api.hip", "rtn.hip", "eh_gemm.hip", "cd_fused.hip", "hessian.hip", "probes.hip", "owc.hip", "stepwise.hip", "owc_cd.hip", "bcd.hip", "cyclic.hip"]
+SOURCES = ["cdq_api.hip", "rtn.hip", "eh_gemm.hip", "cd_fused.hip", "hessian.hip", "probes.hip", "owc.hip", "owc_screen.hip", "stepwise.hip", "owc_cd.hip", "bcd.hip", "cyclic.hip"]
 
 # -ffp-contract=off: every fused multiply-add in the kernels is an explicit fmaf(), which is what
 # makes the fp32 coordinate-descent arithmetic reproducible against an independent implementation.

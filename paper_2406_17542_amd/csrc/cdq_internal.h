@@ -34,7 +34,17 @@ int gradient_launch(const float* H, const float* Wt, const float* scale, const f
                     double* G64 = nullptr);   // G64 non-null: store the fp64 sums there instead of G
 int loss_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
                 int64_t d_out, int64_t d_in, int64_t group, double* loss_per_col, double* loss_total,
-                void* ws, size_t ws_bytes, hipStream_t st);
+                void* ws, size_t ws_bytes, hipStream_t st, const uint8_t* row_block_active = nullptr);
+// row_block_active non-null: one byte per block of loss_block_rows() columns of W; blocks with a zero are skipped and
+// their entries of loss_per_col are unspecified
+int loss_block_rows();
+
+// ---- owc_screen.hip : every clipping strength evaluated in bf16 first, candidates ranked per column
+bool owc_screen_applies(int64_t d_out, int64_t d_in, int n_gamma);
+size_t owc_screen_workspace_bytes(int64_t d_out, int64_t d_in, int n_gamma, int64_t n_blocks);
+int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, const float* lo, const float* hi,
+                      float margin, int block_rows, int64_t n_blocks, void* ws, const uint8_t** cand_out, const uint8_t** active_out,
+                      hipStream_t st);
 
 // ---- owc.hip
 size_t owc_workspace_bytes(int64_t d_out, int64_t d_in);

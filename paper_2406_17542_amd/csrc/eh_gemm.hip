@@ -64,7 +64,7 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
                                                      const uint8_t* __restrict__ Q, int64_t d_out, int64_t d_in,
                                                      int64_t group, float* __restrict__ G,
                                                      double* __restrict__ partial, int chunk_blocks,
-                                                     double* __restrict__ G64) {
+                                                     double* __restrict__ G64, const uint8_t* __restrict__ row_block_active) {
     // two stages of As[k][m] = E[m0+m][k0+k] and Bs[k][n] = H[k0+k][n0+n]: the next step's tiles are written
     // while the current ones are multiplied, one barrier per step
     extern __shared__ __attribute__((aligned(16))) char eh_smem[];
@@ -72,6 +72,8 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
     float (*Bs)[BK][LDP] = reinterpret_cast<float (*)[BK][LDP]>(eh_smem + 2 * sizeof(float) * BK * LDP);
     double (*red)[BM] = reinterpret_cast<double (*)[BM]>(eh_smem + 4 * sizeof(float) * BK * LDP);
 
+    // loss: the caller may only want some blocks of BM rows (the partial sums of the others are left as they are)
+    if (LOSS && row_block_active != nullptr && row_block_active[blockIdx.x] == 0) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
     // loss: consecutive workgroups take the same item for consecutive column tiles (they share the H blocks, and the
@@ -318,6 +320,8 @@ bool vec4_ok(const float* H, const float* Wt, const uint8_t* Q, int64_t d_in, in
 
 }  // namespace
 
+int loss_block_rows() { return BM; }
+
 size_t loss_workspace_bytes(int64_t d_out, int64_t d_in) {
     int chunk;
     int64_t n_items;
@@ -333,17 +337,17 @@ int gradient_launch(const float* H, const float* Wt, const float* scale, const f
     if (!eh_allow_lds<false, true>() || !eh_allow_lds<false, false>()) return CDQ_EHIP;
     if (vec4_ok(H, Wt, Q, d_in, group))
         hipLaunchKernelGGL((eh_gemm_kernel<false, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, G, (double*)nullptr, 0, G64);
+                           d_out, d_in, group, G, (double*)nullptr, 0, G64, (const uint8_t*)nullptr);
     else
         hipLaunchKernelGGL((eh_gemm_kernel<false, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, G, (double*)nullptr, 0, G64);
+                           d_out, d_in, group, G, (double*)nullptr, 0, G64, (const uint8_t*)nullptr);
     CDQ_LAUNCH_CHECK();
     return CDQ_OK;
 }
 
 int loss_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
                 int64_t d_out, int64_t d_in, int64_t group, double* loss_per_col, double* loss_total,
-                void* ws, size_t ws_bytes, hipStream_t st) {
+                void* ws, size_t ws_bytes, hipStream_t st, const uint8_t* row_block_active) {
     if (d_out == 0) {                 // empty layer: the total is an empty sum
         if (loss_total) {
             hipLaunchKernelGGL(loss_total_kernel, dim3(1), dim3(1024), 0, st, (const double*)nullptr, (int64_t)0, loss_total);
@@ -363,10 +367,10 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
     if (!eh_allow_lds<true, true>() || !eh_allow_lds<true, false>()) return CDQ_EHIP;
     if (vec4_ok(H, Wt, Q, d_in, group))
         hipLaunchKernelGGL((eh_gemm_kernel<true, true>), dim3((unsigned)gy, (unsigned)gx), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, (float*)nullptr, partial, chunk, (double*)nullptr);
+                           d_out, d_in, group, (float*)nullptr, partial, chunk, (double*)nullptr, row_block_active);
     else
         hipLaunchKernelGGL((eh_gemm_kernel<true, false>), dim3((unsigned)gy, (unsigned)gx), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, (float*)nullptr, partial, chunk, (double*)nullptr);
+                           d_out, d_in, group, (float*)nullptr, partial, chunk, (double*)nullptr, row_block_active);
     CDQ_LAUNCH_CHECK();
     hipLaunchKernelGGL(loss_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, partial, d_out, (int)gx, rows);
     CDQ_LAUNCH_CHECK();

@@ -2,7 +2,9 @@
 // grid search over the clipping strength gamma for the smallest layer loss of Eq. (1).
 //   b = min w,  a(gamma) = gamma (max w - min w)/(2^c - 1),  q = clamp(round((w - b)/a), 0, 2^c - 1)
 // The grid is gamma_k = k/n_gamma, k = 1..n_gamma (gamma = 1 is MinMax; equal losses keep the
-// larger gamma).  Each gamma costs one pass of the fp64 loss kernel over all columns.
+// larger gamma).  A grid point costs one pass of the fp64 loss kernel over all columns; where the fp16 look at all grid
+// points applies (owc_screen.hip) only the few that can win are evaluated that way, a column's candidates one rank at a
+// time, and blocks of columns without a candidate of that rank are skipped.
 #include "cdq_internal.h"
 
 namespace cdq {
@@ -42,6 +44,7 @@ __global__ __launch_bounds__(256) void owc_quantize_kernel(const float* __restri
     const int64_t j = blockIdx.x;
     const float lo = lo_in[j], hi = hi_in[j];
     const float g = gamma_col ? gamma_col[j] : gamma;
+    if (!(g > 0.0f)) return;                                              // no grid point for this column in this pass
     const float top = (float)((1 << bits) - 1);
     float a = __fdiv_rn(g * (hi - lo), top);
     if (!(a > 0.0f) || isinf(a)) a = 1.0f;
@@ -68,14 +71,49 @@ __global__ __launch_bounds__(256) void owc_update_best_kernel(const double* __re
     }
 }
 
+// rank r of the candidates: the column's gamma (0: none) for the quantize pass
+__global__ __launch_bounds__(256) void owc_rank_gamma_kernel(const uint8_t* __restrict__ cand_r, int64_t d_out, int n_gamma,
+                                                             float* __restrict__ gamma_col) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_out) return;
+    const int k = cand_r[j];
+    gamma_col[j] = k ? (float)k / (float)n_gamma : 0.0f;
+}
+
+// exact losses of one rank folded into the best: smaller wins, equal losses keep the larger gamma -- the result of going
+// through the grid in ascending order with "<=", whatever the order of the ranks
+__global__ __launch_bounds__(256) void owc_update_best_ranked_kernel(const double* __restrict__ cur, const float* __restrict__ gamma_col,
+                                                                     int64_t d_out, double* __restrict__ best,
+                                                                     float* __restrict__ best_gamma) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_out) return;
+    const float g = gamma_col[j];
+    if (!(g > 0.0f)) return;
+    const double c = cur[j];
+    const float bg = best_gamma[j];
+    if (bg == 0.0f || c < best[j] || (c == best[j] && g > bg)) {
+        best[j] = c;
+        best_gamma[j] = g;
+    }
+}
+
+__global__ __launch_bounds__(256) void owc_fill_f32_kernel(float* __restrict__ p, int64_t n, float v) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+constexpr float kScreenMargin = 3e-3f;      // relative; the fp16 evaluation was off by 3e-4 at most on heavy-tailed test layers
+
 }  // namespace
 
 size_t owc_workspace_bytes(int64_t d_out, int64_t d_in) {
     size_t b = 0;
-    b += cdq_align_up((size_t)d_out * sizeof(float), 256) * 4;       // lo, hi, trial scale, best gamma
+    b += cdq_align_up((size_t)d_out * sizeof(float), 256) * 5;       // lo, hi, trial scale, best gamma, a rank's gammas
     b += cdq_align_up((size_t)d_out * sizeof(double), 256) * 2;      // trial loss, best loss
     b += cdq_align_up((size_t)d_out * d_in, 256);                    // trial codes
     b += loss_workspace_bytes(d_out, d_in);
+    const int64_t n_blocks = (d_out + loss_block_rows() - 1) / loss_block_rows();
+    b += owc_screen_workspace_bytes(d_out, d_in, 255, n_blocks);     // sized for the largest grid the screen takes
     return b;
 }
 
@@ -90,6 +128,7 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
     float* hi = (float*)p; p += fsz;
     float* trial_scale = (float*)p; p += fsz;
     float* best_gamma = (float*)p; p += fsz;
+    float* rank_gamma = (float*)p; p += fsz;
     double* trial_loss = (double*)p; p += dsz;
     double* best_loss = (double*)p; p += dsz;
     uint8_t* trial_q = (uint8_t*)p; p += cdq_align_up((size_t)d_out * d_in, 256);
@@ -97,8 +136,33 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
     const size_t loss_ws_bytes = loss_workspace_bytes(d_out, d_in);
     const dim3 cols((unsigned)d_out), t256(256);
 
+    void* screen_ws = (char*)loss_ws + loss_ws_bytes;
+    const dim3 col_blocks((unsigned)((d_out + 255) / 256));
+
     hipLaunchKernelGGL(owc_minmax_kernel, cols, t256, 0, st, Wt, d_in, lo, hi);
     CDQ_LAUNCH_CHECK();
+    if (owc_screen_applies(d_out, d_in, n_gamma)) {
+        const int block_rows = loss_block_rows();
+        const int64_t n_blocks = (d_out + block_rows - 1) / block_rows;
+        const uint8_t *cand, *active;
+        int rc = owc_screen_launch(H, Wt, d_out, d_in, bits, n_gamma, lo, hi, kScreenMargin, block_rows, n_blocks, screen_ws, &cand, &active, st);
+        if (rc != CDQ_OK) return rc;
+        hipLaunchKernelGGL(owc_fill_f32_kernel, col_blocks, t256, 0, st, best_gamma, d_out, 0.0f);      // 0: nothing evaluated yet
+        CDQ_LAUNCH_CHECK();
+        for (int r = 0; r < n_gamma; ++r) {
+            hipLaunchKernelGGL(owc_rank_gamma_kernel, col_blocks, t256, 0, st, cand + (int64_t)r * d_out, d_out, n_gamma, rank_gamma);
+            CDQ_LAUNCH_CHECK();
+            hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, 1.0f, (const float*)rank_gamma, trial_scale,
+                               (float*)nullptr, trial_q);
+            CDQ_LAUNCH_CHECK();
+            rc = loss_launch(H, Wt, trial_scale, lo, trial_q, d_out, d_in, d_in, trial_loss, nullptr, loss_ws, loss_ws_bytes, st,
+                             active + (int64_t)r * n_blocks);
+            if (rc != CDQ_OK) return rc;
+            hipLaunchKernelGGL(owc_update_best_ranked_kernel, col_blocks, t256, 0, st, (const double*)trial_loss, (const float*)rank_gamma,
+                               d_out, best_loss, best_gamma);
+            CDQ_LAUNCH_CHECK();
+        }
+    } else
     for (int k = 1; k <= n_gamma; ++k) {
         const float gamma = (float)k / (float)n_gamma;
         hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, gamma, (const float*)nullptr, trial_scale,

@@ -1,0 +1,301 @@
+// A cheap look at every clipping strength of the OWC grid search (paper Section 3.1, "Initializing a, b, q"; Eq. (2)
+// searched for the smallest loss of Eq. (1)) before the exact evaluation.
+//
+// The search itself stays what it is: per column the grid point with the smallest fp64 loss e^T H e, equal losses
+// keeping the larger gamma.  But the fp64 evaluation of one grid point costs a d_out x d_in x d_in matrix product, and on
+// real layers the best grid point beats the runner-up by half a percent at the median.  So every grid point is first
+// evaluated in fp16 on the matrix cores (fp32 accumulation, ~10 times the fp64 kernel's rate).  To fit fp16's range the
+// product is taken in normalised form: with d = sqrt(diag H), R = H / (d d^T) (entries in [-1, 1]) and f = e * d divided by
+// its largest magnitude s, e^T H e = s^2 f^T R f.  Rounding f and R to 11 bits moves a column's loss by a few 1e-4
+// relative at most (less when many coordinates carry it).  Only grid points whose screened loss is within the margin of
+// the column's smallest screened loss -- between one and two per column on average -- can be the fp64 winner; those are
+// evaluated exactly by the caller, rank by rank.
+//
+// Kernels here: R and f in fp16; C = F R on v_mfma_f32_32x32x16_f16 with the epilogue sum_c C[j][c] F[j][c] per row and
+// column block; the sum over the column blocks; and the ranking of a column's grid points.
+#include "cdq_internal.h"
+
+namespace cdq {
+namespace {
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+constexpr int SB = 128;                 // tile of C: SB rows of E by SB columns of H
+constexpr int SK = 64;                  // contraction step
+constexpr int SROW = SK * 2 + 16;       // LDS bytes per tile row (144: 16-byte aligned, rows 8 apart share banks)
+constexpr int STILE = SB * SROW;        // one operand tile
+constexpr int SNT = 256;                // four wavefronts, 64 x 64 of C each
+
+__global__ __launch_bounds__(256) void fill_words_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t v) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// d[k] = sqrt(H_kk), rd[k] = 1 / d[k]
+__global__ __launch_bounds__(256) void owc_diag_kernel(const float* __restrict__ H, int64_t d_in, float* __restrict__ d, float* __restrict__ rd) {
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k >= d_in) return;
+    const float v = sqrtf(H[k * d_in + k]);
+    d[k] = v;
+    rd[k] = __fdiv_rn(1.0f, v);
+}
+
+// R[c][k] = H[c][k] / (d[c] d[k]) in fp16; one workgroup per row
+__global__ __launch_bounds__(256) void owc_corr_f16_kernel(const float* __restrict__ H, int64_t d_in, const float* __restrict__ rd,
+                                                           _Float16* __restrict__ R) {
+    const int64_t c = blockIdx.x;
+    const float rc = rd[c];
+    for (int64_t k = threadIdx.x; k < d_in; k += 256) R[c * d_in + k] = (_Float16)((H[c * d_in + k] * rc) * rd[k]);
+}
+
+// Eq. (2) at one clipping strength for a column, e = fma(a, q, lo) - w as the loss kernel forms it; f = e * d; the row is
+// stored as f / s in fp16 with s = max |f| (1 when the residual is zero) and s^2 goes to row_scale2.  One workgroup per
+// column; rows past d_out of the padded buffer stay zero.
+__global__ __launch_bounds__(256) void owc_residual_f16_kernel(const float* __restrict__ Wt, int64_t d_in, int bits,
+                                                               const float* __restrict__ lo_in, const float* __restrict__ hi_in,
+                                                               float gamma, const float* __restrict__ d, _Float16* __restrict__ F,
+                                                               float* __restrict__ row_scale2) {
+    __shared__ float smax[4];
+    const int64_t j = blockIdx.x;
+    const float lo = lo_in[j], hi = hi_in[j];
+    const float top = (float)((1 << bits) - 1);
+    float a = __fdiv_rn(gamma * (hi - lo), top);
+    if (!(a > 0.0f) || isinf(a)) a = 1.0f;
+    const float* w = Wt + j * d_in;
+    auto f_of = [&](int64_t k) {
+        const float wk = w[k];
+        const float q = fminf(fmaxf(rintf(__fdiv_rn(wk - lo, a)), 0.0f), top);
+        return (fmaf(a, q, lo) - wk) * d[k];
+    };
+    float m = 0.0f;
+    for (int64_t k = threadIdx.x; k < d_in; k += 256) m = fmaxf(m, fabsf(f_of(k)));
+    for (int o = 32; o; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if ((threadIdx.x & 63) == 0) smax[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(smax[0], smax[1]), fmaxf(smax[2], smax[3]));
+    const float s = (m > 0.0f && m < INFINITY) ? m : 1.0f;
+    const float rs = __fdiv_rn(1.0f, s);
+    if (threadIdx.x == 0) row_scale2[j] = s * s;
+    _Float16* f = F + j * d_in;
+    for (int64_t k = threadIdx.x; k < d_in; k += 256) f[k] = (_Float16)(f_of(k) * rs);
+}
+
+// f^T R f over the blocks of R on and above the diagonal (R is symmetric: its row c is its column c, and the blocks below
+// the diagonal repeat the ones above): for column block cb the contraction runs over k < 128 (cb + 1), and what was
+// accumulated before the diagonal block is doubled -- exactly -- when it is reached.
+// partial[cb * 2 + h][j] = sum over the 64 columns c of half h of column block cb of C[j][c] F[j][c].
+// F [rows][d_in], rows a multiple of SB, d_in a multiple of SB.  grid (d_in / SB, rows / SB), longest column blocks first.
+__global__ __launch_bounds__(SNT) void owc_screen_kernel(const _Float16* __restrict__ E, const _Float16* __restrict__ R, int64_t rows,
+                                                         int64_t d_in, float* __restrict__ partial) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];             // [2 stages][E tile | H tile]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int cb = (int)(gridDim.x - 1 - blockIdx.x);
+    const int64_t c0 = (int64_t)cb * SB, j0 = (int64_t)blockIdx.y * SB;
+    const int wr = (wave >> 1) * 64, wc = (wave & 1) * 64;                   // this wavefront's 64 x 64 of the tile
+    const int n_steps = (cb + 1) * (SB / SK), diag_step = cb * (SB / SK);     // steps before diag_step lie above the diagonal block
+
+    // a thread moves four 16-byte chunks of each operand tile per step: chunk id = tid + 256 i -> row id / 8, chunk id % 8
+    u4 ra[4], rb[4];
+    auto load = [&](int step) {
+        const int64_t k0 = (int64_t)step * SK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int id = tid + SNT * i, row = id >> 3, kc = id & 7;
+            ra[i] = *reinterpret_cast<const u4*>(E + (j0 + row) * d_in + k0 + kc * 8);
+            rb[i] = *reinterpret_cast<const u4*>(R + (c0 + row) * d_in + k0 + kc * 8);
+        }
+    };
+    auto store = [&](int stage) {
+        char* base = lds + stage * 2 * STILE;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int id = tid + SNT * i, row = id >> 3, kc = id & 7;
+            *reinterpret_cast<u4*>(base + row * SROW + kc * 16) = ra[i];
+            *reinterpret_cast<u4*>(base + STILE + row * SROW + kc * 16) = rb[i];
+        }
+    };
+
+    f16v acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    load(0);
+    store(0);
+    __syncthreads();
+    for (int step = 0; step < n_steps; ++step) {
+        if (step + 1 < n_steps) load(step + 1);                    // in flight behind this step's matrix work
+        if (step == diag_step) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[a][b][v] *= 2.0f;
+        }
+        const char* At = lds + (step & 1) * 2 * STILE;
+        const char* Bt = At + STILE;
+        // v_mfma_f32_32x32x16_f16: lane l feeds row (column) l % 32 with the 8 contraction indices 8 (l / 32) .. + 8
+        const int frow = lane & 31, fk = (lane >> 5) * 16;         // byte offset of the lane's 8 values inside a 16-wide group
+#pragma unroll
+        for (int kg = 0; kg < SK / 16; ++kg) {
+            h8 af[2], bf[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) af[a] = *reinterpret_cast<const h8*>(At + (wr + 32 * a + frow) * SROW + kg * 32 + fk);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) bf[b] = *reinterpret_cast<const h8*>(Bt + (wc + 32 * b + frow) * SROW + kg * 32 + fk);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
+        if (step + 1 < n_steps) store((step + 1) & 1);             // the other stage: everybody left it before the last barrier
+        __syncthreads();
+    }
+
+    // 32 x 32 result block: lane l, element v -> row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        float s[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t j = j0 + wr + 32 * a + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            float t = 0.0f;
+#pragma unroll
+            for (int b = 0; b < 2; ++b) t = fmaf(acc[a][b][v], (float)E[j * d_in + c0 + wc + 32 * b + (lane & 31)], t);
+            s[v] = t;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {                             // over the 32 lanes that hold the row's columns, fixed order
+            float t = s[v];
+#pragma unroll
+            for (int o = 16; o; o >>= 1) t += __shfl_xor(t, o);
+            if ((lane & 31) == 0) {
+                const int64_t j = j0 + wr + 32 * a + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                partial[((int64_t)cb * 2 + (wave & 1)) * rows + j] = t;
+            }
+        }
+    }
+}
+
+// screened loss of a column at this grid point: the partial sums in a fixed order
+__global__ __launch_bounds__(256) void owc_screen_rows_kernel(const float* __restrict__ partial, int64_t rows, int64_t d_out, int n_part,
+                                                              const float* __restrict__ row_scale2, float* __restrict__ out) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_out) return;
+    float s = 0.0f;
+    for (int p = 0; p < n_part; ++p) s += partial[(int64_t)p * rows + j];
+    out[j] = s * row_scale2[j];
+}
+
+// Per column: the grid points whose screened loss is within the margin of the smallest, best first.  cand [n_gamma][d_out]:
+// grid index k (1-based) of the column's r-th candidate, 0 when it has fewer; active [n_gamma][row blocks of the loss kernel]:
+// set when some column of the block has an r-th candidate (zeroed by the caller).  A NaN counts as a candidate.
+__global__ __launch_bounds__(256) void owc_rank_kernel(const float* __restrict__ screened, int64_t d_out, int n_gamma, float margin,
+                                                       int block_rows, int64_t n_blocks, uint8_t* __restrict__ cand,
+                                                       uint8_t* __restrict__ active) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_out) return;
+    float best = INFINITY;
+    for (int k = 0; k < n_gamma; ++k) {
+        const float v = screened[(int64_t)k * d_out + j];
+        if (v < best) best = v;
+    }
+    const float limit = best + margin * fabsf(best) + 1e-30f;
+    // selection by repeated minimum over what is left: n_gamma is small
+    float prev = -INFINITY;
+    int prev_k = -1, r = 0;
+    for (;; ++r) {
+        float cur = INFINITY;
+        int cur_k = -1;
+        for (int k = 0; k < n_gamma; ++k) {
+            float v = screened[(int64_t)k * d_out + j];
+            if (!(v == v)) v = -INFINITY;                          // a NaN sorts first: it is evaluated exactly
+            if (!(v <= limit)) continue;
+            if ((v > prev || (v == prev && k > prev_k)) && (cur_k < 0 || v < cur)) { cur = v; cur_k = k; }
+        }
+        if (cur_k < 0) break;
+        cand[(int64_t)r * d_out + j] = (uint8_t)(cur_k + 1);
+        active[(int64_t)r * n_blocks + j / block_rows] = 1;
+        prev = cur;
+        prev_k = cur_k;
+    }
+    for (; r < n_gamma; ++r) cand[(int64_t)r * d_out + j] = 0;
+}
+
+}  // namespace
+
+bool owc_screen_applies(int64_t d_out, int64_t d_in, int n_gamma) {
+    return d_in % SB == 0 && d_in >= 2 * SB && n_gamma >= 4 && n_gamma <= 255 && d_out >= 1 && d_in / SB * 2 <= 0x7fffffffLL;
+}
+
+// R [d_in][d_in] fp16 | F [rows][d_in] fp16 | partial [2 d_in / SB][rows] fp32 | screened [n_gamma][d_out] fp32 |
+// cand [n_gamma][d_out] u8 | active [n_gamma][n_blocks] u8 | d, 1/d [d_in] fp32 each | row scales [d_out] fp32
+size_t owc_screen_workspace_bytes(int64_t d_out, int64_t d_in, int n_gamma, int64_t n_blocks) {
+    const int64_t rows = (d_out + SB - 1) / SB * SB;
+    return cdq_align_up((size_t)d_in * d_in * 2, 256) + cdq_align_up((size_t)rows * d_in * 2, 256) +
+           cdq_align_up((size_t)(2 * d_in / SB) * rows * sizeof(float), 256) + cdq_align_up((size_t)n_gamma * d_out * sizeof(float), 256) +
+           cdq_align_up((size_t)n_gamma * d_out, 256) + cdq_align_up((size_t)n_gamma * n_blocks, 256) +
+           2 * cdq_align_up((size_t)d_in * sizeof(float), 256) + cdq_align_up((size_t)d_out * sizeof(float), 256);
+}
+
+// Screens all n_gamma grid points and ranks them.  On return (stream order) cand and active are filled; both point into ws.
+int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, const float* lo, const float* hi,
+                      float margin, int block_rows, int64_t n_blocks, void* ws, const uint8_t** cand_out, const uint8_t** active_out,
+                      hipStream_t st) {
+    const int64_t rows = (d_out + SB - 1) / SB * SB;
+    const int n_part = (int)(2 * d_in / SB);
+    char* p = (char*)ws;
+    _Float16* R = (_Float16*)p;        p += cdq_align_up((size_t)d_in * d_in * 2, 256);
+    _Float16* F = (_Float16*)p;        p += cdq_align_up((size_t)rows * d_in * 2, 256);
+    float* partial = (float*)p;        p += cdq_align_up((size_t)n_part * rows * sizeof(float), 256);
+    float* screened = (float*)p;       p += cdq_align_up((size_t)n_gamma * d_out * sizeof(float), 256);
+    uint8_t* cand = (uint8_t*)p;       p += cdq_align_up((size_t)n_gamma * d_out, 256);
+    uint8_t* active = (uint8_t*)p;     p += cdq_align_up((size_t)n_gamma * n_blocks, 256);
+    float* d = (float*)p;              p += cdq_align_up((size_t)d_in * sizeof(float), 256);
+    float* rd = (float*)p;             p += cdq_align_up((size_t)d_in * sizeof(float), 256);
+    float* row_scale2 = (float*)p;
+    if (rows / SB > 65535) return CDQ_EUNSUPPORTED;
+    hipLaunchKernelGGL(owc_diag_kernel, dim3((unsigned)((d_in + 255) / 256)), dim3(256), 0, st, H, d_in, d, rd);
+    CDQ_LAUNCH_CHECK();
+    hipLaunchKernelGGL(owc_corr_f16_kernel, dim3((unsigned)d_in), dim3(256), 0, st, H, d_in, (const float*)rd, R);
+    CDQ_LAUNCH_CHECK();
+    if (rows > d_out) {                                            // d_in is a multiple of 128: whole words
+        const int64_t words = (rows - d_out) * d_in / 2;
+        hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, (uint32_t*)(F + d_out * d_in), words, 0u);
+        CDQ_LAUNCH_CHECK();
+    }
+    {
+        const int64_t words = (int64_t)(cdq_align_up((size_t)n_gamma * n_blocks, 256) / 4);     // the region is padded to 256 bytes
+        hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, (uint32_t*)active, words, 0u);
+        CDQ_LAUNCH_CHECK();
+    }
+    static const hipError_t lds_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(owc_screen_kernel),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 2 * STILE);
+    if (lds_rc != hipSuccess) return CDQ_EHIP;
+    for (int k = 1; k <= n_gamma; ++k) {
+        const float gamma = (float)k / (float)n_gamma;
+        hipLaunchKernelGGL(owc_residual_f16_kernel, dim3((unsigned)d_out), dim3(256), 0, st, Wt, d_in, bits, lo, hi, gamma, (const float*)d, F,
+                           row_scale2);
+        CDQ_LAUNCH_CHECK();
+        hipLaunchKernelGGL(owc_screen_kernel, dim3((unsigned)(d_in / SB), (unsigned)(rows / SB)), dim3(SNT), 2 * 2 * STILE, st,
+                           (const _Float16*)F, (const _Float16*)R, rows, d_in, partial);
+        CDQ_LAUNCH_CHECK();
+        hipLaunchKernelGGL(owc_screen_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, (const float*)partial, rows,
+                           d_out, n_part, (const float*)row_scale2, screened + (int64_t)(k - 1) * d_out);
+        CDQ_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(owc_rank_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, (const float*)screened, d_out, n_gamma,
+                       margin, block_rows, n_blocks, cand, active);
+    CDQ_LAUNCH_CHECK();
+    *cand_out = cand;
+    *active_out = active;
+    return CDQ_OK;
+}
+
+}  // namespace cdq
