@@ -128,12 +128,17 @@ def test_hessian_accumulate_and_damping(cdq, oracle):
 
 # ----------------------------------------------------------------------------- OWC
 
-@pytest.mark.parametrize("d_out,d_in,n,bits,n_gamma", [(48, 256, 600, 3, 50), (20, 1000, 1500, 4, 50), (7, 64, 200, 2, 10), (130, 128, 400, 3, 50)])
+@pytest.mark.parametrize("d_out,d_in,n,bits,n_gamma", [(48, 256, 600, 3, 50), (20, 1000, 1500, 4, 50), (7, 64, 200, 2, 10), (130, 128, 400, 3, 50),
+                                                       # shapes that go through the fp16 look at all grid points first (d_in % 128 == 0, >= 256)
+                                                       (300, 384, 900, 3, 50), (70, 1024, 1500, 2, 50), (129, 512, 800, 4, 20), (33, 256, 500, 3, 4)])
 def test_init_owc(cdq, oracle, d_out, d_in, n, bits, n_gamma):
     """Eq. (2) grid search: min-max and the scale of the chosen gamma bit-exact, the chosen gamma
-    equal to the oracle's except where two grid points have (nearly) the same loss."""
+    equal to the oracle's exhaustive fp64 search except where two grid points have (nearly) the same loss."""
     X, Wt = rand_layer(7 + d_in, d_in, d_out, n, corr=0.5)
     rng = np.random.default_rng(d_in)
+    if d_out > 60:                                   # heavy-tailed weights and channel scales: the hard case for a low-precision look
+        Wt *= np.exp(0.7 * rng.standard_normal(Wt.shape)).astype(np.float32)
+        X *= np.exp(0.5 * rng.standard_normal(d_in)).astype(np.float32)
     Wt[:, rng.integers(0, d_in, 3)] *= 5.0           # outlier weights make clipping pay off
     Wt[0, :] = 0.125                                 # a constant column
     H32 = oracle.hessian(X).astype(np.float32)
