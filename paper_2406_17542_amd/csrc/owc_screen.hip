@@ -22,11 +22,11 @@ typedef float f16v __attribute__((ext_vector_type(16)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
-constexpr int SB = 128;                 // tile of C: SB rows of E by SB columns of H
+constexpr int SB = 128;                 // smallest tile of C: SB rows of F by SB columns of R (the rows are padded to 2 SB)
 constexpr int SK = 64;                  // contraction step
 constexpr int SROW = SK * 2 + 16;       // LDS bytes per tile row (144: 16-byte aligned, rows 8 apart share banks)
-constexpr int STILE = SB * SROW;        // one operand tile
-constexpr int SNT = 256;                // four wavefronts, 64 x 64 of C each
+// A tile of TB x TB of C per workgroup of (TB / 64)^2 wavefronts, 64 x 64 each: TB = 256 (16 wavefronts, 144 KiB of LDS)
+// halves the operand traffic from L2 per FLOP (9.5 TB/s of tile loads with the 128 x 128 tile).
 
 __global__ __launch_bounds__(256) void fill_words_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t v) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -85,23 +85,25 @@ __global__ __launch_bounds__(256) void owc_residual_f16_kernel(const float* __re
 // f^T R f over the blocks of R on and above the diagonal (R is symmetric: its row c is its column c, and the blocks below
 // the diagonal repeat the ones above): for column block cb the contraction runs over k < 128 (cb + 1), and what was
 // accumulated before the diagonal block is doubled -- exactly -- when it is reached.
-// partial[cb * 2 + h][j] = sum over the 64 columns c of half h of column block cb of C[j][c] F[j][c].
-// F [rows][d_in], rows a multiple of SB, d_in a multiple of SB.  grid (d_in / SB, rows / SB), longest column blocks first.
-__global__ __launch_bounds__(SNT) void owc_screen_kernel(const _Float16* __restrict__ E, const _Float16* __restrict__ R, int64_t rows,
-                                                         int64_t d_in, float* __restrict__ partial) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];             // [2 stages][E tile | H tile]
+// partial[cb * (TB / 64) + h][j] = sum over the 64 columns c of part h of column block cb of C[j][c] F[j][c].
+// F [rows][d_in], rows a multiple of TB, d_in a multiple of TB.  grid (d_in / TB, rows / TB), longest column blocks first.
+template <int TB>
+__global__ __launch_bounds__((TB / 64) * (TB / 64) * 64) void owc_screen_kernel(const _Float16* __restrict__ E, const _Float16* __restrict__ R,
+                                                                               int64_t rows, int64_t d_in, float* __restrict__ partial) {
+    constexpr int WPR = TB / 64, SNT = WPR * WPR * 64, STILE = TB * SROW, CPT = TB * 8 / SNT;    // wavefronts per tile row, threads, chunks per thread
+    extern __shared__ __attribute__((aligned(16))) char lds[];             // [2 stages][F tile | R tile]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int cb = (int)(gridDim.x - 1 - blockIdx.x);
-    const int64_t c0 = (int64_t)cb * SB, j0 = (int64_t)blockIdx.y * SB;
-    const int wr = (wave >> 1) * 64, wc = (wave & 1) * 64;                   // this wavefront's 64 x 64 of the tile
-    const int n_steps = (cb + 1) * (SB / SK), diag_step = cb * (SB / SK);     // steps before diag_step lie above the diagonal block
+    const int64_t c0 = (int64_t)cb * TB, j0 = (int64_t)blockIdx.y * TB;
+    const int wr = (wave / WPR) * 64, wc = (wave % WPR) * 64;                 // this wavefront's 64 x 64 of the tile
+    const int n_steps = (cb + 1) * (TB / SK), diag_step = cb * (TB / SK);     // steps before diag_step lie above the diagonal block
 
-    // a thread moves four 16-byte chunks of each operand tile per step: chunk id = tid + 256 i -> row id / 8, chunk id % 8
-    u4 ra[4], rb[4];
+    // a thread moves CPT 16-byte chunks of each operand tile per step: chunk id = tid + SNT i -> row id / 8, chunk id % 8
+    u4 ra[CPT], rb[CPT];
     auto load = [&](int step) {
         const int64_t k0 = (int64_t)step * SK;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < CPT; ++i) {
             const int id = tid + SNT * i, row = id >> 3, kc = id & 7;
             ra[i] = *reinterpret_cast<const u4*>(E + (j0 + row) * d_in + k0 + kc * 8);
             rb[i] = *reinterpret_cast<const u4*>(R + (c0 + row) * d_in + k0 + kc * 8);
@@ -110,7 +112,7 @@ __global__ __launch_bounds__(SNT) void owc_screen_kernel(const _Float16* __restr
     auto store = [&](int stage) {
         char* base = lds + stage * 2 * STILE;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < CPT; ++i) {
             const int id = tid + SNT * i, row = id >> 3, kc = id & 7;
             *reinterpret_cast<u4*>(base + row * SROW + kc * 16) = ra[i];
             *reinterpret_cast<u4*>(base + STILE + row * SROW + kc * 16) = rb[i];
@@ -177,7 +179,7 @@ __global__ __launch_bounds__(SNT) void owc_screen_kernel(const _Float16* __restr
             for (int o = 16; o; o >>= 1) t += __shfl_xor(t, o);
             if ((lane & 31) == 0) {
                 const int64_t j = j0 + wr + 32 * a + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                partial[((int64_t)cb * 2 + (wave & 1)) * rows + j] = t;
+                partial[((int64_t)cb * WPR + (wave % WPR)) * rows + j] = t;
             }
         }
     }
@@ -237,7 +239,7 @@ bool owc_screen_applies(int64_t d_out, int64_t d_in, int n_gamma) {
 // R [d_in][d_in] fp16 | F [rows][d_in] fp16 | partial [2 d_in / SB][rows] fp32 | screened [n_gamma][d_out] fp32 |
 // cand [n_gamma][d_out] u8 | active [n_gamma][n_blocks] u8 | d, 1/d [d_in] fp32 each | row scales [d_out] fp32
 size_t owc_screen_workspace_bytes(int64_t d_out, int64_t d_in, int n_gamma, int64_t n_blocks) {
-    const int64_t rows = (d_out + SB - 1) / SB * SB;
+    const int64_t rows = (d_out + 2 * SB - 1) / (2 * SB) * (2 * SB);
     return cdq_align_up((size_t)d_in * d_in * 2, 256) + cdq_align_up((size_t)rows * d_in * 2, 256) +
            cdq_align_up((size_t)(2 * d_in / SB) * rows * sizeof(float), 256) + cdq_align_up((size_t)n_gamma * d_out * sizeof(float), 256) +
            cdq_align_up((size_t)n_gamma * d_out, 256) + cdq_align_up((size_t)n_gamma * n_blocks, 256) +
@@ -248,8 +250,9 @@ size_t owc_screen_workspace_bytes(int64_t d_out, int64_t d_in, int n_gamma, int6
 int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, const float* lo, const float* hi,
                       float margin, int block_rows, int64_t n_blocks, void* ws, const uint8_t** cand_out, const uint8_t** active_out,
                       hipStream_t st) {
-    const int64_t rows = (d_out + SB - 1) / SB * SB;
+    const int64_t rows = (d_out + 2 * SB - 1) / (2 * SB) * (2 * SB);
     const int n_part = (int)(2 * d_in / SB);
+    const bool big = d_in % (2 * SB) == 0;                         // the 256 x 256 tile
     char* p = (char*)ws;
     _Float16* R = (_Float16*)p;        p += cdq_align_up((size_t)d_in * d_in * 2, 256);
     _Float16* F = (_Float16*)p;        p += cdq_align_up((size_t)rows * d_in * 2, 256);
@@ -275,16 +278,23 @@ int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_
         hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, (uint32_t*)active, words, 0u);
         CDQ_LAUNCH_CHECK();
     }
-    static const hipError_t lds_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(owc_screen_kernel),
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 2 * STILE);
-    if (lds_rc != hipSuccess) return CDQ_EHIP;
+    constexpr int lds_small = 2 * 2 * SB * SROW, lds_big = 2 * 2 * 2 * SB * SROW;
+    static const hipError_t lds_rc_small = hipFuncSetAttribute(reinterpret_cast<const void*>(owc_screen_kernel<SB>),
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_small);
+    static const hipError_t lds_rc_big = hipFuncSetAttribute(reinterpret_cast<const void*>(owc_screen_kernel<2 * SB>),
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_big);
+    if (lds_rc_small != hipSuccess || lds_rc_big != hipSuccess) return CDQ_EHIP;
     for (int k = 1; k <= n_gamma; ++k) {
         const float gamma = (float)k / (float)n_gamma;
         hipLaunchKernelGGL(owc_residual_f16_kernel, dim3((unsigned)d_out), dim3(256), 0, st, Wt, d_in, bits, lo, hi, gamma, (const float*)d, F,
                            row_scale2);
         CDQ_LAUNCH_CHECK();
-        hipLaunchKernelGGL(owc_screen_kernel, dim3((unsigned)(d_in / SB), (unsigned)(rows / SB)), dim3(SNT), 2 * 2 * STILE, st,
-                           (const _Float16*)F, (const _Float16*)R, rows, d_in, partial);
+        if (big)
+            hipLaunchKernelGGL(owc_screen_kernel<2 * SB>, dim3((unsigned)(d_in / (2 * SB)), (unsigned)(rows / (2 * SB))), dim3(1024), lds_big, st,
+                               (const _Float16*)F, (const _Float16*)R, rows, d_in, partial);
+        else
+            hipLaunchKernelGGL(owc_screen_kernel<SB>, dim3((unsigned)(d_in / SB), (unsigned)(rows / SB)), dim3(256), lds_small, st,
+                               (const _Float16*)F, (const _Float16*)R, rows, d_in, partial);
         CDQ_LAUNCH_CHECK();
         hipLaunchKernelGGL(owc_screen_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, (const float*)partial, rows,
                            d_out, n_part, (const float*)row_scale2, screened + (int64_t)(k - 1) * d_out);
