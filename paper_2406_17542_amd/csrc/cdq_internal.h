@@ -43,7 +43,7 @@ int loss_block_rows();
 bool owc_screen_applies(int64_t d_out, int64_t d_in, int n_gamma);
 size_t owc_screen_workspace_bytes(int64_t d_out, int64_t d_in, int n_gamma, int64_t n_blocks);
 int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, const float* lo, const float* hi,
-                      float margin, int block_rows, int64_t n_blocks, void* ws, const uint8_t** cand_out, const uint8_t** active_out,
+                      float margin, int block_rows, int64_t n_blocks, void* ws, uint8_t** cand_out, uint8_t** active_out,
                       hipStream_t st);
 
 // ---- owc.hip

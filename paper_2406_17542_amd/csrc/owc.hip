@@ -97,9 +97,120 @@ __global__ __launch_bounds__(256) void owc_update_best_ranked_kernel(const doubl
     }
 }
 
+__global__ __launch_bounds__(256) void owc_fill_u8_kernel(uint8_t* __restrict__ p, int64_t n, uint8_t v) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
 __global__ __launch_bounds__(256) void owc_fill_f32_kernel(float* __restrict__ p, int64_t n, float v) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n) p[i] = v;
+}
+
+// ---- the candidates beyond a column's first, gathered into dense rows for one pass of the loss kernel
+// extras[j]: how many candidates column j has beyond its first (cand [n_gamma][d_out], a column's candidates are contiguous in r)
+__global__ __launch_bounds__(256) void owc_count_extras_kernel(const uint8_t* __restrict__ cand, int64_t d_out, int n_gamma,
+                                                               int32_t* __restrict__ extras) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_out) return;
+    int e = 0;
+    for (int r = 1; r < n_gamma && cand[(int64_t)r * d_out + j] != 0; ++r) ++e;
+    extras[j] = e;
+}
+
+// base[j] = extras[0] + ... + extras[j-1]; one workgroup, the columns in chunks of 1024; total is cleared
+__global__ __launch_bounds__(1024) void owc_scan_extras_kernel(const int32_t* __restrict__ extras, int64_t d_out, int32_t* __restrict__ base,
+                                                               int32_t* __restrict__ total) {
+    __shared__ int32_t sh[1024];
+    __shared__ int32_t carry;
+    if (threadIdx.x == 0) { carry = 0; *total = 0; }
+    __syncthreads();
+    for (int64_t j0 = 0; j0 < d_out; j0 += 1024) {
+        const int64_t j = j0 + threadIdx.x;
+        const int32_t v = j < d_out ? extras[j] : 0;
+        sh[threadIdx.x] = v;
+        __syncthreads();
+        for (int o = 1; o < 1024; o <<= 1) {                       // inclusive scan of the chunk
+            const int32_t t = (int)threadIdx.x >= o ? sh[threadIdx.x - o] : 0;
+            __syncthreads();
+            sh[threadIdx.x] += t;
+            __syncthreads();
+        }
+        if (j < d_out) base[j] = carry + sh[threadIdx.x] - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry += sh[1023];
+        __syncthreads();
+    }
+}
+
+// A column whose extra candidates fit below cap gets rows base[j] .. base[j] + extras[j] - 1: their column and grid index
+// are recorded, they are struck from cand (the rank passes will not see them), total becomes the number of rows in use.
+__global__ __launch_bounds__(256) void owc_assign_rows_kernel(uint8_t* __restrict__ cand, int64_t d_out, const int32_t* __restrict__ extras,
+                                                              const int32_t* __restrict__ base, int32_t cap, int32_t* __restrict__ row_col,
+                                                              uint8_t* __restrict__ row_k, int32_t* __restrict__ total) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_out) return;
+    const int32_t e = extras[j], b = base[j];
+    if (e == 0 || (int64_t)b + e > cap) return;
+    for (int r = 1; r <= e; ++r) {
+        row_col[b + r - 1] = (int32_t)j;
+        row_k[b + r - 1] = cand[(int64_t)r * d_out + j];
+        cand[(int64_t)r * d_out + j] = 0;
+    }
+    atomicMax(total, b + e);
+}
+
+// which blocks of the loss kernel have work: rank r >= 1 of the columns (what the rows above did not take), and the rows
+__global__ __launch_bounds__(256) void owc_flags_kernel(const uint8_t* __restrict__ cand, int64_t d_out, int n_gamma, int block_rows,
+                                                        int64_t n_blocks, const int32_t* __restrict__ total, uint8_t* __restrict__ active,
+                                                        uint8_t* __restrict__ rows_active) {
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;     // over (r, j), r >= 1
+    if (x < n_blocks) rows_active[x] = (x * block_rows < *total) ? 1 : 0;
+    if (x >= (int64_t)(n_gamma - 1) * d_out) return;
+    const int64_t r = 1 + x / d_out, j = x % d_out;
+    if (cand[r * d_out + j] != 0) active[r * n_blocks + j / block_rows] = 1;
+}
+
+// row s < total: minus the residual of its column at its grid point, so that the loss kernel, given scale = zero = 0,
+// forms e = fma(0, q, 0) - (w - fma(a, q, lo)) -- the same bits as fma(a, q, lo) - w
+__global__ __launch_bounds__(256) void owc_row_residual_kernel(const float* __restrict__ Wt, int64_t d_in, int bits, const float* __restrict__ lo_in,
+                                                               const float* __restrict__ hi_in, int n_gamma, const int32_t* __restrict__ row_col,
+                                                               const uint8_t* __restrict__ row_k, const int32_t* __restrict__ total,
+                                                               float* __restrict__ Wc) {
+    const int64_t s = blockIdx.x;
+    if (s >= *total) return;
+    const int64_t j = row_col[s];
+    const float lo = lo_in[j], hi = hi_in[j];
+    const float g = (float)row_k[s] / (float)n_gamma;
+    const float top = (float)((1 << bits) - 1);
+    float a = __fdiv_rn(g * (hi - lo), top);
+    if (!(a > 0.0f) || isinf(a)) a = 1.0f;
+    const float* w = Wt + j * d_in;
+    float* o = Wc + s * d_in;
+    for (int64_t k = threadIdx.x; k < d_in; k += 256) {
+        const float wk = w[k];
+        const float q = fminf(fmaxf(rintf(__fdiv_rn(wk - lo, a)), 0.0f), top);
+        o[k] = wk - fmaf(a, q, lo);
+    }
+}
+
+__global__ __launch_bounds__(256) void owc_update_best_rows_kernel(const double* __restrict__ row_loss, const uint8_t* __restrict__ row_k,
+                                                                   const int32_t* __restrict__ extras, const int32_t* __restrict__ base,
+                                                                   int32_t cap, int n_gamma, int64_t d_out, double* __restrict__ best,
+                                                                   float* __restrict__ best_gamma) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_out) return;
+    const int32_t e = extras[j], b = base[j];
+    if (e == 0 || (int64_t)b + e > cap) return;
+    double bl = best[j];
+    float bg = best_gamma[j];
+    for (int r = 0; r < e; ++r) {
+        const double c = row_loss[b + r];
+        const float g = (float)row_k[b + r] / (float)n_gamma;
+        if (bg == 0.0f || c < bl || (c == bl && g > bg)) { bl = c; bg = g; }
+    }
+    best[j] = bl;
+    best_gamma[j] = bg;
 }
 
 constexpr float kScreenMargin = 3e-3f;      // relative; the fp16 evaluation was off by 3e-4 at most on heavy-tailed test layers
@@ -114,6 +225,10 @@ size_t owc_workspace_bytes(int64_t d_out, int64_t d_in) {
     b += loss_workspace_bytes(d_out, d_in);
     const int64_t n_blocks = (d_out + loss_block_rows() - 1) / loss_block_rows();
     b += owc_screen_workspace_bytes(d_out, d_in, 255, n_blocks);     // sized for the largest grid the screen takes
+    // the gathered candidates: rows of minus-residuals [d_out][d_in], their losses, zeros for scale and zero, extras, base,
+    // row -> column, row -> grid index, total, block flags
+    b += cdq_align_up((size_t)d_out * d_in * sizeof(float), 256) + cdq_align_up((size_t)d_out * sizeof(double), 256);
+    b += cdq_align_up((size_t)d_out * sizeof(float), 256) * 4 + cdq_align_up((size_t)d_out, 256) + 256 + cdq_align_up((size_t)n_blocks, 256);
     return b;
 }
 
@@ -144,12 +259,54 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
     if (owc_screen_applies(d_out, d_in, n_gamma)) {
         const int block_rows = loss_block_rows();
         const int64_t n_blocks = (d_out + block_rows - 1) / block_rows;
-        const uint8_t *cand, *active;
+        uint8_t *cand, *active;
         int rc = owc_screen_launch(H, Wt, d_out, d_in, bits, n_gamma, lo, hi, kScreenMargin, block_rows, n_blocks, screen_ws, &cand, &active, st);
         if (rc != CDQ_OK) return rc;
         hipLaunchKernelGGL(owc_fill_f32_kernel, col_blocks, t256, 0, st, best_gamma, d_out, 0.0f);      // 0: nothing evaluated yet
         CDQ_LAUNCH_CHECK();
+        // the candidates beyond each column's first, gathered into at most d_out dense rows
+        char* gp = (char*)screen_ws + owc_screen_workspace_bytes(d_out, d_in, 255, n_blocks);
+        float* Wc = (float*)gp;             gp += cdq_align_up((size_t)d_out * d_in * sizeof(float), 256);
+        double* row_loss = (double*)gp;     gp += dsz;
+        float* zeros = (float*)gp;          gp += fsz;
+        int32_t* extras = (int32_t*)gp;     gp += fsz;
+        int32_t* base = (int32_t*)gp;       gp += fsz;
+        int32_t* row_col = (int32_t*)gp;    gp += fsz;
+        uint8_t* row_k = (uint8_t*)gp;      gp += cdq_align_up((size_t)d_out, 256);
+        int32_t* total = (int32_t*)gp;      gp += 256;
+        uint8_t* rows_active = (uint8_t*)gp;
+        const int32_t cap = (int32_t)d_out;
+        hipLaunchKernelGGL(owc_fill_f32_kernel, col_blocks, t256, 0, st, zeros, d_out, 0.0f);
+        CDQ_LAUNCH_CHECK();
+        hipLaunchKernelGGL(owc_count_extras_kernel, col_blocks, t256, 0, st, cand, d_out, n_gamma, extras);
+        CDQ_LAUNCH_CHECK();
+        hipLaunchKernelGGL(owc_scan_extras_kernel, dim3(1), dim3(1024), 0, st, (const int32_t*)extras, d_out, base, total);
+        CDQ_LAUNCH_CHECK();
+        hipLaunchKernelGGL(owc_assign_rows_kernel, col_blocks, t256, 0, st, cand, d_out, (const int32_t*)extras, (const int32_t*)base, cap,
+                           row_col, row_k, total);
+        CDQ_LAUNCH_CHECK();
+        {
+            const int64_t flags = (int64_t)(n_gamma - 1) * n_blocks;                 // ranks >= 1 start with no block active
+            hipLaunchKernelGGL(owc_fill_u8_kernel, dim3((unsigned)((flags + 255) / 256)), t256, 0, st, active + n_blocks, flags, (uint8_t)0);
+            CDQ_LAUNCH_CHECK();
+        }
+        {
+            const int64_t items = (int64_t)(n_gamma - 1) * d_out > n_blocks ? (int64_t)(n_gamma - 1) * d_out : n_blocks;
+            hipLaunchKernelGGL(owc_flags_kernel, dim3((unsigned)((items + 255) / 256)), t256, 0, st, (const uint8_t*)cand, d_out, n_gamma,
+                               block_rows, n_blocks, (const int32_t*)total, active, rows_active);
+            CDQ_LAUNCH_CHECK();
+        }
         for (int r = 0; r < n_gamma; ++r) {
+            if (r == 1) {                  // after every column's first candidate: the gathered rows, one pass
+                hipLaunchKernelGGL(owc_row_residual_kernel, cols, t256, 0, st, Wt, d_in, bits, (const float*)lo, (const float*)hi, n_gamma,
+                                   (const int32_t*)row_col, (const uint8_t*)row_k, (const int32_t*)total, Wc);
+                CDQ_LAUNCH_CHECK();
+                rc = loss_launch(H, Wc, zeros, zeros, trial_q, d_out, d_in, d_in, row_loss, nullptr, loss_ws, loss_ws_bytes, st, rows_active);
+                if (rc != CDQ_OK) return rc;
+                hipLaunchKernelGGL(owc_update_best_rows_kernel, col_blocks, t256, 0, st, (const double*)row_loss, (const uint8_t*)row_k,
+                                   (const int32_t*)extras, (const int32_t*)base, cap, n_gamma, d_out, best_loss, best_gamma);
+                CDQ_LAUNCH_CHECK();
+            }
             hipLaunchKernelGGL(owc_rank_gamma_kernel, col_blocks, t256, 0, st, cand + (int64_t)r * d_out, d_out, n_gamma, rank_gamma);
             CDQ_LAUNCH_CHECK();
             hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, 1.0f, (const float*)rank_gamma, trial_scale,

@@ -248,7 +248,7 @@ size_t owc_screen_workspace_bytes(int64_t d_out, int64_t d_in, int n_gamma, int6
 
 // Screens all n_gamma grid points and ranks them.  On return (stream order) cand and active are filled; both point into ws.
 int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, const float* lo, const float* hi,
-                      float margin, int block_rows, int64_t n_blocks, void* ws, const uint8_t** cand_out, const uint8_t** active_out,
+                      float margin, int block_rows, int64_t n_blocks, void* ws, uint8_t** cand_out, uint8_t** active_out,
                       hipStream_t st) {
     const int64_t rows = (d_out + 2 * SB - 1) / (2 * SB) * (2 * SB);
     const int n_part = (int)(2 * d_in / SB);
