@@ -129,8 +129,8 @@ def main():
     ap.add_argument("--no-probes", action="store_true", help="skip the achievable-bandwidth probes")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (columns would shard with no communication; "
-              "see DESIGN.md) -- rerun with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the output columns are independent problems and would shard "
+              "over GPUs with a replica of H and no communication during the loop) -- rerun with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
