@@ -188,9 +188,9 @@ int cdq_init_owc_cd(const float *H, const float *Wt, int64_t d_out, int64_t d_in
  * d_in even, at most 65534.  Three kernels give the same results: several columns per workgroup
  * with their state in LDS (d_in % 16 == 0, d_in up to about 4700), one column per workgroup with
  * its state in LDS (d_in <= 8192, d_in % 4 == 0, 16-byte aligned H), and for wider or differently
- * aligned layers up to eight columns per workgroup with only the pair test's 16-bit margins in LDS
+ * aligned layers up to 16 columns per workgroup with only the pair test's 16-bit margins in LDS
  * and everything else in global memory.  Workspace of CDQ_OP_BCD size (n = T):
- * d_out*d_in*6 + T*(d_in/2)*12 bytes and change.
+ * d_out*d_in*8 + T*(d_in/2)*12 bytes and change.
  */
 int cdq_bcd(const float *H, const float *Wt, const float *scale, const float *zero, uint8_t *Q,
             int64_t d_out, int64_t d_in, int bits, int64_t group, int k, const int32_t *parts, int64_t T,

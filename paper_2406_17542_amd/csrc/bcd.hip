@@ -690,7 +690,7 @@ size_t bcdm_lds_bytes(int64_t d_in, int64_t group, int cw, int nst) {
 
 // ------------------------------------------------------------------------------------------------
 // Wide layers (d_in above what the kernels above hold, up to 65534; any alignment).  A 1024-thread workgroup owns
-// CW in {8, 4, 2, 1} columns.  What bounds an idle iteration here is the two scattered LDS reads per pair of the test,
+// up to 16 columns (rows of CW in {16, 8, 4, 2, 1} margins).  What bounds an idle iteration here is the two scattered LDS reads per pair of the test,
 // so LDS holds only what that test reads for all the columns at once -- the minimum over the columns of v = 1 - u - tau,
 // 16 bits a coordinate -- and one pass over the pairs serves CW columns.  Everything else stays in global memory: the
 // per-column v (rows of CW values, read for the few pairs that fail the test on the minimum), 2g (the workspace's
@@ -709,7 +709,13 @@ constexpr int BCDW_CUNR = 6;         // coordinates per thread whose loads are i
 // the CW 16-bit margins of one coordinate, one load
 template <int CW>
 __device__ __forceinline__ void bcdw_load_row(const uint16_t* p, uint32_t (&v)[CW]) {
-    if constexpr (CW == 8) {
+    if constexpr (CW == 16) {
+        const uint4 w0 = *reinterpret_cast<const uint4*>(p), w1 = *reinterpret_cast<const uint4*>(p + 8);
+        v[0] = w0.x & 0xffffu; v[1] = w0.x >> 16; v[2] = w0.y & 0xffffu; v[3] = w0.y >> 16;
+        v[4] = w0.z & 0xffffu; v[5] = w0.z >> 16; v[6] = w0.w & 0xffffu; v[7] = w0.w >> 16;
+        v[8] = w1.x & 0xffffu; v[9] = w1.x >> 16; v[10] = w1.y & 0xffffu; v[11] = w1.y >> 16;
+        v[12] = w1.z & 0xffffu; v[13] = w1.z >> 16; v[14] = w1.w & 0xffffu; v[15] = w1.w >> 16;
+    } else if constexpr (CW == 8) {
         const uint4 w = *reinterpret_cast<const uint4*>(p);
         v[0] = w.x & 0xffffu; v[1] = w.x >> 16; v[2] = w.y & 0xffffu; v[3] = w.y >> 16;
         v[4] = w.z & 0xffffu; v[5] = w.z >> 16; v[6] = w.w & 0xffffu; v[7] = w.w >> 16;
@@ -729,11 +735,12 @@ __global__ __launch_bounds__(BCDW_NT) void bcd2_wide_kernel(const float* __restr
                                                             uint16_t* Vg_all, const float* __restrict__ scale, uint8_t* Q,
                                                             const uint32_t* __restrict__ pair_ik, const uint16_t* __restrict__ pair_thr,
                                                             const float* __restrict__ pair_h2, const int32_t* __restrict__ bad_parts,
-                                                            int d_out, int d_in, int group, int T, int score_all,
+                                                            int d_out, int d_in, int group, int T, int cpw, int score_all,
                                                             int32_t* __restrict__ moves_out, float* __restrict__ G_out,
                                                             int32_t* __restrict__ trace, int trace_cap) {
     constexpr int L = 1 << BITS, NC = L * L;
     constexpr int LPE = 16, CPL = NC / LPE;
+    constexpr int CUNR = CW > 8 ? 3 : BCDW_CUNR;                  // fewer coordinates in flight at a commit where a row of margins is long
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __shared__ unsigned long long colkey[3][CW];                  // per iteration mod 3: the columns' best (score image, pair, levels)
     __shared__ int cnt[4];                                        // ring of queue lengths
@@ -747,8 +754,8 @@ __global__ __launch_bounds__(BCDW_NT) void bcd2_wide_kernel(const float* __restr
     const int n_grp = d_in / group, n_pairs = d_in / 2;
     const uint32_t grp_mul = (uint32_t)((0x100000000ull + (uint32_t)group - 1u) / (uint32_t)group);   // exact below 2^16 (group > 1)
     auto grp = [&](int i) { return n_grp == 1 ? 0 : (group == 1 ? i : (int)__umulhi((uint32_t)i, grp_mul)); };
-    const int j0 = blockIdx.x * CW;
-    const int ncol = (d_out - j0 < CW) ? d_out - j0 : CW;
+    const int j0 = blockIdx.x * cpw;                              // cpw <= CW columns per workgroup; rows of margins are CW long
+    const int ncol = (d_out - j0 < cpw) ? d_out - j0 : cpw;
     if (*bad_parts != 0) {                                        // invalid partitions: leave the columns untouched
         if (tid < ncol && moves_out != nullptr) moves_out[j0 + tid] = -1;
         return;
@@ -917,18 +924,18 @@ __global__ __launch_bounds__(BCDW_NT) void bcd2_wide_kernel(const float* __restr
             const float di2 = 2.0f * (ac[grp(i)] * (float)(ri - (int)qc[i])), dk2 = 2.0f * (ac[grp(k)] * (float)(rk - (int)qc[k]));
             const float* hi = H + (int64_t)i * d_in;
             const float* hk = H + (int64_t)k * d_in;
-            for (int x0 = tid; x0 < d_in; x0 += BCDW_NT * BCDW_CUNR) {
-                float vi[BCDW_CUNR], vk[BCDW_CUNR], gv[BCDW_CUNR], hv[BCDW_CUNR], av[BCDW_CUNR];
-                int qv[BCDW_CUNR];
-                uint32_t rows[BCDW_CUNR][CW];
+            for (int x0 = tid; x0 < d_in; x0 += BCDW_NT * CUNR) {
+                float vi[CUNR], vk[CUNR], gv[CUNR], hv[CUNR], av[CUNR];
+                int qv[CUNR];
+                uint32_t rows[CUNR][CW];
 #pragma unroll
-                for (int u = 0; u < BCDW_CUNR; ++u) {             // all loads of a batch of coordinates in flight together
+                for (int u = 0; u < CUNR; ++u) {             // all loads of a batch of coordinates in flight together
                     const int x = x0 + u * BCDW_NT, xc = x < d_in ? x : x0;
                     vi[u] = hi[xc]; vk[u] = hk[xc]; gv[u] = g2c[xc]; hv[u] = hdiag[xc]; av[u] = ac[grp(xc)]; qv[u] = qc[xc];
                     if (CW > 1) bcdw_load_row<CW>(V + (size_t)xc * CW, rows[u]);
                 }
 #pragma unroll
-                for (int u = 0; u < BCDW_CUNR; ++u) {
+                for (int u = 0; u < CUNR; ++u) {
                     const int x = x0 + u * BCDW_NT;
                     if (x < d_in) {
                         const float g = fmaf(dk2, vk[u], fmaf(di2, vi[u], gv[u]));
@@ -989,12 +996,12 @@ size_t bcd_lds_bytes(int64_t d_in, int64_t group) {
 }  // namespace
 
 // workspace: G0 [d_out][d_in] fp32 | hdiag [d_in] | pair table, 12 bytes per (iteration, pair) | flag |
-// the wide-layer kernel's 16-bit margins, [d_out rounded up to 8][d_in].
+// the wide-layer kernel's 16-bit margins, a row of up to 16 per coordinate and workgroup: at most [2 d_out + 16][d_in].
 // (pair_rec int2 + pair_h2 for the one-column kernel, ik + R16 + 2 spare + pair_h2 for the others)
 size_t bcd_workspace_bytes(int64_t d_out, int64_t d_in, int64_t T) {
     return cdq_align_up((size_t)d_out * d_in * sizeof(float), 256) + cdq_align_up((size_t)d_in * sizeof(float), 256) +
            cdq_align_up((size_t)T * (d_in / 2) * 12, 256) + 256 +
-           cdq_align_up((size_t)(d_out + 7) / 8 * 8 * d_in * sizeof(uint16_t), 256);
+           cdq_align_up((size_t)(2 * d_out + 16) * d_in * sizeof(uint16_t), 256);
 }
 
 int bcd_launch(const float* H, const float* Wt, const float* scale, const float* zero, uint8_t* Q, int64_t d_out, int64_t d_in,
@@ -1014,9 +1021,18 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
     const size_t lds = bcd_lds_bytes(d_in, group);
     // one column per workgroup with its state in LDS; failing that, the wide-layer kernel (any alignment)
     const bool single_ok = nt <= 1024 && lds <= 160 * 1024 && d_in % 4 == 0 && ((uintptr_t)H & 15) == 0;
-    int wcw = 0;                                                  // columns per workgroup of the wide-layer kernel
-    if (d_in < 65536 && bcdw_lds_bytes(d_in) + 4096 <= 160 * 1024) wcw = 8;
-    while (!wide && wcw > 1 && (d_out + wcw - 1) / wcw < 256) wcw /= 2;   // rather more workgroups than CUs (the flag keeps 8)
+    // wide-layer kernel: cpw columns per workgroup, chosen so that the workgroups fill the 256 CUs a whole number of times
+    // (one workgroup per CU at a time), at most 16; its rows of margins are wcw = 1, 2, 4, 8 or 16 long.  The flag keeps 8.
+    int wcw = 0, cpw = 0;
+    if (d_in < 65536 && bcdw_lds_bytes(d_in) + 4096 <= 160 * 1024) {
+        if (wide) cpw = 8;
+        else
+            for (int64_t k = 1; cpw == 0; ++k) {
+                const int64_t c = (d_out + 256 * k - 1) / (256 * k);
+                if (c <= 16) cpw = (int)c;
+            }
+        wcw = cpw > 8 ? 16 : cpw > 4 ? 8 : cpw > 2 ? 4 : cpw;
+    }
     const bool wide_ok = wcw != 0;
     if ((!single_ok && !wide_ok) || T > 0x7fffffffLL || d_out > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
     if (ws == nullptr || ((uintptr_t)ws & 255) || ws_bytes < bcd_workspace_bytes(d_out, d_in, T)) return CDQ_EWORKSPACE;
@@ -1052,7 +1068,7 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
         }
     // the wide-layer kernel where nothing else applies, and where it shares a pass over the pairs among more columns than
     // the kernels with the columns' state in LDS would (measured, d_in = 4608: 2 columns 363 ms, 8 columns here 205 ms)
-    const bool use_wide = !single_ok || (wide && wide_ok) || (!single && cw < 4 && wcw >= 4);
+    const bool use_wide = !single_ok || (wide && wide_ok) || (!single && cw < 4 && cpw >= 3);
     if (use_wide) {
         uint32_t* t_ik = (uint32_t*)table;
         uint16_t* t_thr = (uint16_t*)(table + 4 * (size_t)n_items);
@@ -1061,7 +1077,7 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
         CDQ_LAUNCH_CHECK();
         const int tc = (int)(trace_cap > 0x7fffffffLL ? 0x7fffffffLL : trace_cap);
         const size_t wlds = bcdw_lds_bytes(d_in);
-        const dim3 grid((unsigned)((d_out + wcw - 1) / wcw));
+        const dim3 grid((unsigned)((d_out + cpw - 1) / cpw));
 #define BCDW_CASE(B, C)                                                                                                          \
     if (bits == B && wcw == C) {                                                                                                 \
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(bcd2_wide_kernel<B, C>), hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -1069,13 +1085,13 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
             return CDQ_EHIP;                                                                                                     \
         hipLaunchKernelGGL((bcd2_wide_kernel<B, C>), grid, dim3(BCDW_NT), wlds, st, H, (const float*)hdiag, G0, Vg, scale, Q,    \
                            (const uint32_t*)t_ik, (const uint16_t*)t_thr, (const float*)pair_h2, (const int32_t*)bad, (int)d_out, \
-                           (int)d_in, (int)group, (int)T, score_all ? 1 : 0, moves, G_out, trace, tc);                           \
+                           (int)d_in, (int)group, (int)T, cpw, score_all ? 1 : 0, moves, G_out, trace, tc);                      \
         CDQ_LAUNCH_CHECK();                                                                                                      \
         return CDQ_OK;                                                                                                           \
     }
-        BCDW_CASE(2, 8) BCDW_CASE(2, 4) BCDW_CASE(2, 2) BCDW_CASE(2, 1)
-        BCDW_CASE(3, 8) BCDW_CASE(3, 4) BCDW_CASE(3, 2) BCDW_CASE(3, 1)
-        BCDW_CASE(4, 8) BCDW_CASE(4, 4) BCDW_CASE(4, 2) BCDW_CASE(4, 1)
+        BCDW_CASE(2, 16) BCDW_CASE(2, 8) BCDW_CASE(2, 4) BCDW_CASE(2, 2) BCDW_CASE(2, 1)
+        BCDW_CASE(3, 16) BCDW_CASE(3, 8) BCDW_CASE(3, 4) BCDW_CASE(3, 2) BCDW_CASE(3, 1)
+        BCDW_CASE(4, 16) BCDW_CASE(4, 8) BCDW_CASE(4, 4) BCDW_CASE(4, 2) BCDW_CASE(4, 1)
 #undef BCDW_CASE
         return CDQ_EINVAL;
     }

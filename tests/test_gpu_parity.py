@@ -245,8 +245,10 @@ def bcd_moves_from_gpu(trace_j):
     (5, 4096, 6000, 3, 4096, 24, "rtn"), (6, 3072, 4000, 3, 128, 16, "rtn"),
     # d_in not a multiple of 4: the wide-layer kernel whatever the flags
     (7, 130, 400, 3, 26, 60, "random"), (5, 1002, 1500, 4, 1002, 40, "rtn"), (3, 6, 40, 2, 6, 10, "random"), (4, 2050, 2600, 2, 410, 30, "cd"),
-    # ... with 4 and with 2 columns per workgroup (what it picks for this many columns), last workgroup not full
-    (1501, 130, 400, 3, 130, 24, "rtn"), (701, 66, 300, 2, 22, 20, "random")])
+    # ... with 6 and with 3 columns per workgroup (what it picks for this many columns), last workgroup not full
+    (1501, 130, 400, 3, 130, 24, "rtn"), (701, 66, 300, 2, 22, 20, "random"),
+    # ... and with 10 and 16 columns per workgroup (rows of 16 margins)
+    (2400, 66, 300, 3, 66, 20, "random"), (4000, 130, 400, 2, 26, 12, "rtn")])
 @pytest.mark.parametrize("score_all,kernel", [(False, "auto"), (True, "auto"), (False, "single"), (True, "single"), (False, "wide"),
                                               (True, "wide")])
 def test_bcd_vs_oracle(cdq, oracle, d_out, d_in, n, bits, group, T, start, score_all, kernel):
