@@ -65,9 +65,9 @@ typedef struct {
 /* Optional controls for cdq_greedy_cd_ex; zero-initialise for defaults. */
 typedef struct {
     int32_t  waves_per_column;  /* 0 = choose; else 1,2,4,8,16 wavefronts cooperating on a column */
-    int32_t  elems_per_lane;    /* 0 = choose; else 4,8,16,32 coordinates held per lane; 36 (with 16
-                                   wavefronts) is the kernel that keeps the Hessian diagonal in LDS, the one
-                                   chosen for d_in above 32768 */
+    int32_t  elems_per_lane;    /* 0 = choose; else 4,8,16,32 coordinates held per lane; 24 or 36, and 32 for
+                                   16-byte aligned layers, with 16 wavefronts are the kernel that keeps the
+                                   Hessian diagonal in LDS, the one chosen for d_in above 16384 */
     int32_t  exact_scorer_only; /* 0 = nearest-level scorer with the two-level scorer as arbiter
                                    (default); 1 = two-level scorer on every iteration.  Both
                                    select the same moves; 1 exists for testing and timing. */

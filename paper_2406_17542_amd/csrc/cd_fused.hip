@@ -307,7 +307,7 @@ int extract_diag_launch(const float* H, int64_t d_in, float* hdiag, hipStream_t 
 // Launch shape: a team of `waves` wavefronts per column, `elems` coordinates per lane.
 // Measured on MI355X: 16 coordinates per lane is the best trade between the serial scoring chain
 // of a lane, registers (occupancy) and the cost of the cross-wavefront step, for every d_in from
-// 2048 to 16384; 32 per lane is only used beyond 16384.  With few columns the chain is split
+// 2048 to 16384; beyond that 24, 32 or 36 per lane on 16 wavefronts with the Hessian diagonal in LDS.  With few columns the chain is split
 // over more wavefronts so the 256 CUs x 4 SIMDs still have work in flight.
 int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int* elems, int* vec) {
     const int v = (d_in % 4 == 0 && group % 4 == 0) ? 4 : 1;
@@ -320,7 +320,7 @@ int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int*
     int e = (d_in <= 1024) ? 8 : 16;
     int w = team(e);
     if (w > 16) {
-        e = 32;
+        e = (v == 4 && d_in <= 64 * 16 * 24) ? 24 : 32;
         w = team(e);
         if (w > 16) {                          // beyond 32768: 36 per lane with the Hessian diagonal in LDS (16-byte chunks only)
             e = 36;
@@ -328,7 +328,7 @@ int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int*
             if (v != 4 || d_in > (int64_t)64 * w * e) return CDQ_EUNSUPPORTED;
         }
     }
-    while (e > 4 && e <= 32 && d_out * w < 2048 && team(e / 2) <= 8) {
+    while (e > 4 && e <= 32 && e != 24 && d_out * w < 2048 && team(e / 2) <= 8) {
         e /= 2;
         w = team(e);
     }
@@ -359,6 +359,14 @@ int cd_launch(const float* H, const float* hdiag, const float* G0, const float* 
         gshift = 0;
         while (((int64_t)1 << gshift) < group) ++gshift;
     }
+    // 16 wavefronts with more than 16 coordinates per lane do not fit the 128 registers a lane has there without spilling
+    // in the loop (measured at d_in = 24576: 19 us per update); the variant with the Hessian diagonal in LDS does, or nearly
+    if (waves == 16 && elems == 24 && vec == 4)
+        return launch_one<16, 24, 4, true>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, exact_only, stats, trace,
+                                           trace_cap, G_out, st);
+    if (waves == 16 && elems == 32 && vec == 4)
+        return launch_one<16, 32, 4, true>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, exact_only, stats, trace,
+                                           trace_cap, G_out, st);
     CDQ_CD_CASE(1, 4) CDQ_CD_CASE(1, 8) CDQ_CD_CASE(1, 16) CDQ_CD_CASE(1, 32)
     CDQ_CD_CASE(2, 4) CDQ_CD_CASE(2, 8) CDQ_CD_CASE(2, 16) CDQ_CD_CASE(2, 32)
     CDQ_CD_CASE(4, 4) CDQ_CD_CASE(4, 8) CDQ_CD_CASE(4, 16) CDQ_CD_CASE(4, 32)

@@ -134,12 +134,12 @@ int cdq_greedy_cd_ex(const float* H, const float* Wt, const float* scale, const 
     if (opts != nullptr && (opts->waves_per_column != 0 || opts->elems_per_lane != 0)) {
         const int w = opts->waves_per_column, e = opts->elems_per_lane;
         const bool w_ok = (w == 1 || w == 2 || w == 4 || w == 8 || w == 16);
-        const bool e_ok = (e == 4 || e == 8 || e == 16 || e == 32 || (e == 36 && w == 16));
+        const bool e_ok = (e == 4 || e == 8 || e == 16 || e == 32 || ((e == 24 || e == 36) && w == 16));
         if (!w_ok || !e_ok || (int64_t)64 * w * e < d_in) return CDQ_EINVAL;
         waves = w;
         elems = e;
     }
-    if (elems == 36 && vec != 4) return CDQ_EUNSUPPORTED;      // the kernel with the Hessian diagonal in LDS takes 16-byte chunks only
+    if ((elems == 36 || elems == 24) && vec != 4) return CDQ_EUNSUPPORTED;      // the kernel with the Hessian diagonal in LDS takes 16-byte chunks only
     if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < cd_workspace_bytes(d_out, d_in)) return CDQ_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     float* G0 = (float*)workspace;

@@ -256,12 +256,13 @@ def test_attn_proj_bcd_after_cd(cdq, oracle):
     assert np.array_equal(moves[cols], ref["moves"])
 
 
-def test_widest_layer_36864_columns_against_the_oracle(cdq, oracle):
-    """d_in = 36864 (the FFN2 width of the largest model in the paper's runtime table) is above what the
-    registers alone can hold: the fused loop keeps the Hessian diagonal in LDS there.  A few columns, the
-    default launch shape, RTN start; the oracle reruns them from the GPU's fp32 H: codes, move counts and the
-    per-column loss must match."""
-    d_in, d_out, n, bits, T = 36864, 6, 2048, 3, 96
+@pytest.mark.parametrize("d_in", [24576, 32768, 36864])
+def test_wide_layers_against_the_oracle(cdq, oracle, d_in):
+    """Above d_in = 16384 the fused loop keeps the Hessian diagonal in LDS (24, 32 or 36 coordinates per lane on 16
+    wavefronts); 24576 and 36864 are FFN2 widths of the paper's runtime table.  A few columns, the default launch
+    shape, RTN start; the oracle reruns them from the GPU's fp32 H: codes, move counts and the per-column loss
+    must match."""
+    d_out, n, bits, T = 6, 2048, 3, 96
     say(f"generating X [{n}x{d_in}] on the GPU and Wt [{d_out}x{d_in}]")
     g = torch.Generator(device="cuda")
     g.manual_seed(11)

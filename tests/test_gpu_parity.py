@@ -474,6 +474,8 @@ CD_CASES = [
     (6, 4096, 4500, 3, 4096, 300, True, 16, 36),     # the kernel with the Hessian diagonal in LDS (d_in above 32768)
     (7, 2048, 2600, 2, 128, 500, False, 16, 36),
     (3, 1032, 1500, 4, 8, 300, True, 16, 36),
+    (5, 3072, 3600, 3, 3072, 300, True, 16, 24),     # ... and its 24- and 32-per-lane forms (d_in above 16384)
+    (4, 1028, 1500, 2, 4, 400, False, 16, 24), (6, 2048, 2600, 4, 512, 300, True, 16, 32), (3, 1000, 1400, 3, 1000, 300, False, 16, 32),
     (5, 64, 256, 3, 64, 0, True, 0, 0),              # T = 0: nothing changes
     (5, 64, 256, 3, 64, 3, True, 0, 0),              # tiny budget: stops after 3 moves
     (1, 8, 64, 2, 8, 50, True, 0, 0),
