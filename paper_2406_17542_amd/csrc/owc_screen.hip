@@ -83,19 +83,22 @@ __global__ __launch_bounds__(256) void owc_residual_f16_kernel(const float* __re
 }
 
 // f^T R f over the blocks of R on and above the diagonal (R is symmetric: its row c is its column c, and the blocks below
-// the diagonal repeat the ones above): for column block cb the contraction runs over k < 128 (cb + 1), and what was
-// accumulated before the diagonal block is doubled -- exactly -- when it is reached.
-// partial[cb * (TB / 64) + h][j] = sum over the 64 columns c of part h of column block cb of C[j][c] F[j][c].
+// the diagonal repeat the ones above): for column block cb the contraction runs over k < TB (cb + 1); the diagonal block
+// enters at half weight and the sum is doubled at the end.
+// A wavefront owns BLK x BLK blocks of 32 x 32 of the tile; partial[cb * WPR + h][j] = sum over the 32 BLK columns c of
+// part h of column block cb of C[j][c] F[j][c], WPR = TB / (32 BLK) wavefronts side by side.
 // F [rows][d_in], rows a multiple of TB, d_in a multiple of TB.  grid (d_in / TB, rows / TB), longest column blocks first.
-template <int TB>
-__global__ __launch_bounds__((TB / 64) * (TB / 64) * 64) void owc_screen_kernel(const _Float16* __restrict__ E, const _Float16* __restrict__ R,
-                                                                               int64_t rows, int64_t d_in, float* __restrict__ partial) {
-    constexpr int WPR = TB / 64, SNT = WPR * WPR * 64, STILE = TB * SROW, CPT = TB * 8 / SNT;    // wavefronts per tile row, threads, chunks per thread
+template <int TB, int BLK>
+__global__ __launch_bounds__((TB / (32 * BLK)) * (TB / (32 * BLK)) * 64) void owc_screen_kernel(const _Float16* __restrict__ E,
+                                                                                               const _Float16* __restrict__ R, int64_t rows,
+                                                                                               int64_t d_in, float* __restrict__ partial) {
+    constexpr int WT = 32 * BLK;                                                                 // a wavefront's rows and columns of the tile
+    constexpr int WPR = TB / WT, SNT = WPR * WPR * 64, STILE = TB * SROW, CPT = TB * 8 / SNT;    // wavefronts per tile row, threads, chunks per thread
     extern __shared__ __attribute__((aligned(16))) char lds[];             // [2 stages][F tile | R tile]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int cb = (int)(gridDim.x - 1 - blockIdx.x);
     const int64_t c0 = (int64_t)cb * TB, j0 = (int64_t)blockIdx.y * TB;
-    const int wr = (wave / WPR) * 64, wc = (wave % WPR) * 64;                 // this wavefront's 64 x 64 of the tile
+    const int wr = (wave / WPR) * WT, wc = (wave % WPR) * WT;                 // this wavefront's part of the tile
     const int n_steps = (cb + 1) * (TB / SK), diag_step = cb * (TB / SK);     // steps before diag_step lie above the diagonal block
 
     // a thread moves CPT 16-byte chunks of each operand tile per step: chunk id = tid + SNT i -> row id / 8, chunk id % 8
@@ -109,67 +112,66 @@ __global__ __launch_bounds__((TB / 64) * (TB / 64) * 64) void owc_screen_kernel(
             rb[i] = *reinterpret_cast<const u4*>(R + (c0 + row) * d_in + k0 + kc * 8);
         }
     };
-    auto store = [&](int stage) {
+    // halve: the steps of the diagonal block enter with F / 2 (the epilogue doubles everything: 2 (above + diagonal / 2));
+    // scaling the accumulators in the middle of the loop instead costs a copy of all of them through the vector registers
+    auto store = [&](int stage, bool halve) {
         char* base = lds + stage * 2 * STILE;
 #pragma unroll
         for (int i = 0; i < CPT; ++i) {
             const int id = tid + SNT * i, row = id >> 3, kc = id & 7;
+            if (halve) {
+                h8 x = __builtin_bit_cast(h8, ra[i]);
+                x *= (_Float16)0.5f;
+                ra[i] = __builtin_bit_cast(u4, x);
+            }
             *reinterpret_cast<u4*>(base + row * SROW + kc * 16) = ra[i];
             *reinterpret_cast<u4*>(base + STILE + row * SROW + kc * 16) = rb[i];
         }
     };
 
-    f16v acc[2][2];
+    f16v acc[BLK][BLK];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < BLK; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < BLK; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
     load(0);
-    store(0);
+    store(0, diag_step == 0);
     __syncthreads();
     for (int step = 0; step < n_steps; ++step) {
         if (step + 1 < n_steps) load(step + 1);                    // in flight behind this step's matrix work
-        if (step == diag_step) {
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[a][b][v] *= 2.0f;
-        }
         const char* At = lds + (step & 1) * 2 * STILE;
         const char* Bt = At + STILE;
         // v_mfma_f32_32x32x16_f16: lane l feeds row (column) l % 32 with the 8 contraction indices 8 (l / 32) .. + 8
         const int frow = lane & 31, fk = (lane >> 5) * 16;         // byte offset of the lane's 8 values inside a 16-wide group
 #pragma unroll
         for (int kg = 0; kg < SK / 16; ++kg) {
-            h8 af[2], bf[2];
+            h8 af[BLK], bf[BLK];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) af[a] = *reinterpret_cast<const h8*>(At + (wr + 32 * a + frow) * SROW + kg * 32 + fk);
+            for (int a = 0; a < BLK; ++a) af[a] = *reinterpret_cast<const h8*>(At + (wr + 32 * a + frow) * SROW + kg * 32 + fk);
 #pragma unroll
-            for (int b = 0; b < 2; ++b) bf[b] = *reinterpret_cast<const h8*>(Bt + (wc + 32 * b + frow) * SROW + kg * 32 + fk);
+            for (int b = 0; b < BLK; ++b) bf[b] = *reinterpret_cast<const h8*>(Bt + (wc + 32 * b + frow) * SROW + kg * 32 + fk);
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < BLK; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[b], acc[a][b], 0, 0, 0);
+                for (int b = 0; b < BLK; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[b], acc[a][b], 0, 0, 0);
         }
-        if (step + 1 < n_steps) store((step + 1) & 1);             // the other stage: everybody left it before the last barrier
+        if (step + 1 < n_steps) store((step + 1) & 1, step + 1 >= diag_step);      // the other stage: everybody left it before the last barrier
         __syncthreads();
     }
 
     // 32 x 32 result block: lane l, element v -> row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
+    for (int a = 0; a < BLK; ++a) {
         float s[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int64_t j = j0 + wr + 32 * a + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
             float t = 0.0f;
 #pragma unroll
-            for (int b = 0; b < 2; ++b) t = fmaf(acc[a][b][v], (float)E[j * d_in + c0 + wc + 32 * b + (lane & 31)], t);
+            for (int b = 0; b < BLK; ++b) t = fmaf(acc[a][b][v], (float)E[j * d_in + c0 + wc + 32 * b + (lane & 31)], t);
             s[v] = t;
         }
 #pragma unroll
@@ -179,7 +181,7 @@ __global__ __launch_bounds__((TB / 64) * (TB / 64) * 64) void owc_screen_kernel(
             for (int o = 16; o; o >>= 1) t += __shfl_xor(t, o);
             if ((lane & 31) == 0) {
                 const int64_t j = j0 + wr + 32 * a + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                partial[((int64_t)cb * WPR + (wave % WPR)) * rows + j] = t;
+                partial[((int64_t)cb * WPR + (wave % WPR)) * rows + j] = 2.0f * t;
             }
         }
     }
@@ -253,6 +255,7 @@ int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_
     const int64_t rows = (d_out + 2 * SB - 1) / (2 * SB) * (2 * SB);
     const int n_part = (int)(2 * d_in / SB);
     const bool big = d_in % (2 * SB) == 0;                         // the 256 x 256 tile
+    const int n_sum = n_part;                                      // partial sums per row that the kernel writes
     char* p = (char*)ws;
     _Float16* R = (_Float16*)p;        p += cdq_align_up((size_t)d_in * d_in * 2, 256);
     _Float16* F = (_Float16*)p;        p += cdq_align_up((size_t)rows * d_in * 2, 256);
@@ -279,9 +282,9 @@ int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_
         CDQ_LAUNCH_CHECK();
     }
     constexpr int lds_small = 2 * 2 * SB * SROW, lds_big = 2 * 2 * 2 * SB * SROW;
-    static const hipError_t lds_rc_small = hipFuncSetAttribute(reinterpret_cast<const void*>(owc_screen_kernel<SB>),
+    static const hipError_t lds_rc_small = hipFuncSetAttribute(reinterpret_cast<const void*>(owc_screen_kernel<SB, 2>),
                                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_small);
-    static const hipError_t lds_rc_big = hipFuncSetAttribute(reinterpret_cast<const void*>(owc_screen_kernel<2 * SB>),
+    static const hipError_t lds_rc_big = hipFuncSetAttribute(reinterpret_cast<const void*>(owc_screen_kernel<2 * SB, 2>),
                                                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_big);
     if (lds_rc_small != hipSuccess || lds_rc_big != hipSuccess) return CDQ_EHIP;
     for (int k = 1; k <= n_gamma; ++k) {
@@ -290,14 +293,14 @@ int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_
                            row_scale2);
         CDQ_LAUNCH_CHECK();
         if (big)
-            hipLaunchKernelGGL(owc_screen_kernel<2 * SB>, dim3((unsigned)(d_in / (2 * SB)), (unsigned)(rows / (2 * SB))), dim3(1024), lds_big, st,
+            hipLaunchKernelGGL((owc_screen_kernel<2 * SB, 2>), dim3((unsigned)(d_in / (2 * SB)), (unsigned)(rows / (2 * SB))), dim3(1024), lds_big, st,
                                (const _Float16*)F, (const _Float16*)R, rows, d_in, partial);
         else
-            hipLaunchKernelGGL(owc_screen_kernel<SB>, dim3((unsigned)(d_in / SB), (unsigned)(rows / SB)), dim3(256), lds_small, st,
+            hipLaunchKernelGGL((owc_screen_kernel<SB, 2>), dim3((unsigned)(d_in / SB), (unsigned)(rows / SB)), dim3(256), lds_small, st,
                                (const _Float16*)F, (const _Float16*)R, rows, d_in, partial);
         CDQ_LAUNCH_CHECK();
         hipLaunchKernelGGL(owc_screen_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, (const float*)partial, rows,
-                           d_out, n_part, (const float*)row_scale2, screened + (int64_t)(k - 1) * d_out);
+                           d_out, n_sum, (const float*)row_scale2, screened + (int64_t)(k - 1) * d_out);
         CDQ_LAUNCH_CHECK();
     }
     hipLaunchKernelGGL(owc_rank_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, (const float*)screened, d_out, n_gamma,
