@@ -1067,8 +1067,9 @@ int bcd_launch(const float* H, const float* Wt, const float* scale, const float*
             break;
         }
     // the wide-layer kernel where nothing else applies, and where it shares a pass over the pairs among more columns than
-    // the kernels with the columns' state in LDS would (measured, d_in = 4608: 2 columns 363 ms, 8 columns here 205 ms)
-    const bool use_wide = !single_ok || (wide && wide_ok) || (!single && cw < 4 && cpw >= 3);
+    // the kernels with the columns' state in LDS would (measured: d_in = 4608, 2 columns there 363 ms, 8 here 205 ms;
+    // d_in = 3072, 4 there 106 ms, 16 here 64 ms; d_in = 2048, 8 there 24.1 ms, 16 here 26.6 ms)
+    const bool use_wide = !single_ok || (wide && wide_ok) || (!single && cw < 8 && cpw >= 3);
     if (use_wide) {
         uint32_t* t_ik = (uint32_t*)table;
         uint16_t* t_thr = (uint16_t*)(table + 4 * (size_t)n_items);
