@@ -178,7 +178,7 @@ def main():
         cdq.hessian(Xd, H=H, workspace=ws_h)
         rec(1)
         if init == "owc":
-            scale, zero, Q, _, _ = cdq.init_owc(H, Wd, cfg.bits, cfg.group, 50, workspace=ws_owc)
+            scale, zero, Q, _, _ = cdq.init_owc(H, Wd, cfg.bits, cfg.group, 50, workspace=ws_owc, want_loss=False)
         elif init == "owc_cd":
             o = cdq.init_owc_cd(H, Wd, cfg.bits, cfg.group, 50, workspace=ws_owc)
             scale, zero, Q = o["scale"], o["zero"], o["Q"]

@@ -122,7 +122,8 @@ int cdq_init_rtn(const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t
  *   larger gamma.  Only the upper end is clipped, as Eq. (2) is written.
  * Needs group == d_in (one clipping strength per column), else CDQ_EUNSUPPORTED.
  *   scale, zero [d_out] out; Q [d_out][d_in] out; gamma_out NULL or [d_out] fp32;
- *   loss_out NULL or [d_out] fp64 (loss of the chosen grid).
+ *   loss_out NULL or [d_out] fp64 (loss of the chosen grid; with NULL, columns whose choice is
+ *   clear from the fp16 look described below are not evaluated in fp64 at all).
  * Cost.  When d_in is a multiple of 128 (at least 256) and 4 <= n_gamma <= 255, every grid point is
  * first evaluated in fp16 on the matrix cores in the normalised form s^2 f^T R f (R = H scaled to
  * unit diagonal, f = e sqrt(diag H) / s); its relative error stayed below 3e-4 on the test layers,

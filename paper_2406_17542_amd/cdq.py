@@ -139,17 +139,18 @@ def init_rtn(Wt: torch.Tensor, bits: int, group: int):
     return scale, zero, Q
 
 
-def init_owc(H, Wt, bits: int, group: int, n_gamma: int = 50, workspace: torch.Tensor | None = None):
-    """OWC grid search (per-channel).  Returns (scale, zero, Q, gamma, loss_per_col)."""
+def init_owc(H, Wt, bits: int, group: int, n_gamma: int = 50, workspace: torch.Tensor | None = None, want_loss: bool = True):
+    """OWC grid search (per-channel).  Returns (scale, zero, Q, gamma, loss_per_col); loss_per_col is None when
+    want_loss is False (the library then skips the fp64 evaluation of columns whose choice is already clear)."""
     d_out, d_in = Wt.shape
     scale = torch.empty((d_out, 1), dtype=torch.float32, device=Wt.device)
     zero = torch.empty((d_out, 1), dtype=torch.float32, device=Wt.device)
     Q = torch.empty((d_out, d_in), dtype=torch.uint8, device=Wt.device)
     gamma = torch.empty(d_out, dtype=torch.float32, device=Wt.device)
-    per = torch.empty(d_out, dtype=torch.float64, device=Wt.device)
+    per = torch.empty(d_out, dtype=torch.float64, device=Wt.device) if want_loss else None
     ws = _workspace(OP_INIT_OWC, 0, d_out, d_in, workspace)
     _check(lib().cdq_init_owc(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), d_out, d_in, bits, group, n_gamma,
-                              scale.data_ptr(), zero.data_ptr(), Q.data_ptr(), gamma.data_ptr(), per.data_ptr(),
+                              scale.data_ptr(), zero.data_ptr(), Q.data_ptr(), gamma.data_ptr(), per.data_ptr() if want_loss else None,
                               ws.data_ptr(), ws.numel(), _stream()), "cdq_init_owc")
     return scale, zero, Q, gamma, per
 

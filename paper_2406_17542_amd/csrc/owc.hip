@@ -107,15 +107,18 @@ __global__ __launch_bounds__(256) void owc_fill_f32_kernel(float* __restrict__ p
     if (i < n) p[i] = v;
 }
 
-// ---- the candidates beyond a column's first, gathered into dense rows for one pass of the loss kernel
-// extras[j]: how many candidates column j has beyond its first (cand [n_gamma][d_out], a column's candidates are contiguous in r)
-__global__ __launch_bounds__(256) void owc_count_extras_kernel(const uint8_t* __restrict__ cand, int64_t d_out, int n_gamma,
+// ---- candidates gathered into dense rows for one pass of the loss kernel.  first = 1: every column's best-screened
+// candidate is evaluated with all columns in a pass of its own (the caller wants each column's loss) and the rows take the
+// others; first = 0: a column with a single candidate needs no evaluation at all, and the rows take all candidates of the
+// columns that have several.
+// extras[j]: how many rows column j asks for (cand [n_gamma][d_out], a column's candidates are contiguous in r)
+__global__ __launch_bounds__(256) void owc_count_extras_kernel(const uint8_t* __restrict__ cand, int64_t d_out, int n_gamma, int first,
                                                                int32_t* __restrict__ extras) {
     const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= d_out) return;
-    int e = 0;
-    for (int r = 1; r < n_gamma && cand[(int64_t)r * d_out + j] != 0; ++r) ++e;
-    extras[j] = e;
+    int n = 0;
+    for (int r = 0; r < n_gamma && cand[(int64_t)r * d_out + j] != 0; ++r) ++n;
+    extras[j] = first == 1 ? (n > 0 ? n - 1 : 0) : (n >= 2 ? n : 0);
 }
 
 // base[j] = extras[0] + ... + extras[j-1]; one workgroup, the columns in chunks of 1024; total is cleared
@@ -143,31 +146,39 @@ __global__ __launch_bounds__(1024) void owc_scan_extras_kernel(const int32_t* __
     }
 }
 
-// A column whose extra candidates fit below cap gets rows base[j] .. base[j] + extras[j] - 1: their column and grid index
-// are recorded, they are struck from cand (the rank passes will not see them), total becomes the number of rows in use.
-__global__ __launch_bounds__(256) void owc_assign_rows_kernel(uint8_t* __restrict__ cand, int64_t d_out, const int32_t* __restrict__ extras,
-                                                              const int32_t* __restrict__ base, int32_t cap, int32_t* __restrict__ row_col,
-                                                              uint8_t* __restrict__ row_k, int32_t* __restrict__ total) {
+// A column whose rows fit below cap gets rows base[j] .. base[j] + extras[j] - 1 for its candidates first, first + 1, ...:
+// their column and grid index are recorded, they are struck from cand (the rank passes will not see them), total becomes
+// the number of rows in use.  With first = 0 a column with one candidate takes that grid point without evaluation.
+__global__ __launch_bounds__(256) void owc_assign_rows_kernel(uint8_t* __restrict__ cand, int64_t d_out, int n_gamma, int first,
+                                                              const int32_t* __restrict__ extras, const int32_t* __restrict__ base,
+                                                              int32_t cap, int32_t* __restrict__ row_col, uint8_t* __restrict__ row_k,
+                                                              int32_t* __restrict__ total, float* __restrict__ best_gamma) {
     const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= d_out) return;
     const int32_t e = extras[j], b = base[j];
+    if (first == 0 && e == 0 && cand[j] != 0 && (n_gamma < 2 || cand[d_out + j] == 0)) {
+        best_gamma[j] = (float)cand[j] / (float)n_gamma;
+        cand[j] = 0;
+        return;
+    }
     if (e == 0 || (int64_t)b + e > cap) return;
-    for (int r = 1; r <= e; ++r) {
-        row_col[b + r - 1] = (int32_t)j;
-        row_k[b + r - 1] = cand[(int64_t)r * d_out + j];
-        cand[(int64_t)r * d_out + j] = 0;
+    for (int r = 0; r < e; ++r) {
+        row_col[b + r] = (int32_t)j;
+        row_k[b + r] = cand[(int64_t)(first + r) * d_out + j];
+        cand[(int64_t)(first + r) * d_out + j] = 0;
     }
     atomicMax(total, b + e);
 }
 
-// which blocks of the loss kernel have work: rank r >= 1 of the columns (what the rows above did not take), and the rows
-__global__ __launch_bounds__(256) void owc_flags_kernel(const uint8_t* __restrict__ cand, int64_t d_out, int n_gamma, int block_rows,
+// which blocks of the loss kernel have work: rank r >= first of the columns (what the rows above did not take; the flags of
+// those ranks were cleared by the caller), and the rows
+__global__ __launch_bounds__(256) void owc_flags_kernel(const uint8_t* __restrict__ cand, int64_t d_out, int n_gamma, int first, int block_rows,
                                                         int64_t n_blocks, const int32_t* __restrict__ total, uint8_t* __restrict__ active,
                                                         uint8_t* __restrict__ rows_active) {
-    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;     // over (r, j), r >= 1
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;     // over (r, j), r >= first
     if (x < n_blocks) rows_active[x] = (x * block_rows < *total) ? 1 : 0;
-    if (x >= (int64_t)(n_gamma - 1) * d_out) return;
-    const int64_t r = 1 + x / d_out, j = x % d_out;
+    if (x >= (int64_t)(n_gamma - first) * d_out) return;
+    const int64_t r = first + x / d_out, j = x % d_out;
     if (cand[r * d_out + j] != 0) active[r * n_blocks + j / block_rows] = 1;
 }
 
@@ -264,7 +275,8 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
         if (rc != CDQ_OK) return rc;
         hipLaunchKernelGGL(owc_fill_f32_kernel, col_blocks, t256, 0, st, best_gamma, d_out, 0.0f);      // 0: nothing evaluated yet
         CDQ_LAUNCH_CHECK();
-        // the candidates beyond each column's first, gathered into at most d_out dense rows
+        // candidates gathered into at most d_out dense rows; every column's first one too when nobody asks for the losses
+        const int first = loss_out != nullptr ? 1 : 0;
         char* gp = (char*)screen_ws + owc_screen_workspace_bytes(d_out, d_in, 255, n_blocks);
         float* Wc = (float*)gp;             gp += cdq_align_up((size_t)d_out * d_in * sizeof(float), 256);
         double* row_loss = (double*)gp;     gp += dsz;
@@ -278,26 +290,27 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
         const int32_t cap = (int32_t)d_out;
         hipLaunchKernelGGL(owc_fill_f32_kernel, col_blocks, t256, 0, st, zeros, d_out, 0.0f);
         CDQ_LAUNCH_CHECK();
-        hipLaunchKernelGGL(owc_count_extras_kernel, col_blocks, t256, 0, st, cand, d_out, n_gamma, extras);
+        hipLaunchKernelGGL(owc_count_extras_kernel, col_blocks, t256, 0, st, cand, d_out, n_gamma, first, extras);
         CDQ_LAUNCH_CHECK();
         hipLaunchKernelGGL(owc_scan_extras_kernel, dim3(1), dim3(1024), 0, st, (const int32_t*)extras, d_out, base, total);
         CDQ_LAUNCH_CHECK();
-        hipLaunchKernelGGL(owc_assign_rows_kernel, col_blocks, t256, 0, st, cand, d_out, (const int32_t*)extras, (const int32_t*)base, cap,
-                           row_col, row_k, total);
+        hipLaunchKernelGGL(owc_assign_rows_kernel, col_blocks, t256, 0, st, cand, d_out, n_gamma, first, (const int32_t*)extras,
+                           (const int32_t*)base, cap, row_col, row_k, total, best_gamma);
         CDQ_LAUNCH_CHECK();
         {
-            const int64_t flags = (int64_t)(n_gamma - 1) * n_blocks;                 // ranks >= 1 start with no block active
-            hipLaunchKernelGGL(owc_fill_u8_kernel, dim3((unsigned)((flags + 255) / 256)), t256, 0, st, active + n_blocks, flags, (uint8_t)0);
+            const int64_t flags = (int64_t)(n_gamma - first) * n_blocks;             // ranks >= first start with no block active
+            hipLaunchKernelGGL(owc_fill_u8_kernel, dim3((unsigned)((flags + 255) / 256)), t256, 0, st, active + first * n_blocks, flags,
+                               (uint8_t)0);
             CDQ_LAUNCH_CHECK();
         }
         {
-            const int64_t items = (int64_t)(n_gamma - 1) * d_out > n_blocks ? (int64_t)(n_gamma - 1) * d_out : n_blocks;
+            const int64_t items = (int64_t)(n_gamma - first) * d_out > n_blocks ? (int64_t)(n_gamma - first) * d_out : n_blocks;
             hipLaunchKernelGGL(owc_flags_kernel, dim3((unsigned)((items + 255) / 256)), t256, 0, st, (const uint8_t*)cand, d_out, n_gamma,
-                               block_rows, n_blocks, (const int32_t*)total, active, rows_active);
+                               first, block_rows, n_blocks, (const int32_t*)total, active, rows_active);
             CDQ_LAUNCH_CHECK();
         }
         for (int r = 0; r < n_gamma; ++r) {
-            if (r == 1) {                  // after every column's first candidate: the gathered rows, one pass
+            if (r == 0) {                  // the gathered rows, one pass (the order of the passes does not matter to the result)
                 hipLaunchKernelGGL(owc_row_residual_kernel, cols, t256, 0, st, Wt, d_in, bits, (const float*)lo, (const float*)hi, n_gamma,
                                    (const int32_t*)row_col, (const uint8_t*)row_k, (const int32_t*)total, Wc);
                 CDQ_LAUNCH_CHECK();

@@ -84,7 +84,7 @@ def quantize_layer(chunks: Iterable[torch.Tensor], Wt: torch.Tensor, bits: int, 
     if init == "rtn":
         scale, zero, Q = timed("init", lambda: cdq.init_rtn(Wt, bits, group))
     elif init == "owc":
-        scale, zero, Q, _, _ = timed("init", lambda: cdq.init_owc(H, Wt, bits, group, n_gamma))
+        scale, zero, Q, _, _ = timed("init", lambda: cdq.init_owc(H, Wt, bits, group, n_gamma, want_loss=False))
     elif init == "owc_cd":
         o = timed("init", lambda: cdq.init_owc_cd(H, Wt, bits, group, n_gamma))
         scale, zero, Q = o["scale"], o["zero"], o["Q"]

@@ -145,6 +145,10 @@ def test_init_owc(cdq, oracle, d_out, d_in, n, bits, n_gamma):
     a, b, q, gam, all_loss = oracle.init_owc(H32, Wt, bits, d_in, n_gamma)
     s, z, Q, g, per = cdq.init_owc(dev(H32), dev(Wt), bits, d_in, n_gamma)
     s, z, Q, g, per = (t.cpu().numpy() for t in (s, z, Q, g, per))
+    # without the per-column losses the library evaluates fewer grid points in fp64; the choice must not change
+    s2, z2, Q2, g2, none = cdq.init_owc(dev(H32), dev(Wt), bits, d_in, n_gamma, want_loss=False)
+    assert none is None
+    assert np.array_equal(g2.cpu().numpy(), g) and np.array_equal(s2.cpu().numpy(), s) and np.array_equal(Q2.cpu().numpy(), Q)
     assert np.array_equal(z, b)
     same = g == gam
     # a different gamma is acceptable only when the two grid points tie within fp32 residual rounding
