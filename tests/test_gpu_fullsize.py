@@ -146,6 +146,10 @@ def test_large_owc_init_column_subset(cdq, oracle):
     Wd = torch.from_numpy(Wt).cuda()
     say("OWC grid search on the GPU")
     scale, zero, Q, gamma, per = cdq.init_owc(Hd, Wd, cfg.bits, cfg.group, 50)
+    # bench.py does not ask for the per-column losses, which takes another path through the search: same choice
+    s_b, z_b, Q_b, gamma_b, _ = cdq.init_owc(Hd, Wd, cfg.bits, cfg.group, 50, want_loss=False)
+    assert torch.equal(gamma_b, gamma) and torch.equal(s_b, scale) and torch.equal(Q_b, Q)
+    del s_b, z_b, Q_b, gamma_b
     s_rtn, z_rtn, Q_rtn = cdq.init_rtn(Wd, cfg.bits, cfg.group)
     l_rtn = cdq.loss(Hd, Wd, s_rtn, z_rtn, Q_rtn, cfg.group)[0]
     assert torch.all(per <= l_rtn * (1 + 1e-9)), "gamma = 1 is on the grid, so OWC can not be worse than MinMax"
