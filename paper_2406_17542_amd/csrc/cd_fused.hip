@@ -41,9 +41,10 @@ __device__ __forceinline__ float curvature_inv(float h, float a) {
 // the curvature reciprocal is recomputed per use -- the same operations on the same values, hence the same numbers.
 // It frees 2E registers per lane and is what lets a team of 16 wavefronts cover d_in up to 36864 (the diagonal of a
 // longer column would not fit the 160 KiB of LDS).
-template <int W, int E, int VEC, bool LDSH>
+// FF: recognise a column that moves one coordinate up and down for the rest of its budget and jump to the end (see the loop).
+template <int W, int E, int VEC, bool LDSH, bool FF>
 __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
-    const float* __restrict__ H, const float* __restrict__ hdiag, const float* __restrict__ G0,
+    const float* __restrict__ H, const float* __restrict__ hdiag, float* G0,
     const float* __restrict__ scale, uint8_t* __restrict__ Q, int d_in, int bits, int group, int group_shift,
     int n_grp, int T, int exact_only, cdq_col_stats* __restrict__ stats, int32_t* __restrict__ trace,
     int64_t trace_cap, float* __restrict__ G_out) {
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
     const int64_t j = blockIdx.x;
     const float* scale_j = scale + j * n_grp;
     uint8_t* Qj = Q + j * (int64_t)d_in;
-    const float* G0j = G0 + j * (int64_t)d_in;
+    const float* G0j = G0 + j * (int64_t)d_in;    // the start gradient; once it is loaded, the row serves as a snapshot of 2g (below)
     const float top = (float)((1 << bits) - 1);
 
     float g2[E], hd[LDSH ? 1 : E], cinv[LDSH ? 1 : E], a_c[NCH];
@@ -185,6 +186,30 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
         return team_min(bs, bu, be, 0u);
     };
 
+    // A coordinate whose two neighbouring levels have the same loss to within the rounding of 2g can be moved up and down
+    // for ever: both moves compute to a (tiny) negative score.  The paper's loop, and the oracle, go on to the end of the
+    // budget.  So does this one, but not step by step: when a move undoes the previous one, 2g is written to the column's
+    // row of the start gradient; if two moves later the codes are back (the two moves again undid each other) and 2g has
+    // exactly the same bits, the state is that of two iterations ago, the loop is periodic from here on, and only the
+    // parity of what is left of the budget matters.  Not done when the moves are traced, and only built into the kernels for
+    // 16 wavefronts and up to 24 coordinates per lane (FF): there a column that spends its whole budget holds a CU for
+    // 0.1 to 0.4 s after everything else has finished, while the bookkeeping costs 2 to 6 % of the loop; in the smaller
+    // shapes it costs 5 % and the budget is short, and at 32 and 36 coordinates per lane it adds register spills.
+    auto team_all = [&](bool ok) -> bool {
+        uint64_t v = (__ballot(ok) == ~0ull) ? 1u : 0u;
+        if (W > 1) {
+            const int p = n_reduce & 1;
+            ++n_reduce;
+            if (lane == 0) slots[p][wave] = v;
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < W; ++w) v = umin64(v, (uint64_t)slots[p][w]);
+        }
+        return v != 0;
+    };
+    uint32_t prev_move = 0xffffffffu;         // coordinate << 6 | (level change + 32) of the previous move
+    int snap_t = -1;                          // iteration whose 2g the snapshot holds
+
     for (int t = 0; t < T; ++t) {
         // ---- 1 + 2. score and arg-min
         uint64_t key = exact_only ? score_exact() : score_fast();
@@ -250,6 +275,42 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
         if (trace != nullptr && tid == 0 && moves < trace_cap) trace[j * trace_cap + moves] = (int32_t)(klo >> 1);
         last_hi = khi;
         ++moves;
+        // ---- the same coordinate moved back: snapshot, or compare with the snapshot of two iterations ago (uniform branches).
+        // Two moves that undo each other restore the codes whatever came before, so the comparison of 2g is the whole test.
+        const uint32_t this_move = FF ? (klo >> 1) : 0u;
+        if (FF && trace == nullptr && (this_move >> 6) == (prev_move >> 6) && (this_move & 63u) + (prev_move & 63u) == 64u) {
+            float* snap = G0 + j * (int64_t)d_in;                        // the start gradient is not needed any more
+            bool take = !(snap_t >= 0 && t == snap_t + 1);               // keep the snapshot for the comparison one move on
+            if (snap_t >= 0 && t == snap_t + 2) {
+                bool same = true;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    const int base = c * STRIDE + tid * VEC;
+                    if (base < d_in) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) same &= __float_as_uint(snap[base + v]) == __float_as_uint(g2[c * VEC + v]);
+                    }
+                }
+                if (team_all(same)) {                                    // periodic from here: only the parity of the rest matters
+                    const int left = T - (t + 1);
+                    moves += left & ~1;
+                    T = t + 1 + (left & 1);
+                    take = false;
+                }
+            }
+            if (take) {
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    const int base = c * STRIDE + tid * VEC;
+                    if (base < d_in) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) snap[base + v] = g2[c * VEC + v];
+                    }
+                }
+                snap_t = t;
+            }
+        }
+        if (FF) prev_move = this_move;
     }
 
     // ---- write back
@@ -281,16 +342,17 @@ __global__ __launch_bounds__(256) void extract_diag_kernel(const float* __restri
 }
 
 template <int W, int E, int VEC, bool LDSH = false>
-int launch_one(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q, int64_t d_out,
+int launch_one(const float* H, const float* hdiag, float* G0, const float* scale, uint8_t* Q, int64_t d_out,
                int d_in, int bits, int group, int group_shift, int n_grp, int T, int exact_only, cdq_col_stats* stats,
                int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
+    constexpr bool FF = (W == 16 && E <= 24 && VEC == 4);
     const size_t lds = LDSH ? sizeof(float) * 64 * W * E : 0;
     if (LDSH) {
-        static const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(cd_fused_kernel<W, E, VEC, LDSH>),
+        static const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(cd_fused_kernel<W, E, VEC, LDSH, FF>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (rc != hipSuccess) return CDQ_EHIP;
     }
-    hipLaunchKernelGGL((cd_fused_kernel<W, E, VEC, LDSH>), dim3((unsigned)d_out), dim3(64 * W), lds, st, H, hdiag, G0, scale, Q, d_in,
+    hipLaunchKernelGGL((cd_fused_kernel<W, E, VEC, LDSH, FF>), dim3((unsigned)d_out), dim3(64 * W), lds, st, H, hdiag, G0, scale, Q, d_in,
                        bits, group, group_shift, n_grp, T, exact_only, stats, trace, trace_cap, G_out);
     CDQ_LAUNCH_CHECK();
     return CDQ_OK;
@@ -346,7 +408,7 @@ int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int*
                                                 stats, trace, trace_cap, G_out, st);                               \
     }
 
-int cd_launch(const float* H, const float* hdiag, const float* G0, const float* scale, uint8_t* Q, int64_t d_out,
+int cd_launch(const float* H, const float* hdiag, float* G0, const float* scale, uint8_t* Q, int64_t d_out,
               int64_t d_in, int bits, int64_t group, int64_t T, cdq_col_stats* stats, int waves, int elems, int vec,
               int exact_only, int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
     if (d_out == 0) return CDQ_OK;

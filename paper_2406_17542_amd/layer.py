@@ -127,7 +127,7 @@ def main():
     ap.add_argument("--model", default="gemma2_9b", choices=sorted(MODEL_SHAPES))
     ap.add_argument("--bits", type=int, default=3)
     ap.add_argument("--tokens", type=int, default=1280 * 2048, help="calibration tokens (Section 4: 1280 sequences of 2048)")
-    ap.add_argument("--chunk", type=int, default=16384)
+    ap.add_argument("--chunk", type=int, default=131072, help="tokens per cdq_hessian call (each call ends with a pass over H: larger chunks, fewer passes)")
     ap.add_argument("--lambda-rel", type=float, default=0.01)
     ap.add_argument("--t-div", type=int, default=1, help="run CD for d_in / t_div iterations (appendix: d_in/8 suffices)")
     ap.add_argument("--bcd", action="store_true", help="also run BCD (k=2, d_in iterations) from CD's result where it is supported")

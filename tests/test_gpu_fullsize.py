@@ -326,3 +326,50 @@ def test_wide_layer_bcd_against_the_oracle(cdq, oracle, d_in, d_out, n_cd, T):
     assert np.array_equal(moves[cols], ref["moves"])
     assert np.array_equal(Q.cpu().numpy()[cols], ref["Q"])
     assert np.array_equal(out["G"].cpu().numpy()[cols], ref["G"])
+
+
+def test_a_column_that_moves_one_coordinate_up_and_down_to_the_end_of_the_budget(cdq, oracle):
+    """Where two neighbouring levels of a coordinate have the same loss to within the rounding of the gradient, both moves
+    compute to a tiny negative score and the loop of Algorithm 1, run in fp32, alternates between them until the budget
+    T is spent (the oracle does the same).  The fused kernel recognises the exact period-2 state and jumps to the end;
+    codes, move count and last score must still be those of the oracle, which takes every step.  The layer is the one
+    where this was first seen: the Gemma-1 7B FFN2 shape of the layer driver with 65536-token chunks, column 2111."""
+    from paper_2406_17542_amd.layer import synthetic_chunks, HessianAccumulator
+    d_in, d_out, bits = 24576, 3072, 3
+    say("streaming the Hessian of 2 621 440 synthetic tokens")
+    acc = HessianAccumulator(d_in, "cuda")
+    it = iter(synthetic_chunks(1280 * 2048, d_in, 65536, seed=3))
+    cur = next(it)
+    while cur is not None:
+        nxt = next(it, None)
+        acc.add(cur, last=nxt is None, lambda_rel=0.01)
+        cur = nxt
+    Hd = acc.H
+    Wt = inputs.make_wt(d_out, d_in, seed=1)
+    Wd = torch.from_numpy(Wt).cuda()
+    scale, zero, Q, _, _ = cdq.init_owc(Hd, Wd, bits, d_in, 50, want_loss=False)
+    q0 = Q.cpu().numpy().copy()
+    say("greedy CD on the GPU, T = d_in")
+    t0 = time.perf_counter()
+    out = cdq.greedy_cd(Hd, Wd, scale, zero, Q, bits, d_in, d_in)
+    torch.cuda.synchronize()
+    say(f"  {time.perf_counter() - t0:.3f} s")
+    st = out["stats"].cpu().numpy()
+    spent = np.where(st[:, 0] == d_in)[0]
+    say(f"  columns that used the whole budget: {spent.tolist()}")
+    assert len(spent) >= 1, "the case should contain a column that alternates to the end of the budget"
+    cols = np.unique(np.concatenate([spent[:2], [0, 1500, d_out - 1]]))
+    say("copying H to the host; the oracle takes every step of these columns")
+    H32 = Hd.cpu().numpy()
+    a, b = scale.cpu().numpy()[cols], zero.cpu().numpy()[cols]
+    ref = oracle.greedy_cd(H32, np.ascontiguousarray(Wt[cols]), a, b, q0[cols], bits, d_in, d_in)
+    assert np.array_equal(st[cols, 0], ref["moves"])
+    assert np.array_equal(Q.cpu().numpy()[cols], ref["Q"])
+    # an odd budget ends in the other state of the pair
+    Q2 = torch.from_numpy(q0[spent[:1]]).cuda()
+    j = spent[:1]
+    out2 = cdq.greedy_cd(Hd, Wd[j].contiguous(), scale[j].contiguous(), zero[j].contiguous(), Q2, bits, d_in, d_in - 1)
+    ref2 = oracle.greedy_cd(H32, np.ascontiguousarray(Wt[j]), scale.cpu().numpy()[j], zero.cpu().numpy()[j], q0[j], bits, d_in, d_in - 1)
+    assert np.array_equal(out2["stats"].cpu().numpy()[:, 0], ref2["moves"]) and ref2["moves"][0] == d_in - 1
+    assert np.array_equal(Q2.cpu().numpy(), ref2["Q"])
+    assert not np.array_equal(ref2["Q"], ref["Q"][np.searchsorted(cols, j)])
