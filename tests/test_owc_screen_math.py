@@ -1,0 +1,76 @@
+"""The algebra and the precision behind the two-stage OWC grid search (Section 3.1, "Initializing a, b, q": Eq. (2)
+searched for the smallest loss of Eq. (1)), checked on the CPU in plain numpy, independently of the library.
+
+The library looks at every clipping strength in fp16 first, in the normalised form s^2 f^T R f, and evaluates in fp64 only
+the grid points whose screened loss is within a margin of the column's smallest.  That is the exhaustive search as long as
+the fp16 evaluation is closer to the truth than the margin: these tests pin the identity and the size of the error on
+layers with heavy-tailed weights and channel scales."""
+import numpy as np
+
+MARGIN = 3e-3          # the library's margin (relative)
+
+
+def layer(seed, d_in, d_out, n, tail):
+    r = np.random.default_rng(seed)
+    X = r.standard_normal((n, d_in)) * np.exp(0.5 * r.standard_normal(d_in)) + 0.5 * r.standard_normal((n, 1))
+    W = r.standard_normal((d_out, d_in)) / np.sqrt(d_in)
+    if tail:
+        W *= np.exp(0.7 * r.standard_normal(W.shape))
+        W[:, r.integers(0, d_in, 3)] *= 5.0
+    return (X.T @ X).astype(np.float32).astype(np.float64), W.astype(np.float32)
+
+
+def residuals(W, bits, n_gamma):
+    """e(gamma) of Eq. (2) for every grid point, in fp32 as the kernels form it: [n_gamma][d_out][d_in]."""
+    lo, hi = W.min(axis=1, keepdims=True), W.max(axis=1, keepdims=True)
+    top = np.float32((1 << bits) - 1)
+    out = []
+    for k in range(1, n_gamma + 1):
+        a = (np.float32(k) / np.float32(n_gamma)) * (hi - lo) / top
+        q = np.clip(np.rint((W - lo) / a), 0, top).astype(np.float32)
+        out.append((a * q + lo - W).astype(np.float32))
+    return np.stack(out)
+
+
+def test_normalised_form_and_half_weight_diagonal_are_identities():
+    H, W = layer(1, 96, 5, 300, tail=True)
+    E = residuals(W, 3, 10)[4].astype(np.float64)
+    exact = np.einsum("ji,ik,jk->j", E, H, E)
+    d = np.sqrt(np.diag(H))
+    R = H / np.outer(d, d)
+    F = E * d
+    s = np.abs(F).max(axis=1, keepdims=True)
+    F = F / s
+    np.testing.assert_allclose(s[:, 0] ** 2 * np.einsum("ji,ik,jk->j", F, R, F), exact, rtol=1e-12)
+    # upper blocks only: blocks above the diagonal at full weight, the diagonal blocks at half weight, all doubled
+    B = 32
+    acc = np.zeros(len(F))
+    for cb in range(96 // B):
+        c = slice(cb * B, (cb + 1) * B)
+        above = F[:, :cb * B] @ R[:cb * B, c]
+        diag = (0.5 * F[:, c]) @ R[c, c]
+        acc += 2.0 * np.einsum("jc,jc->j", above + diag, F[:, c])
+    np.testing.assert_allclose(s[:, 0] ** 2 * acc, exact, rtol=1e-12)
+
+
+def test_fp16_screen_keeps_the_exact_winner_inside_the_margin():
+    worst_err = worst_slack = 0.0
+    for seed, d_in, d_out, bits, tail in [(2, 256, 48, 3, True), (3, 384, 40, 4, True), (4, 256, 40, 2, False), (5, 512, 24, 3, True)]:
+        H, W = layer(seed, d_in, d_out, 3 * d_in, tail)
+        E = residuals(W, bits, 50)
+        exact = np.einsum("gji,ik,gjk->gj", E.astype(np.float64), H, E.astype(np.float64))
+        d = np.sqrt(np.diag(H)).astype(np.float32)
+        R16 = (H / np.outer(d, d)).astype(np.float32).astype(np.float16).astype(np.float64)
+        F = E * d
+        s = np.abs(F).max(axis=2, keepdims=True)
+        s[s == 0] = 1.0
+        F16 = (F / s).astype(np.float16).astype(np.float64)
+        screened = s[:, :, 0].astype(np.float64) ** 2 * np.einsum("gji,ik,gjk->gj", F16, R16, F16)
+        ok = exact > 0
+        worst_err = max(worst_err, float(np.abs(screened[ok] / exact[ok] - 1).max()))
+        win = exact.argmin(axis=0)
+        slack = screened[win, np.arange(d_out)] / screened.min(axis=0) - 1
+        worst_slack = max(worst_slack, float(slack.max()))
+        assert (slack <= MARGIN).all()
+    assert worst_err < 1e-3, worst_err            # measured on the GPU on larger layers: 3e-4
+    assert worst_slack < MARGIN / 5, worst_slack
