@@ -9,6 +9,8 @@ the same seeded inputs.  Bars:
   loss              within 1e-6 relative of the oracle's fp64 value (the kernel rounds e to fp32
                     first; given that fp32 e it matches an fp64 evaluation to 1e-12)
 """
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -124,6 +126,72 @@ def test_hessian_accumulate_and_damping(cdq, oracle):
     # the damping really is there: compare the diagonal against the undamped oracle
     lam = 0.01 * np.mean(np.diag(oracle.hessian(X)))
     np.testing.assert_allclose(np.diag(Hn) - np.diag(oracle.hessian(X)), lam, rtol=1e-3)
+
+
+def layer_with_exact_ties(seed=0, d_in=256, d_out=4, n=2000):
+    """Every weight on a grid point of Eq. (2) (scale 21/16, zero 0, 3 bits) except one per column, which sits exactly half
+    way between two levels on a coordinate whose (21/16) H_ii rounds up in fp32 by less than a quarter of a unit in the
+    last place.  Moving that coordinate up or down leaves the loss unchanged, and in fp32 both moves compute to a tiny
+    negative score: Algorithm 1 alternates between them until its budget is spent."""
+    from fractions import Fraction
+    r = np.random.default_rng(seed)
+    X = r.standard_normal((n, d_in)).astype(np.float32)
+    H32 = np.ascontiguousarray(np.float32(X.astype(np.float64).T @ X.astype(np.float64)))
+    good = []
+    for i in range(2, d_in):
+        p = Fraction(21, 16) * Fraction(float(H32[i, i]))
+        f32 = np.float32(float(p))
+        if 0 < Fraction(float(f32)) - p < Fraction(float(np.spacing(f32))) / 4:
+            good.append(i)
+    Wt = (np.float32(1.3125) * r.integers(0, 8, (d_out, d_in))).astype(np.float32)
+    Wt[:, 0], Wt[:, 1] = 0.0, 9.1875
+    for j in range(d_out):
+        Wt[j, good[j]] = 3.28125
+    return H32, Wt, good[:d_out]
+
+
+@pytest.mark.parametrize("waves,elems", [(0, 0), (2, 16), (16, 4), (16, 16), (16, 24), (16, 36)])
+def test_greedy_cd_alternating_between_two_levels_of_equal_loss(cdq, oracle, waves, elems):
+    """The kernels for 16 wavefronts and up to 24 coordinates per lane jump over the rest of the budget once the state
+    repeats; the others take every step; the oracle takes every step.  Same moves, same codes, for even and odd budgets,
+    and the same trajectory when it is traced (tracing switches the jump off)."""
+    H32, Wt, ties = layer_with_exact_ties()
+    d_out, d_in = Wt.shape
+    a, b, q0 = oracle.init_grid(Wt, 3, d_in)
+    assert np.all(a == np.float32(1.3125)) and np.all(b == 0)
+    for T in (1, 2, 3, 50, 51, 400):
+        ref = oracle.greedy_cd(H32, Wt, a, b, q0, 3, d_in, T)
+        assert np.all(ref["moves"] == T), "the case should alternate to the end of every budget"
+        Q = dev(q0.copy())
+        out = cdq.greedy_cd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, d_in, T, waves_per_column=waves, elems_per_lane=elems, want_G=True)
+        st = out["stats"].cpu().numpy()
+        assert np.array_equal(st[:, 0], ref["moves"]) and np.all(st[:, 2] == 0), (T, st)
+        assert np.array_equal(Q.cpu().numpy(), ref["Q"]), T
+        assert np.array_equal(out["G"].cpu().numpy(), ref["G"]), T
+        assert [int(Q.cpu().numpy()[j, i]) for j, i in enumerate(ties)] == [2 + T % 2] * d_out
+    ref = oracle.greedy_cd(H32, Wt, a, b, q0, 3, d_in, 60, trace_cap=60)
+    Q = dev(q0.copy())
+    out = cdq.greedy_cd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, d_in, 60, waves_per_column=waves, elems_per_lane=elems, trace_cap=60)
+    ti, tu = out["trace"].cpu().numpy().astype(np.int64) >> 6, (out["trace"].cpu().numpy().astype(np.int64) & 63) - 32
+    assert np.array_equal(ti, ref["trace_i"]) and np.all(np.abs(tu) == 1) and np.all(tu[:, 1:] == -tu[:, :-1])
+    assert np.array_equal(Q.cpu().numpy(), ref["Q"])
+
+
+def test_greedy_cd_alternating_for_a_long_budget(cdq, oracle):
+    """A budget of 100 001 iterations: the kernel that jumps is done in microseconds, the oracle takes every step."""
+    H32, Wt, ties = layer_with_exact_ties(seed=1, d_in=128, d_out=2, n=1000)
+    d_out, d_in = Wt.shape
+    a, b, q0 = oracle.init_grid(Wt, 3, d_in)
+    T = 100001
+    ref = oracle.greedy_cd(H32, Wt, a, b, q0, 3, d_in, T)
+    assert np.all(ref["moves"] == T)
+    Q = dev(q0.copy())
+    t0 = time.perf_counter()
+    out = cdq.greedy_cd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, d_in, T, waves_per_column=16, elems_per_lane=16, want_G=True)
+    torch.cuda.synchronize()
+    assert time.perf_counter() - t0 < 0.05, "the kernel for 16 wavefronts should not have taken every step"
+    assert np.array_equal(out["stats"].cpu().numpy()[:, 0], ref["moves"])
+    assert np.array_equal(Q.cpu().numpy(), ref["Q"]) and np.array_equal(out["G"].cpu().numpy(), ref["G"])
 
 
 # ----------------------------------------------------------------------------- OWC
