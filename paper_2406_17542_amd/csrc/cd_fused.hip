@@ -192,9 +192,9 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
     // row of the start gradient; if two moves later the codes are back (the two moves again undid each other) and 2g has
     // exactly the same bits, the state is that of two iterations ago, the loop is periodic from here on, and only the
     // parity of what is left of the budget matters.  Not done when the moves are traced, and only built into the kernels for
-    // 16 wavefronts and up to 24 coordinates per lane (FF): there a column that spends its whole budget holds a CU for
-    // 0.1 to 0.4 s after everything else has finished, while the bookkeeping costs 2 to 6 % of the loop; in the smaller
-    // shapes it costs 5 % and the budget is short, and at 32 and 36 coordinates per lane it adds register spills.
+    // 4 or more wavefronts and up to 24 coordinates per lane (FF): there a column that spends its whole budget runs on for
+    // tens to hundreds of milliseconds after everything else has finished, while the bookkeeping costs 1 to 6 % of the loop;
+    // with one or two wavefronts it costs 5 % and the budget is short, and at 32 and 36 coordinates per lane it adds spills.
     auto team_all = [&](bool ok) -> bool {
         uint64_t v = (__ballot(ok) == ~0ull) ? 1u : 0u;
         if (W > 1) {
@@ -345,7 +345,7 @@ template <int W, int E, int VEC, bool LDSH = false>
 int launch_one(const float* H, const float* hdiag, float* G0, const float* scale, uint8_t* Q, int64_t d_out,
                int d_in, int bits, int group, int group_shift, int n_grp, int T, int exact_only, cdq_col_stats* stats,
                int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
-    constexpr bool FF = (W == 16 && E <= 24 && VEC == 4);
+    constexpr bool FF = (W >= 4 && E <= 24 && VEC == 4);
     const size_t lds = LDSH ? sizeof(float) * 64 * W * E : 0;
     if (LDSH) {
         static const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(cd_fused_kernel<W, E, VEC, LDSH, FF>),
