@@ -185,11 +185,14 @@ def test_greedy_cd_alternating_for_a_long_budget(cdq, oracle):
     T = 100001
     ref = oracle.greedy_cd(H32, Wt, a, b, q0, 3, d_in, T)
     assert np.all(ref["moves"] == T)
+    Hd, Wd, ad, bd = dev(H32), dev(Wt), dev(a), dev(b)
+    cdq.greedy_cd(Hd, Wd, ad, bd, dev(q0.copy()), 3, d_in, 1, waves_per_column=16, elems_per_lane=16)      # first use of this kernel
     Q = dev(q0.copy())
-    t0 = time.perf_counter()
-    out = cdq.greedy_cd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, d_in, T, waves_per_column=16, elems_per_lane=16, want_G=True)
     torch.cuda.synchronize()
-    assert time.perf_counter() - t0 < 0.05, "the kernel for 16 wavefronts should not have taken every step"
+    t0 = time.perf_counter()
+    out = cdq.greedy_cd(Hd, Wd, ad, bd, Q, 3, d_in, T, waves_per_column=16, elems_per_lane=16, want_G=True)
+    torch.cuda.synchronize()
+    assert time.perf_counter() - t0 < 0.05, "the kernel for 16 wavefronts should not have taken every step (that takes 0.15 s)"
     assert np.array_equal(out["stats"].cpu().numpy()[:, 0], ref["moves"])
     assert np.array_equal(Q.cpu().numpy(), ref["Q"]) and np.array_equal(out["G"].cpu().numpy(), ref["G"])
 
