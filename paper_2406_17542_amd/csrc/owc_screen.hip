@@ -82,6 +82,63 @@ __global__ __launch_bounds__(256) void owc_residual_f16_kernel(const float* __re
     for (int64_t k = threadIdx.x; k < d_in; k += 256) f[k] = (_Float16)(f_of(k) * rs);
 }
 
+// The same rows for a 16-byte aligned Wt (d_in is a multiple of 128 here): four coordinates per lane and load, the first
+// 8192 coordinates' f kept in registers between the pass that finds s and the pass that stores, the rest formed again.
+// Every value is formed by the expressions of the kernel above, so the two kernels store the same bits.
+__global__ __launch_bounds__(256) void owc_residual_f16_vec_kernel(const float* __restrict__ Wt, int64_t d_in, int bits,
+                                                                   const float* __restrict__ lo_in, const float* __restrict__ hi_in,
+                                                                   float gamma, const float* __restrict__ d, _Float16* __restrict__ F,
+                                                                   float* __restrict__ row_scale2) {
+    constexpr int KEEP = 8;
+    __shared__ float smax[4];
+    const int64_t j = blockIdx.x;
+    const float lo = lo_in[j], hi = hi_in[j];
+    const float top = (float)((1 << bits) - 1);
+    float a = __fdiv_rn(gamma * (hi - lo), top);
+    if (!(a > 0.0f) || isinf(a)) a = 1.0f;
+    const float4* w4 = reinterpret_cast<const float4*>(Wt + j * d_in);
+    const float4* d4 = reinterpret_cast<const float4*>(d);
+    const int n4 = (int)(d_in >> 2);
+    auto f_one = [&](float wk, float dk) {
+        const float q = fminf(fmaxf(rintf(__fdiv_rn(wk - lo, a)), 0.0f), top);
+        return (fmaf(a, q, lo) - wk) * dk;
+    };
+    auto f_of = [&](int c) {
+        const float4 w = w4[c], dd = d4[c];
+        return make_float4(f_one(w.x, dd.x), f_one(w.y, dd.y), f_one(w.z, dd.z), f_one(w.w, dd.w));
+    };
+    auto amax = [](float m, const float4& f) { return fmaxf(fmaxf(m, fabsf(f.x)), fmaxf(fabsf(f.y), fmaxf(fabsf(f.z), fabsf(f.w)))); };
+    float4 kept[KEEP];
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < KEEP; ++i) {
+        const int c = (int)threadIdx.x + 256 * i;
+        kept[i] = c < n4 ? f_of(c) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        m = amax(m, kept[i]);
+    }
+    for (int c = (int)threadIdx.x + 256 * KEEP; c < n4; c += 256) m = amax(m, f_of(c));
+    for (int o = 32; o; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if ((threadIdx.x & 63) == 0) smax[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(smax[0], smax[1]), fmaxf(smax[2], smax[3]));
+    const float s = (m > 0.0f && m < INFINITY) ? m : 1.0f;
+    const float rs = __fdiv_rn(1.0f, s);
+    if (threadIdx.x == 0) row_scale2[j] = s * s;
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    h4* f = reinterpret_cast<h4*>(F + j * d_in);
+    auto put = [&](int c, const float4& v) {
+        h4 o;
+        o.x = (_Float16)(v.x * rs), o.y = (_Float16)(v.y * rs), o.z = (_Float16)(v.z * rs), o.w = (_Float16)(v.w * rs);
+        f[c] = o;
+    };
+#pragma unroll
+    for (int i = 0; i < KEEP; ++i) {
+        const int c = (int)threadIdx.x + 256 * i;
+        if (c < n4) put(c, kept[i]);
+    }
+    for (int c = (int)threadIdx.x + 256 * KEEP; c < n4; c += 256) put(c, f_of(c));
+}
+
 // f^T R f over the blocks of R on and above the diagonal (R is symmetric: its row c is its column c, and the blocks below
 // the diagonal repeat the ones above): for column block cb the contraction runs over k < TB (cb + 1); the diagonal block
 // enters at half weight and the sum is doubled at the end.
@@ -289,8 +346,12 @@ int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_
     if (lds_rc_small != hipSuccess || lds_rc_big != hipSuccess) return CDQ_EHIP;
     for (int k = 1; k <= n_gamma; ++k) {
         const float gamma = (float)k / (float)n_gamma;
-        hipLaunchKernelGGL(owc_residual_f16_kernel, dim3((unsigned)d_out), dim3(256), 0, st, Wt, d_in, bits, lo, hi, gamma, (const float*)d, F,
-                           row_scale2);
+        if (((uintptr_t)Wt & 15) == 0)
+            hipLaunchKernelGGL(owc_residual_f16_vec_kernel, dim3((unsigned)d_out), dim3(256), 0, st, Wt, d_in, bits, lo, hi, gamma,
+                               (const float*)d, F, row_scale2);
+        else
+            hipLaunchKernelGGL(owc_residual_f16_kernel, dim3((unsigned)d_out), dim3(256), 0, st, Wt, d_in, bits, lo, hi, gamma,
+                               (const float*)d, F, row_scale2);
         CDQ_LAUNCH_CHECK();
         if (big)
             hipLaunchKernelGGL((owc_screen_kernel<2 * SB, 2>), dim3((unsigned)(d_in / (2 * SB)), (unsigned)(rows / (2 * SB))), dim3(1024), lds_big, st,

@@ -236,6 +236,30 @@ def test_init_owc(cdq, oracle, d_out, d_in, n, bits, n_gamma):
     assert (gam < 1).any(), "the case should exercise clipping"
 
 
+def test_init_owc_weights_at_an_odd_address(cdq, oracle):
+    """Eq. (2) grid search with Wt 4 bytes off a 16-byte boundary (the library's scalar-load kernels) chooses, for every
+    column, what it chooses for the aligned copy, and that is the oracle's choice."""
+    d_out, d_in, n, bits, n_gamma = 150, 384, 900, 3, 50
+    X, Wt = rand_layer(77, d_in, d_out, n, corr=0.5)
+    rng = np.random.default_rng(77)
+    Wt *= np.exp(0.7 * rng.standard_normal(Wt.shape)).astype(np.float32)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q, gam, all_loss = oracle.init_owc(H32, Wt, bits, d_in, n_gamma)
+    Hd = dev(H32)
+    buf = torch.zeros(d_out * d_in + 4, dtype=torch.float32, device="cuda")
+    odd = buf[1:1 + d_out * d_in].view(d_out, d_in)
+    odd.copy_(dev(Wt))
+    assert odd.data_ptr() % 16 == 4 and odd.is_contiguous()
+    ref = [t.cpu().numpy() for t in cdq.init_owc(Hd, dev(Wt), bits, d_in, n_gamma)]
+    got = [t.cpu().numpy() for t in cdq.init_owc(Hd, odd, bits, d_in, n_gamma)]
+    for r, g in zip(ref[:4], got[:4]):
+        assert np.array_equal(r, g)
+    np.testing.assert_allclose(got[4], ref[4], rtol=1e-9)
+    same = got[3] == gam
+    assert same.mean() >= 0.98
+    assert np.array_equal(got[0][same], a[same]) and np.array_equal(got[1], b) and np.array_equal(got[2][same], q[same])
+
+
 # ----------------------------------------------------------------------------- OWC-CD (Algorithm 3)
 
 def owc_cd_score(oracle, H64, wj, bits, group, n_gamma, cur, i, k):
