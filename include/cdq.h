@@ -96,7 +96,10 @@ size_t cdq_workspace_bytes(int op, int64_t n, int64_t d_out, int64_t d_in);
  *               % 4 == 0 for fp32 (rows must be 16-byte aligned)
  *   H           [d_in][d_in] fp32 out (both triangles written, exactly symmetric)
  *   accumulate  0: H = X^T X;  1: H += X^T X (streaming over chunks of tokens; H must already
- *               hold a symmetric matrix).  Damping, if requested, is applied after the sum.
+ *               hold a symmetric matrix).
+ *   lambda_rel  damping added at the end of THIS call, after the sum, from the diagonal H then has.
+ *               When streaming, pass it on the last chunk only and 0 on the others: a non-zero
+ *               value on every chunk would add damping once per call.
  * Products are exact (bf16) or fp32, accumulation is fp32 on the matrix cores; the summation
  * order over tokens is fixed, so results are reproducible run to run.
  */
@@ -248,6 +251,16 @@ int cdq_greedy_cd_ex(const float *H, const float *Wt, const float *scale, const 
                      uint8_t *Q, int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T,
                      cdq_col_stats *stats, const cdq_cd_options *opts,
                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The launch shape cdq_greedy_cd takes for a layer when nothing is forced: wavefronts cooperating on
+ * a column and coordinates held per lane (64 * waves * elems >= d_in).  Host-only, no GPU access.
+ * `aligned16` tells whether H rows and Q rows are 16- and 4-byte aligned (they are when the base
+ * pointers are and d_in % 4 == 0); without it the kernels fall back to scalar loads.
+ * Returns CDQ_EUNSUPPORTED where cdq_greedy_cd would.
+ */
+int cdq_greedy_cd_shape(int64_t d_out, int64_t d_in, int64_t group, int aligned16,
+                        int32_t *waves_per_column, int32_t *elems_per_lane);
 
 /*
  * One iteration of Algorithm 1 as separate steps, on a gradient G = E H kept in global memory

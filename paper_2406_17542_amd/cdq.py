@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.cdq_bcd.restype = i32
         L.cdq_cyclic_cd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, vp, i64, vp, sz, vp]
         L.cdq_cyclic_cd.restype = i32
+        L.cdq_greedy_cd_shape.argtypes = [i64, i64, i64, i32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+        L.cdq_greedy_cd_shape.restype = i32
         L.cdq_probe_mfma.argtypes = [i32, i64, i64, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.cdq_probe_mfma.restype = i32
         L.cdq_probe_copy.argtypes = [vp, vp, sz, vp]
@@ -261,6 +263,13 @@ def greedy_cd(H, Wt, scale, zero, Q, bits: int, group: int, T: int, stats: bool 
                                   ws.data_ptr(), ws.numel(), _stream()), "cdq_greedy_cd")
     out["stats"] = st
     return out
+
+
+def greedy_cd_shape(d_out: int, d_in: int, group: int, aligned16: bool = True):
+    """(wavefronts per column, coordinates per lane) that greedy_cd takes for a layer by default."""
+    w, e = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().cdq_greedy_cd_shape(d_out, d_in, group, int(aligned16), ctypes.byref(w), ctypes.byref(e)), "cdq_greedy_cd_shape")
+    return int(w.value), int(e.value)
 
 
 def score_argmin(Hdiag, scale, Q, G, bits: int, group: int):

@@ -371,8 +371,9 @@ int extract_diag_launch(const float* H, int64_t d_in, float* hdiag, hipStream_t 
 // of a lane, registers (occupancy) and the cost of the cross-wavefront step, for every d_in from
 // 2048 to 16384; beyond that 24, 32 or 36 per lane on 16 wavefronts with the Hessian diagonal in LDS.  With few columns the chain is split
 // over more wavefronts so the 256 CUs x 4 SIMDs still have work in flight.
-int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int* elems, int* vec) {
-    const int v = (d_in % 4 == 0 && group % 4 == 0) ? 4 : 1;
+// `aligned16`: rows of H start on 16-byte and rows of Q on 4-byte boundaries, so 16-byte chunks can be used.
+int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, bool aligned16, int* waves, int* elems, int* vec) {
+    const int v = (aligned16 && d_in % 4 == 0 && group % 4 == 0) ? 4 : 1;
     auto team = [&](int e) {
         const int64_t need = (d_in + 64 * (int64_t)e - 1) / (64 * (int64_t)e);
         int w = 1;

@@ -128,9 +128,9 @@ int cdq_greedy_cd_ex(const float* H, const float* Wt, const float* scale, const 
     if (d_in > CDQ_MAX_D_IN) return CDQ_EUNSUPPORTED;
     if (opts != nullptr && opts->trace != nullptr && opts->trace_cap <= 0) return CDQ_EINVAL;
     int waves = 0, elems = 0, vec = 0;
-    int rc = cdq::cd_choose_shape(d_out, d_in, group, &waves, &elems, &vec);
+    // the shape is chosen for the vector width the pointers allow: a misaligned layer gets a scalar-load shape
+    int rc = cdq::cd_choose_shape(d_out, d_in, group, !(misaligned(Q, 4) || misaligned(H, 16)), &waves, &elems, &vec);
     if (rc != CDQ_OK) return rc;
-    if (misaligned(Q, 4) || misaligned(H, 16)) vec = 1;
     if (opts != nullptr && (opts->waves_per_column != 0 || opts->elems_per_lane != 0)) {
         const int w = opts->waves_per_column, e = opts->elems_per_lane;
         const bool w_ok = (w == 1 || w == 2 || w == 4 || w == 8 || w == 16);
@@ -153,6 +153,18 @@ int cdq_greedy_cd_ex(const float* H, const float* Wt, const float* scale, const 
                         (opts != nullptr && opts->exact_scorer_only) ? 1 : 0, opts ? opts->trace : nullptr, opts ? opts->trace_cap : 0, opts ? opts->G_out : nullptr, st);
     if (rc != CDQ_OK) return rc;
     if (opts != nullptr && opts->ev_loop_end != nullptr) CDQ_HIP_CHECK(hipEventRecord((hipEvent_t)opts->ev_loop_end, st));
+    return CDQ_OK;
+}
+
+int cdq_greedy_cd_shape(int64_t d_out, int64_t d_in, int64_t group, int aligned16, int32_t* waves_per_column,
+                        int32_t* elems_per_lane) {
+    if (bad_layer(d_out, d_in, group) || waves_per_column == nullptr || elems_per_lane == nullptr) return CDQ_EINVAL;
+    if (d_in > CDQ_MAX_D_IN) return CDQ_EUNSUPPORTED;
+    int waves = 0, elems = 0, vec = 0;
+    const int rc = cdq::cd_choose_shape(d_out, d_in, group, aligned16 != 0, &waves, &elems, &vec);
+    if (rc != CDQ_OK) return rc;
+    *waves_per_column = waves;
+    *elems_per_lane = elems;
     return CDQ_OK;
 }
 

@@ -76,7 +76,7 @@ int gather_update_launch(const float* H, const float* scale, uint8_t* Q, float* 
                          const int32_t* sel_i, const int32_t* sel_r, int32_t* moves, hipStream_t st);
 
 // ---- cd_fused.hip
-int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, int* waves, int* elems, int* vec);
+int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, bool aligned16, int* waves, int* elems, int* vec);
 int cd_launch(const float* H, const float* hdiag, float* G0, const float* scale, uint8_t* Q,          // G0 is overwritten
               int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T, cdq_col_stats* stats,
               int waves, int elems, int vec, int exact_only, int32_t* trace, int64_t trace_cap, float* G_out,

@@ -2,6 +2,7 @@
 // benchmark quotes next to the coordinate-descent loop, and a copy of known size used to scale
 // hardware byte counters.  They compute nothing of the method.
 #include "cdq_internal.h"
+#include "cdq_probe.h"
 
 namespace cdq {
 namespace {

@@ -5,13 +5,12 @@
 // each step checkable on its own.  The fused kernel (cd_fused.hip) is the fast path; it keeps
 // the same state in registers and never writes the gradient back.
 #include "cdq_internal.h"
+#include "wave_min.h"
 
 namespace cdq {
 namespace {
 
-constexpr uint32_t kNoMove = 0x80000000u;
-__device__ __forceinline__ uint32_t order_bits(float s) { return (s < 0.0f) ? ~__float_as_uint(s) : kNoMove; }
-__device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
+constexpr uint32_t kNoMove = kOrderedZero;
 
 // one workgroup per column; key = (ordered score, coordinate, level)
 __global__ __launch_bounds__(256) void score_argmin_kernel(const float* __restrict__ hdiag, const float* __restrict__ scale,

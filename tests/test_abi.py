@@ -1,13 +1,14 @@
 """CPU-side checks of the C ABI: the library loads, exports every symbol the header declares,
 and rejects bad arguments on the host before anything touches a GPU."""
 import ctypes
+import glob
 import os
 import re
 
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "cdq.h")
+HEADERS = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
 
 
 @pytest.fixture(scope="module")
@@ -17,16 +18,19 @@ def L():
 
 
 def _declared():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(cdq_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for h in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(cdq_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_exported(L):
     names = _declared()
-    assert {"cdq_hessian", "cdq_init_rtn", "cdq_greedy_cd", "cdq_loss", "cdq_workspace_bytes", "cdq_strerror"} <= set(names)
+    assert {"cdq_hessian", "cdq_init_rtn", "cdq_greedy_cd", "cdq_loss", "cdq_workspace_bytes", "cdq_strerror",
+            "cdq_probe_copy", "cdq_greedy_cd_shape"} <= set(names)
     for n in names:
-        assert hasattr(L, n), f"{n} declared in include/cdq.h but not exported by libcdq.so"
+        assert hasattr(L, n), f"{n} declared in include/*.h but not exported by libcdq.so"
 
 
 def test_strerror(L):
@@ -100,3 +104,22 @@ def test_argument_checks_of_the_wider_entry_points(L):
     assert L.cdq_cyclic_cd(p, p, p, p, p, 4, 256, 3, 256, i64(8), n, n, n, 0, n, 0, n) == EWS
     assert L.cdq_cyclic_cd(p, p, p, p, p, 4, 254, 3, 254, i64(8), n, n, n, 0, p, 1 << 30, n) == EUNSUP   # d_in % 4
     assert L.cdq_cyclic_cd(p, p, p, p, p, 0, 256, 3, 256, i64(8), n, n, n, 0, n, 0, n) == 0             # empty layer
+
+
+def test_launch_shape_query(L):
+    """The default launch shape is a host-side rule: 16 coordinates per lane up to d_in = 16384, the kernels with the
+    Hessian diagonal in LDS above, and a scalar-load shape when the rows are not 16-byte aligned."""
+    from paper_2406_17542_amd import cdq
+    assert cdq.greedy_cd_shape(2048, 2048, 2048) == (2, 16)
+    assert cdq.greedy_cd_shape(32768, 8192, 8192) == (8, 16)
+    assert cdq.greedy_cd_shape(2048, 16384, 16384) == (16, 16)
+    assert cdq.greedy_cd_shape(3072, 24576, 24576) == (16, 24)
+    assert cdq.greedy_cd_shape(3072, 24576, 24576, aligned16=False) == (16, 32)      # 24 per lane needs 16-byte chunks
+    assert cdq.greedy_cd_shape(4608, 36864, 36864) == (16, 36)
+    w, e = cdq.greedy_cd_shape(6, 2048, 2048)                                         # few columns: the chain is split further
+    assert 64 * w * e >= 2048 and e < 16
+    with pytest.raises(cdq.CdqError) as err:
+        cdq.greedy_cd_shape(4608, 36864, 36864, aligned16=False)
+    assert err.value.code == -4
+    with pytest.raises(cdq.CdqError):
+        cdq.greedy_cd_shape(16, 65536, 65536)
