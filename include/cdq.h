@@ -298,6 +298,23 @@ int cdq_loss(const float *H, const float *Wt, const float *scale, const float *z
              double *loss_per_col, double *loss_total,
              void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * cdq_loss for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same sums in
+ * the same order and therefore the same results as cdq_loss; the partial sums go to an array that
+ * is part of the library's device image (CDQ_LOSS_STATIC_SCRATCH_BYTES per GPU, held until the
+ * process ends) instead of a workspace.  The call allocates and frees nothing.
+ * Layers for which cdq_workspace_bytes(CDQ_OP_LOSS, 0, d_out, d_in) exceeds
+ * CDQ_LOSS_STATIC_SCRATCH_BYTES are rejected with CDQ_EUNSUPPORTED before any GPU work (the limit
+ * covers d_out * ceil(d_in/128) up to about 2.1 million, e.g. 32768 x 8192).
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams,
+ * different threads) race; order them on one stream.  Nothing has to be cleared between calls.
+ */
+#define CDQ_LOSS_STATIC_SCRATCH_BYTES (24u << 20)
+int cdq_loss_static(const float *H, const float *Wt, const float *scale, const float *zero,
+                    const uint8_t *Q, int64_t d_out, int64_t d_in, int64_t group,
+                    double *loss_per_col, double *loss_total, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

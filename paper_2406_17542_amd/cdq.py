@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.cdq_bcd.restype = i32
         L.cdq_cyclic_cd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, vp, i64, vp, sz, vp]
         L.cdq_cyclic_cd.restype = i32
+        L.cdq_loss_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
+        L.cdq_loss_static.restype = i32
         L.cdq_greedy_cd_shape.argtypes = [i64, i64, i64, i32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
         L.cdq_greedy_cd_shape.restype = i32
         L.cdq_probe_mfma.argtypes = [i32, i64, i64, vp, ctypes.POINTER(ctypes.c_double), vp]
@@ -314,6 +316,15 @@ def loss(H, Wt, scale, zero, Q, group: int, workspace: torch.Tensor | None = Non
                           _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, group,
                           per.data_ptr(), tot.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "cdq_loss")
     return per, tot
+
+
+def loss_static(H, Wt, scale, zero, Q, group: int, per: torch.Tensor, tot: torch.Tensor) -> None:
+    """cdq_loss_static: the loss with the partial sums in the library's own static device array.  The call allocates
+    nothing, so the caller passes the outputs: per [d_out] fp64, tot [1] fp64."""
+    d_out, d_in = Wt.shape
+    _check(lib().cdq_loss_static(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), _dev(scale, torch.float32, "scale"),
+                                 _dev(zero, torch.float32, "zero"), _dev(Q, torch.uint8, "Q"), d_out, d_in, group,
+                                 _dev(per, torch.float64, "per"), _dev(tot, torch.float64, "tot"), _stream()), "cdq_loss_static")
 
 
 # ---- measurement helpers (see include/cdq.h): thin wrappers, used by bench.py only

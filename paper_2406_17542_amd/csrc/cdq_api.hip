@@ -233,4 +233,12 @@ int cdq_loss(const float* H, const float* Wt, const float* scale, const float* z
                             (hipStream_t)stream);
 }
 
+int cdq_loss_static(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q, int64_t d_out,
+                    int64_t d_in, int64_t group, double* loss_per_col, double* loss_total, void* stream) {
+    if (bad_layer(d_out, d_in, group)) return CDQ_EINVAL;
+    if (loss_per_col == nullptr && loss_total == nullptr) return CDQ_EINVAL;
+    if (d_out > 0 && (H == nullptr || Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr)) return CDQ_EINVAL;
+    return cdq::loss_static_launch(H, Wt, scale, zero, Q, d_out, d_in, group, loss_per_col, loss_total, (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -38,6 +38,8 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
 // row_block_active non-null: one byte per block of loss_block_rows() columns of W; blocks with a zero are skipped and
 // their entries of loss_per_col are unspecified
 int loss_block_rows();
+int loss_static_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
+                       int64_t d_out, int64_t d_in, int64_t group, double* loss_per_col, double* loss_total, hipStream_t st);
 
 // ---- owc_screen.hip : every clipping strength evaluated in bf16 first, candidates ranked per column
 bool owc_screen_applies(int64_t d_out, int64_t d_in, int n_gamma);

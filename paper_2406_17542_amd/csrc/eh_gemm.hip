@@ -16,6 +16,8 @@
 // the matrix core fed across barriers and global-load latency.
 #include "cdq_internal.h"
 
+#include <mutex>
+
 namespace cdq {
 
 namespace {
@@ -379,6 +381,47 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
         CDQ_LAUNCH_CHECK();
     }
     return CDQ_OK;
+}
+
+// ---- the loss for callers that cannot allocate: the kernels above with their partial sums in a static device array
+
+namespace {
+
+constexpr size_t kLossScratchBytes = CDQ_LOSS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char loss_scratch[kLossScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* loss_scratch_ptr[kMaxDevices];          // device address of this GPU's copy of the array, looked up once per device
+std::mutex loss_scratch_mutex;
+
+// The array's name is a host-side stand-in; the address the kernels can use comes from the runtime, per device.
+int loss_scratch_of_current_device(void** out) {
+    int dev = -1;
+    CDQ_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return CDQ_EUNSUPPORTED;
+    std::lock_guard<std::mutex> hold(loss_scratch_mutex);
+    if (loss_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        CDQ_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(loss_scratch)));
+        if (p == nullptr || ((uintptr_t)p & 255) != 0) return CDQ_EHIP;
+        loss_scratch_ptr[dev] = p;
+    }
+    *out = loss_scratch_ptr[dev];
+    return CDQ_OK;
+}
+
+}  // namespace
+
+int loss_static_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
+                       int64_t d_out, int64_t d_in, int64_t group, double* loss_per_col, double* loss_total, hipStream_t st) {
+    if (loss_workspace_bytes(d_out, d_in) > kLossScratchBytes) return CDQ_EUNSUPPORTED;     // before anything touches the GPU
+    void* scratch = nullptr;
+    if (d_out > 0) {
+        const int rc = loss_scratch_of_current_device(&scratch);
+        if (rc != CDQ_OK) return rc;
+    }
+    // every partial sum the second kernel reads is written by the first one in the same call, so nothing has to be cleared
+    return loss_launch(H, Wt, scale, zero, Q, d_out, d_in, group, loss_per_col, loss_total, scratch, kLossScratchBytes, st);
 }
 
 }  // namespace cdq
