@@ -14,6 +14,8 @@
 // token chunks), and mirrors into the lower triangle.
 #include "cdq_internal.h"
 
+#include <type_traits>
+
 namespace cdq {
 
 namespace {
@@ -34,36 +36,59 @@ __device__ __forceinline__ void tile_from_linear(int lin, int n_t, int* I, int* 
     *J = i + rem;
 }
 
-// Tile order for large matrices: workgroups are handed to the 8 XCDs round-robin, and each XCD has its own L2, so
-// the 32 workgroups an XCD runs at a time should share operand column blocks.  Workgroup w belongs to XCD w % 8 and
-// is that XCD's (w / 8)-th; consecutive runs of 32 of them form a patch of 4 x 8 tiles (12 column blocks for 32
-// tiles instead of ~36 in row-major order).  Patches that lie wholly below the diagonal are not enumerated; tiles of
-// a patch below the diagonal or outside the matrix return at once.  `rot` rotates the patch-to-XCD assignment
-// (one value per token split) so that no XCD always gets the surplus patch.
+// Work distribution for large matrices (n_t >= kBalancedMinTiles tiles per side).  Workgroups are handed to the 8 XCDs
+// round-robin (workgroup w runs on XCD w % 8) and each XCD has its own L2, so the 32 workgroups an XCD runs at a time
+// should share operand column blocks.  The tiles on and above the diagonal are therefore listed patch by patch
+// (PATCH_R x PATCH_C tiles: 12 column blocks for 32 tiles instead of ~36 in row-major order), and XCD x takes the
+// x-th eighth of that list, 32 tiles -- one per CU -- at a time.  What is left of an XCD's share after its last whole
+// round of 32 would keep a few CUs busy for a whole tile while the rest idle: those tiles are cut along the tokens
+// into as many slices as it takes to occupy all 32 CUs, each slice writes a partial tile, and a small kernel adds the
+// partial tiles in ascending order (so the result does not depend on timing).
 constexpr int PATCH_R = 4, PATCH_C = 8;
+constexpr int kBalancedMinTiles = 23;        // 276 tiles: the first size that does not fit one round of 256 CUs
+constexpr int kCusPerXcd = 32, kXcds = 8;
 
 __host__ __device__ inline int patch_row_first(int pi) { return (PATCH_R * pi) / PATCH_C; }     // first patch column reaching row block pi
-__host__ __device__ inline int patch_count(int n_t) {
-    const int PI = (n_t + PATCH_R - 1) / PATCH_R, PJ = (n_t + PATCH_C - 1) / PATCH_C;
+__host__ __device__ inline int patch_valid(int pi, int pj, int n_t) {                           // tiles of the patch with I <= J < n_t
     int c = 0;
-    for (int pi = 0; pi < PI; ++pi) c += PJ - patch_row_first(pi);
+    for (int r = 0; r < PATCH_R; ++r) {
+        const int I = PATCH_R * pi + r;
+        if (I >= n_t) break;
+        const int lo = I > PATCH_C * pj ? I : PATCH_C * pj;
+        const int hi = PATCH_C * pj + PATCH_C < n_t ? PATCH_C * pj + PATCH_C : n_t;
+        if (hi > lo) c += hi - lo;
+    }
     return c;
 }
-__device__ __forceinline__ bool tile_from_patch(int w, int rot, int n_t, int* I, int* J) {
-    const int xcd = (w + rot) & 7, s = w >> 3;
-    int p = (s >> 5) * 8 + xcd;
-    const int pos = s & 31;
+// the L-th tile of the patch-by-patch list
+__host__ __device__ inline void tile_from_list(int L, int n_t, int* I, int* J) {
     const int PI = (n_t + PATCH_R - 1) / PATCH_R, PJ = (n_t + PATCH_C - 1) / PATCH_C;
-    int pi = 0;
-    for (; pi < PI; ++pi) {
-        const int cnt = PJ - patch_row_first(pi);
-        if (p < cnt) break;
-        p -= cnt;
-    }
-    if (pi >= PI) return false;
-    *I = PATCH_R * pi + (pos >> 3);
-    *J = PATCH_C * (patch_row_first(pi) + p) + (pos & 7);
-    return *I < n_t && *J < n_t && *J >= *I;
+    for (int pi = 0; pi < PI; ++pi)
+        for (int pj = patch_row_first(pi); pj < PJ; ++pj) {
+            const int c = patch_valid(pi, pj, n_t);
+            if (L >= c) { L -= c; continue; }
+            for (int r = 0; r < PATCH_R; ++r) {
+                const int i = PATCH_R * pi + r;
+                const int lo = i > PATCH_C * pj ? i : PATCH_C * pj;
+                const int hi = PATCH_C * pj + PATCH_C < n_t ? PATCH_C * pj + PATCH_C : n_t;
+                const int cnt = hi > lo ? hi - lo : 0;
+                if (L < cnt) { *I = i; *J = lo + L; return; }
+                L -= cnt;
+            }
+        }
+    *I = *J = 0;        // not reached for L < number of tiles
+}
+// XCD x's share of the list: tiles [first, first + count); `whole` of them run as whole tiles, the remaining `rest`
+// are cut into `slices` token slices each
+struct XcdShare { int first, count, whole, rest, slices; };
+__host__ __device__ inline XcdShare xcd_share(int x, int tiles) {
+    XcdShare sh;
+    sh.first = (int)(((int64_t)tiles * x) / kXcds);
+    sh.count = (int)(((int64_t)tiles * (x + 1)) / kXcds) - sh.first;
+    sh.rest = sh.count % kCusPerXcd;
+    sh.whole = sh.count - sh.rest;
+    sh.slices = sh.rest ? kCusPerXcd / sh.rest : 1;
+    return sh;
 }
 
 // ------------------------------------------------------------------------------------------ bf16
@@ -72,27 +97,28 @@ __device__ __forceinline__ bool tile_from_patch(int w, int rot, int n_t, int* I,
 // 4 x 4 MFMA blocks with the 256 accumulator registers in AGPRs (a third less LDS traffic per FLOP
 // than 128 x 64 on 8 wavefronts).  The token range is consumed in steps of 32; LDS is a ring of NSTAGE stages,
 // each holding the two operand tiles of one step as 32 token rows of 256 columns (512 bytes).
-// Loads run NSTAGE-1 steps ahead: a wavefront's direct global->LDS load moves 64 x 16 bytes = two
-// token rows; lane l writes chunk position l%32 of row l/32 and fetches the global 16-byte chunk
-// (l%32) ^ 4(row%4), i.e. the chunks of a row are XOR-swizzled by the row.  A transposing read by
-// the 16 lanes j of a group fetches the 8-byte pieces (token tb + j/4, columns fb + 4(j%4) .. +3)
-// and returns to lane j the tokens tb .. tb+3 of column fb + j; with the swizzle, the four token
-// rows of a group fall into four different 64-byte bank groups, so reads and writes are
-// conflict-free.  With a single wavefront per SIMD nothing else hides a stall, so the loop is a
-// software pipeline over 16-token halves: the fragments of the next half are read while the MFMAs
-// of the current one run (scheduling hints interleave one read behind each MFMA), the one barrier
-// per step sits between the two halves, and issuing a step's loads costs a few scalar
-// instructions (fixed per-lane offsets, a scalar base per step).  Tiles that stick out of the
-// matrix, and a token range that is not a multiple of 32, take a plain path through registers
-// with zero fill (same layout).
+// A wavefront's direct global->LDS load moves 64 x 16 bytes = two token rows; lane l writes chunk position l%32 of
+// row l/32 and fetches the global 16-byte chunk (l%32) ^ 4(row%4), i.e. the chunks of a row are XOR-swizzled by the
+// row.  A transposing read by the 16 lanes j of a group fetches the 8-byte pieces (token tb + j/4, columns
+// fb + 4(j%4) .. +3) and returns to lane j the tokens tb .. tb+3 of column fb + j; with the swizzle, the four token
+// rows of a group fall into four different 64-byte bank groups, so reads and writes are conflict-free.
+// With a single wavefront per SIMD nothing else hides a stall, so the loop is a software pipeline over quarters of a
+// 16-token half step: four MFMAs, the four LDS reads that fetch a quarter of the next half's fragments, and ONE of the
+// wavefront's eight loads of a later step.  Issuing a step's loads in one burst (as an earlier version did) held every
+// wavefront in its issue sequence while the CU's single address unit worked through 32 KiB -- about 500 cycles per
+// 1000-cycle step with the matrix cores idle; spread out, a load costs the wavefront a scalar add and a move.
+// Loads run NSTAGE-1 steps ahead; the one barrier per step sits between the two halves.  Tiles that stick out of the
+// matrix and token ranges that are not a multiple of 32 take a plain path through registers with zero fill (same
+// LDS layout).
 
 constexpr int T2 = 256;                 // tile of H: T2 x T2 per workgroup
 constexpr int BK16 = 64;                // granularity of the token split (two steps)
 constexpr int BKS = 32;                 // tokens per step
 constexpr int ROWB = T2 * 2;            // LDS bytes per token row of a tile
 constexpr int TILE_BYTES = BKS * ROWB;  // 16 KiB per operand per stage
+constexpr int STAGE = 2 * TILE_BYTES;
 constexpr int NSTAGE = 4;
-constexpr int HESS_LDS = NSTAGE * 2 * TILE_BYTES;      // 128 KiB
+constexpr int HESS_LDS = NSTAGE * STAGE;               // 128 KiB
 
 typedef short s4v __attribute__((ext_vector_type(4)));
 typedef short s8v __attribute__((ext_vector_type(8)));
@@ -106,51 +132,122 @@ __device__ __forceinline__ bf8 read_frag(const char* p) {
     return __builtin_bit_cast(bf8, both);
 }
 
-// 16 bytes per lane from global memory straight into LDS at dst + 16 * lane (dst uniform over the wavefront).
-// Written as assembly so that the waits stay ours: the compiler would make every LDS read wait for all
-// direct loads in flight, the ones for later stages included.
-__device__ __forceinline__ void lds_direct_load16(const void* src, const char* dst) {
-    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)dst);
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src) : "m0", "memory");
-}
-
 template <int N>
 __device__ __forceinline__ void wait_vmem() {          // until at most N of this wavefront's vector-memory operations are pending
-    if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else if (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-    else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else if (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// The barrier alone: every wavefront has waited for its own loads before it, and the LDS reads still in flight touch
+// a stage that nobody writes before the next barrier, so nothing else has to drain here.
+__device__ __forceinline__ void stage_barrier() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
 }
 
-__global__ __launch_bounds__(256) void hessian_bf16_kernel(const uint16_t* __restrict__ X, int64_t n, int64_t d_in,
-                                                           int n_t, int64_t tokens_per_split,
-                                                           float* __restrict__ out, int64_t split_stride, int patched) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];       // [NSTAGE][A tile | B tile]
-    int I, J;
-    if (patched) {
-        if (!tile_from_patch((int)blockIdx.x, (int)blockIdx.z, n_t, &I, &J)) return;
-    } else {
-        tile_from_linear(blockIdx.x, n_t, &I, &J);
-    }
-    const bool diag = (I == J);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;           // 2 x 2 wavefronts, each 128 rows x 128 columns
-    const int64_t i0 = (int64_t)I * T2, j0 = (int64_t)J * T2;
-    const int64_t t_begin = (int64_t)blockIdx.z * tokens_per_split;
-    const int64_t t_end = (t_begin + tokens_per_split < n) ? t_begin + tokens_per_split : n;
-    const int n_steps = (int)((t_end - t_begin + BKS - 1) / BKS);
-
-    f16v acc[4][4];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
-
+// The pipelined loop over `n_steps` >= 1 steps of 32 tokens starting at token t_begin, for an interior tile.
+// A tile on the diagonal is not special here: its column block is loaded into both operand tiles (there are n_t such
+// tiles among n_t (n_t + 1) / 2, and a second code path would double the registers the compiler has to place).
+__device__ __forceinline__ void hessian_tile_pipelined(const uint16_t* __restrict__ X, int64_t d_in, int64_t i0, int64_t j0,
+                                                       int64_t t_begin, int n_steps, char* lds, f16v (&acc)[4][4]) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // uniform, and the compiler knows it
+    const int wm = wave >> 1, wn = wave & 1;                            // 2 x 2 wavefronts, each 128 rows x 128 columns
     // fragment read roles: 16-lane group g = lane/16 takes columns 16 (g%2) .. +15 of a 32-column fragment and the
-    // token half g/2 of a 16-token sub-step; lane j of the group addresses token j/4, columns 4 (j%4) .. +3
+    // token half g/2 of a 16-token half step; lane j of the group addresses token j/4, columns 4 (j%4) .. +3
+    const int jj = lane & 15, gg = lane >> 4;
+    const int rd_row = (8 * (gg >> 1) + (jj >> 2)) * ROWB + 8 * (jj & 1);
+    const int rd_chunk = 2 * (gg & 1) + ((jj & 3) >> 1), rd_swz = jj & 12;
+    int offA[4], offB[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) offA[b] = rd_row + (((wm * 16 + 4 * b + rd_chunk) ^ rd_swz) << 4);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) offB[b] = rd_row + (((wn * 16 + 4 * b + rd_chunk) ^ rd_swz) << 4) + TILE_BYTES;
+    // loads: a step's tiles are 32 loads of two token rows each; wavefront w issues loads w, w+4, ...
+    // Per load the lane's byte offset from the first token row of the step is fixed, and so is the load's place in a stage.
+    constexpr int PW = 8;                  // loads of this wavefront per step
+    const int lrow = lane >> 5, lpos = lane & 31;
+    uint32_t src_off[PW];                  // per lane
+    uint32_t dst_off[PW];                  // uniform
+#pragma unroll
+    for (int q = 0; q < PW; ++q) {
+        const int g = wave + 4 * q;                           // 0..15: A tile, 16..31: B tile
+        const int op = g >> 4, rp = g & 15;
+        const int row = 2 * rp + lrow;
+        const int chunk = lpos ^ (4 * (row & 3));
+        src_off[q] = (uint32_t)(((int64_t)row * d_in + (op ? j0 - i0 : 0) + 8 * chunk) * 2);
+        dst_off[q] = (uint32_t)(op * TILE_BYTES + 2 * rp * ROWB);
+    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds;
+    const char* xbase = reinterpret_cast<const char*>(X + t_begin * d_in + i0);
+    const int64_t step_bytes = (int64_t)BKS * d_in * 2;
+    // 16 bytes per lane from global memory straight into LDS at (stage + dst_off) + 16 * lane.  Written as assembly so
+    // that the waits stay ours: with the builtin the compiler makes every LDS read wait for all direct loads in flight.
+    auto issue_one = [&](const char* base, uint32_t stage_lds, int q) {
+        const uint32_t m0v = stage_lds + dst_off[q];
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(src_off[q]), "s"(base) : "m0", "memory");
+    };
+    // A half step: 16 MFMAs on (af, bfr), the 8 fragments of the next half into (an, bn) from stage address Rn, and one
+    // load per quarter (loads lq0 .. lq0+3 of the step whose first token row is lbase, into stage lstage).
+    auto half = [&](const bf8 (&af)[4], const bf8 (&bfr)[4], bf8 (&an)[4], bf8 (&bn)[4], const char* Rn, const char* lbase,
+                    uint32_t lstage, int lq0) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            issue_one(lbase, lstage, lq0 + a);
+            // in the order the next half's MFMAs want them
+            if (a == 0) { an[0] = read_frag(Rn + offA[0]); bn[0] = read_frag(Rn + offB[0]); }
+            if (a == 1) { bn[1] = read_frag(Rn + offB[1]); bn[2] = read_frag(Rn + offB[2]); }
+            if (a == 2) { bn[3] = read_frag(Rn + offB[3]); an[1] = read_frag(Rn + offA[1]); }
+            if (a == 3) { an[2] = read_frag(Rn + offA[2]); an[3] = read_frag(Rn + offA[3]); }
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+            // one LDS read behind each MFMA instead of a block of reads, then a block of MFMAs
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // The loads of step k are issued during steps k-AHEAD (second half) and k-AHEAD+1 (first half).  Past the end of the
+    // token range the last step is simply loaded again (into a stage nobody reads any more) and the fragments read for
+    // the "next" half are not used: every step then runs the same instructions with the same number of loads in flight,
+    // the loop needs no special first or last iterations, and the wait counts are constants.
+    constexpr int AHEAD = NSTAGE - 1;
+    const int last = n_steps - 1;
+    auto step_base = [&](int k) { return xbase + (int64_t)(k < last ? k : last) * step_bytes; };
+    for (int k = 0; k < AHEAD - 1; ++k)
+#pragma unroll
+        for (int q = 0; q < PW; ++q) issue_one(step_base(k), lds_base + k * STAGE, q);
+#pragma unroll
+    for (int q = 0; q < PW / 2; ++q) issue_one(step_base(AHEAD - 1), lds_base + (AHEAD - 1) * STAGE, q);
+    wait_vmem<(AHEAD - 2) * PW + PW / 2>();                    // step 0 has landed
+    stage_barrier();
+    bf8 a0[4], b0[4], a1[4], b1[4];
+    a0[0] = read_frag(lds + offA[0]);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) b0[b] = read_frag(lds + offB[b]);
+#pragma unroll
+    for (int b = 1; b < 4; ++b) a0[b] = read_frag(lds + offA[b]);
+    int slot = 0;                                              // stage of the current step
+    for (int step = 0; step < n_steps; ++step) {
+        const char* At = lds + slot * STAGE;
+        int s1 = slot + AHEAD - 1; if (s1 >= NSTAGE) s1 -= NSTAGE;
+        // first half: tokens 0..15; fragments of tokens 16..31; the second half of step+AHEAD-1's loads
+        half(a0, b0, a1, b1, At + 16 * ROWB, step_base(step + AHEAD - 1), lds_base + s1 * STAGE, PW / 2);
+        wait_vmem<(AHEAD - 2) * PW>();                         // step+1 has landed (each wavefront waits for its own loads)
+        stage_barrier();                                       // ... everybody's; and the stage of step-1 is free
+        int s2 = slot + AHEAD; if (s2 >= NSTAGE) s2 -= NSTAGE;
+        int sn = slot + 1; if (sn >= NSTAGE) sn -= NSTAGE;
+        // second half: tokens 16..31; fragments of the next step's tokens 0..15; the first half of step+AHEAD's loads
+        half(a1, b1, a0, b0, lds + sn * STAGE, step_base(step + AHEAD), lds_base + s2 * STAGE, 0);
+        slot = sn;
+    }
+    wait_vmem<0>();            // nothing may still be on its way into LDS when the workgroup ends
+}
+
+// Edge tiles and ragged token ranges: through registers with zero fill, one stage, same LDS layout.
+__device__ __forceinline__ void hessian_tile_plain(const uint16_t* __restrict__ X, int64_t d_in, int64_t i0, int64_t j0, bool diag,
+                                                   int64_t t_begin, int64_t t_end, char* lds, f16v (&acc)[4][4]) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
     const int jj = lane & 15, gg = lane >> 4;
     const int rd_row = (8 * (gg >> 1) + (jj >> 2)) * ROWB + 8 * (jj & 1);
     const int rd_chunk = 2 * (gg & 1) + ((jj & 3) >> 1), rd_swz = jj & 12;
@@ -159,149 +256,167 @@ __global__ __launch_bounds__(256) void hessian_bf16_kernel(const uint16_t* __res
     for (int b = 0; b < 4; ++b) offA[b] = rd_row + (((wm * 16 + 4 * b + rd_chunk) ^ rd_swz) << 4);
 #pragma unroll
     for (int b = 0; b < 4; ++b) offB[b] = rd_row + (((wn * 16 + 4 * b + rd_chunk) ^ rd_swz) << 4);
-
-    // one wavefront per SIMD: the fragments of the next 16-token sub-step are fetched while the MFMAs of the
-    // current one run (the matrix core works asynchronously to the wavefront's instruction stream)
-    auto load_frags = [&](const char* At, const char* Bt, int ks, bf8 (&af)[4], bf8 (&bfr)[4]) {
-        // in the order the MFMAs below want them: the first row block, all column blocks, the other row blocks
-        af[0] = read_frag(At + offA[0] + ks * 16 * ROWB);
+    const int n_steps = (int)((t_end - t_begin + BKS - 1) / BKS);
+    const int cpos = tid & 31, rgrp = tid >> 5;                 // 8 row groups of 4 token rows, 32 chunks per row
+    const char* At = lds;
+    const char* Bt = diag ? At : At + TILE_BYTES;
+    for (int step = 0; step < n_steps; ++step) {
+        const int64_t t0 = t_begin + (int64_t)step * BKS;
+        u4 r[2][4];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) bfr[b] = read_frag(Bt + offB[b] + ks * 16 * ROWB);
+        for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-        for (int b = 1; b < 4; ++b) af[b] = read_frag(At + offA[b] + ks * 16 * ROWB);
-    };
-    auto mfmas = [&](const bf8 (&af)[4], const bf8 (&bfr)[4]) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
-    };
-    auto interleave = [&]() {          // ask for one LDS read behind each MFMA instead of a block of reads, then a block of MFMAs
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-    };
-    auto compute = [&](int stage) {    // plain form, for the path through registers
-        const char* At = lds + stage * 2 * TILE_BYTES;
-        const char* Bt = diag ? At : At + TILE_BYTES;
-        static_assert(BKS == 32, "two sub-steps per step");
-        bf8 a0[4], b0[4], a1[4], b1[4];
-        load_frags(At, Bt, 0, a0, b0);
-        load_frags(At, Bt, 1, a1, b1);
-        mfmas(a0, b0);
-        mfmas(a1, b1);
-    };
-
-    const bool interior = (i0 + T2 <= d_in) && (j0 + T2 <= d_in);
-    if (n_steps <= 0) {
-        // empty token range: the partial tile is zero
-    } else if (interior && (t_end - t_begin) % BKS == 0) {
-        // ---- direct global->LDS loads, NSTAGE-1 steps ahead.  A step's tiles are 32 (16 on the diagonal) loads of two
-        // token rows each; wavefront w issues loads w, w+8, ... so every wavefront has the same number in flight.
-        // Per load q the lane's byte offset from the first token row of the step is fixed; only a scalar base moves
-        // from step to step, so issuing a step's loads costs a handful of scalar instructions.
-        const int per_wave = diag ? 4 : 8;
-        const int lrow = lane >> 5, lpos = lane & 31;
-        uint32_t src_off[8];
-        uint32_t dst_off[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int g = wave + 4 * q;                           // 0..15: A tile, 16..31: B tile
-            const int op = g >> 4, row = 2 * (g & 15) + lrow;
-            const int chunk = lpos ^ (4 * (row & 3));
-            src_off[q] = (uint32_t)(((int64_t)row * d_in + (op ? j0 - i0 : 0) + 8 * chunk) * 2);
-            dst_off[q] = (uint32_t)(op * TILE_BYTES + 2 * (g & 15) * ROWB);
-        }
-        const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds;
-        const char* xbase = reinterpret_cast<const char*>(X + t_begin * d_in + i0);
-        const int64_t step_bytes = (int64_t)BKS * d_in * 2;
-        auto issue = [&](int step) {
-            const char* base = xbase + (int64_t)step * step_bytes;
-            const uint32_t stage_lds = lds_base + (uint32_t)((step % NSTAGE) * 2 * TILE_BYTES);
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                if (q < per_wave) {
-                    const uint32_t m0v = __builtin_amdgcn_readfirstlane(stage_lds + dst_off[q]);
-                    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(src_off[q]), "s"(base) : "m0", "memory");
-                }
+            for (int q = 0; q < 4; ++q) {
+                const int row = rgrp * 4 + q;
+                const int64_t t = t0 + row, col = (hf ? j0 : i0) + 8 * (cpos ^ (4 * q));
+                r[hf][q] = (u4){0u, 0u, 0u, 0u};
+                if (!(hf && diag) && t < t_end && col < d_in) r[hf][q] = *reinterpret_cast<const u4*>(X + t * d_in + col);
             }
-        };
-        // Software pipeline over half steps.  While the MFMAs of one 16-token half run, the fragments of the next half
-        // are read; the barrier sits between the two halves of a step: behind it the next step's tiles are visible
-        // (each wavefront has waited for its own loads) and the previous step's stage is free for new loads.
-        auto wait_loads = [&](int groups_left) {          // until at most `groups_left` steps' worth of this wavefront's loads are pending
-            if (diag) { if (groups_left >= 2) wait_vmem<8>(); else if (groups_left == 1) wait_vmem<4>(); else wait_vmem<0>(); }
-            else      { if (groups_left >= 2) wait_vmem<16>(); else if (groups_left == 1) wait_vmem<8>(); else wait_vmem<0>(); }
-        };
-        static_assert(NSTAGE == 4, "the wait counts below assume three steps in flight");
-        const int pro = n_steps < NSTAGE - 1 ? n_steps : NSTAGE - 1;
-        for (int s0 = 0; s0 < pro; ++s0) issue(s0);
-        wait_loads(pro - 1);
+        __syncthreads();                 // previous step's reads are done
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (!(hf && diag))
+                    *reinterpret_cast<u4*>(lds + hf * TILE_BYTES + (rgrp * 4 + q) * ROWB + cpos * 16) = r[hf][q];
         __syncthreads();
-        bf8 a0[4], b0[4], a1[4], b1[4];
-        load_frags(lds, diag ? lds : lds + TILE_BYTES, 0, a0, b0);
-        for (int step = 0; step + 1 < n_steps; ++step) {
-            const char* At = lds + (step % NSTAGE) * 2 * TILE_BYTES;
-            const char* Bt = diag ? At : At + TILE_BYTES;
-            load_frags(At, Bt, 1, a1, b1);
-            mfmas(a0, b0);
-            interleave();
-            const int in_flight = (n_steps - 1 - step < NSTAGE - 2) ? n_steps - 1 - step : NSTAGE - 2;   // steps step+1 .. already issued
-            wait_loads(in_flight - 1);
-            __syncthreads();
-            if (step + NSTAGE - 1 < n_steps) issue(step + NSTAGE - 1);       // into the stage of step-1, which nobody reads any more
-            const char* An = lds + ((step + 1) % NSTAGE) * 2 * TILE_BYTES;
-            load_frags(An, diag ? An : An + TILE_BYTES, 0, a0, b0);
-            mfmas(a1, b1);
-            interleave();
-        }
-        {       // last step: nothing left to fetch behind it
-            const char* At = lds + ((n_steps - 1) % NSTAGE) * 2 * TILE_BYTES;
-            load_frags(At, diag ? At : At + TILE_BYTES, 1, a1, b1);
-            mfmas(a0, b0);
-            mfmas(a1, b1);
-        }
-    } else {
-        // ---- edge tiles / ragged token range: through registers with zero fill, one stage, same layout
-        const int cpos = tid & 31, rgrp = tid >> 5;                 // 8 row groups of 4 token rows, 32 chunks per row
-        for (int step = 0; step < n_steps; ++step) {
-            const int64_t t0 = t_begin + (int64_t)step * BKS;
-            u4 r[2][4];
 #pragma unroll
-            for (int half = 0; half < 2; ++half)
+        for (int ks = 0; ks < 2; ++ks) {
+            bf8 af[4], bfr[4];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int row = rgrp * 4 + q;
-                    const int64_t t = t0 + row, col = (half ? j0 : i0) + 8 * (cpos ^ (4 * q));
-                    r[half][q] = (u4){0u, 0u, 0u, 0u};
-                    if (!(half && diag) && t < t_end && col < d_in) r[half][q] = *reinterpret_cast<const u4*>(X + t * d_in + col);
-                }
-            __syncthreads();                 // previous step's reads are done
+            for (int b = 0; b < 4; ++b) {
+                af[b] = read_frag(At + offA[b] + ks * 16 * ROWB);
+                bfr[b] = read_frag(Bt + offB[b] + ks * 16 * ROWB);
+            }
 #pragma unroll
-            for (int half = 0; half < 2; ++half)
+            for (int a = 0; a < 4; ++a)
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (!(half && diag))
-                        *reinterpret_cast<u4*>(lds + half * TILE_BYTES + (rgrp * 4 + q) * ROWB + cpos * 16) = r[half][q];
-            __syncthreads();
-            compute(0);
+                for (int b = 0; b < 4; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
         }
     }
-    // 32x32 result block: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
-    float* dst = out + (int64_t)blockIdx.z * split_stride;
+}
+
+// 32x32 result block: lane l, element v -> row 8*(v/4) + 4*(l/32) + v%4, column l%32
+__device__ __forceinline__ void hessian_tile_store(const f16v (&acc)[4][4], int64_t d_in, int64_t i0, int64_t j0, float* __restrict__ dst,
+                                                   int64_t ld, bool add_old) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int64_t row = i0 + wm * 128 + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
-                const int64_t col = j0 + wn * 128 + b * 32 + (lane & 31);
-                if (row < d_in && col < d_in) dst[row * d_in + col] = acc[a][b][v];
+                const int row = wm * 128 + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
+                const int col = wn * 128 + b * 32 + (lane & 31);
+                if (i0 + row < d_in && j0 + col < d_in) {
+                    float* p = dst + row * ld + col;
+                    *p = add_old ? acc[a][b][v] + *p : acc[a][b][v];
+                }
             }
+}
+
+// The plain path as a function of its own (a call, not inlined): the compiler then places its 256 accumulators without
+// regard to the pipelined loop's.
+__device__ __attribute__((noinline)) void hessian_tile_slow(const uint16_t* __restrict__ X, int64_t d_in, int I, int J, int64_t t_begin,
+                                                            int64_t t_end, float* __restrict__ dst, int64_t ld, bool add_old, char* lds) {
+    const int64_t i0 = (int64_t)I * T2, j0 = (int64_t)J * T2;
+    f16v acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+    if (t_end > t_begin) hessian_tile_plain(X, d_in, i0, j0, I == J, t_begin, t_end, lds, acc);       // an empty range leaves the partial tile zero
+    hessian_tile_store(acc, d_in, i0, j0, dst, ld, add_old);
+}
+
+// One work item: tile (I, J) over the tokens [t_begin, t_end).  `dst` points at the tile's first element in a matrix of
+// leading dimension `ld` (H itself, a split's partial matrix, or a 256 x 256 slot).  `add_old`: add what dst holds
+// (streaming over chunks of tokens).  The two paths are kept apart down to the store, so that the 256 accumulators of
+// one never have to be reconciled with those of the other.
+__device__ __forceinline__ void hessian_tile(const uint16_t* __restrict__ X, int64_t d_in, int I, int J, int64_t t_begin, int64_t t_end,
+                                             float* __restrict__ dst, int64_t ld, bool add_old, char* lds) {
+    const int64_t i0 = (int64_t)I * T2, j0 = (int64_t)J * T2;
+    const bool interior = (i0 + T2 <= d_in) && (j0 + T2 <= d_in);
+    const int64_t len = t_end - t_begin;
+    if (interior && len > 0 && len % BKS == 0) {
+        f16v acc[4][4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+        hessian_tile_pipelined(X, d_in, i0, j0, t_begin, (int)(len / BKS), lds, acc);
+        hessian_tile_store(acc, d_in, i0, j0, dst, ld, add_old);
+    } else {
+        hessian_tile_slow(X, d_in, I, J, t_begin, t_end, dst, ld, add_old, lds);
+    }
+}
+
+// Small matrices: one workgroup per (tile, token split); every split writes its partial matrix, the finalize kernel adds them.
+__global__ __launch_bounds__(256) void hessian_bf16_kernel(const uint16_t* __restrict__ X, int64_t n, int64_t d_in,
+                                                           int n_t, int64_t tokens_per_split,
+                                                           float* __restrict__ out, int64_t split_stride) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];       // [NSTAGE][A tile | B tile]
+    int I, J;
+    tile_from_linear(blockIdx.x, n_t, &I, &J);
+    const int64_t t_begin = (int64_t)blockIdx.z * tokens_per_split;
+    const int64_t t_end = (t_begin + tokens_per_split < n) ? t_begin + tokens_per_split : n;
+    hessian_tile(X, d_in, I, J, t_begin, t_end, out + (int64_t)blockIdx.z * split_stride + (int64_t)I * T2 * d_in + (int64_t)J * T2, d_in,
+                 false, lds);
+}
+
+// Large matrices: workgroup w is the (w / 8)-th of XCD w % 8 and works through that XCD's share of the tile list (see the top
+// of this file): whole tiles go straight into H (added to what is there when accumulating), slices of the share's last
+// tiles go to their slot of `partial` ([8 XCDs][32 slots][256 x 256]).
+__global__ __launch_bounds__(256) void hessian_bf16_balanced_kernel(const uint16_t* __restrict__ X, int64_t n, int64_t d_in, int n_t,
+                                                                    int tiles, float* __restrict__ H, int accumulate,
+                                                                    float* __restrict__ partial) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int x = blockIdx.x % kXcds, k = blockIdx.x / kXcds;
+    const XcdShare sh = xcd_share(x, tiles);
+    int I, J;
+    if (k < sh.whole) {
+        tile_from_list(sh.first + k, n_t, &I, &J);
+        hessian_tile(X, d_in, I, J, 0, n, H + (int64_t)I * T2 * d_in + (int64_t)J * T2, d_in, accumulate != 0, lds);
+        return;
+    }
+    const int e = k - sh.whole;                   // slice e % slices of the share's (e / slices)-th leftover tile
+    if (e >= sh.rest * sh.slices) return;
+    tile_from_list(sh.first + sh.whole + e / sh.slices, n_t, &I, &J);
+    int64_t per = (n + sh.slices - 1) / sh.slices;
+    per = (per + BK16 - 1) / BK16 * BK16;
+    const int64_t t_begin = (int64_t)(e % sh.slices) * per;
+    const int64_t t_end = t_begin + per < n ? t_begin + per : n;
+    hessian_tile(X, d_in, I, J, t_begin, t_end, partial + ((int64_t)x * kCusPerXcd + e) * T2 * T2, T2, false, lds);
+}
+
+// The leftover tiles of every XCD's share: H tile = (previous H tile when accumulating) + the slices' partial tiles in
+// ascending order.  Grid: (leftover tile, XCD, 16 blocks of 16 rows); 256 threads = the tile's columns.
+__global__ __launch_bounds__(256) void hessian_add_slices_kernel(const float* __restrict__ partial, float* __restrict__ H, int64_t d_in, int n_t,
+                                                                 int tiles, int accumulate) {
+    const int x = blockIdx.y, r = blockIdx.x;
+    const XcdShare sh = xcd_share(x, tiles);
+    if (r >= sh.rest) return;
+    int I, J;
+    tile_from_list(sh.first + sh.whole + r, n_t, &I, &J);
+    const float* src = partial + ((int64_t)x * kCusPerXcd + (int64_t)r * sh.slices) * T2 * T2;
+    const int64_t i0 = (int64_t)I * T2, j0 = (int64_t)J * T2;
+    const int col = threadIdx.x;
+    if (j0 + col >= d_in) return;
+#pragma unroll 4
+    for (int rr = 0; rr < 16; ++rr) {
+        const int row = blockIdx.z * 16 + rr;
+        if (i0 + row < d_in) {
+            float* h = H + (i0 + row) * d_in + j0 + col;
+            float v = accumulate ? *h : 0.0f;
+            for (int z = 0; z < sh.slices; ++z) v += src[((int64_t)z * T2 + row) * T2 + col];
+            *h = v;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------ fp32
@@ -462,16 +577,74 @@ int choose_splits(int64_t n, int64_t d_in, int bk, int tile) {
     return (int)splits;
 }
 
+bool use_balanced(int x_dtype, int64_t d_in) { return x_dtype == CDQ_BF16 && (d_in + T2 - 1) / T2 >= kBalancedMinTiles; }
+constexpr size_t kSliceSlotsBytes = (size_t)kXcds * kCusPerXcd * T2 * T2 * sizeof(float);      // 64 MiB
+
 }  // namespace
 
 size_t hessian_workspace_bytes(int64_t n, int64_t d_in) {
-    const int s32 = choose_splits(n, d_in, BK32, TB), s16 = choose_splits(n, d_in, BK16, T2);
-    const int splits = s32 > s16 ? s32 : s16;          // the dtype is not known here: cover both paths
-    return cdq_align_up((size_t)splits * d_in * d_in * sizeof(float), 256) + 256;
+    // the dtype is not known here: cover both paths
+    const int s32 = choose_splits(n, d_in, BK32, TB);
+    size_t bytes = cdq_align_up((size_t)s32 * d_in * d_in * sizeof(float), 256);
+    const size_t b16 = use_balanced(CDQ_BF16, d_in) ? kSliceSlotsBytes
+                                                    : cdq_align_up((size_t)choose_splits(n, d_in, BK16, T2) * d_in * d_in * sizeof(float), 256);
+    if (b16 > bytes) bytes = b16;
+    return bytes + 256;
 }
+
+namespace {
+
+int launch_damping(float* H, int64_t d_in, float lambda_rel, float* mean_slot, hipStream_t st) {
+    hipLaunchKernelGGL(diag_mean_kernel, dim3(1), dim3(1024), 0, st, H, d_in, mean_slot);
+    CDQ_LAUNCH_CHECK();
+    hipLaunchKernelGGL(add_damping_kernel, dim3((unsigned)((d_in + 255) / 256)), dim3(256), 0, st, H, d_in, lambda_rel, mean_slot);
+    CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
+
+// bf16, at least kBalancedMinTiles tiles per side: whole tiles straight into H, the leftover tiles of every XCD's share in
+// token slices through 64 MiB of workspace, then the mirror
+int hessian_launch_balanced(const uint16_t* X, int64_t n, int64_t d_in, float* H, bool accumulate, float lambda_rel, void* ws,
+                            size_t ws_bytes, hipStream_t st) {
+    const int64_t n_t = (d_in + T2 - 1) / T2;
+    const int64_t tiles64 = n_t * (n_t + 1) / 2;
+    if (tiles64 > 0x3fffffffLL) return CDQ_EUNSUPPORTED;
+    const int tiles = (int)tiles64;
+    if (ws == nullptr || ((uintptr_t)ws & 255) || ws_bytes < kSliceSlotsBytes + 256) return CDQ_EWORKSPACE;
+    float* partial = (float*)ws;
+    float* mean_slot = (float*)((char*)ws + kSliceSlotsBytes);
+    static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(hessian_bf16_balanced_kernel),
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize, HESS_LDS);
+    if (attr_rc != hipSuccess) return CDQ_EHIP;
+    int per_xcd = 0, max_rest = 0;
+    for (int x = 0; x < kXcds; ++x) {
+        const XcdShare sh = xcd_share(x, tiles);
+        const int w = sh.whole + sh.rest * sh.slices;
+        if (w > per_xcd) per_xcd = w;
+        if (sh.rest > max_rest) max_rest = sh.rest;
+    }
+    hipLaunchKernelGGL(hessian_bf16_balanced_kernel, dim3((unsigned)(kXcds * per_xcd)), dim3(256), HESS_LDS, st, X, n, d_in, (int)n_t, tiles, H,
+                       accumulate ? 1 : 0, partial);
+    CDQ_LAUNCH_CHECK();
+    if (max_rest > 0) {
+        hipLaunchKernelGGL(hessian_add_slices_kernel, dim3((unsigned)max_rest, kXcds, T2 / 16), dim3(256), 0, st, partial, H, d_in, (int)n_t, tiles,
+                           accumulate ? 1 : 0);
+        CDQ_LAUNCH_CHECK();
+    }
+    const int64_t nb = (d_in + 31) / 32;
+    if (nb > 65535) return CDQ_EUNSUPPORTED;
+    // the upper triangle is complete: one split, in place, nothing to add -- the finalize kernel only mirrors
+    hipLaunchKernelGGL(hessian_finalize_kernel, dim3((unsigned)nb, (unsigned)nb), dim3(256), 0, st, H, 1, d_in * d_in, H, d_in, (int)nb, 0);
+    CDQ_LAUNCH_CHECK();
+    if (lambda_rel != 0.0f) return launch_damping(H, d_in, lambda_rel, mean_slot, st);
+    return CDQ_OK;
+}
+
+}  // namespace
 
 int hessian_launch(const void* X, int x_dtype, int64_t n, int64_t d_in, float* H, int accumulate, float lambda_rel,
                    void* ws, size_t ws_bytes, hipStream_t st) {
+    if (use_balanced(x_dtype, d_in)) return hessian_launch_balanced((const uint16_t*)X, n, d_in, H, accumulate != 0, lambda_rel, ws, ws_bytes, st);
     const int bk = (x_dtype == CDQ_BF16) ? BK16 : BK32;
     const int tile = (x_dtype == CDQ_BF16) ? T2 : TB;
     int splits = choose_splits(n, d_in, bk, tile);
@@ -493,10 +666,7 @@ int hessian_launch(const void* X, int x_dtype, int64_t n, int64_t d_in, float* H
         static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(hessian_bf16_kernel),
                                                               hipFuncAttributeMaxDynamicSharedMemorySize, HESS_LDS);
         if (attr_rc != hipSuccess) return CDQ_EHIP;
-        const bool patched = n_t >= 24;                  // enough tiles for every XCD to fill whole patches
-        if (patched) grid.x = (unsigned)(8 * ((patch_count((int)n_t) + 7) / 8) * PATCH_R * PATCH_C);
-        hipLaunchKernelGGL(hessian_bf16_kernel, grid, dim3(256), HESS_LDS, st, (const uint16_t*)X, n, d_in, (int)n_t, per, parts, stride,
-                           patched ? 1 : 0);
+        hipLaunchKernelGGL(hessian_bf16_kernel, grid, dim3(256), HESS_LDS, st, (const uint16_t*)X, n, d_in, (int)n_t, per, parts, stride);
     }
     else
         hipLaunchKernelGGL(hessian_f32_kernel, grid, dim3(256), 0, st, (const float*)X, n, d_in, (int)n_t, per, parts, stride);
@@ -506,12 +676,7 @@ int hessian_launch(const void* X, int x_dtype, int64_t n, int64_t d_in, float* H
     hipLaunchKernelGGL(hessian_finalize_kernel, dim3((unsigned)nb, (unsigned)nb), dim3(256), 0, st, parts, splits, stride, H, d_in,
                        (int)nb, accumulate);
     CDQ_LAUNCH_CHECK();
-    if (lambda_rel != 0.0f) {
-        hipLaunchKernelGGL(diag_mean_kernel, dim3(1), dim3(1024), 0, st, H, d_in, mean_slot);
-        CDQ_LAUNCH_CHECK();
-        hipLaunchKernelGGL(add_damping_kernel, dim3((unsigned)((d_in + 255) / 256)), dim3(256), 0, st, H, d_in, lambda_rel, mean_slot);
-        CDQ_LAUNCH_CHECK();
-    }
+    if (lambda_rel != 0.0f) return launch_damping(H, d_in, lambda_rel, mean_slot, st);
     return CDQ_OK;
 }
 

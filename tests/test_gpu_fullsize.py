@@ -52,7 +52,21 @@ def check_hessian_samples(H, X, n_samples=4096, seed=0):
     assert np.array_equal(H[ii, kk], H[kk, ii])
 
 
-def run_layer(cdq, oracle, cfg, d_out, T, sample_cols, q0_random=False, seed=0):
+def recheck_diverged_columns(cdq, oracle, Hd, H32, Wt, a, b, q0, cols_bad, bits, group, T, shape):
+    """Columns whose final codes differ from the oracle's: rerun them on the GPU with a move trace, in the launch
+    shape of the full run, and require the first different move to be a tie of the two candidates' scores."""
+    from test_gpu_parity import assert_divergence_is_tie
+    for j in cols_bad:
+        sl = slice(j, j + 1)
+        Qd = torch.from_numpy(q0[sl].copy()).cuda()
+        out = cdq.greedy_cd(Hd, torch.from_numpy(np.ascontiguousarray(Wt[sl])).cuda(), torch.from_numpy(a[sl].copy()).cuda(),
+                            torch.from_numpy(b[sl].copy()).cuda(), Qd, bits, group, T, trace_cap=T,
+                            waves_per_column=shape[0], elems_per_lane=shape[1])
+        ref = oracle.greedy_cd(H32, Wt[sl], a[sl], b[sl], q0[sl], bits, group, T, trace_cap=T)
+        assert_divergence_is_tie(oracle, ref, out["trace"].cpu().numpy()[0], 0, H32, Wt[sl], a[sl], b[sl], q0[sl], bits, group)
+
+
+def run_layer(cdq, oracle, cfg, d_out, T, sample_cols, q0_random=False, seed=0, include_busiest=0):
     say(f"{cfg.name}: generating X [{cfg.n}x{cfg.d_in}] and Wt [{d_out}x{cfg.d_in}]")
     X, Wt = inputs.make_layer(cfg, d_out=d_out)
     Xd = x_to_dev(X, cfg.x_dtype)
@@ -87,8 +101,11 @@ def run_layer(cdq, oracle, cfg, d_out, T, sample_cols, q0_random=False, seed=0):
     assert np.all(changed <= stats[:, 0])
     # sampled columns through the oracle
     rng = np.random.default_rng(seed + 1)
-    cols = np.sort(rng.choice(d_out, size=min(sample_cols, d_out), replace=False))
-    say(f"oracle on {len(cols)} sampled columns")
+    cols = rng.choice(d_out, size=min(sample_cols, d_out), replace=False)
+    if include_busiest:                 # the longest trajectories are where drift of the gradient would show
+        cols = np.concatenate([cols, np.argsort(-stats[:, 0], kind="stable")[:include_busiest]])
+    cols = np.unique(cols)
+    say(f"oracle on {len(cols)} sampled columns for the full T={T} (most moves in the sample: {int(stats[cols, 0].max())})")
     ref = oracle.greedy_cd(H32, Wt[cols], a[cols], b[cols], q0[cols], cfg.bits, cfg.group, T)
     same = Qn[cols] == ref["Q"]
     frac = same.mean()
@@ -97,6 +114,10 @@ def run_layer(cdq, oracle, cfg, d_out, T, sample_cols, q0_random=False, seed=0):
     assert frac >= 0.999
     good = same.all(axis=1)
     assert good.mean() >= 0.98, "too many sampled columns diverged"
+    if not good.all():
+        say(f"columns {cols[~good].tolist()} differ: checking that each diverges at a tie")
+        recheck_diverged_columns(cdq, oracle, Hd, H32, Wt, a, b, q0, cols[~good].tolist(), cfg.bits, cfg.group, T,
+                                 cdq.greedy_cd_shape(d_out, cfg.d_in, cfg.group))
     assert np.array_equal(stats[cols][good, 0], ref["moves"][good])
     assert np.array_equal(stats[cols][good, 2], ref["converged"][good])
     l_ref = oracle.loss(H32, Wt[cols], ref["Q"], a[cols], b[cols], cfg.group)
@@ -125,16 +146,21 @@ def test_mlp_up_column_subset(cdq, oracle):
 
 
 def test_mlp_down_column_subset(cdq, oracle):
-    """d_in = 16384 (H is 1 GiB): 256 columns, first 192 iterations, 8 wavefronts per column."""
+    """d_in = 16384 (H is 1 GiB): 256 columns in the full layer's launch shape for the configured T = 16384; the
+    oracle reruns 10 random columns and the 4 with the most moves (several thousand each) for that full budget."""
     cfg = inputs.CONFIGS["mlp_down"]
-    run_layer(cdq, oracle, cfg, 256, 192, sample_cols=24)
+    assert cdq.greedy_cd_shape(256, cfg.d_in, cfg.group) == cdq.greedy_cd_shape(cfg.d_out, cfg.d_in, cfg.group)
+    stats = run_layer(cdq, oracle, cfg, 256, cfg.T, sample_cols=10, include_busiest=4)
+    assert stats[:, 0].max() > 2000, "the sample should contain long trajectories"
 
 
 def test_large_owc_init_column_subset(cdq, oracle):
-    """d_in = 8192, 3-bit per-channel with the scale chosen by OWC (grid of 50), then greedy CD:
-    256 columns on the GPU, 16 of them through the oracle (OWC and 256 CD iterations)."""
+    """d_in = 8192, 3-bit per-channel with the scale chosen by OWC (grid of 50), then greedy CD for the configured
+    T = 8192: 256 columns on the GPU in the full layer's launch shape; 12 of them (8 random, the 4 with the most
+    moves) through the oracle's exhaustive fp64 grid search and its full-T CD."""
     cfg = inputs.CONFIGS["large"]
-    d_out, T = 256, 256
+    d_out, T = 256, cfg.T
+    assert cdq.greedy_cd_shape(d_out, cfg.d_in, cfg.group) == cdq.greedy_cd_shape(cfg.d_out, cfg.d_in, cfg.group)
     say(f"{cfg.name}: generating X [{cfg.n}x{cfg.d_in}] and Wt [{d_out}x{cfg.d_in}]")
     X, Wt = inputs.make_layer(cfg, d_out=d_out)
     Xd = x_to_dev(X, cfg.x_dtype)
@@ -158,20 +184,40 @@ def test_large_owc_init_column_subset(cdq, oracle):
     out = cdq.greedy_cd(Hd, Wd, scale, zero, Q, cfg.bits, cfg.group, T)
     l1 = cdq.loss(Hd, Wd, scale, zero, Q, cfg.group)[0].cpu().numpy()
     assert np.all(l1 <= per.cpu().numpy() * (1 + 1e-9))
-    cols = np.sort(np.random.default_rng(5).choice(d_out, size=16, replace=False))
-    say("oracle OWC + CD on 16 sampled columns")
-    a, b, q, gam, _ = oracle.init_owc(H32, Wt[cols], cfg.bits, cfg.group, 50)
+    stats = out["stats"].cpu().numpy()
+    assert np.all((stats[:, 2] == 1) | (stats[:, 0] == T))
+    cols = np.unique(np.concatenate([np.random.default_rng(5).choice(d_out, size=8, replace=False),
+                                     np.argsort(-stats[:, 0], kind="stable")[:4]]))
+    say(f"oracle OWC (exhaustive fp64 search) + CD for T={T} on {len(cols)} sampled columns; most moves in the sample {int(stats[cols, 0].max())}")
+    a, b, q, gam, l_all = oracle.init_owc(H32, Wt[cols], cfg.bits, cfg.group, 50)
+    l_owc = l_all.min(axis=0)                     # [n_gamma][columns] -> the loss of each column's best grid point
     g_gpu = gamma.cpu().numpy()[cols]
     same = g_gpu == gam
-    say(f"gamma equal on {int(same.sum())}/16 sampled columns; gamma range {gam.min():.2f}..{gam.max():.2f}")
-    assert same.sum() >= 15
+    say(f"gamma equal on {int(same.sum())}/{len(cols)} sampled columns; gamma range {gam.min():.2f}..{gam.max():.2f}")
+    # a different clipping strength is acceptable only where the two grid points' losses tie
+    per_n = per.cpu().numpy()
+    for c in np.where(~same)[0]:
+        assert abs(per_n[cols[c]] - l_owc[c]) <= 1e-6 * l_owc[c], (int(cols[c]), float(g_gpu[c]), float(gam[c]))
+    assert same.sum() >= len(cols) - 1
+    np.testing.assert_allclose(per_n[cols][same], l_owc[same], rtol=1e-6)
     assert np.array_equal(scale.cpu().numpy()[cols][same, 0], a[same, 0])
     assert np.array_equal(q0[cols][same], q[same])
-    ref = oracle.greedy_cd(H32, Wt[cols][same], a[same], b[same], q[same], cfg.bits, cfg.group, T)
-    eq = (Q.cpu().numpy()[cols][same] == ref["Q"]).mean()
-    say(f"CD codes equal on {eq:.6f} of sampled entries")
-    assert eq >= 0.999
-    assert np.array_equal(out["stats"].cpu().numpy()[cols][same, 0], ref["moves"])
+    cs = cols[same]
+    ref = oracle.greedy_cd(H32, Wt[cs], a[same], b[same], q[same], cfg.bits, cfg.group, T)
+    Qn = Q.cpu().numpy()
+    eq = Qn[cs] == ref["Q"]
+    say(f"CD codes equal on {eq.mean():.6f} of sampled entries; moves per sampled column {stats[cs, 0].tolist()}")
+    assert eq.mean() >= 0.999
+    good = eq.all(axis=1)
+    if not good.all():
+        say(f"columns {cs[~good].tolist()} differ: checking that each diverges at a tie")
+        recheck_diverged_columns(cdq, oracle, Hd, H32, Wt, scale.cpu().numpy(), zero.cpu().numpy(), q0, cs[~good].tolist(),
+                                 cfg.bits, cfg.group, T, cdq.greedy_cd_shape(d_out, cfg.d_in, cfg.group))
+    assert np.array_equal(stats[cs][good, 0], ref["moves"][good])
+    assert np.array_equal(stats[cs][good, 2], ref["converged"][good])
+    l_ref = oracle.loss(H32, Wt[cs], ref["Q"], a[same], b[same], cfg.group)
+    np.testing.assert_allclose(l1[cs][good], l_ref[good], rtol=1e-6)
+    assert abs(l1[cs].sum() - l_ref.sum()) <= 1e-4 * l_ref.sum()
 
 
 def test_mlp_up_owc_cd_init(cdq, oracle):

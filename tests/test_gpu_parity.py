@@ -91,6 +91,10 @@ def test_init_rtn_tiny_config(cdq, oracle):
     ("bf16", 512, 128), ("bf16", 333, 136), ("bf16", 4096, 392), ("bf16", 7, 8), ("bf16", 2500, 1024),
     # interior 256-wide tiles with 1, 2, 3, 4 and 5 steps of 32 tokens: every length of the load pipeline's start-up
     ("bf16", 32, 256), ("bf16", 64, 512), ("bf16", 96, 256), ("bf16", 128, 512), ("bf16", 160, 256), ("bf16", 1056, 768),
+    # 23 and more tiles per side: the tile list is shared out over the XCDs, whole tiles go straight into H and every
+    # share's leftover tiles are cut into token slices (ragged width and token count; slices long enough for the pipelined
+    # loop; a single token)
+    ("bf16", 200, 5896), ("bf16", 4096, 6144), ("bf16", 1, 6144),
 ])
 def test_hessian(cdq, oracle, x_dtype, n, d_in):
     X = inputs.make_x("outlier8x20", n, d_in, seed=n, x_dtype=x_dtype)
@@ -126,6 +130,26 @@ def test_hessian_accumulate_and_damping(cdq, oracle):
     # the damping really is there: compare the diagonal against the undamped oracle
     lam = 0.01 * np.mean(np.diag(oracle.hessian(X)))
     np.testing.assert_allclose(np.diag(Hn) - np.diag(oracle.hessian(X)), lam, rtol=1e-3)
+
+
+def test_hessian_accumulate_on_wide_layers(cdq, oracle):
+    """Streaming over token chunks where the tiles are shared out over the XCDs: whole tiles add to H in place, sliced tiles
+    through the partial sums; chunks of different lengths, the last one with damping."""
+    d_in = 6152
+    X = inputs.make_x("lognormal_scales", 1000, d_in, seed=5, x_dtype="bf16")
+    Xd = x_to_dev(X, "bf16")
+    H = cdq.hessian(Xd[:512].contiguous())
+    H = cdq.hessian(Xd[512:520].contiguous(), H=H, accumulate=True)
+    H = cdq.hessian(Xd[520:].contiguous(), H=H, accumulate=True, lambda_rel=0.02)
+    Hn = H.cpu().numpy()
+    assert np.array_equal(Hn, Hn.T)
+    ok, worst, fro = hessian_tolerance_ok(Hn, oracle.hessian(X, lambda_rel=0.02), 1000)
+    assert ok and fro <= 1e-5, (worst, fro)
+    # the same call twice gives the same bits (the slices are added in a fixed order)
+    H2 = cdq.hessian(Xd[:512].contiguous())
+    H2 = cdq.hessian(Xd[512:520].contiguous(), H=H2, accumulate=True)
+    H2 = cdq.hessian(Xd[520:].contiguous(), H=H2, accumulate=True, lambda_rel=0.02)
+    assert torch.equal(H, H2)
 
 
 def layer_with_exact_ties(seed=0, d_in=256, d_out=4, n=2000):
