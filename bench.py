@@ -204,8 +204,10 @@ class Layer:
         cdq.hessian(self.Xd, H=self.H, workspace=self.ws_h)
         rec(1)
         if init == "owc":
-            scale, zero, Q, gamma, _ = cdq.init_owc(self.H, self.Wd, cfg.bits, cfg.group, 50, workspace=self.ws_owc, want_loss=False)
+            scale, zero, Q, gamma, _, cnt = cdq.init_owc(self.H, self.Wd, cfg.bits, cfg.group, 50, workspace=self.ws_owc, want_loss=False,
+                                                         want_researched=True)
             self.state["gamma"] = gamma
+            self.state["owc_researched"] = cnt
         elif init == "owc_cd":
             o = cdq.init_owc_cd(self.H, self.Wd, cfg.bits, cfg.group, 50, workspace=self.ws_owc)
             scale, zero, Q = o["scale"], o["zero"], o["Q"]
@@ -315,11 +317,14 @@ def probes(cfg, H, shape, ev, stream, cdq, want_stream=True):
         ev.record(e1, stream)
         achievable["cache_stream_read_GBps_32MiB"] = 200 * small.numel() * 4 / (ev.elapsed_ms(e0, e1) * 1e-3) * 1e-9
         del small
-        for kind, key in ((0, "mfma_bf16_only_TFLOPs"), (1, "mfma_f64_only_TFLOPs")):
-            cdq.probe_mfma(kind, 256 * 2, 200, sink)
+        # the matrix cores alone, no memory traffic: on constant operands (the instruction rate at the clock an idle data
+        # path allows) and on pseudo-random ones (what the chip sustains when the operand bits toggle as real data does)
+        for kind, key, blocks, iters in ((0, "mfma_bf16_only_TFLOPs", 512, 20000), (2, "mfma_bf16_only_random_operands_TFLOPs", 1024, 4000),
+                                         (1, "mfma_f64_only_TFLOPs", 512, 5000)):
+            cdq.probe_mfma(kind, blocks, 200, sink)
             torch.cuda.synchronize()
             ev.record(e0, stream)
-            flop = cdq.probe_mfma(kind, 256 * 2, 20000 if kind == 0 else 5000, sink)
+            flop = cdq.probe_mfma(kind, blocks, iters, sink)
             ev.record(e1, stream)
             achievable[key] = flop / (ev.elapsed_ms(e0, e1) * 1e-3) * 1e-12
     waves = shape[0]
@@ -478,7 +483,10 @@ def main():
         "hessian": {"tflops_executed": h_tflops_exec, "tflops_effective": h_tflops_eff, "mfma_peak_tflops": mfma_peak,
                     "frac_of_mfma_peak": h_tflops_exec / mfma_peak,
                     "frac_of_measured_mfma_only": (h_tflops_exec / achievable["mfma_bf16_only_TFLOPs"])
-                    if cfg.x_dtype == "bf16" and "mfma_bf16_only_TFLOPs" in achievable else None},
+                    if cfg.x_dtype == "bf16" and "mfma_bf16_only_TFLOPs" in achievable else None,
+                    # the ceiling that binds on data: the matrix cores alone on pseudo-random operands (clock under that load included)
+                    "frac_of_measured_mfma_only_random_operands": (h_tflops_exec / achievable["mfma_bf16_only_random_operands_TFLOPs"])
+                    if cfg.x_dtype == "bf16" and "mfma_bf16_only_random_operands_TFLOPs" in achievable else None},
         "fp64_gemm": {"gradient_init_tflops": 2.0 * cfg.d_out * cfg.d_in * cfg.d_in / (stages["cd_gradient_init"] * 1e-3) * 1e-12,
                       # the loss multiplies only the 128-wide blocks of H on and above the diagonal (H is symmetric)
                       "loss_tflops_executed": 2.0 * cfg.d_out * 128.0 * 128.0 * sum(range(1, (cfg.d_in + 127) // 128 + 1))
@@ -490,6 +498,9 @@ def main():
     }
     if owc_cd_info is not None:
         result["owc_cd"] = owc_cd_info
+    if "owc_researched" in state:
+        # columns whose fp16 estimate of the grid search failed its check against the fp64 loss and were searched exhaustively
+        result["owc"] = {"grid": 50, "columns_searched_exhaustively": int(state["owc_researched"].item()), "ms": stages["init_grid"]}
 
     if not args.no_parity:
         # one more, untimed, step that keeps the start codes, then the oracle on sampled columns of exactly that run

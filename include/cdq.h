@@ -68,9 +68,18 @@ typedef struct {
     int32_t  elems_per_lane;    /* 0 = choose; else 4,8,16,32 coordinates held per lane; 24 or 36, and 32 for
                                    16-byte aligned layers, with 16 wavefronts are the kernel that keeps the
                                    Hessian diagonal in LDS, the one chosen for d_in above 16384 */
-    int32_t  exact_scorer_only; /* 0 = nearest-level scorer with the two-level scorer as arbiter
-                                   (default); 1 = two-level scorer on every iteration.  Both
-                                   select the same moves; 1 exists for testing and timing. */
+    int32_t  exact_scorer_only; /* 1 = two-level scorer on every iteration: per coordinate the two levels next to the
+                                   parabola's minimiser, both by the formula below -- the arg-min of Algorithm 1 over
+                                   all levels, unconditionally (about 1.3 times the loop time).
+                                   0 (default) = nearest-level scorer: one level per coordinate; the iteration is
+                                   redone with the two-level scorer when the winner's minimiser lies within 2^-9 of a
+                                   half-integer or no move was found.  A coordinate whose minimiser is farther than
+                                   that from a half-integer is scored identically by both.  The selected move can
+                                   differ from Algorithm 1's arg-min in one situation only: a coordinate OTHER than
+                                   the winner whose minimiser lies within 2^-15 of a half-integer gets the worse of
+                                   its two levels -- worse by at most 2^-15 a^2 H_ii + 2^-21 |s| -- and its better
+                                   level would have beaten the winner by less than that.  Both moves then lower the
+                                   loss, by amounts that agree to about 1e-5 of a grid step's worth. */
     int32_t  reserved;
     int32_t *trace;             /* NULL, or [d_out][trace_cap]: move m of column j is stored as
                                    i* * 64 + (u* + 32), u* = r* - q_i* the signed level change */
@@ -125,22 +134,24 @@ int cdq_init_rtn(const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t
  *   larger gamma.  Only the upper end is clipped, as Eq. (2) is written.
  * Needs group == d_in (one clipping strength per column), else CDQ_EUNSUPPORTED.
  *   scale, zero [d_out] out; Q [d_out][d_in] out; gamma_out NULL or [d_out] fp32;
- *   loss_out NULL or [d_out] fp64 (loss of the chosen grid; with NULL, columns whose choice is
- *   clear from the fp16 look described below are not evaluated in fp64 at all).
- * Cost.  When d_in is a multiple of 128 (at least 256) and 4 <= n_gamma <= 255, every grid point is
- * first evaluated in fp16 on the matrix cores in the normalised form s^2 f^T R f (R = H scaled to
- * unit diagonal, f = e sqrt(diag H) / s); its relative error stayed below 3e-4 on the test layers,
- * and only the grid points within 3e-3 of a column's smallest such value -- one or two per column --
- * go through the fp64 loss kernel, which decides among them as above.  The result equals that of
- * the exhaustive fp64 search unless the fp16 evaluation were off by more than that margin.
- * H then needs a positive diagonal to gain anything (otherwise every grid point is evaluated in
- * fp64, as it is for the other shapes): n_gamma passes of the loss kernel, d_out d_in^2 fp64 FLOP
- * each (H is taken to be symmetric and only its blocks on and above the diagonal are multiplied,
- * see cdq_loss).
+ *   loss_out NULL or [d_out] fp64 (loss of the chosen grid point);
+ *   researched NULL or one int32 (device): number of columns that failed the check below (not written when d_out == 0).
+ * Cost and safeguard.  The exhaustive search costs n_gamma passes of the fp64 loss kernel (d_out d_in^2 FLOP each).  When
+ * d_in is a multiple of 128 (at least 256) and 4 <= n_gamma <= 255, every grid point is first evaluated in fp16 on the
+ * matrix cores in the normalised form s^2 f^T R f (R = H scaled to unit diagonal, f = e sqrt(diag H) / s), and only the
+ * grid points within `screen_margin` (relative; 0 selects the default 3e-3) of a column's smallest such value -- one or
+ * two per column on typical layers -- are evaluated in fp64, which decides among them as above.  The fp16 value is an
+ * estimate (its relative error stayed below 3e-4 on the test layers, but it grows when channels are nearly collinear, where
+ * rounding R moves f^T R f), so it is checked column by column: the chosen grid point has both values, and a column where
+ * they differ by more than a third of the margin is searched exhaustively in fp64 after all.  The result therefore equals
+ * the exhaustive search's for every column that fails the check, and for the others whenever the fp16 error at the
+ * grid points that were not evaluated is no larger than the margin -- three times what was measured on that column.
+ * H needs a positive diagonal for the fp16 stage to say anything (otherwise every grid point fails over to fp64).
+ * H is taken to be symmetric and only its blocks on and above the diagonal are multiplied, see cdq_loss.
  */
 int cdq_init_owc(const float *H, const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t group,
-                 int n_gamma, float *scale, float *zero, uint8_t *Q, float *gamma_out, double *loss_out,
-                 void *workspace, size_t workspace_bytes, void *stream);
+                 int n_gamma, float screen_margin, float *scale, float *zero, uint8_t *Q, float *gamma_out,
+                 double *loss_out, int32_t *researched, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * OWC-CD, the paper's initialisation for sub-channel grids (Algorithm 3; Section 3.2,

@@ -56,7 +56,7 @@ def lib() -> ctypes.CDLL:
         L.cdq_greedy_cd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, sz, vp]
         L.cdq_greedy_cd_ex.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, ctypes.POINTER(CdOptions), vp, sz, vp]
         L.cdq_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
-        L.cdq_init_owc.argtypes = [vp, vp, i64, i64, i32, i64, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.cdq_init_owc.argtypes = [vp, vp, i64, i64, i32, i64, i32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cdq_init_owc.restype = i32
         L.cdq_score_argmin.argtypes = [vp, vp, vp, vp, i64, i64, i32, i64, vp, vp, vp, vp]
         L.cdq_gather_update.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp]
@@ -143,19 +143,25 @@ def init_rtn(Wt: torch.Tensor, bits: int, group: int):
     return scale, zero, Q
 
 
-def init_owc(H, Wt, bits: int, group: int, n_gamma: int = 50, workspace: torch.Tensor | None = None, want_loss: bool = True):
+def init_owc(H, Wt, bits: int, group: int, n_gamma: int = 50, workspace: torch.Tensor | None = None, want_loss: bool = True,
+             screen_margin: float = 0.0, want_researched: bool = False):
     """OWC grid search (per-channel).  Returns (scale, zero, Q, gamma, loss_per_col); loss_per_col is None when
-    want_loss is False (the library then skips the fp64 evaluation of columns whose choice is already clear)."""
+    want_loss is False.  With want_researched a sixth value: an int32 tensor [1], the number of columns whose fp16
+    estimate failed its check and were searched exhaustively in fp64."""
     d_out, d_in = Wt.shape
     scale = torch.empty((d_out, 1), dtype=torch.float32, device=Wt.device)
     zero = torch.empty((d_out, 1), dtype=torch.float32, device=Wt.device)
     Q = torch.empty((d_out, d_in), dtype=torch.uint8, device=Wt.device)
     gamma = torch.empty(d_out, dtype=torch.float32, device=Wt.device)
     per = torch.empty(d_out, dtype=torch.float64, device=Wt.device) if want_loss else None
+    cnt = torch.zeros(1, dtype=torch.int32, device=Wt.device) if want_researched else None
     ws = _workspace(OP_INIT_OWC, 0, d_out, d_in, workspace)
     _check(lib().cdq_init_owc(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), d_out, d_in, bits, group, n_gamma,
-                              scale.data_ptr(), zero.data_ptr(), Q.data_ptr(), gamma.data_ptr(), per.data_ptr() if want_loss else None,
+                              float(screen_margin), scale.data_ptr(), zero.data_ptr(), Q.data_ptr(), gamma.data_ptr(),
+                              per.data_ptr() if want_loss else None, cnt.data_ptr() if want_researched else None,
                               ws.data_ptr(), ws.numel(), _stream()), "cdq_init_owc")
+    if want_researched:
+        return scale, zero, Q, gamma, per, cnt
     return scale, zero, Q, gamma, per
 
 

@@ -12,10 +12,17 @@
 //        exact scorer: scores floor(rf) and ceil(rf), both with exactly the formula above, so it
 //                      selects what a scan of all 2^c levels would select (the levels left out
 //                      are >= 0.75 a^2 H_ii worse, far above rounding error).
-//      The two can only disagree when rf is within rounding distance of a half-integer (the two
-//      neighbouring levels tie) or when no strictly improving move is left.  The fast scorer
+//      For one coordinate the two can only disagree when rf is within rounding distance of a
+//      half-integer (within 2^-15: there the fp32 scores of the two neighbouring levels round to within
+//      a few units of each other) or when no strictly improving move is left.  The fast scorer
 //      therefore flags a winner whose rf lies within 2^-9 of a half-integer, and the iteration is
-//      redone with the exact scorer when the winner is flagged or when no move was found.
+//      redone with the exact scorer when the winner is flagged or when no move was found.  What this
+//      does not catch is a coordinate that is NOT the winner, sits within 2^-15 of a half-integer, was
+//      given the worse of its two levels (worse by at most 2^-15 a^2 H_ii + 2^-21 |s|) and would have
+//      won with the better one: the winner is then taken instead, a move whose gain agrees with the
+//      arg-min's to about 1e-5 of a grid step's worth.  Checking every coordinate costs three to five
+//      more vector instructions per coordinate in a loop that is bound by exactly those; callers that
+//      need Algorithm 1's arg-min unconditionally set exact_scorer_only.
 //   2. the team reduces (ordered score, then i, then level change) with unsigned minima: the
 //      result does not depend on the reduction tree and implements the tie-break "smallest s,
 //      then smallest i, then smallest r".  Within a wavefront: DPP minima over the 32-bit score

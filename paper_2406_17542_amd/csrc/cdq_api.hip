@@ -65,14 +65,15 @@ int cdq_init_rtn(const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t
 }
 
 int cdq_init_owc(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, int n_gamma,
-                 float* scale, float* zero, uint8_t* Q, float* gamma_out, double* loss_out, void* workspace,
-                 size_t workspace_bytes, void* stream) {
+                 float screen_margin, float* scale, float* zero, uint8_t* Q, float* gamma_out, double* loss_out,
+                 int32_t* researched, void* workspace, size_t workspace_bytes, void* stream) {
     if (bad_bits(bits) || bad_layer(d_out, d_in, group) || n_gamma < 1 || n_gamma > 4096) return CDQ_EINVAL;
+    if (!(screen_margin >= 0.0f) || screen_margin > 1.0f) return CDQ_EINVAL;
     if (group != d_in) return CDQ_EUNSUPPORTED;       // Eq. (2) has one clipping strength per column
     if (d_out == 0) return CDQ_OK;
     if (H == nullptr || Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr) return CDQ_EINVAL;
-    return cdq::owc_launch(H, Wt, d_out, d_in, bits, n_gamma, scale, zero, Q, gamma_out, loss_out, workspace, workspace_bytes,
-                           (hipStream_t)stream);
+    return cdq::owc_launch(H, Wt, d_out, d_in, bits, n_gamma, screen_margin, scale, zero, Q, gamma_out, loss_out, researched, workspace,
+                           workspace_bytes, (hipStream_t)stream);
 }
 
 int cdq_init_owc_cd(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, int n_gamma,

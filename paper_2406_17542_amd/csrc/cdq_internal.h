@@ -46,12 +46,12 @@ bool owc_screen_applies(int64_t d_out, int64_t d_in, int n_gamma);
 size_t owc_screen_workspace_bytes(int64_t d_out, int64_t d_in, int n_gamma, int64_t n_blocks);
 int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, const float* lo, const float* hi,
                       float margin, int block_rows, int64_t n_blocks, void* ws, uint8_t** cand_out, uint8_t** active_out,
-                      hipStream_t st);
+                      const float** screened_out, hipStream_t st);
 
 // ---- owc.hip
 size_t owc_workspace_bytes(int64_t d_out, int64_t d_in);
-int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, float* scale, float* zero,
-               uint8_t* Q, float* gamma_out, double* loss_out, void* ws, size_t ws_bytes, hipStream_t st);
+int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, float screen_margin, float* scale,
+               float* zero, uint8_t* Q, float* gamma_out, double* loss_out, int32_t* researched, void* ws, size_t ws_bytes, hipStream_t st);
 
 // ---- owc_cd.hip
 int owc_cd_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, int n_gamma, int64_t T,

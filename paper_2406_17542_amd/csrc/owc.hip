@@ -226,6 +226,30 @@ __global__ __launch_bounds__(256) void owc_update_best_rows_kernel(const double*
 
 constexpr float kScreenMargin = 3e-3f;      // relative; the fp16 evaluation was off by 3e-4 at most on heavy-tailed test layers
 
+// The check that makes the two-stage search safe to use: every column's chosen grid point has been evaluated both ways, so
+// the error of the fp16 look on this column is known there.  Where it exceeds a third of the margin (or is not a number) the
+// look is not trusted for the column: all grid points become its candidates, to be evaluated in fp64 by the rank passes that
+// follow, and the column is counted.  Every other column's candidate list is cleared.
+__global__ __launch_bounds__(256) void owc_guard_kernel(const float* __restrict__ screened, const double* __restrict__ best_loss,
+                                                        const float* __restrict__ best_gamma, int64_t d_out, int n_gamma, float margin,
+                                                        int block_rows, int64_t n_blocks, uint8_t* __restrict__ cand,
+                                                        uint8_t* __restrict__ active, int32_t* __restrict__ count) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_out) return;
+    const float g = best_gamma[j];
+    int k = (int)rintf(g * (float)n_gamma);                    // best_gamma is k / n_gamma in fp32
+    if (k < 1) k = 1;
+    if (k > n_gamma) k = n_gamma;
+    const double exact = best_loss[j], seen = (double)screened[(int64_t)(k - 1) * d_out + j];
+    // a residual of zero (exact == 0: a constant column) is screened as zero too
+    const bool trusted = (g > 0.0f) && (exact == seen || fabs(exact - seen) <= (double)(margin / 3.0f) * fabs(exact));
+    for (int r = 0; r < n_gamma; ++r) cand[(int64_t)r * d_out + j] = trusted ? (uint8_t)0 : (uint8_t)(r + 1);
+    if (!trusted) {
+        for (int r = 0; r < n_gamma; ++r) active[(int64_t)r * n_blocks + j / block_rows] = 1;
+        atomicAdd(count, 1);
+    }
+}
+
 }  // namespace
 
 size_t owc_workspace_bytes(int64_t d_out, int64_t d_in) {
@@ -243,9 +267,16 @@ size_t owc_workspace_bytes(int64_t d_out, int64_t d_in) {
     return b;
 }
 
-int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, float* scale, float* zero,
-               uint8_t* Q, float* gamma_out, double* loss_out, void* ws, size_t ws_bytes, hipStream_t st) {
-    if (d_out == 0) return CDQ_OK;
+int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, float screen_margin, float* scale,
+               float* zero, uint8_t* Q, float* gamma_out, double* loss_out, int32_t* researched, void* ws, size_t ws_bytes, hipStream_t st) {
+    if (d_out == 0) {
+        if (researched != nullptr) {
+            hipLaunchKernelGGL(owc_fill_f32_kernel, dim3(1), dim3(256), 0, st, (float*)researched, (int64_t)1, 0.0f);     // the bits of +0.0f are the integer 0
+            CDQ_LAUNCH_CHECK();
+        }
+        return CDQ_OK;
+    }
+    const float margin = screen_margin > 0.0f ? screen_margin : kScreenMargin;
     if (ws == nullptr || ((uintptr_t)ws & 255) || ws_bytes < owc_workspace_bytes(d_out, d_in)) return CDQ_EWORKSPACE;
     if (d_out > 0x7fffffffLL) return CDQ_EUNSUPPORTED;
     char* p = (char*)ws;
@@ -271,12 +302,14 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
         const int block_rows = loss_block_rows();
         const int64_t n_blocks = (d_out + block_rows - 1) / block_rows;
         uint8_t *cand, *active;
-        int rc = owc_screen_launch(H, Wt, d_out, d_in, bits, n_gamma, lo, hi, kScreenMargin, block_rows, n_blocks, screen_ws, &cand, &active, st);
+        const float* screened;
+        int rc = owc_screen_launch(H, Wt, d_out, d_in, bits, n_gamma, lo, hi, margin, block_rows, n_blocks, screen_ws, &cand, &active, &screened, st);
         if (rc != CDQ_OK) return rc;
         hipLaunchKernelGGL(owc_fill_f32_kernel, col_blocks, t256, 0, st, best_gamma, d_out, 0.0f);      // 0: nothing evaluated yet
         CDQ_LAUNCH_CHECK();
-        // candidates gathered into at most d_out dense rows; every column's first one too when nobody asks for the losses
-        const int first = loss_out != nullptr ? 1 : 0;
+        // Every column's best-screened grid point is evaluated in fp64 in a pass over all columns (that value is also what the
+        // check of the fp16 look compares with); the other candidates are gathered into at most d_out dense rows.
+        const int first = 1;
         char* gp = (char*)screen_ws + owc_screen_workspace_bytes(d_out, d_in, 255, n_blocks);
         float* Wc = (float*)gp;             gp += cdq_align_up((size_t)d_out * d_in * sizeof(float), 256);
         double* row_loss = (double*)gp;     gp += dsz;
@@ -332,7 +365,37 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
                                d_out, best_loss, best_gamma);
             CDQ_LAUNCH_CHECK();
         }
-    } else
+        // the check of the fp16 look, and the exhaustive search for the columns that fail it (idle launches otherwise)
+        int32_t* count = total;             // the rows are done with: reuse the counter
+        hipLaunchKernelGGL(owc_fill_f32_kernel, dim3(1), t256, 0, st, (float*)count, (int64_t)1, 0.0f);                   // bits of +0.0f: integer 0
+        CDQ_LAUNCH_CHECK();
+        {
+            const int64_t flags = (int64_t)n_gamma * n_blocks;
+            hipLaunchKernelGGL(owc_fill_u8_kernel, dim3((unsigned)((flags + 255) / 256)), t256, 0, st, active, flags, (uint8_t)0);
+            CDQ_LAUNCH_CHECK();
+        }
+        hipLaunchKernelGGL(owc_guard_kernel, col_blocks, t256, 0, st, screened, (const double*)best_loss, (const float*)best_gamma, d_out, n_gamma,
+                           margin, block_rows, n_blocks, cand, active, count);
+        CDQ_LAUNCH_CHECK();
+        for (int r = 0; r < n_gamma; ++r) {
+            hipLaunchKernelGGL(owc_rank_gamma_kernel, col_blocks, t256, 0, st, cand + (int64_t)r * d_out, d_out, n_gamma, rank_gamma);
+            CDQ_LAUNCH_CHECK();
+            hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, 1.0f, (const float*)rank_gamma, trial_scale,
+                               (float*)nullptr, trial_q);
+            CDQ_LAUNCH_CHECK();
+            rc = loss_launch(H, Wt, trial_scale, lo, trial_q, d_out, d_in, d_in, trial_loss, nullptr, loss_ws, loss_ws_bytes, st,
+                             active + (int64_t)r * n_blocks);
+            if (rc != CDQ_OK) return rc;
+            hipLaunchKernelGGL(owc_update_best_ranked_kernel, col_blocks, t256, 0, st, (const double*)trial_loss, (const float*)rank_gamma,
+                               d_out, best_loss, best_gamma);
+            CDQ_LAUNCH_CHECK();
+        }
+        if (researched != nullptr) CDQ_HIP_CHECK(hipMemcpyAsync(researched, count, sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    } else {
+    if (researched != nullptr) {            // the exhaustive search needs no check
+        hipLaunchKernelGGL(owc_fill_f32_kernel, dim3(1), t256, 0, st, (float*)researched, (int64_t)1, 0.0f);
+        CDQ_LAUNCH_CHECK();
+    }
     for (int k = 1; k <= n_gamma; ++k) {
         const float gamma = (float)k / (float)n_gamma;
         hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, gamma, (const float*)nullptr, trial_scale,
@@ -343,6 +406,7 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
         hipLaunchKernelGGL(owc_update_best_kernel, dim3((unsigned)((d_out + 255) / 256)), t256, 0, st, trial_loss, d_out, gamma,
                            k == 1 ? 1 : 0, best_loss, best_gamma);
         CDQ_LAUNCH_CHECK();
+    }
     }
     hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, 1.0f, best_gamma, scale, zero, Q);
     CDQ_LAUNCH_CHECK();

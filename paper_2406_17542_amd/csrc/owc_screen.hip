@@ -305,10 +305,11 @@ size_t owc_screen_workspace_bytes(int64_t d_out, int64_t d_in, int n_gamma, int6
            2 * cdq_align_up((size_t)d_in * sizeof(float), 256) + cdq_align_up((size_t)d_out * sizeof(float), 256);
 }
 
-// Screens all n_gamma grid points and ranks them.  On return (stream order) cand and active are filled; both point into ws.
+// Screens all n_gamma grid points and ranks them.  On return (stream order) cand, active and the screened losses
+// [n_gamma][d_out] are filled; all three point into ws.
 int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, const float* lo, const float* hi,
                       float margin, int block_rows, int64_t n_blocks, void* ws, uint8_t** cand_out, uint8_t** active_out,
-                      hipStream_t st) {
+                      const float** screened_out, hipStream_t st) {
     const int64_t rows = (d_out + 2 * SB - 1) / (2 * SB) * (2 * SB);
     const int n_part = (int)(2 * d_in / SB);
     const bool big = d_in % (2 * SB) == 0;                         // the 256 x 256 tile
@@ -369,6 +370,7 @@ int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_
     CDQ_LAUNCH_CHECK();
     *cand_out = cand;
     *active_out = active;
+    *screened_out = screened;
     return CDQ_OK;
 }
 

@@ -67,6 +67,42 @@ __global__ __launch_bounds__(512) void probe_mfma_bf16_kernel(int iters, float* 
     if (t == 1.2345678e-30f) sink[0] = t;
 }
 
+// The same matrix-core loop on operands that look like data: 16 different pseudo-random bf16 fragments per wavefront
+// (random sign and mantissa, exponents over four binades), cycled through 32 MFMAs per round on 16 accumulators.  What
+// the matrix cores draw depends on how many operand bits toggle, and with it the clock the chip holds: this is the ceiling
+// for a bf16 GEMM on real activations, the constant-operand loop above the ceiling for an idle data path.
+__global__ __launch_bounds__(256) void probe_mfma_bf16_random_kernel(int iters, float* __restrict__ sink) {
+    pf16v acc[4][4];
+    for (int a = 0; a < 4; ++a)
+        for (int b = 0; b < 4; ++b)
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+    pbf8 xa[2][4], xb[2][4];
+    uint32_t s = threadIdx.x * 2654435761u + blockIdx.x * 97u + 12345u;
+    for (int h = 0; h < 2; ++h)
+        for (int q = 0; q < 4; ++q)
+            for (int e = 0; e < 8; ++e) {
+                s = s * 1664525u + 1013904223u;
+                const uint16_t ba = (uint16_t)(((s >> 9) & 0x807Fu) | ((125u + ((s >> 5) & 3u)) << 7));
+                s = s * 1664525u + 1013904223u;
+                const uint16_t bb = (uint16_t)(((s >> 9) & 0x807Fu) | ((125u + ((s >> 5) & 3u)) << 7));
+                xa[h][q][e] = __builtin_bit_cast(__bf16, ba);
+                xb[h][q][e] = __builtin_bit_cast(__bf16, bb);
+            }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[h][a], xb[h][b], acc[a][b], 0, 0, 0);
+    }
+    float t = 0.0f;
+    for (int a = 0; a < 4; ++a)
+        for (int b = 0; b < 4; ++b)
+            for (int v = 0; v < 16; ++v) t += acc[a][b][v];
+    if (t == 1.2345678e-30f) sink[0] = t;
+}
+
 __global__ __launch_bounds__(1024) void probe_mfma_f64_kernel(int iters, float* __restrict__ sink) {
     pd4 acc[4];
     for (int a = 0; a < 4; ++a) acc[a] = (pd4){0.0, 0.0, 0.0, 0.0};
@@ -85,11 +121,14 @@ __global__ __launch_bounds__(1024) void probe_mfma_f64_kernel(int iters, float* 
 extern "C" {
 
 int cdq_probe_mfma(int kind, int64_t blocks, int64_t iters, float* sink, double* flop, void* stream) {
-    if (sink == nullptr || blocks <= 0 || blocks > 0x7fffffffLL || iters < 0 || iters > 0x7fffffffLL || (kind != 0 && kind != 1))
+    if (sink == nullptr || blocks <= 0 || blocks > 0x7fffffffLL || iters < 0 || iters > 0x7fffffffLL || kind < 0 || kind > 2)
         return CDQ_EINVAL;
     if (kind == 0) {        // 8 wavefronts per block, 8 MFMAs of 32x32x16 per round
         hipLaunchKernelGGL(cdq::probe_mfma_bf16_kernel, dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream, (int)iters, sink);
         if (flop != nullptr) *flop = (double)blocks * 8.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
+    } else if (kind == 2) { // 4 wavefronts per block (one per SIMD, as the Hessian kernel runs), 32 MFMAs of 32x32x16 per round
+        hipLaunchKernelGGL(cdq::probe_mfma_bf16_random_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (int)iters, sink);
+        if (flop != nullptr) *flop = (double)blocks * 4.0 * (double)iters * 32.0 * (2.0 * 32 * 32 * 16);
     } else {                // 16 wavefronts per block, 4 MFMAs of 16x16x4 (fp64) per round
         hipLaunchKernelGGL(cdq::probe_mfma_f64_kernel, dim3((unsigned)blocks), dim3(1024), 0, (hipStream_t)stream, (int)iters, sink);
         if (flop != nullptr) *flop = (double)blocks * 16.0 * (double)iters * 4.0 * (2.0 * 16 * 16 * 4);

@@ -260,6 +260,48 @@ def test_init_owc(cdq, oracle, d_out, d_in, n, bits, n_gamma):
     assert (gam < 1).any(), "the case should exercise clipping"
 
 
+@pytest.mark.parametrize("kind", ["tiny_margin", "collinear_channels"])
+def test_init_owc_columns_that_fail_the_check_are_searched_exhaustively(cdq, oracle, kind):
+    """The fp16 look at the grid is checked column by column against the fp64 loss of the chosen grid point; a column that
+    fails is searched exhaustively.  Forced two ways: a margin so small that rounding alone fails the check, and a layer
+    whose input channels are nearly collinear, where fp16 cannot hold 1 - correlation and the estimate is off by percents.
+    Either way the result must be the oracle's exhaustive fp64 search, and the failures must be counted."""
+    d_out, d_in, n, bits, n_gamma = 96, 384, 900, 3, 50
+    rng = np.random.default_rng(21)
+    if kind == "collinear_channels":
+        z = rng.standard_normal((n, 1)).astype(np.float32)
+        X = (z + 0.05 * rng.standard_normal((n, d_in))).astype(np.float32)          # every channel is the same signal + 5 % noise
+        margin = 0.0
+    else:
+        X, _ = rand_layer(5, d_in, d_out, n, corr=0.5)
+        margin = 1e-7
+    Wt = (rng.standard_normal((d_out, d_in)) / np.sqrt(d_in)).astype(np.float32)
+    Wt[:, rng.integers(0, d_in, 3)] *= 5.0
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q, gam, all_loss = oracle.init_owc(H32, Wt, bits, d_in, n_gamma)
+    for want_loss in (True, False):
+        s, z_, Q, g, per, cnt = cdq.init_owc(dev(H32), dev(Wt), bits, d_in, n_gamma, want_loss=want_loss, screen_margin=margin,
+                                            want_researched=True)
+        g = g.cpu().numpy()
+        n_failed = int(cnt.item())
+        assert n_failed >= d_out // 3, f"only {n_failed} of {d_out} columns failed the check: the case does not exercise it"
+        same = g == gam
+        gammas = oracle.owc_gammas(n_gamma)
+        for j in np.where(~same)[0]:                 # only exact ties of two grid points may differ
+            k_gpu = int(np.argmin(np.abs(gammas - g[j])))
+            k_ref = int(np.argmin(np.abs(gammas - gam[j])))
+            assert abs(all_loss[k_gpu, j] - all_loss[k_ref, j]) <= 1e-6 * abs(all_loss[k_ref, j]) + 1e-30, (j, g[j], gam[j])
+        assert same.mean() >= 0.97
+        assert np.array_equal(s.cpu().numpy()[same], a[same]) and np.array_equal(Q.cpu().numpy()[same], q[same])
+        if want_loss:
+            # with collinear channels e^T H e cancels to a small fraction of |e|^2 |H|: the two sides' roundings of e show
+            np.testing.assert_allclose(per.cpu().numpy()[same], all_loss.min(axis=0)[same], rtol=1e-6 if kind == "tiny_margin" else 1e-4, atol=1e-30)
+    # on an ordinary layer with the default margin nothing fails
+    X, _ = rand_layer(6, d_in, d_out, n, corr=0.5)
+    cnt = cdq.init_owc(dev(oracle.hessian(X).astype(np.float32)), dev(Wt), bits, d_in, n_gamma, want_researched=True)[5]
+    assert int(cnt.item()) == 0
+
+
 def test_init_owc_weights_at_an_odd_address(cdq, oracle):
     """Eq. (2) grid search with Wt 4 bytes off a 16-byte boundary (the library's scalar-load kernels) chooses, for every
     column, what it chooses for the aligned copy, and that is the oracle's choice."""

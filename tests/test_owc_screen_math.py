@@ -74,3 +74,44 @@ def test_fp16_screen_keeps_the_exact_winner_inside_the_margin():
         assert (slack <= MARGIN).all()
     assert worst_err < 1e-3, worst_err            # measured on the GPU on larger layers: 3e-4
     assert worst_slack < MARGIN / 5, worst_slack
+
+
+def screened_and_exact(H, W, bits, n_gamma=50):
+    E = residuals(W, bits, n_gamma)
+    exact = np.einsum("gji,ik,gjk->gj", E.astype(np.float64), H, E.astype(np.float64))
+    d = np.sqrt(np.diag(H)).astype(np.float32)
+    R16 = (H / np.outer(d, d)).astype(np.float32).astype(np.float16).astype(np.float64)
+    F = E * d
+    s = np.abs(F).max(axis=2, keepdims=True)
+    s[s == 0] = 1.0
+    F16 = (F / s).astype(np.float16).astype(np.float64)
+    return s[:, :, 0].astype(np.float64) ** 2 * np.einsum("gji,ik,gjk->gj", F16, R16, F16), exact
+
+
+def test_nearly_collinear_channels_break_the_fp16_estimate_and_the_check_sees_it():
+    """Where the estimate can fail: with correlations close to 1 the loss is carried by 1 - R_ik, which fp16 (spacing
+    2^-11 below 1) cannot hold, and the estimate is off by far more than the margin.  The library does not rely on the
+    margin alone: it compares the estimate with the fp64 loss at the chosen grid point of every column and searches a
+    column exhaustively when they differ by more than a third of the margin.  On such a layer that check must fire on
+    most columns (the error is largest exactly where the loss is smallest, i.e. at the grid points that win); on the
+    ordinary layers above it must not fire at all."""
+    r = np.random.default_rng(9)
+    n, d_in, d_out = 900, 256, 40
+    z = r.standard_normal((n, 1))
+    X = z + 0.05 * r.standard_normal((n, d_in))                                      # every channel: the same signal + 5 % noise
+    H = (X.T @ X).astype(np.float32).astype(np.float64)
+    W = (r.standard_normal((d_out, d_in)) / np.sqrt(d_in)).astype(np.float32)
+    screened, exact = screened_and_exact(H, W, 3)
+    err = np.abs(screened / exact - 1)
+    assert err.max() > 10 * MARGIN, err.max()                                        # the estimate alone is useless here
+    chosen = screened.argmin(axis=0)                                                 # what pass 0 evaluates in fp64
+    cols = np.arange(d_out)
+    fires = err[chosen, cols] > MARGIN / 3
+    assert fires.mean() >= 0.5, fires.mean()
+    # ordinary layers: the check stays quiet and the margin holds (same cases as above)
+    for seed, d, do, bits, tail in [(2, 256, 48, 3, True), (4, 256, 40, 2, False)]:
+        H, W = layer(seed, d, do, 3 * d, tail)
+        screened, exact = screened_and_exact(H, W, bits)
+        ok = exact > 0
+        e = np.where(ok, np.abs(screened / np.where(ok, exact, 1) - 1), 0)
+        assert (e[screened.argmin(axis=0), np.arange(do)] <= MARGIN / 3).all()
