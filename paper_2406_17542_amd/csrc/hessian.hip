@@ -13,8 +13,7 @@
 // fixed order (so results are reproducible), optionally adds the previous H (streaming over
 // token chunks), and mirrors into the lower triangle.
 #include "cdq_internal.h"
-
-#include <type_traits>
+#include "tile256.h"
 
 namespace cdq {
 
@@ -93,155 +92,19 @@ __host__ __device__ inline XcdShare xcd_share(int x, int tiles) {
 
 // ------------------------------------------------------------------------------------------ bf16
 //
-// 256 x 256 tile of H per workgroup of 4 wavefronts (one per SIMD), each wavefront 128 x 128 =
-// 4 x 4 MFMA blocks with the 256 accumulator registers in AGPRs (a third less LDS traffic per FLOP
-// than 128 x 64 on 8 wavefronts).  The token range is consumed in steps of 32; LDS is a ring of NSTAGE stages,
-// each holding the two operand tiles of one step as 32 token rows of 256 columns (512 bytes).
-// A wavefront's direct global->LDS load moves 64 x 16 bytes = two token rows; lane l writes chunk position l%32 of
-// row l/32 and fetches the global 16-byte chunk (l%32) ^ 4(row%4), i.e. the chunks of a row are XOR-swizzled by the
-// row.  A transposing read by the 16 lanes j of a group fetches the 8-byte pieces (token tb + j/4, columns
-// fb + 4(j%4) .. +3) and returns to lane j the tokens tb .. tb+3 of column fb + j; with the swizzle, the four token
-// rows of a group fall into four different 64-byte bank groups, so reads and writes are conflict-free.
-// With a single wavefront per SIMD nothing else hides a stall, so the loop is a software pipeline over quarters of a
-// 16-token half step: four MFMAs, the four LDS reads that fetch a quarter of the next half's fragments, and ONE of the
-// wavefront's eight loads of a later step.  Issuing a step's loads in one burst (as an earlier version did) held every
-// wavefront in its issue sequence while the CU's single address unit worked through 32 KiB -- about 500 cycles per
-// 1000-cycle step with the matrix cores idle; spread out, a load costs the wavefront a scalar add and a move.
-// Loads run NSTAGE-1 steps ahead; the one barrier per step sits between the two halves.  Tiles that stick out of the
-// matrix and token ranges that are not a multiple of 32 take a plain path through registers with zero fill (same
-// LDS layout).
+// 256 x 256 tile of H per workgroup of 4 wavefronts: the pipelined matrix-core loop of tile256.h with both operand tiles
+// taken from X (rows = tokens).  Tiles that stick out of the matrix and token ranges that are not a multiple of 32 take a
+// plain path through registers with zero fill (same LDS layout).
 
-constexpr int T2 = 256;                 // tile of H: T2 x T2 per workgroup
+using tile256::T2;
+using tile256::BKS;
+using tile256::ROWB;
+using tile256::TILE_BYTES;
 constexpr int BK16 = 64;                // granularity of the token split (two steps)
-constexpr int BKS = 32;                 // tokens per step
-constexpr int ROWB = T2 * 2;            // LDS bytes per token row of a tile
-constexpr int TILE_BYTES = BKS * ROWB;  // 16 KiB per operand per stage
-constexpr int STAGE = 2 * TILE_BYTES;
-constexpr int NSTAGE = 4;
-constexpr int HESS_LDS = NSTAGE * STAGE;               // 128 KiB
+constexpr int HESS_LDS = tile256::LDS_BYTES;           // 128 KiB
 
-typedef short s4v __attribute__((ext_vector_type(4)));
-typedef short s8v __attribute__((ext_vector_type(8)));
-
-// tokens tb..tb+3 (first read) and tb+4..tb+7 (second read) of this lane's column: the 8 contraction
-// elements one lane feeds to v_mfma_f32_32x32x16_bf16
-__device__ __forceinline__ bf8 read_frag(const char* p) {
-    const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4v*)(p));
-    const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4v*)(p + 4 * ROWB));
-    const s8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf8, both);
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmem() {          // until at most N of this wavefront's vector-memory operations are pending
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-// The barrier alone: every wavefront has waited for its own loads before it, and the LDS reads still in flight touch
-// a stage that nobody writes before the next barrier, so nothing else has to drain here.
-__device__ __forceinline__ void stage_barrier() {
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-}
-
-// The pipelined loop over `n_steps` >= 1 steps of 32 tokens starting at token t_begin, for an interior tile.
-// A tile on the diagonal is not special here: its column block is loaded into both operand tiles (there are n_t such
-// tiles among n_t (n_t + 1) / 2, and a second code path would double the registers the compiler has to place).
-__device__ __forceinline__ void hessian_tile_pipelined(const uint16_t* __restrict__ X, int64_t d_in, int64_t i0, int64_t j0,
-                                                       int64_t t_begin, int n_steps, char* lds, f16v (&acc)[4][4]) {
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // uniform, and the compiler knows it
-    const int wm = wave >> 1, wn = wave & 1;                            // 2 x 2 wavefronts, each 128 rows x 128 columns
-    // fragment read roles: 16-lane group g = lane/16 takes columns 16 (g%2) .. +15 of a 32-column fragment and the
-    // token half g/2 of a 16-token half step; lane j of the group addresses token j/4, columns 4 (j%4) .. +3
-    const int jj = lane & 15, gg = lane >> 4;
-    const int rd_row = (8 * (gg >> 1) + (jj >> 2)) * ROWB + 8 * (jj & 1);
-    const int rd_chunk = 2 * (gg & 1) + ((jj & 3) >> 1), rd_swz = jj & 12;
-    int offA[4], offB[4];
-#pragma unroll
-    for (int b = 0; b < 4; ++b) offA[b] = rd_row + (((wm * 16 + 4 * b + rd_chunk) ^ rd_swz) << 4);
-#pragma unroll
-    for (int b = 0; b < 4; ++b) offB[b] = rd_row + (((wn * 16 + 4 * b + rd_chunk) ^ rd_swz) << 4) + TILE_BYTES;
-    // loads: a step's tiles are 32 loads of two token rows each; wavefront w issues loads w, w+4, ...
-    // Per load the lane's byte offset from the first token row of the step is fixed, and so is the load's place in a stage.
-    constexpr int PW = 8;                  // loads of this wavefront per step
-    const int lrow = lane >> 5, lpos = lane & 31;
-    uint32_t src_off[PW];                  // per lane
-    uint32_t dst_off[PW];                  // uniform
-#pragma unroll
-    for (int q = 0; q < PW; ++q) {
-        const int g = wave + 4 * q;                           // 0..15: A tile, 16..31: B tile
-        const int op = g >> 4, rp = g & 15;
-        const int row = 2 * rp + lrow;
-        const int chunk = lpos ^ (4 * (row & 3));
-        src_off[q] = (uint32_t)(((int64_t)row * d_in + (op ? j0 - i0 : 0) + 8 * chunk) * 2);
-        dst_off[q] = (uint32_t)(op * TILE_BYTES + 2 * rp * ROWB);
-    }
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds;
-    const char* xbase = reinterpret_cast<const char*>(X + t_begin * d_in + i0);
-    const int64_t step_bytes = (int64_t)BKS * d_in * 2;
-    // 16 bytes per lane from global memory straight into LDS at (stage + dst_off) + 16 * lane.  Written as assembly so
-    // that the waits stay ours: with the builtin the compiler makes every LDS read wait for all direct loads in flight.
-    auto issue_one = [&](const char* base, uint32_t stage_lds, int q) {
-        const uint32_t m0v = stage_lds + dst_off[q];
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0v), "v"(src_off[q]), "s"(base) : "m0", "memory");
-    };
-    // A half step: 16 MFMAs on (af, bfr), the 8 fragments of the next half into (an, bn) from stage address Rn, and one
-    // load per quarter (loads lq0 .. lq0+3 of the step whose first token row is lbase, into stage lstage).
-    auto half = [&](const bf8 (&af)[4], const bf8 (&bfr)[4], bf8 (&an)[4], bf8 (&bn)[4], const char* Rn, const char* lbase,
-                    uint32_t lstage, int lq0) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            issue_one(lbase, lstage, lq0 + a);
-            // in the order the next half's MFMAs want them
-            if (a == 0) { an[0] = read_frag(Rn + offA[0]); bn[0] = read_frag(Rn + offB[0]); }
-            if (a == 1) { bn[1] = read_frag(Rn + offB[1]); bn[2] = read_frag(Rn + offB[2]); }
-            if (a == 2) { bn[3] = read_frag(Rn + offB[3]); an[1] = read_frag(Rn + offA[1]); }
-            if (a == 3) { an[2] = read_frag(Rn + offA[2]); an[3] = read_frag(Rn + offA[3]); }
-#pragma unroll
-            for (int b = 0; b < 4; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
-            // one LDS read behind each MFMA instead of a block of reads, then a block of MFMAs
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    // The loads of step k are issued during steps k-AHEAD (second half) and k-AHEAD+1 (first half).  Past the end of the
-    // token range the last step is simply loaded again (into a stage nobody reads any more) and the fragments read for
-    // the "next" half are not used: every step then runs the same instructions with the same number of loads in flight,
-    // the loop needs no special first or last iterations, and the wait counts are constants.
-    constexpr int AHEAD = NSTAGE - 1;
-    const int last = n_steps - 1;
-    auto step_base = [&](int k) { return xbase + (int64_t)(k < last ? k : last) * step_bytes; };
-    for (int k = 0; k < AHEAD - 1; ++k)
-#pragma unroll
-        for (int q = 0; q < PW; ++q) issue_one(step_base(k), lds_base + k * STAGE, q);
-#pragma unroll
-    for (int q = 0; q < PW / 2; ++q) issue_one(step_base(AHEAD - 1), lds_base + (AHEAD - 1) * STAGE, q);
-    wait_vmem<(AHEAD - 2) * PW + PW / 2>();                    // step 0 has landed
-    stage_barrier();
-    bf8 a0[4], b0[4], a1[4], b1[4];
-    a0[0] = read_frag(lds + offA[0]);
-#pragma unroll
-    for (int b = 0; b < 4; ++b) b0[b] = read_frag(lds + offB[b]);
-#pragma unroll
-    for (int b = 1; b < 4; ++b) a0[b] = read_frag(lds + offA[b]);
-    int slot = 0;                                              // stage of the current step
-    for (int step = 0; step < n_steps; ++step) {
-        const char* At = lds + slot * STAGE;
-        int s1 = slot + AHEAD - 1; if (s1 >= NSTAGE) s1 -= NSTAGE;
-        // first half: tokens 0..15; fragments of tokens 16..31; the second half of step+AHEAD-1's loads
-        half(a0, b0, a1, b1, At + 16 * ROWB, step_base(step + AHEAD - 1), lds_base + s1 * STAGE, PW / 2);
-        wait_vmem<(AHEAD - 2) * PW>();                         // step+1 has landed (each wavefront waits for its own loads)
-        stage_barrier();                                       // ... everybody's; and the stage of step-1 is free
-        int s2 = slot + AHEAD; if (s2 >= NSTAGE) s2 -= NSTAGE;
-        int sn = slot + 1; if (sn >= NSTAGE) sn -= NSTAGE;
-        // second half: tokens 16..31; fragments of the next step's tokens 0..15; the first half of step+AHEAD's loads
-        half(a1, b1, a0, b0, lds + sn * STAGE, step_base(step + AHEAD), lds_base + s2 * STAGE, 0);
-        slot = sn;
-    }
-    wait_vmem<0>();            // nothing may still be on its way into LDS when the workgroup ends
-}
+// tokens tb..tb+7 of this lane's column, as the plain path feeds them to the MFMA
+__device__ __forceinline__ bf8 read_frag(const char* p) { return __builtin_bit_cast(bf8, tile256::read_frag(p)); }
 
 // Edge tiles and ragged token ranges: through registers with zero fill, one stage, same LDS layout.
 __device__ __forceinline__ void hessian_tile_plain(const uint16_t* __restrict__ X, int64_t d_in, int64_t i0, int64_t j0, bool diag,
@@ -349,7 +212,11 @@ __device__ __forceinline__ void hessian_tile(const uint16_t* __restrict__ X, int
             for (int b = 0; b < 4; ++b)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
-        hessian_tile_pipelined(X, d_in, i0, j0, t_begin, (int)(len / BKS), lds, acc);
+        // a tile on the diagonal is not special here: its column block is loaded into both operand tiles (there are n_t such
+        // tiles among n_t (n_t + 1) / 2, and a second code path would double the registers the compiler has to place)
+        const int n_steps = (int)(len / BKS);
+        const char* rows = reinterpret_cast<const char*>(X + t_begin * d_in);
+        tile256::pipelined<tile256::Bf16>(rows + i0 * 2, d_in * 2, nullptr, n_steps, rows + j0 * 2, d_in * 2, n_steps, lds, acc);
         hessian_tile_store(acc, d_in, i0, j0, dst, ld, add_old);
     } else {
         hessian_tile_slow(X, d_in, I, J, t_begin, t_end, dst, ld, add_old, lds);

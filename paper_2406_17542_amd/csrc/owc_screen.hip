@@ -14,6 +14,7 @@
 // Kernels here: R and f in fp16; C = F R on v_mfma_f32_32x32x16_f16 with the epilogue sum_c C[j][c] F[j][c] per row and
 // column block; the sum over the column blocks; and the ranking of a column's grid points.
 #include "cdq_internal.h"
+#include "tile256.h"
 
 namespace cdq {
 namespace {
@@ -244,6 +245,146 @@ __global__ __launch_bounds__((TB / (32 * BLK)) * (TB / (32 * BLK)) * 64) void ow
     }
 }
 
+// ---- the same product on the pipelined 256 x 256 tile of tile256.h (d_in a multiple of 256)
+//
+// tile256 wants both operands contraction-major, so the residuals are kept transposed: Ft [d_in][rows] (row k holds f_k of
+// every column of W).  The tile is C^T: its 256 rows are a column block cb of R (R is symmetric: row k of R, elements
+// c0 .. c0+255), its 256 columns are columns j0 .. j0+255 of W; the contraction runs over k < 256 (cb + 1), and for the
+// steps of the diagonal block the R rows come from Rh, a copy of R whose diagonal 256 x 256 blocks are halved (the
+// epilogue doubles everything: 2 (above + diagonal / 2)).  A lane then holds one column j and 64 values of c per 32 x 32
+// block, so the epilogue's sum over c of C[c][j] f_c[j] is a sum inside the lane plus one exchange between its two halves,
+// and its reads of Ft are contiguous across the lanes.  partial[cb * 2 + h][j]: the sum over the 128 rows c of half h.
+
+// Rh[c][k] = R[c][k] / 2 inside the diagonal 256 x 256 blocks, R[c][k] elsewhere
+__global__ __launch_bounds__(256) void owc_corr_half_diag_kernel(const _Float16* __restrict__ R, int64_t d_in, _Float16* __restrict__ Rh) {
+    const int64_t c = blockIdx.x;
+    for (int64_t k = threadIdx.x; k < d_in; k += 256) {
+        const _Float16 v = R[c * d_in + k];
+        Rh[c * d_in + k] = (k / 256 == c / 256) ? (_Float16)(v * (_Float16)0.5f) : v;
+    }
+}
+
+// largest d[k]
+__global__ __launch_bounds__(1024) void owc_dmax_kernel(const float* __restrict__ d, int64_t d_in, float* __restrict__ out) {
+    __shared__ float sh[16];
+    float m = 0.0f;
+    for (int64_t k = threadIdx.x; k < d_in; k += 1024) m = fmaxf(m, d[k]);
+    for (int o = 32; o; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w) m = fmaxf(m, sh[w]);
+        out[0] = m;
+    }
+}
+
+// Eq. (2) at one clipping strength for 64 columns of W and 1024 coordinates, stored transposed: Ft[k][j] = f_k / s_j in fp16,
+// f = e * d with e = fma(a, q, lo) - w as the loss kernel forms it.  Here s_j is not the largest |f| of the column but a
+// bound on it that needs no pass over the column: |e| <= max(a / 2, (hi - lo) - a (2^bits - 1)) -- half a step inside the
+// grid, the clipped part above it -- times the largest d.  Any s that keeps |f / s| <= 1 serves (fp16 has the same
+// relative precision over its whole normal range); s^2 goes to row_scale2.  Columns past d_out are written as zeros.
+// 64 x 64 pieces go through LDS so that both the reads of W and the writes of Ft are contiguous.
+__global__ __launch_bounds__(256) void owc_residual_f16_t_kernel(const float* __restrict__ Wt, int64_t d_out, int64_t d_in, int bits,
+                                                                 const float* __restrict__ lo_in, const float* __restrict__ hi_in, float gamma,
+                                                                 const float* __restrict__ d, const float* __restrict__ dmax,
+                                                                 _Float16* __restrict__ Ft, int64_t rows, float* __restrict__ row_scale2) {
+    constexpr int TS = 68;                                                   // halves per tile row: 136 bytes, 8-byte aligned
+    __shared__ __attribute__((aligned(16))) _Float16 tile[64][TS];          // [j][k]
+    __shared__ float a_sh[64], lo_sh[64], rs_sh[64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t j0 = (int64_t)blockIdx.x * 64, kb = (int64_t)blockIdx.y * 1024;
+    const float top = (float)((1 << bits) - 1);
+    if (tid < 64) {                                      // the columns' grids and scales
+        const int64_t j = j0 + tid;
+        float a = 1.0f, lo = 0.0f, rs = 0.0f;
+        if (j < d_out) {
+            lo = lo_in[j];
+            const float hi = hi_in[j];
+            a = __fdiv_rn(gamma * (hi - lo), top);
+            if (!(a > 0.0f) || isinf(a)) a = 1.0f;
+            float sc = fmaxf(0.5f * a, (hi - lo) - a * top) * dmax[0] * 1.001f;
+            if (!(sc > 0.0f) || isinf(sc)) sc = 1.0f;
+            rs = __fdiv_rn(1.0f, sc);
+            if (blockIdx.y == 0) row_scale2[j] = sc * sc;
+        }
+        a_sh[tid] = a;
+        lo_sh[tid] = lo;
+        rs_sh[tid] = rs;                                 // 0 for a column past d_out: its entries become zeros
+    }
+    __syncthreads();
+    // reading: per instruction a wavefront takes 4 columns x 64 coordinates (16 lanes x 4 consecutive floats each)
+    const int rq = (lane & 15) * 4, rr = wave * 4 + (lane >> 4);
+    // writing: coordinate wk, columns 16 wg .. 16 wg + 15
+    const int wk = tid >> 2, wg = tid & 3;
+    for (int64_t k0 = kb; k0 < kb + 1024 && k0 < d_in; k0 += 64) {
+        const bool k_ok = k0 + rq < d_in;                // d_in is a multiple of 128 here, so a float4 is inside or outside
+        const float4 dd = k_ok ? *reinterpret_cast<const float4*>(d + k0 + rq) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = i * 16 + rr;
+            const float a = a_sh[row], lo = lo_sh[row], rs = rs_sh[row];
+            float4 w = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (k_ok && rs != 0.0f) w = *reinterpret_cast<const float4*>(Wt + (j0 + row) * d_in + k0 + rq);
+            auto f_one = [&](float wv, float dk) {
+                const float q = fminf(fmaxf(rintf(__fdiv_rn(wv - lo, a)), 0.0f), top);
+                return ((fmaf(a, q, lo) - wv) * dk) * rs;
+            };
+            typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+            h4 o;
+            o.x = (_Float16)f_one(w.x, dd.x), o.y = (_Float16)f_one(w.y, dd.y), o.z = (_Float16)f_one(w.z, dd.z), o.w = (_Float16)f_one(w.w, dd.w);
+            *reinterpret_cast<h4*>(&tile[row][rq]) = o;
+        }
+        __syncthreads();
+        if (k0 + wk < d_in) {
+            typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+            h8 o0, o1;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { o0[i] = tile[wg * 16 + i][wk]; o1[i] = tile[wg * 16 + 8 + i][wk]; }
+            h8* dst = reinterpret_cast<h8*>(Ft + (k0 + wk) * rows + j0 + wg * 16);
+            dst[0] = o0;
+            dst[1] = o1;
+        }
+        __syncthreads();
+    }
+}
+
+// grid.x = (d_in / 256) * (rows / 256) tiles, longest column blocks first; workgroups that follow each other take the same
+// column block of R and different columns of W.
+__global__ __launch_bounds__(256) void owc_screen_t256_kernel(const _Float16* __restrict__ Ft, const _Float16* __restrict__ R,
+                                                              const _Float16* __restrict__ Rh, int64_t rows, int64_t d_in,
+                                                              float* __restrict__ partial) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int n_jt = (int)(rows / 256), n_cb = (int)(d_in / 256);
+    const int cb = n_cb - 1 - (int)(blockIdx.x / n_jt), jt = (int)(blockIdx.x % n_jt);
+    const int64_t c0 = (int64_t)cb * 256, j0 = (int64_t)jt * 256;
+    const int n_steps = (cb + 1) * (256 / tile256::BKS), alt_from = cb * (256 / tile256::BKS);
+    tile256::acc16 acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+    tile256::pipelined<tile256::F16>(reinterpret_cast<const char*>(R + c0), d_in * 2, reinterpret_cast<const char*>(Rh + c0), alt_from,
+                                     reinterpret_cast<const char*>(Ft + j0), rows * 2, n_steps, lds, acc);
+    // 32x32 block: lane l, element v -> row (c) 8*(v/4) + 4*(l/32) + v%4, column (j) l%32
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int64_t j = j0 + wn * 128 + b * 32 + (lane & 31);
+        float t = 0.0f;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t c = c0 + wm * 128 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                t = fmaf(acc[a][b][v], (float)Ft[c * rows + j], t);
+            }
+        t += __shfl_xor(t, 32);
+        if (lane < 32) partial[((int64_t)cb * 2 + wm) * rows + j] = 2.0f * t;
+    }
+}
+
 // screened loss of a column at this grid point: the partial sums in a fixed order
 __global__ __launch_bounds__(256) void owc_screen_rows_kernel(const float* __restrict__ partial, int64_t rows, int64_t d_out, int n_part,
                                                               const float* __restrict__ row_scale2, float* __restrict__ out) {
@@ -295,14 +436,14 @@ bool owc_screen_applies(int64_t d_out, int64_t d_in, int n_gamma) {
     return d_in % SB == 0 && d_in >= 2 * SB && n_gamma >= 4 && n_gamma <= 255 && d_out >= 1 && d_in / SB * 2 <= 0x7fffffffLL;
 }
 
-// R [d_in][d_in] fp16 | F [rows][d_in] fp16 | partial [2 d_in / SB][rows] fp32 | screened [n_gamma][d_out] fp32 |
+// R [d_in][d_in] fp16 | Rh (R with halved diagonal blocks) | F [rows][d_in] fp16 (Ft [d_in][rows] on the 256-wide path) | partial [2 d_in / SB][rows] fp32 | screened [n_gamma][d_out] fp32 |
 // cand [n_gamma][d_out] u8 | active [n_gamma][n_blocks] u8 | d, 1/d [d_in] fp32 each | row scales [d_out] fp32
 size_t owc_screen_workspace_bytes(int64_t d_out, int64_t d_in, int n_gamma, int64_t n_blocks) {
     const int64_t rows = (d_out + 2 * SB - 1) / (2 * SB) * (2 * SB);
-    return cdq_align_up((size_t)d_in * d_in * 2, 256) + cdq_align_up((size_t)rows * d_in * 2, 256) +
+    return 2 * cdq_align_up((size_t)d_in * d_in * 2, 256) + cdq_align_up((size_t)rows * d_in * 2, 256) +
            cdq_align_up((size_t)(2 * d_in / SB) * rows * sizeof(float), 256) + cdq_align_up((size_t)n_gamma * d_out * sizeof(float), 256) +
            cdq_align_up((size_t)n_gamma * d_out, 256) + cdq_align_up((size_t)n_gamma * n_blocks, 256) +
-           2 * cdq_align_up((size_t)d_in * sizeof(float), 256) + cdq_align_up((size_t)d_out * sizeof(float), 256);
+           2 * cdq_align_up((size_t)d_in * sizeof(float), 256) + cdq_align_up((size_t)d_out * sizeof(float), 256) + 256;
 }
 
 // Screens all n_gamma grid points and ranks them.  On return (stream order) cand, active and the screened losses
@@ -316,6 +457,7 @@ int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_
     const int n_sum = n_part;                                      // partial sums per row that the kernel writes
     char* p = (char*)ws;
     _Float16* R = (_Float16*)p;        p += cdq_align_up((size_t)d_in * d_in * 2, 256);
+    _Float16* Rh = (_Float16*)p;       p += cdq_align_up((size_t)d_in * d_in * 2, 256);
     _Float16* F = (_Float16*)p;        p += cdq_align_up((size_t)rows * d_in * 2, 256);
     float* partial = (float*)p;        p += cdq_align_up((size_t)n_part * rows * sizeof(float), 256);
     float* screened = (float*)p;       p += cdq_align_up((size_t)n_gamma * d_out * sizeof(float), 256);
@@ -323,13 +465,21 @@ int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_
     uint8_t* active = (uint8_t*)p;     p += cdq_align_up((size_t)n_gamma * n_blocks, 256);
     float* d = (float*)p;              p += cdq_align_up((size_t)d_in * sizeof(float), 256);
     float* rd = (float*)p;             p += cdq_align_up((size_t)d_in * sizeof(float), 256);
-    float* row_scale2 = (float*)p;
+    float* row_scale2 = (float*)p;     p += cdq_align_up((size_t)d_out * sizeof(float), 256);
+    float* dmax = (float*)p;
     if (rows / SB > 65535) return CDQ_EUNSUPPORTED;
     hipLaunchKernelGGL(owc_diag_kernel, dim3((unsigned)((d_in + 255) / 256)), dim3(256), 0, st, H, d_in, d, rd);
     CDQ_LAUNCH_CHECK();
     hipLaunchKernelGGL(owc_corr_f16_kernel, dim3((unsigned)d_in), dim3(256), 0, st, H, d_in, (const float*)rd, R);
     CDQ_LAUNCH_CHECK();
-    if (rows > d_out) {                                            // d_in is a multiple of 128: whole words
+    const bool t256 = big && d_in <= 65536 && rows * 2 <= 128 * 1024;      // the pipelined tile: rows of Ft at most 128 KiB apart
+    if (t256) {
+        hipLaunchKernelGGL(owc_corr_half_diag_kernel, dim3((unsigned)d_in), dim3(256), 0, st, (const _Float16*)R, d_in, Rh);
+        CDQ_LAUNCH_CHECK();
+        hipLaunchKernelGGL(owc_dmax_kernel, dim3(1), dim3(1024), 0, st, (const float*)d, d_in, dmax);
+        CDQ_LAUNCH_CHECK();
+    }
+    if (rows > d_out && !t256) {                                   // d_in is a multiple of 128: whole words
         const int64_t words = (rows - d_out) * d_in / 2;
         hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, (uint32_t*)(F + d_out * d_in), words, 0u);
         CDQ_LAUNCH_CHECK();
@@ -344,9 +494,23 @@ int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_
                                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_small);
     static const hipError_t lds_rc_big = hipFuncSetAttribute(reinterpret_cast<const void*>(owc_screen_kernel<2 * SB, 2>),
                                                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_big);
-    if (lds_rc_small != hipSuccess || lds_rc_big != hipSuccess) return CDQ_EHIP;
+    static const hipError_t lds_rc_t256 = hipFuncSetAttribute(reinterpret_cast<const void*>(owc_screen_t256_kernel),
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize, tile256::LDS_BYTES);
+    if (lds_rc_small != hipSuccess || lds_rc_big != hipSuccess || lds_rc_t256 != hipSuccess) return CDQ_EHIP;
     for (int k = 1; k <= n_gamma; ++k) {
         const float gamma = (float)k / (float)n_gamma;
+        if (t256) {
+            hipLaunchKernelGGL(owc_residual_f16_t_kernel, dim3((unsigned)(rows / 64), (unsigned)((d_in + 1023) / 1024)), dim3(256), 0, st, Wt, d_out,
+                               d_in, bits, lo, hi, gamma, (const float*)d, (const float*)dmax, F, rows, row_scale2);
+            CDQ_LAUNCH_CHECK();
+            hipLaunchKernelGGL(owc_screen_t256_kernel, dim3((unsigned)((d_in / 256) * (rows / 256))), dim3(256), tile256::LDS_BYTES, st,
+                               (const _Float16*)F, (const _Float16*)R, (const _Float16*)Rh, rows, d_in, partial);
+            CDQ_LAUNCH_CHECK();
+            hipLaunchKernelGGL(owc_screen_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, (const float*)partial, rows,
+                               d_out, (int)(d_in / 128), (const float*)row_scale2, screened + (int64_t)(k - 1) * d_out);
+            CDQ_LAUNCH_CHECK();
+            continue;
+        }
         if (((uintptr_t)Wt & 15) == 0)
             hipLaunchKernelGGL(owc_residual_f16_vec_kernel, dim3((unsigned)d_out), dim3(256), 0, st, Wt, d_in, bits, lo, hi, gamma,
                                (const float*)d, F, row_scale2);
