@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void hessian_bf16_balanced_kernel(const uint16
 }
 
 // The leftover tiles of every XCD's share: H tile = (previous H tile when accumulating) + the slices' partial tiles in
-// ascending order.  Grid: (leftover tile, XCD, 16 blocks of 16 rows); 256 threads = the tile's columns.
+// ascending order.  Grid: (leftover tile, XCD, 64 blocks of 4 rows); 256 threads = the tile's columns.
 __global__ __launch_bounds__(256) void hessian_add_slices_kernel(const float* __restrict__ partial, float* __restrict__ H, int64_t d_in, int n_t,
                                                                  int tiles, int accumulate) {
     const int x = blockIdx.y, r = blockIdx.x;
@@ -274,13 +274,20 @@ __global__ __launch_bounds__(256) void hessian_add_slices_kernel(const float* __
     const int64_t i0 = (int64_t)I * T2, j0 = (int64_t)J * T2;
     const int col = threadIdx.x;
     if (j0 + col >= d_in) return;
-#pragma unroll 4
-    for (int rr = 0; rr < 16; ++rr) {
-        const int row = blockIdx.z * 16 + rr;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int row = blockIdx.z * 4 + rr;
         if (i0 + row < d_in) {
             float* h = H + (i0 + row) * d_in + j0 + col;
             float v = accumulate ? *h : 0.0f;
-            for (int z = 0; z < sh.slices; ++z) v += src[((int64_t)z * T2 + row) * T2 + col];
+            for (int z0 = 0; z0 < sh.slices; z0 += 8) {           // eight slices' loads in flight, added in ascending order
+                float pv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) pv[u] = src[((int64_t)(z0 + u < sh.slices ? z0 + u : z0) * T2 + row) * T2 + col];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (z0 + u < sh.slices) v += pv[u];
+            }
             *h = v;
         }
     }
@@ -494,7 +501,7 @@ int hessian_launch_balanced(const uint16_t* X, int64_t n, int64_t d_in, float* H
                        accumulate ? 1 : 0, partial);
     CDQ_LAUNCH_CHECK();
     if (max_rest > 0) {
-        hipLaunchKernelGGL(hessian_add_slices_kernel, dim3((unsigned)max_rest, kXcds, T2 / 16), dim3(256), 0, st, partial, H, d_in, (int)n_t, tiles,
+        hipLaunchKernelGGL(hessian_add_slices_kernel, dim3((unsigned)max_rest, kXcds, T2 / 4), dim3(256), 0, st, partial, H, d_in, (int)n_t, tiles,
                            accumulate ? 1 : 0);
         CDQ_LAUNCH_CHECK();
     }
