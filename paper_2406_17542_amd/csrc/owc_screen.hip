@@ -348,14 +348,22 @@ __global__ __launch_bounds__(256) void owc_residual_f16_t_kernel(const float* __
     }
 }
 
-// grid.x = (d_in / 256) * (rows / 256) tiles, longest column blocks first; workgroups that follow each other take the same
-// column block of R and different columns of W.
+// grid.x = (d_in / 256) * (rows / 256) tiles, longest column blocks first.  Workgroup w runs on XCD w % 8 and each XCD has its
+// own L2, so the tiles are handed out in patches of 4 column blocks of R x 8 blocks of columns of W, one patch per XCD at a
+// time: its 32 tiles start at the same contraction index and read 12 operand blocks per step between them instead of 33.
+// Shapes that do not divide into patches keep the plain order (same column block of R, consecutive columns of W).
 __global__ __launch_bounds__(256) void owc_screen_t256_kernel(const _Float16* __restrict__ Ft, const _Float16* __restrict__ R,
                                                               const _Float16* __restrict__ Rh, int64_t rows, int64_t d_in,
                                                               float* __restrict__ partial) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int n_jt = (int)(rows / 256), n_cb = (int)(d_in / 256);
-    const int cb = n_cb - 1 - (int)(blockIdx.x / n_jt), jt = (int)(blockIdx.x % n_jt);
+    int cb = n_cb - 1 - (int)(blockIdx.x / n_jt), jt = (int)(blockIdx.x % n_jt);
+    if (n_cb % 4 == 0 && n_jt % 8 == 0 && ((n_cb / 4) * (n_jt / 8)) % 8 == 0) {
+        const int xcd = (int)(blockIdx.x % 8), slot = (int)(blockIdx.x / 8);
+        const int patch = (slot / 32) * 8 + xcd, t = slot % 32, n_jg = n_jt / 8;
+        cb = n_cb - 1 - ((patch / n_jg) * 4 + t / 8);
+        jt = (patch % n_jg) * 8 + t % 8;
+    }
     const int64_t c0 = (int64_t)cb * 256, j0 = (int64_t)jt * 256;
     const int n_steps = (cb + 1) * (256 / tile256::BKS), alt_from = cb * (256 / tile256::BKS);
     tile256::acc16 acc[4][4];
