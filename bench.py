@@ -34,7 +34,8 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4
 # vector-ALU instructions of the loop kernel per wavefront and iteration at 16 coordinates per lane (SQ_INSTS_VALU
 # over the iterations of attn_proj: 13 per coordinate for the score and the running arg-min, 1 per coordinate for the
-# update, the rest reduction and bookkeeping); scaled by coordinates per lane for other shapes
+# update, the rest reduction and bookkeeping); scaled by coordinates per lane for other shapes.  A model, and a low one:
+# the same counter gives 321 on `large` and 343 on `mlp_down`, whose kernels carry the period-2 bookkeeping
 VALU_PER_WAVE_ITER_AT_16 = 290.0
 
 
@@ -192,7 +193,15 @@ class Layer:
             return torch.empty(max(cdq.workspace_bytes(op, n, d_out, cfg.d_in), 256), dtype=torch.uint8, device="cuda")
         self.H = torch.empty((cfg.d_in, cfg.d_in), dtype=torch.float32, device="cuda")
         self.ws_h = ws(cdq.OP_HESSIAN, cfg.n, 0)
-        self.ws_cd = ws(cdq.OP_GREEDY_CD)
+        # with the OWC start the grid search hands the start gradient over (it is a by-product of its fp64 pass), so
+        # Algorithm 1's own gradient initialisation, and the room for it, fall away
+        self.fused_g0 = init == "owc" and mode != "stress"
+        if self.fused_g0:
+            self.G0 = torch.empty((cfg.d_out, cfg.d_in), dtype=torch.float32, device="cuda")
+            self.ws_cd = torch.empty((4 * cfg.d_in + 255) // 256 * 256, dtype=torch.uint8, device="cuda")
+        else:
+            self.G0 = None
+            self.ws_cd = ws(cdq.OP_GREEDY_CD)
         self.ws_l = ws(cdq.OP_LOSS)
         self.ws_owc = ws(cdq.OP_INIT_OWC) if init == "owc" else ws(cdq.OP_INIT_OWC_CD) if init == "owc_cd" else None
         self.state = {}
@@ -205,7 +214,7 @@ class Layer:
         rec(1)
         if init == "owc":
             scale, zero, Q, gamma, _, cnt = cdq.init_owc(self.H, self.Wd, cfg.bits, cfg.group, 50, workspace=self.ws_owc, want_loss=False,
-                                                         want_researched=True)
+                                                         want_researched=True, G_out=self.G0)
             self.state["gamma"] = gamma
             self.state["owc_researched"] = cnt
         elif init == "owc_cd":
@@ -221,7 +230,7 @@ class Layer:
         rec(2)
         out = cdq.greedy_cd(self.H, self.Wd, scale, zero, Q, cfg.bits, cfg.group, cfg.T, workspace=self.ws_cd,
                             waves_per_column=self.args.waves, elems_per_lane=self.args.elems,
-                            loop_events=(evs[3], evs[4]) if evs is not None else None)
+                            loop_events=(evs[3], evs[4]) if evs is not None else None, G0=self.G0)
         rec(5)
         per, tot = cdq.loss(self.H, self.Wd, scale, zero, Q, cfg.group, workspace=self.ws_l)
         rec(6)
@@ -487,7 +496,10 @@ def main():
                     # the ceiling that binds on data: the matrix cores alone on pseudo-random operands (clock under that load included)
                     "frac_of_measured_mfma_only_random_operands": (h_tflops_exec / achievable["mfma_bf16_only_random_operands_TFLOPs"])
                     if cfg.x_dtype == "bf16" and "mfma_bf16_only_random_operands_TFLOPs" in achievable else None},
-        "fp64_gemm": {"gradient_init_tflops": 2.0 * cfg.d_out * cfg.d_in * cfg.d_in / (stages["cd_gradient_init"] * 1e-3) * 1e-12,
+        "fp64_gemm": {"gradient_init_tflops": None if layer.fused_g0 else
+                      2.0 * cfg.d_out * cfg.d_in * cfg.d_in / (stages["cd_gradient_init"] * 1e-3) * 1e-12,
+                      "gradient_init": "inside init_grid: the grid search's fp64 pass leaves the start gradient" if layer.fused_g0
+                      else "cdq_greedy_cd's own",
                       # the loss multiplies only the 128-wide blocks of H on and above the diagonal (H is symmetric)
                       "loss_tflops_executed": 2.0 * cfg.d_out * 128.0 * 128.0 * sum(range(1, (cfg.d_in + 127) // 128 + 1))
                       / (stages["loss"] * 1e-3) * 1e-12,

@@ -88,6 +88,11 @@ typedef struct {
     void    *ev_loop_begin;     /* NULL, or hipEvent_t recorded on `stream` just before ... */
     void    *ev_loop_end;       /* ... and just after the iteration-loop kernel, so a caller can
                                    time the loop apart from the gradient initialisation */
+    float   *G0;                /* NULL, or [d_out][d_in], 16-byte aligned: the start gradient H e of the codes passed in, as
+                                   cdq_gradient or cdq_init_owc's G_out give it.  The gradient initialisation is then
+                                   skipped, the workspace only needs 4 d_in bytes (rounded up to 256), and the array is
+                                   OVERWRITTEN (the loop uses it as scratch).  A G0 that is not the gradient of
+                                   (scale, zero, Q) makes the result meaningless; nothing checks it. */
 } cdq_cd_options;
 
 const char *cdq_strerror(int code);
@@ -136,6 +141,10 @@ int cdq_init_rtn(const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t
  *   scale, zero [d_out] out; Q [d_out][d_in] out; gamma_out NULL or [d_out] fp32;
  *   loss_out NULL or [d_out] fp64 (loss of the chosen grid point);
  *   researched NULL or one int32 (device): number of columns that failed the check below (not written when d_out == 0).
+ *   G_out NULL or [d_out][d_in] fp32: the gradient H e of the returned grid and codes, bit for bit what cdq_gradient
+ *   computes for them, for cdq_cd_options.G0.  It costs less here than there: the fp64 pass over every column's best
+ *   grid point is run as the full product E H, which leaves the gradient and yields the loss from the same sums; only
+ *   the columns that end at another grid point are multiplied again.
  * Cost and safeguard.  The exhaustive search costs n_gamma passes of the fp64 loss kernel (d_out d_in^2 FLOP each).  When
  * d_in is a multiple of 128 (at least 256) and 4 <= n_gamma <= 255, every grid point is first evaluated in fp16 on the
  * matrix cores in the normalised form s^2 f^T R f (R = H scaled to unit diagonal, f = e sqrt(diag H) / s), and only the
@@ -151,7 +160,8 @@ int cdq_init_rtn(const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t
  */
 int cdq_init_owc(const float *H, const float *Wt, int64_t d_out, int64_t d_in, int bits, int64_t group,
                  int n_gamma, float screen_margin, float *scale, float *zero, uint8_t *Q, float *gamma_out,
-                 double *loss_out, int32_t *researched, void *workspace, size_t workspace_bytes, void *stream);
+                 double *loss_out, int32_t *researched, float *G_out, void *workspace, size_t workspace_bytes,
+                 void *stream);
 
 /*
  * OWC-CD, the paper's initialisation for sub-channel grids (Algorithm 3; Section 3.2,

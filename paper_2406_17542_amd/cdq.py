@@ -34,7 +34,7 @@ class CdOptions(ctypes.Structure):
     _fields_ = [("waves_per_column", ctypes.c_int32), ("elems_per_lane", ctypes.c_int32),
                 ("exact_scorer_only", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("trace", ctypes.c_void_p), ("trace_cap", ctypes.c_int64), ("G_out", ctypes.c_void_p),
-                ("ev_loop_begin", ctypes.c_void_p), ("ev_loop_end", ctypes.c_void_p)]
+                ("ev_loop_begin", ctypes.c_void_p), ("ev_loop_end", ctypes.c_void_p), ("G0", ctypes.c_void_p)]
 
 
 def lib() -> ctypes.CDLL:
@@ -56,7 +56,7 @@ def lib() -> ctypes.CDLL:
         L.cdq_greedy_cd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, vp, sz, vp]
         L.cdq_greedy_cd_ex.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i64, i64, vp, ctypes.POINTER(CdOptions), vp, sz, vp]
         L.cdq_loss.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
-        L.cdq_init_owc.argtypes = [vp, vp, i64, i64, i32, i64, i32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.cdq_init_owc.argtypes = [vp, vp, i64, i64, i32, i64, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cdq_init_owc.restype = i32
         L.cdq_score_argmin.argtypes = [vp, vp, vp, vp, i64, i64, i32, i64, vp, vp, vp, vp]
         L.cdq_gather_update.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp]
@@ -98,6 +98,12 @@ def _dev(t: torch.Tensor, dtype, what: str) -> int:
     if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
         raise TypeError(f"{what}: need a contiguous CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
     return t.data_ptr()
+
+
+def _out(t: torch.Tensor, dtype, shape, what: str) -> int:
+    if tuple(t.shape) != tuple(shape):
+        raise TypeError(f"{what}: need shape {tuple(shape)}, got {tuple(t.shape)}")
+    return _dev(t, dtype, what)
 
 
 def workspace_bytes(op: int, n: int, d_out: int, d_in: int) -> int:
@@ -144,10 +150,11 @@ def init_rtn(Wt: torch.Tensor, bits: int, group: int):
 
 
 def init_owc(H, Wt, bits: int, group: int, n_gamma: int = 50, workspace: torch.Tensor | None = None, want_loss: bool = True,
-             screen_margin: float = 0.0, want_researched: bool = False):
+             screen_margin: float = 0.0, want_researched: bool = False, G_out: torch.Tensor | None = None):
     """OWC grid search (per-channel).  Returns (scale, zero, Q, gamma, loss_per_col); loss_per_col is None when
     want_loss is False.  With want_researched a sixth value: an int32 tensor [1], the number of columns whose fp16
-    estimate failed its check and were searched exhaustively in fp64."""
+    estimate failed its check and were searched exhaustively in fp64.  G_out: an fp32 [d_out][d_in] tensor that
+    receives the gradient H e of the returned grid (to be handed to greedy_cd as G0)."""
     d_out, d_in = Wt.shape
     scale = torch.empty((d_out, 1), dtype=torch.float32, device=Wt.device)
     zero = torch.empty((d_out, 1), dtype=torch.float32, device=Wt.device)
@@ -159,6 +166,7 @@ def init_owc(H, Wt, bits: int, group: int, n_gamma: int = 50, workspace: torch.T
     _check(lib().cdq_init_owc(_dev(H, torch.float32, "H"), _dev(Wt, torch.float32, "Wt"), d_out, d_in, bits, group, n_gamma,
                               float(screen_margin), scale.data_ptr(), zero.data_ptr(), Q.data_ptr(), gamma.data_ptr(),
                               per.data_ptr() if want_loss else None, cnt.data_ptr() if want_researched else None,
+                              _out(G_out, torch.float32, (d_out, d_in), "G_out") if G_out is not None else None,
                               ws.data_ptr(), ws.numel(), _stream()), "cdq_init_owc")
     if want_researched:
         return scale, zero, Q, gamma, per, cnt
@@ -246,15 +254,25 @@ def gradient(H, Wt, scale, zero, Q, group: int) -> torch.Tensor:
 
 def greedy_cd(H, Wt, scale, zero, Q, bits: int, group: int, T: int, stats: bool = True,
               workspace: torch.Tensor | None = None, waves_per_column: int = 0, elems_per_lane: int = 0,
-              trace_cap: int = 0, want_G: bool = False, loop_events=None, exact_scorer_only: bool = False):
+              trace_cap: int = 0, want_G: bool = False, loop_events=None, exact_scorer_only: bool = False,
+              G0: torch.Tensor | None = None):
     """Greedy coordinate descent in place on Q.  Returns a dict with 'stats' (int32 [d_out][4] view:
     moves, iters, converged, last_score bits), and optionally 'trace' and 'G'.  loop_events is an
-    optional pair of raw hipEvent_t handles recorded around the iteration-loop kernel."""
+    optional pair of raw hipEvent_t handles recorded around the iteration-loop kernel.  G0: the start gradient
+    of (scale, zero, Q) from gradient() or init_owc(G_out=...); it is consumed (overwritten) and the gradient
+    initialisation is skipped."""
     d_out, d_in = Wt.shape
-    ws = _workspace(OP_GREEDY_CD, 0, d_out, d_in, workspace)
+    if G0 is None:
+        ws = _workspace(OP_GREEDY_CD, 0, d_out, d_in, workspace)
+    elif workspace is not None:
+        ws = workspace
+    else:
+        ws = torch.empty((4 * d_in + 255) // 256 * 256, dtype=torch.uint8, device=Wt.device)
     st = torch.zeros((d_out, 4), dtype=torch.int32, device=Wt.device) if stats else None
     out = {}
-    opts = CdOptions(waves_per_column, elems_per_lane, int(exact_scorer_only), 0, None, 0, None, None, None)
+    opts = CdOptions(waves_per_column, elems_per_lane, int(exact_scorer_only), 0, None, 0, None, None, None, None)
+    if G0 is not None:
+        opts.G0 = _out(G0, torch.float32, (d_out, d_in), "G0")
     if loop_events is not None:            # (begin, end) raw hipEvent_t handles
         opts.ev_loop_begin, opts.ev_loop_end = loop_events
     if trace_cap > 0:

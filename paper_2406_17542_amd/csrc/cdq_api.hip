@@ -66,14 +66,14 @@ int cdq_init_rtn(const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t
 
 int cdq_init_owc(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, int n_gamma,
                  float screen_margin, float* scale, float* zero, uint8_t* Q, float* gamma_out, double* loss_out,
-                 int32_t* researched, void* workspace, size_t workspace_bytes, void* stream) {
+                 int32_t* researched, float* G_out, void* workspace, size_t workspace_bytes, void* stream) {
     if (bad_bits(bits) || bad_layer(d_out, d_in, group) || n_gamma < 1 || n_gamma > 4096) return CDQ_EINVAL;
     if (!(screen_margin >= 0.0f) || screen_margin > 1.0f) return CDQ_EINVAL;
     if (group != d_in) return CDQ_EUNSUPPORTED;       // Eq. (2) has one clipping strength per column
     if (d_out == 0) return CDQ_OK;
     if (H == nullptr || Wt == nullptr || scale == nullptr || zero == nullptr || Q == nullptr) return CDQ_EINVAL;
-    return cdq::owc_launch(H, Wt, d_out, d_in, bits, n_gamma, screen_margin, scale, zero, Q, gamma_out, loss_out, researched, workspace,
-                           workspace_bytes, (hipStream_t)stream);
+    return cdq::owc_launch(H, Wt, d_out, d_in, bits, n_gamma, screen_margin, scale, zero, Q, gamma_out, loss_out, researched, G_out,
+                           workspace, workspace_bytes, (hipStream_t)stream);
 }
 
 int cdq_init_owc_cd(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, int n_gamma,
@@ -141,12 +141,21 @@ int cdq_greedy_cd_ex(const float* H, const float* Wt, const float* scale, const 
         elems = e;
     }
     if ((elems == 36 || elems == 24) && vec != 4) return CDQ_EUNSUPPORTED;      // the kernel with the Hessian diagonal in LDS takes 16-byte chunks only
-    if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < cd_workspace_bytes(d_out, d_in)) return CDQ_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    float* G0 = (float*)workspace;
-    float* hdiag = (float*)((char*)workspace + cdq_align_up((size_t)d_out * d_in * sizeof(float), 256));
-    rc = cdq::gradient_launch(H, Wt, scale, zero, Q, d_out, d_in, group, G0, st);
-    if (rc != CDQ_OK) return rc;
+    float *G0, *hdiag;
+    if (opts != nullptr && opts->G0 != nullptr) {             // the caller brings the start gradient: only the diagonal needs room
+        if (misaligned(opts->G0, 16)) return CDQ_EINVAL;
+        if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < cdq_align_up((size_t)d_in * sizeof(float), 256))
+            return CDQ_EWORKSPACE;
+        G0 = opts->G0;
+        hdiag = (float*)workspace;
+    } else {
+        if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < cd_workspace_bytes(d_out, d_in)) return CDQ_EWORKSPACE;
+        G0 = (float*)workspace;
+        hdiag = (float*)((char*)workspace + cdq_align_up((size_t)d_out * d_in * sizeof(float), 256));
+        rc = cdq::gradient_launch(H, Wt, scale, zero, Q, d_out, d_in, group, G0, st);
+        if (rc != CDQ_OK) return rc;
+    }
     rc = cdq::extract_diag_launch(H, d_in, hdiag, st);
     if (rc != CDQ_OK) return rc;
     if (opts != nullptr && opts->ev_loop_begin != nullptr) CDQ_HIP_CHECK(hipEventRecord((hipEvent_t)opts->ev_loop_begin, st));

@@ -37,6 +37,12 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
                 void* ws, size_t ws_bytes, hipStream_t st, const uint8_t* row_block_active = nullptr);
 // row_block_active non-null: one byte per block of loss_block_rows() columns of W; blocks with a zero are skipped and
 // their entries of loss_per_col are unspecified
+// The product G = E H and, from the same fp64 sums, each row's loss (loss_per_col NULL: product only; else ws as for
+// loss_launch).  row_map / n_rows_dev (both or neither): operand row s < *n_rows_dev is written to row row_map[s] of G, the
+// other rows are not written.
+int gradient_loss_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
+                         int64_t d_out, int64_t d_in, int64_t group, float* G, double* loss_per_col, void* ws, size_t ws_bytes,
+                         hipStream_t st, const uint8_t* row_block_active, const int32_t* row_map, const int32_t* n_rows_dev);
 int loss_block_rows();
 int loss_static_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
                        int64_t d_out, int64_t d_in, int64_t group, double* loss_per_col, double* loss_total, hipStream_t st);
@@ -51,7 +57,8 @@ int owc_screen_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_
 // ---- owc.hip
 size_t owc_workspace_bytes(int64_t d_out, int64_t d_in);
 int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, float screen_margin, float* scale,
-               float* zero, uint8_t* Q, float* gamma_out, double* loss_out, int32_t* researched, void* ws, size_t ws_bytes, hipStream_t st);
+               float* zero, uint8_t* Q, float* gamma_out, double* loss_out, int32_t* researched, float* G_out, void* ws, size_t ws_bytes,
+               hipStream_t st);
 
 // ---- owc_cd.hip
 int owc_cd_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int64_t group, int n_gamma, int64_t T,

@@ -60,13 +60,19 @@ __device__ __forceinline__ void residual4(const float* __restrict__ Wt, const ui
     }
 }
 
-template <bool LOSS, bool VEC4>
+// MODE 0: the product (gradient).  MODE 1: the loss from the blocks of H on and above the diagonal.  MODE 2: the product
+// and, from the same accumulators, each row's loss sum_k C_jk e_jk as one partial sum per (row, column block of H); blocks of
+// rows can be switched off, and the rows can be sent elsewhere: row s of the operands goes to row row_map[s] of G, only
+// rows below *n_rows_dev exist.
+template <int MODE, bool VEC4>
 __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H, const float* __restrict__ Wt,
                                                      const float* __restrict__ scale, const float* __restrict__ zero,
                                                      const uint8_t* __restrict__ Q, int64_t d_out, int64_t d_in,
                                                      int64_t group, float* __restrict__ G,
                                                      double* __restrict__ partial, int chunk_blocks,
-                                                     double* __restrict__ G64, const uint8_t* __restrict__ row_block_active) {
+                                                     double* __restrict__ G64, const uint8_t* __restrict__ row_block_active,
+                                                     const int32_t* __restrict__ row_map, const int32_t* __restrict__ n_rows_dev) {
+    constexpr bool LOSS = MODE == 1;
     // two stages of As[k][m] = E[m0+m][k0+k] and Bs[k][n] = H[k0+k][n0+n]: the next step's tiles are written
     // while the current ones are multiplied, one barrier per step
     extern __shared__ __attribute__((aligned(16))) char eh_smem[];
@@ -76,6 +82,7 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
 
     // loss: the caller may only want some blocks of BM rows (the partial sums of the others are left as they are)
     if (LOSS && row_block_active != nullptr && row_block_active[blockIdx.x] == 0) return;
+    if (MODE == 2 && row_block_active != nullptr && row_block_active[blockIdx.y] == 0) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
     // loss: consecutive workgroups take the same item for consecutive column tiles (they share the H blocks, and the
@@ -220,18 +227,25 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int64_t row = m0 + wm * 32 + i * 16 + 4 * v + r_in;
-                if (row < d_out) {
+                int64_t dst = row;
+                bool live = row < d_out;
+                if (MODE == 2 && row_map != nullptr) {
+                    live = live && row < (int64_t)*n_rows_dev;
+                    dst = live ? (int64_t)row_map[row] : 0;
+                }
+                if (live) {
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         const int64_t col = n0 + wn * 32 + j * 16 + c_in;
                         if (col < d_in) {
-                            if (G64 != nullptr) G64[row * d_in + col] = acc[i][j][v];
-                            else G[row * d_in + col] = (float)acc[i][j][v];
+                            if (G64 != nullptr) G64[dst * d_in + col] = acc[i][j][v];
+                            else G[dst * d_in + col] = (float)acc[i][j][v];
                         }
                     }
                 }
             }
-    } else {
+    }
+    if (MODE != 0 && (LOSS || partial != nullptr)) {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -251,12 +265,13 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
                 }
                 // sum over the 16 lanes that share this row (fixed butterfly order)
                 for (int o = 8; o; o >>= 1) s += __shfl_xor(s, o);
-                if (c_in == 0) red[wn][lrow] = has_diag ? s : 2.0 * s;
+                if (c_in == 0) red[wn][lrow] = (!LOSS || has_diag) ? s : 2.0 * s;
             }
         __syncthreads();
         if (tid < BM) {
             const int64_t row = m0 + tid;
-            if (row < d_out) partial[(int64_t)blockIdx.y * d_out + row] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+            if (row < d_out)
+                partial[(int64_t)(LOSS ? blockIdx.y : blockIdx.x) * d_out + row] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
         }
     }
 }
@@ -309,9 +324,9 @@ __global__ __launch_bounds__(1024) void loss_total_kernel(const double* __restri
     if (threadIdx.x == 0) total[0] = sh[0];
 }
 
-template <bool LOSS, bool VEC4>
+template <int MODE, bool VEC4>
 bool eh_allow_lds() {
-    static const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(eh_gemm_kernel<LOSS, VEC4>),
+    static const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(eh_gemm_kernel<MODE, VEC4>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)EH_LDS);
     return rc == hipSuccess;
 }
@@ -336,14 +351,46 @@ int gradient_launch(const float* H, const float* Wt, const float* scale, const f
     if (d_out == 0) return CDQ_OK;
     const int64_t gx = (d_in + BN - 1) / BN, gy = (d_out + BM - 1) / BM;
     if (gy > 65535) return CDQ_EUNSUPPORTED;
-    if (!eh_allow_lds<false, true>() || !eh_allow_lds<false, false>()) return CDQ_EHIP;
+    if (!eh_allow_lds<0, true>() || !eh_allow_lds<0, false>()) return CDQ_EHIP;
     if (vec4_ok(H, Wt, Q, d_in, group))
-        hipLaunchKernelGGL((eh_gemm_kernel<false, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, G, (double*)nullptr, 0, G64, (const uint8_t*)nullptr);
+        hipLaunchKernelGGL((eh_gemm_kernel<0, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, G, (double*)nullptr, 0, G64, (const uint8_t*)nullptr, (const int32_t*)nullptr,
+                           (const int32_t*)nullptr);
     else
-        hipLaunchKernelGGL((eh_gemm_kernel<false, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, G, (double*)nullptr, 0, G64, (const uint8_t*)nullptr);
+        hipLaunchKernelGGL((eh_gemm_kernel<0, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, G, (double*)nullptr, 0, G64, (const uint8_t*)nullptr, (const int32_t*)nullptr,
+                           (const int32_t*)nullptr);
     CDQ_LAUNCH_CHECK();
+    return CDQ_OK;
+}
+
+// The product and, where loss_per_col is given, each row's loss from the same accumulators (ws as for loss_launch: one
+// partial sum per row and column block of H).  row_block_active, row_map, n_rows_dev: see the kernel.
+int gradient_loss_launch(const float* H, const float* Wt, const float* scale, const float* zero, const uint8_t* Q,
+                         int64_t d_out, int64_t d_in, int64_t group, float* G, double* loss_per_col, void* ws, size_t ws_bytes,
+                         hipStream_t st, const uint8_t* row_block_active, const int32_t* row_map, const int32_t* n_rows_dev) {
+    if (d_out == 0) return CDQ_OK;
+    const int64_t gx = (d_in + BN - 1) / BN, gy = (d_out + BM - 1) / BM;
+    if (gy > 65535) return CDQ_EUNSUPPORTED;
+    if ((row_map == nullptr) != (n_rows_dev == nullptr)) return CDQ_EINVAL;
+    double* partial = nullptr;
+    if (loss_per_col != nullptr) {          // the loss's own workspace holds at least one partial sum per row and column block
+        if (ws == nullptr || ws_bytes < loss_workspace_bytes(d_out, d_in) || ((uintptr_t)ws & 255)) return CDQ_EWORKSPACE;
+        partial = (double*)ws;
+    }
+    if (!eh_allow_lds<2, true>() || !eh_allow_lds<2, false>()) return CDQ_EHIP;
+    if (vec4_ok(H, Wt, Q, d_in, group))
+        hipLaunchKernelGGL((eh_gemm_kernel<2, true>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, G, partial, 0, (double*)nullptr, row_block_active, row_map, n_rows_dev);
+    else
+        hipLaunchKernelGGL((eh_gemm_kernel<2, false>), dim3((unsigned)gx, (unsigned)gy), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, G, partial, 0, (double*)nullptr, row_block_active, row_map, n_rows_dev);
+    CDQ_LAUNCH_CHECK();
+    if (loss_per_col != nullptr) {
+        hipLaunchKernelGGL(loss_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, (const double*)partial, d_out, (int)gx,
+                           loss_per_col);
+        CDQ_LAUNCH_CHECK();
+    }
     return CDQ_OK;
 }
 
@@ -366,13 +413,15 @@ int loss_launch(const float* H, const float* Wt, const float* scale, const float
     double* partial = (double*)ws;
     double* rows_ws = (double*)((char*)ws + cdq_align_up((size_t)d_out * gx * sizeof(double), 256));
     double* rows = loss_per_col ? loss_per_col : rows_ws;
-    if (!eh_allow_lds<true, true>() || !eh_allow_lds<true, false>()) return CDQ_EHIP;
+    if (!eh_allow_lds<1, true>() || !eh_allow_lds<1, false>()) return CDQ_EHIP;
     if (vec4_ok(H, Wt, Q, d_in, group))
-        hipLaunchKernelGGL((eh_gemm_kernel<true, true>), dim3((unsigned)gy, (unsigned)gx), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, (float*)nullptr, partial, chunk, (double*)nullptr, row_block_active);
+        hipLaunchKernelGGL((eh_gemm_kernel<1, true>), dim3((unsigned)gy, (unsigned)gx), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, (float*)nullptr, partial, chunk, (double*)nullptr, row_block_active,
+                           (const int32_t*)nullptr, (const int32_t*)nullptr);
     else
-        hipLaunchKernelGGL((eh_gemm_kernel<true, false>), dim3((unsigned)gy, (unsigned)gx), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
-                           d_out, d_in, group, (float*)nullptr, partial, chunk, (double*)nullptr, row_block_active);
+        hipLaunchKernelGGL((eh_gemm_kernel<1, false>), dim3((unsigned)gy, (unsigned)gx), dim3(NT), EH_LDS, st, H, Wt, scale, zero, Q,
+                           d_out, d_in, group, (float*)nullptr, partial, chunk, (double*)nullptr, row_block_active,
+                           (const int32_t*)nullptr, (const int32_t*)nullptr);
     CDQ_LAUNCH_CHECK();
     hipLaunchKernelGGL(loss_rows_kernel, dim3((unsigned)((d_out + 255) / 256)), dim3(256), 0, st, partial, d_out, (int)gx, rows);
     CDQ_LAUNCH_CHECK();

@@ -224,6 +224,36 @@ __global__ __launch_bounds__(256) void owc_update_best_rows_kernel(const double*
     best_gamma[j] = bg;
 }
 
+// ---- the start gradient as a by-product: the pass over every column's best-screened grid point leaves H e of that grid
+// point in G; the columns that ended at another grid point get their row again.
+// changed[j] = 1 where the chosen strength is not the one the row of G was computed for
+__global__ __launch_bounds__(256) void owc_changed_kernel(const float* __restrict__ best_gamma, const float* __restrict__ first_gamma,
+                                                          int64_t d_out, int32_t* __restrict__ changed) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j < d_out) changed[j] = best_gamma[j] != first_gamma[j] ? 1 : 0;
+}
+
+// the changed columns, in order, as rows: row base[j] is column j at its chosen grid index; total = their number; flags for
+// the blocks of rows that exist
+__global__ __launch_bounds__(256) void owc_changed_rows_kernel(const int32_t* __restrict__ changed, const int32_t* __restrict__ base,
+                                                               const float* __restrict__ best_gamma, int n_gamma, int64_t d_out,
+                                                               int32_t* __restrict__ row_col, uint8_t* __restrict__ row_k,
+                                                               int32_t* __restrict__ total) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d_out || changed[j] == 0) return;
+    int k = (int)rintf(best_gamma[j] * (float)n_gamma);
+    k = k < 1 ? 1 : (k > n_gamma ? n_gamma : k);
+    row_col[base[j]] = (int32_t)j;
+    row_k[base[j]] = (uint8_t)k;
+    atomicMax(total, base[j] + 1);
+}
+
+__global__ __launch_bounds__(256) void owc_row_blocks_kernel(const int32_t* __restrict__ total, int block_rows, int64_t n_blocks,
+                                                             uint8_t* __restrict__ rows_active) {
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (x < n_blocks) rows_active[x] = (x * block_rows < *total) ? 1 : 0;
+}
+
 constexpr float kScreenMargin = 3e-3f;      // relative; the fp16 evaluation was off by 3e-4 at most on heavy-tailed test layers
 
 // The check that makes the two-stage search safe to use: every column's chosen grid point has been evaluated both ways, so
@@ -264,11 +294,13 @@ size_t owc_workspace_bytes(int64_t d_out, int64_t d_in) {
     // row -> column, row -> grid index, total, block flags
     b += cdq_align_up((size_t)d_out * d_in * sizeof(float), 256) + cdq_align_up((size_t)d_out * sizeof(double), 256);
     b += cdq_align_up((size_t)d_out * sizeof(float), 256) * 4 + cdq_align_up((size_t)d_out, 256) + 256 + cdq_align_up((size_t)n_blocks, 256);
+    b += cdq_align_up((size_t)d_out * sizeof(float), 256);           // the strength each row of the start gradient was computed for
     return b;
 }
 
 int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int bits, int n_gamma, float screen_margin, float* scale,
-               float* zero, uint8_t* Q, float* gamma_out, double* loss_out, int32_t* researched, void* ws, size_t ws_bytes, hipStream_t st) {
+               float* zero, uint8_t* Q, float* gamma_out, double* loss_out, int32_t* researched, float* G_out, void* ws, size_t ws_bytes,
+               hipStream_t st) {
     if (d_out == 0) {
         if (researched != nullptr) {
             hipLaunchKernelGGL(owc_fill_f32_kernel, dim3(1), dim3(256), 0, st, (float*)researched, (int64_t)1, 0.0f);     // the bits of +0.0f are the integer 0
@@ -298,6 +330,11 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
 
     hipLaunchKernelGGL(owc_minmax_kernel, cols, t256, 0, st, Wt, d_in, lo, hi);
     CDQ_LAUNCH_CHECK();
+    bool g_from_first_pass = false;
+    float* first_gamma = nullptr;
+    int32_t *g_changed = nullptr, *g_base = nullptr, *g_row_col = nullptr, *g_total = nullptr;
+    uint8_t *g_row_k = nullptr, *g_rows_active = nullptr;
+    float *g_Wc = nullptr, *g_zeros = nullptr;
     if (owc_screen_applies(d_out, d_in, n_gamma)) {
         const int block_rows = loss_block_rows();
         const int64_t n_blocks = (d_out + block_rows - 1) / block_rows;
@@ -319,7 +356,10 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
         int32_t* row_col = (int32_t*)gp;    gp += fsz;
         uint8_t* row_k = (uint8_t*)gp;      gp += cdq_align_up((size_t)d_out, 256);
         int32_t* total = (int32_t*)gp;      gp += 256;
-        uint8_t* rows_active = (uint8_t*)gp;
+        uint8_t* rows_active = (uint8_t*)gp;  gp += cdq_align_up((size_t)n_blocks, 256);
+        first_gamma = (float*)gp;
+        g_changed = extras; g_base = base; g_row_col = row_col; g_total = total; g_row_k = row_k; g_rows_active = rows_active;
+        g_Wc = Wc; g_zeros = zeros;
         const int32_t cap = (int32_t)d_out;
         hipLaunchKernelGGL(owc_fill_f32_kernel, col_blocks, t256, 0, st, zeros, d_out, 0.0f);
         CDQ_LAUNCH_CHECK();
@@ -358,9 +398,18 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
             hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, 1.0f, (const float*)rank_gamma, trial_scale,
                                (float*)nullptr, trial_q);
             CDQ_LAUNCH_CHECK();
-            rc = loss_launch(H, Wt, trial_scale, lo, trial_q, d_out, d_in, d_in, trial_loss, nullptr, loss_ws, loss_ws_bytes, st,
-                             active + (int64_t)r * n_blocks);
-            if (rc != CDQ_OK) return rc;
+            if (r == 0 && G_out != nullptr) {
+                // every column is in this pass: the whole product, which leaves H e in G_out, with the loss taken from the same sums
+                rc = gradient_loss_launch(H, Wt, trial_scale, lo, trial_q, d_out, d_in, d_in, G_out, trial_loss, loss_ws, loss_ws_bytes, st,
+                                          nullptr, nullptr, nullptr);
+                if (rc != CDQ_OK) return rc;
+                CDQ_HIP_CHECK(hipMemcpyAsync(first_gamma, rank_gamma, (size_t)d_out * sizeof(float), hipMemcpyDeviceToDevice, st));
+                g_from_first_pass = true;
+            } else {
+                rc = loss_launch(H, Wt, trial_scale, lo, trial_q, d_out, d_in, d_in, trial_loss, nullptr, loss_ws, loss_ws_bytes, st,
+                                 active + (int64_t)r * n_blocks);
+                if (rc != CDQ_OK) return rc;
+            }
             hipLaunchKernelGGL(owc_update_best_ranked_kernel, col_blocks, t256, 0, st, (const double*)trial_loss, (const float*)rank_gamma,
                                d_out, best_loss, best_gamma);
             CDQ_LAUNCH_CHECK();
@@ -410,6 +459,33 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
     }
     hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, 1.0f, best_gamma, scale, zero, Q);
     CDQ_LAUNCH_CHECK();
+    if (G_out != nullptr) {
+        if (!g_from_first_pass) {
+            const int rc = gradient_launch(H, Wt, scale, zero, Q, d_out, d_in, d_in, G_out, st);
+            if (rc != CDQ_OK) return rc;
+        } else {
+            // rows of the columns that ended at another grid point than their best-screened one, gathered as minus-residuals
+            // (the same bits as the residual of scale, zero, Q) and multiplied again into their place
+            const int block_rows = loss_block_rows();
+            const int64_t n_blocks = (d_out + block_rows - 1) / block_rows;
+            hipLaunchKernelGGL(owc_changed_kernel, col_blocks, t256, 0, st, (const float*)best_gamma, (const float*)first_gamma, d_out, g_changed);
+            CDQ_LAUNCH_CHECK();
+            hipLaunchKernelGGL(owc_scan_extras_kernel, dim3(1), dim3(1024), 0, st, (const int32_t*)g_changed, d_out, g_base, g_total);
+            CDQ_LAUNCH_CHECK();
+            hipLaunchKernelGGL(owc_changed_rows_kernel, col_blocks, t256, 0, st, (const int32_t*)g_changed, (const int32_t*)g_base,
+                               (const float*)best_gamma, n_gamma, d_out, g_row_col, g_row_k, g_total);
+            CDQ_LAUNCH_CHECK();
+            hipLaunchKernelGGL(owc_row_blocks_kernel, dim3((unsigned)((n_blocks + 255) / 256)), t256, 0, st, (const int32_t*)g_total, block_rows,
+                               n_blocks, g_rows_active);
+            CDQ_LAUNCH_CHECK();
+            hipLaunchKernelGGL(owc_row_residual_kernel, cols, t256, 0, st, Wt, d_in, bits, (const float*)lo, (const float*)hi, n_gamma,
+                               (const int32_t*)g_row_col, (const uint8_t*)g_row_k, (const int32_t*)g_total, g_Wc);
+            CDQ_LAUNCH_CHECK();
+            const int rc = gradient_loss_launch(H, g_Wc, g_zeros, g_zeros, trial_q, d_out, d_in, d_in, G_out, nullptr, nullptr, 0, st,
+                                                g_rows_active, g_row_col, g_total);
+            if (rc != CDQ_OK) return rc;
+        }
+    }
     if (gamma_out != nullptr) CDQ_HIP_CHECK(hipMemcpyAsync(gamma_out, best_gamma, (size_t)d_out * sizeof(float), hipMemcpyDeviceToDevice, st));
     if (loss_out != nullptr) CDQ_HIP_CHECK(hipMemcpyAsync(loss_out, best_loss, (size_t)d_out * sizeof(double), hipMemcpyDeviceToDevice, st));
     return CDQ_OK;

@@ -81,10 +81,13 @@ def quantize_layer(chunks: Iterable[torch.Tensor], Wt: torch.Tensor, bits: int, 
         cur = nxt
     H = acc.H
 
+    G0 = None
     if init == "rtn":
         scale, zero, Q = timed("init", lambda: cdq.init_rtn(Wt, bits, group))
     elif init == "owc":
-        scale, zero, Q, _, _ = timed("init", lambda: cdq.init_owc(H, Wt, bits, group, n_gamma, want_loss=False))
+        # the grid search's fp64 pass leaves the start gradient of Algorithm 1 behind: CD below starts from it
+        G0 = torch.empty(Wt.shape, dtype=torch.float32, device=Wt.device)
+        scale, zero, Q, _, _ = timed("init", lambda: cdq.init_owc(H, Wt, bits, group, n_gamma, want_loss=False, G_out=G0))
     elif init == "owc_cd":
         o = timed("init", lambda: cdq.init_owc_cd(H, Wt, bits, group, n_gamma))
         scale, zero, Q = o["scale"], o["zero"], o["Q"]
@@ -92,7 +95,8 @@ def quantize_layer(chunks: Iterable[torch.Tensor], Wt: torch.Tensor, bits: int, 
         raise ValueError(f"unknown init {init!r}")
     loss_init = timed("loss", lambda: cdq.loss(H, Wt, scale, zero, Q, group))[1]
 
-    out = timed("cd", lambda: cdq.greedy_cd(H, Wt, scale, zero, Q, bits, group, T))
+    out = timed("cd", lambda: cdq.greedy_cd(H, Wt, scale, zero, Q, bits, group, T, G0=G0))
+    del G0
     res = {"H": H, "scale": scale, "zero": zero, "Q": Q, "stats": out["stats"], "n_tokens": acc.n_tokens,
            "loss_init": float(loss_init.item())}
     per, tot = timed("loss", lambda: cdq.loss(H, Wt, scale, zero, Q, group))

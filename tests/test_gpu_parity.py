@@ -302,6 +302,40 @@ def test_init_owc_columns_that_fail_the_check_are_searched_exhaustively(cdq, ora
     assert int(cnt.item()) == 0
 
 
+@pytest.mark.parametrize("d_out,d_in,n,bits,n_gamma,margin", [(300, 384, 900, 3, 50, 0.0),      # screened: a few columns end elsewhere
+                                                              (96, 384, 900, 3, 50, 1e-7),      # every column searched exhaustively
+                                                              (129, 512, 800, 4, 20, 0.0), (33, 256, 500, 2, 4, 0.0),
+                                                              (48, 200, 600, 3, 50, 0.0),       # no screen for this d_in
+                                                              (5, 1024, 1500, 3, 50, 0.0)])
+def test_init_owc_start_gradient(cdq, oracle, d_out, d_in, n, bits, n_gamma, margin):
+    """The start gradient that the grid search leaves as a by-product (gradient init of Algorithm 1 for the grid of Eq. (2)
+    it returns) is, bit for bit, what cdq_gradient computes for that grid; asking for it does not change the search; and
+    Algorithm 1 started from it makes the moves it makes when it computes the gradient itself -- and the oracle's."""
+    X, Wt = rand_layer(31 + d_in, d_in, d_out, n, corr=0.5)
+    rng = np.random.default_rng(d_in + 1)
+    Wt *= np.exp(0.7 * rng.standard_normal(Wt.shape)).astype(np.float32)
+    Wt[:, rng.integers(0, d_in, 3)] *= 5.0
+    Wt[0, :] = 0.125
+    H32 = oracle.hessian(X).astype(np.float32)
+    Hd, Wd = dev(H32), dev(Wt)
+    s0, z0, Q0, g0, per0 = cdq.init_owc(Hd, Wd, bits, d_in, n_gamma, screen_margin=margin)
+    G = torch.full((d_out, d_in), float("nan"), dtype=torch.float32, device="cuda")
+    s, z, Q, g, per = cdq.init_owc(Hd, Wd, bits, d_in, n_gamma, screen_margin=margin, G_out=G)
+    for u, v in ((s0, s), (z0, z), (Q0, Q), (g0, g)):
+        assert torch.equal(u, v)
+    np.testing.assert_allclose(per.cpu().numpy(), per0.cpu().numpy(), rtol=1e-12, atol=1e-300)     # same sums, another order
+    G_ref = cdq.gradient(Hd, Wd, s, z, Q, d_in)
+    assert torch.equal(G.view(torch.int32), G_ref.view(torch.int32)), "the by-product is not the gradient of the returned grid"
+    # Algorithm 1 from the supplied gradient
+    T = 64
+    Qa, Qb = Q.clone(), Q.clone()
+    out_a = cdq.greedy_cd(Hd, Wd, s, z, Qa, bits, d_in, T, want_G=True)
+    out_b = cdq.greedy_cd(Hd, Wd, s, z, Qb, bits, d_in, T, want_G=True, G0=G)
+    assert torch.equal(Qa, Qb) and torch.equal(out_a["stats"], out_b["stats"]) and torch.equal(out_a["G"], out_b["G"])
+    ref = oracle.greedy_cd(H32, Wt, s.cpu().numpy(), z.cpu().numpy(), Q.cpu().numpy(), bits, d_in, T)
+    assert np.array_equal(Qb.cpu().numpy(), ref["Q"]) and np.array_equal(out_b["stats"].cpu().numpy()[:, 0], ref["moves"])
+
+
 def test_init_owc_weights_at_an_odd_address(cdq, oracle):
     """Eq. (2) grid search with Wt 4 bytes off a 16-byte boundary (the library's scalar-load kernels) chooses, for every
     column, what it chooses for the aligned copy, and that is the oracle's choice."""
