@@ -380,14 +380,24 @@ __global__ __launch_bounds__(256) void owc_screen_t256_kernel(const _Float16* __
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         const int64_t j = j0 + wn * 128 + b * 32 + (lane & 31);
+        const _Float16* col = Ft + (c0 + wm * 128 + 4 * (lane >> 5)) * rows + j;
         float t = 0.0f;
+        // the residuals of two 32-row blocks are fetched together, then used: left to itself the compiler waits for every
+        // two-byte load before it issues the next, 256 round trips to L2 per tile
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int a2 = 0; a2 < 4; a2 += 2) {
+            _Float16 f[2][16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t c = c0 + wm * 128 + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                t = fmaf(acc[a][b][v], (float)Ft[c * rows + j], t);
-            }
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) f[u][v] = col[(int64_t)((a2 + u) * 32 + 8 * (v >> 2) + (v & 3)) * rows];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) t = fmaf(acc[a2 + u][b][v], (float)f[u][v], t);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         t += __shfl_xor(t, 32);
         if (lane < 32) partial[((int64_t)cb * 2 + wm) * rows + j] = 2.0f * t;
     }
