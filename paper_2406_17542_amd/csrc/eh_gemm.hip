@@ -246,23 +246,32 @@ __global__ __launch_bounds__(NT) void eh_gemm_kernel(const float* __restrict__ H
             }
     }
     if (MODE != 0 && (LOSS || partial != nullptr)) {
+        // the residuals this lane's 16 sums meet, all fetched before the first is used (elements outside the matrix read
+        // element (0, 0) and count as zero)
+        float ev[2][4][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int64_t row = m0 + wm * 32 + i * 16 + 4 * v + r_in;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int64_t col = n0 + wn * 32 + j * 16 + c_in;
+                    const bool ok = row < d_out && col < d_in;
+                    const int64_t at = ok ? row * d_in + col : 0, ag = ok ? row * n_grp + col / group : 0;
+                    const float e = fmaf(scale[ag], (float)Q[at], zero[ag]) - Wt[at];
+                    ev[i][v][j] = ok ? e : 0.0f;
+                }
+            }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int lrow = wm * 32 + i * 16 + 4 * v + r_in;
-                const int64_t row = m0 + lrow;
                 double s = 0.0;
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int64_t col = n0 + wn * 32 + j * 16 + c_in;
-                    if (row < d_out && col < d_in) {
-                        const int64_t gi = col / group;
-                        const float e = fmaf(scale[row * n_grp + gi], (float)Q[row * d_in + col], zero[row * n_grp + gi]) -
-                                        Wt[row * d_in + col];
-                        s += acc[i][j][v] * (double)e;
-                    }
-                }
+                for (int j = 0; j < 2; ++j) s += acc[i][j][v] * (double)ev[i][v][j];
                 // sum over the 16 lanes that share this row (fixed butterfly order)
                 for (int o = 8; o; o >>= 1) s += __shfl_xor(s, o);
                 if (c_in == 0) red[wn][lrow] = (!LOSS || has_diag) ? s : 2.0 * s;

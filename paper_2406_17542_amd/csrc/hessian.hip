@@ -167,16 +167,28 @@ __device__ __forceinline__ void hessian_tile_store(const f16v (&acc)[4][4], int6
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+        for (int b = 0; b < 4; ++b) {
+            const int col = wn * 128 + b * 32 + (lane & 31);
+            // what dst holds is fetched for the whole 32x32 block before any of it is used (element by element the compiler
+            // waits out one round trip per value); elements outside the matrix read the tile's first element instead
+            float old[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) old[v] = 0.0f;
+            if (add_old) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = wm * 128 + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
+                    const bool ok = i0 + row < d_in && j0 + col < d_in;
+                    old[v] = dst[ok ? row * ld + col : 0];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = wm * 128 + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v & 3);
-                const int col = wn * 128 + b * 32 + (lane & 31);
-                if (i0 + row < d_in && j0 + col < d_in) {
-                    float* p = dst + row * ld + col;
-                    *p = add_old ? acc[a][b][v] + *p : acc[a][b][v];
-                }
+                if (i0 + row < d_in && j0 + col < d_in) dst[row * ld + col] = add_old ? acc[a][b][v] + old[v] : acc[a][b][v];
             }
+        }
 }
 
 // The plain path as a function of its own (a call, not inlined): the compiler then places its 256 accumulators without
