@@ -39,9 +39,13 @@ namespace {
 
 constexpr float kHalfWindow = 1.0f / 512.0f;     // |frac(rf) - 1/2| below this: neighbouring levels may tie
 
-// reciprocal of the parabola's curvature 2 a H_ii; only steers which levels are scored
+// reciprocal of the parabola's curvature 2 a H_ii.  It only steers which levels are scored (every score is computed from
+// H_ii itself), so the hardware's one-instruction reciprocal, good to one unit in the last place, serves: a level chosen
+// differently because of that last place lies at a half-integer minimiser, where the two-level scorer takes over anyway.
+// The kernels that keep the diagonal in LDS recompute it at every use; a correctly rounded division there cost more than
+// the scoring itself (a dozen instructions and a branch per coordinate).
 __device__ __forceinline__ float curvature_inv(float h, float a) {
-    return (h > 0.0f) ? fminf(__frcp_rn(2.0f * a * h), 3.0e38f) : 0.0f;
+    return (h > 0.0f) ? fminf(__builtin_amdgcn_rcpf(2.0f * a * h), 3.0e38f) : 0.0f;
 }
 
 // LDSH: the Hessian diagonal lives in LDS (each lane reads back only what it wrote, so no barrier is involved) and
@@ -109,12 +113,17 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
             }
         }
     }
+    // The lane's index as the loop sees it.  In the kernels with the diagonal in LDS it is passed through an empty asm at
+    // the top of every iteration, so that what is derived from it (chunk offsets, validity masks, LDS addresses: two dozen
+    // values that never change) is recomputed where it is used, one or two instructions each, instead of being hoisted out
+    // of the loop into registers that do not exist and reloaded from scratch memory in front of every row load.
+    int tl = tid;
     // Hessian diagonal and curvature reciprocal of the lane's chunk c
     auto diag_of = [&](int c, float (&h)[VEC], float (&ci)[VEC]) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             if constexpr (LDSH) {
-                h[v] = hd_lds[(c * 64 * W + tid) * VEC + v];
+                h[v] = hd_lds[(c * 64 * W + tl) * VEC + v];
                 ci[v] = curvature_inv(h[v], a_c[c]);
             } else {
                 h[v] = hd[c * VEC + v];
@@ -128,7 +137,7 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
 
     // (ordered score, payload) of this lane's best candidate -> team-wide winner, uniform
     auto team_min = [&](float bs, float bu, int be, uint32_t flag) -> uint64_t {
-        const int bi = (be / VEC) * STRIDE + tid * VEC + (be % VEC);
+        const int bi = (be / VEC) * STRIDE + tl * VEC + (be % VEC);
         const uint32_t payload = ((uint32_t)bi << 7) | ((uint32_t)((int)bu + 32) << 1) | flag;
         uint64_t key = wave_min_key(order_bits(bs), payload);
         if (W > 1) {
@@ -198,10 +207,10 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
     // budget.  So does this one, but not step by step: when a move undoes the previous one, 2g is written to the column's
     // row of the start gradient; if two moves later the codes are back (the two moves again undid each other) and 2g has
     // exactly the same bits, the state is that of two iterations ago, the loop is periodic from here on, and only the
-    // parity of what is left of the budget matters.  Not done when the moves are traced, and only built into the kernels for
-    // 4 or more wavefronts and up to 24 coordinates per lane (FF): there a column that spends its whole budget runs on for
-    // tens to hundreds of milliseconds after everything else has finished, while the bookkeeping costs 1 to 6 % of the loop;
-    // with one or two wavefronts it costs 5 % and the budget is short, and at 32 and 36 coordinates per lane it adds spills.
+    // parity of what is left of the budget matters.  Not done when the moves are traced.  Built into every kernel for 16-byte
+    // chunks with up to 24 coordinates per lane and into the 32-per-lane kernel with the diagonal in LDS (FF); the test reads
+    // the snapshot one chunk at a time, so it costs no registers in the loop.  The 36-per-lane kernel is built without: it
+    // spills as it is, and the extra code made it 30 % slower.
     auto team_all = [&](bool ok) -> bool {
         uint64_t v = (__ballot(ok) == ~0ull) ? 1u : 0u;
         if (W > 1) {
@@ -218,6 +227,10 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
     int snap_t = -1;                          // iteration whose 2g the snapshot holds
 
     for (int t = 0; t < T; ++t) {
+        if constexpr (LDSH) {
+            tl = tid;
+            asm volatile("" : "+v"(tl));
+        }
         // ---- 1 + 2. score and arg-min
         uint64_t key = exact_only ? score_exact() : score_fast();
         uint32_t khi = __builtin_amdgcn_readfirstlane((uint32_t)(key >> 32));
@@ -238,14 +251,14 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
 
         const int cstar = istar / STRIDE;
         const int within = istar - cstar * STRIDE;
-        const uint32_t inc = (within / VEC == tid) ? ((uint32_t)ustar << (8 * (within % VEC))) : 0u;
+        const uint32_t inc = (within / VEC == tl) ? ((uint32_t)ustar << (8 * (within % VEC))) : 0u;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) qpack[c] += (c == cstar) ? inc : 0u;
 
         // all loads of the row first (lanes past the end read the row's start and add nothing), so that the
         // chunks' memory latencies overlap instead of following one another
         if constexpr (VEC == 4) {
-            constexpr int BATCH = LDSH ? 3 : NCH;        // chunks whose loads are in flight together (registers)
+            constexpr int BATCH = NCH;        // chunks whose loads are in flight together: all of them
 #pragma unroll
             for (int c0 = 0; c0 < NCH; c0 += BATCH) {
                 float4 hv[BATCH];
@@ -253,7 +266,7 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
                 for (int cb = 0; cb < BATCH; ++cb) {
                     const int c = c0 + cb;
                     if (c < NCH) {
-                        const int base = c * STRIDE + tid * VEC;
+                        const int base = c * STRIDE + tl * VEC;
                         hv[cb] = hrow4[(base < d_in ? base : 0) >> 2];
                     }
                 }
@@ -261,7 +274,7 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
                 for (int cb = 0; cb < BATCH; ++cb) {
                     const int c = c0 + cb;
                     if (c < NCH) {
-                        const float m = (c * STRIDE + tid * VEC < d_in) ? delta2 : 0.0f;
+                        const float m = (c * STRIDE + tl * VEC < d_in) ? delta2 : 0.0f;
                         g2[c * 4 + 0] = fmaf(m, hv[cb].x, g2[c * 4 + 0]);
                         g2[c * 4 + 1] = fmaf(m, hv[cb].y, g2[c * 4 + 1]);
                         g2[c * 4 + 2] = fmaf(m, hv[cb].z, g2[c * 4 + 2]);
@@ -292,11 +305,12 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
                 bool same = true;
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
-                    const int base = c * STRIDE + tid * VEC;
+                    const int base = c * STRIDE + tl * VEC;
                     if (base < d_in) {
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) same &= __float_as_uint(snap[base + v]) == __float_as_uint(g2[c * VEC + v]);
                     }
+                    __builtin_amdgcn_sched_barrier(0);       // one chunk of the snapshot in registers at a time: this path is rare
                 }
                 if (team_all(same)) {                                    // periodic from here: only the parity of the rest matters
                     const int left = T - (t + 1);
@@ -308,7 +322,7 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
             if (take) {
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
-                    const int base = c * STRIDE + tid * VEC;
+                    const int base = c * STRIDE + tl * VEC;
                     if (base < d_in) {
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) snap[base + v] = g2[c * VEC + v];
@@ -352,7 +366,7 @@ template <int W, int E, int VEC, bool LDSH = false>
 int launch_one(const float* H, const float* hdiag, float* G0, const float* scale, uint8_t* Q, int64_t d_out,
                int d_in, int bits, int group, int group_shift, int n_grp, int T, int exact_only, cdq_col_stats* stats,
                int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
-    constexpr bool FF = (W >= 4 && E <= 24 && VEC == 4);
+    constexpr bool FF = (VEC == 4 && (E <= 24 || (LDSH && E == 32)));
     const size_t lds = LDSH ? sizeof(float) * 64 * W * E : 0;
     if (LDSH) {
         static const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(cd_fused_kernel<W, E, VEC, LDSH, FF>),

@@ -174,11 +174,11 @@ def layer_with_exact_ties(seed=0, d_in=256, d_out=4, n=2000):
     return H32, Wt, good[:d_out]
 
 
-@pytest.mark.parametrize("waves,elems", [(0, 0), (2, 16), (16, 4), (16, 16), (16, 24), (16, 36)])
+@pytest.mark.parametrize("waves,elems", [(0, 0), (1, 8), (1, 16), (2, 16), (4, 8), (16, 4), (16, 16), (16, 24), (16, 32), (16, 36)])
 def test_greedy_cd_alternating_between_two_levels_of_equal_loss(cdq, oracle, waves, elems):
-    """The kernels for 16 wavefronts and up to 24 coordinates per lane jump over the rest of the budget once the state
-    repeats; the others take every step; the oracle takes every step.  Same moves, same codes, for even and odd budgets,
-    and the same trajectory when it is traced (tracing switches the jump off)."""
+    """Every kernel for 16-byte chunks except the one with 36 coordinates per lane jumps over the rest of the budget once
+    the state repeats; that one takes every step; the oracle takes every step.  Same moves, same codes, for even and odd
+    budgets, and the same trajectory when it is traced (tracing switches the jump off)."""
     H32, Wt, ties = layer_with_exact_ties()
     d_out, d_in = Wt.shape
     a, b, q0 = oracle.init_grid(Wt, 3, d_in)
