@@ -277,14 +277,16 @@ def loop_roofline(cfg, mode, moves, loop_ms, shape, gather_gbs):
     h_bytes = 4.0 * cfg.d_in * cfg.d_in
     cd_bytes = moves * 4.0 * cfg.d_in
     gbs = cd_bytes / (loop_ms * 1e-3) * 1e-9
-    waves, elems = shape
+    waves, elems, teams_per_cu = shape
+    kernel = "cd_fused_pair_kernel" if teams_per_cu == 2 else "cd_fused_kernel"
     valu_per_update = waves * VALU_PER_WAVE_ITER_AT_16 * elems / 16.0
     valu_rate = moves * valu_per_update / (loop_ms * 1e-3)
     traffic, source = load_traffic("cd_fused_kernel", f"{cfg.name}:{mode}")
-    r = {"kernel": "cd_fused_kernel", "bound": "hbm" if h_bytes > INFINITY_CACHE_BYTES else "cache",
+    r = {"kernel": kernel, "bound": "hbm" if h_bytes > INFINITY_CACHE_BYTES else "cache",
          "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
          "traffic": traffic, "algorithmic_bytes_per_launch": cd_bytes, "avg_launch_ms": loop_ms,
-         "launch_shape": {"wavefronts_per_column": waves, "coordinates_per_lane": elems},
+         "launch_shape": {"wavefronts_per_column": waves, "coordinates_per_lane": elems,
+                          "columns_resident_per_cu": teams_per_cu * max(1, 16 // waves)},
          "valu_issue": {"instr_per_update_model": valu_per_update, "achieved_instr_per_s": valu_rate,
                         "chip_issue_rate_instr_per_s": VALU_ISSUE_PEAK, "frac": valu_rate / VALU_ISSUE_PEAK}}
     if traffic is not None:
@@ -337,7 +339,7 @@ def probes(cfg, H, shape, ev, stream, cdq, want_stream=True):
             ev.record(e1, stream)
             achievable[key] = flop / (ev.elapsed_ms(e0, e1) * 1e-3) * 1e-12
     waves = shape[0]
-    teams = 256 * max(1, 16 // waves)          # as many teams as the loop kernel keeps resident: 16 wavefronts per CU
+    teams = 256 * max(1, 16 // waves) * shape[2]          # as many teams as the loop kernel keeps resident per CU
     row_bytes = 4 * cfg.d_in
     iters = max(50, int(2e11 / (teams * row_bytes)))
     cdq.probe_gather(H, cfg.d_in, row_bytes, teams, waves, iters, sink)
@@ -447,7 +449,7 @@ def main():
     moves = int(state["stats"][:, 0].sum().item())
     converged = int(state["stats"][:, 2].sum().item())
     loss_final = float(state["loss"].item())
-    shape = (args.waves, args.elems) if args.waves and args.elems else cdq.greedy_cd_shape(cfg.d_out, cfg.d_in, cfg.group)
+    shape = (args.waves, args.elems, 1) if args.waves and args.elems else cdq.greedy_cd_launch(cfg.d_out, cfg.d_in, cfg.group)
 
     achievable = {} if args.no_probes else probes(cfg, layer.H, shape, ev, stream, cdq)
     flop_exec, h_tflops_exec, h_tflops_eff = layer.hessian_rates(stages)
@@ -535,7 +537,7 @@ def main():
             lay = Layer(c, "rtn", c.init, args)
             ms, stg = lay.timed(ev, stream, args.others_steps, 1)
             mv = int(lay.state["stats"][:, 0].sum().item())
-            shp = cdq.greedy_cd_shape(c.d_out, c.d_in, c.group)
+            shp = cdq.greedy_cd_launch(c.d_out, c.d_in, c.group)
             gath = None if args.no_probes else probes(c, lay.H, shp, ev, stream, cdq, want_stream=False).get("h_row_gather_GBps")
             roof = loop_roofline(c, "rtn", mv, stg["cd_loop"], shp, gath)
             _, h_exec, h_eff = lay.hessian_rates(stg)

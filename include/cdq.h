@@ -80,7 +80,12 @@ typedef struct {
                                    its two levels -- worse by at most 2^-15 a^2 H_ii + 2^-21 |s| -- and its better
                                    level would have beaten the winner by less than that.  Both moves then lower the
                                    loss, by amounts that agree to about 1e-5 of a grid step's worth. */
-    int32_t  reserved;
+    int32_t  teams_per_cu;      /* 0 = choose; 1 = one column per compute unit at a time with its state in registers;
+                                   2 = two, with the Hessian diagonal in LDS and 64 registers per lane, so that one
+                                   column is scored while the other waits for its row of H.  2 exists for 16 wavefronts
+                                   x 16 coordinates per lane (8192 < d_in <= 16384, 16-byte chunks) only, CDQ_EINVAL
+                                   elsewhere; chosen there when the layer has more columns than the chip has compute
+                                   units.  Same moves either way. */
     int32_t *trace;             /* NULL, or [d_out][trace_cap]: move m of column j is stored as
                                    i* * 64 + (u* + 32), u* = r* - q_i* the signed level change */
     int64_t  trace_cap;
@@ -275,13 +280,14 @@ int cdq_greedy_cd_ex(const float *H, const float *Wt, const float *scale, const 
 
 /*
  * The launch shape cdq_greedy_cd takes for a layer when nothing is forced: wavefronts cooperating on
- * a column and coordinates held per lane (64 * waves * elems >= d_in).  Host-only, no GPU access.
+ * a column, coordinates held per lane (64 * waves * elems >= d_in) and, if teams_per_cu is not NULL,
+ * columns resident per compute unit (cdq_cd_options.teams_per_cu).  Host-only, no GPU access.
  * `aligned16` tells whether H rows and Q rows are 16- and 4-byte aligned (they are when the base
  * pointers are and d_in % 4 == 0); without it the kernels fall back to scalar loads.
  * Returns CDQ_EUNSUPPORTED where cdq_greedy_cd would.
  */
 int cdq_greedy_cd_shape(int64_t d_out, int64_t d_in, int64_t group, int aligned16,
-                        int32_t *waves_per_column, int32_t *elems_per_lane);
+                        int32_t *waves_per_column, int32_t *elems_per_lane, int32_t *teams_per_cu);
 
 /*
  * One iteration of Algorithm 1 as separate steps, on a gradient G = E H kept in global memory

@@ -32,7 +32,7 @@ class ColStats(ctypes.Structure):
 
 class CdOptions(ctypes.Structure):
     _fields_ = [("waves_per_column", ctypes.c_int32), ("elems_per_lane", ctypes.c_int32),
-                ("exact_scorer_only", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("exact_scorer_only", ctypes.c_int32), ("teams_per_cu", ctypes.c_int32),
                 ("trace", ctypes.c_void_p), ("trace_cap", ctypes.c_int64), ("G_out", ctypes.c_void_p),
                 ("ev_loop_begin", ctypes.c_void_p), ("ev_loop_end", ctypes.c_void_p), ("G0", ctypes.c_void_p)]
 
@@ -71,7 +71,8 @@ def lib() -> ctypes.CDLL:
         L.cdq_cyclic_cd.restype = i32
         L.cdq_loss_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
         L.cdq_loss_static.restype = i32
-        L.cdq_greedy_cd_shape.argtypes = [i64, i64, i64, i32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+        L.cdq_greedy_cd_shape.argtypes = [i64, i64, i64, i32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
+                                          ctypes.POINTER(ctypes.c_int32)]
         L.cdq_greedy_cd_shape.restype = i32
         L.cdq_probe_mfma.argtypes = [i32, i64, i64, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.cdq_probe_mfma.restype = i32
@@ -255,7 +256,7 @@ def gradient(H, Wt, scale, zero, Q, group: int) -> torch.Tensor:
 def greedy_cd(H, Wt, scale, zero, Q, bits: int, group: int, T: int, stats: bool = True,
               workspace: torch.Tensor | None = None, waves_per_column: int = 0, elems_per_lane: int = 0,
               trace_cap: int = 0, want_G: bool = False, loop_events=None, exact_scorer_only: bool = False,
-              G0: torch.Tensor | None = None):
+              G0: torch.Tensor | None = None, teams_per_cu: int = 0):
     """Greedy coordinate descent in place on Q.  Returns a dict with 'stats' (int32 [d_out][4] view:
     moves, iters, converged, last_score bits), and optionally 'trace' and 'G'.  loop_events is an
     optional pair of raw hipEvent_t handles recorded around the iteration-loop kernel.  G0: the start gradient
@@ -270,7 +271,7 @@ def greedy_cd(H, Wt, scale, zero, Q, bits: int, group: int, T: int, stats: bool 
         ws = torch.empty((4 * d_in + 255) // 256 * 256, dtype=torch.uint8, device=Wt.device)
     st = torch.zeros((d_out, 4), dtype=torch.int32, device=Wt.device) if stats else None
     out = {}
-    opts = CdOptions(waves_per_column, elems_per_lane, int(exact_scorer_only), 0, None, 0, None, None, None, None)
+    opts = CdOptions(waves_per_column, elems_per_lane, int(exact_scorer_only), int(teams_per_cu), None, 0, None, None, None, None)
     if G0 is not None:
         opts.G0 = _out(G0, torch.float32, (d_out, d_in), "G0")
     if loop_events is not None:            # (begin, end) raw hipEvent_t handles
@@ -293,9 +294,15 @@ def greedy_cd(H, Wt, scale, zero, Q, bits: int, group: int, T: int, stats: bool 
 
 def greedy_cd_shape(d_out: int, d_in: int, group: int, aligned16: bool = True):
     """(wavefronts per column, coordinates per lane) that greedy_cd takes for a layer by default."""
-    w, e = ctypes.c_int32(0), ctypes.c_int32(0)
-    _check(lib().cdq_greedy_cd_shape(d_out, d_in, group, int(aligned16), ctypes.byref(w), ctypes.byref(e)), "cdq_greedy_cd_shape")
-    return int(w.value), int(e.value)
+    return greedy_cd_launch(d_out, d_in, group, aligned16)[:2]
+
+
+def greedy_cd_launch(d_out: int, d_in: int, group: int, aligned16: bool = True):
+    """(wavefronts per column, coordinates per lane, columns resident per compute unit) of greedy_cd's default launch."""
+    w, e, t = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().cdq_greedy_cd_shape(d_out, d_in, group, int(aligned16), ctypes.byref(w), ctypes.byref(e), ctypes.byref(t)),
+           "cdq_greedy_cd_shape")
+    return int(w.value), int(e.value), int(t.value)
 
 
 def score_argmin(Hdiag, scale, Q, G, bits: int, group: int):

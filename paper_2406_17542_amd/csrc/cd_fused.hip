@@ -54,7 +54,7 @@ __device__ __forceinline__ float curvature_inv(float h, float a) {
 // longer column would not fit the 160 KiB of LDS).
 // FF: recognise a column that moves one coordinate up and down for the rest of its budget and jump to the end (see the loop).
 template <int W, int E, int VEC, bool LDSH, bool FF>
-__global__ __launch_bounds__(64 * W) void cd_fused_kernel(
+__device__ __forceinline__ void cd_fused_body(
     const float* __restrict__ H, const float* __restrict__ hdiag, float* G0,
     const float* __restrict__ scale, uint8_t* __restrict__ Q, int d_in, int bits, int group, int group_shift,
     int n_grp, int T, int exact_only, cdq_col_stats* __restrict__ stats, int32_t* __restrict__ trace,
@@ -357,6 +357,28 @@ __global__ __launch_bounds__(64 * W) void cd_fused_kernel(
     }
 }
 
+template <int W, int E, int VEC, bool LDSH, bool FF>
+__global__ __launch_bounds__(64 * W) void cd_fused_kernel(
+    const float* __restrict__ H, const float* __restrict__ hdiag, float* G0,
+    const float* __restrict__ scale, uint8_t* __restrict__ Q, int d_in, int bits, int group, int group_shift,
+    int n_grp, int T, int exact_only, cdq_col_stats* __restrict__ stats, int32_t* __restrict__ trace,
+    int64_t trace_cap, float* __restrict__ G_out) {
+    cd_fused_body<W, E, VEC, LDSH, FF>(H, hdiag, G0, scale, Q, d_in, bits, group, group_shift, n_grp, T, exact_only, stats, trace,
+                                       trace_cap, G_out);
+}
+
+// Two columns per CU for d_in up to 16384: the diagonal in LDS (64 KiB per column) and the kernel held to 64 registers, so
+// that two teams of 16 wavefronts are resident and one column's scoring runs while the other waits for its row of H.
+template <int E, bool FF>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void cd_fused_pair_kernel(
+    const float* __restrict__ H, const float* __restrict__ hdiag, float* G0,
+    const float* __restrict__ scale, uint8_t* __restrict__ Q, int d_in, int bits, int group, int group_shift,
+    int n_grp, int T, int exact_only, cdq_col_stats* __restrict__ stats, int32_t* __restrict__ trace,
+    int64_t trace_cap, float* __restrict__ G_out) {
+    cd_fused_body<16, E, 4, true, FF>(H, hdiag, G0, scale, Q, d_in, bits, group, group_shift, n_grp, T, exact_only, stats, trace,
+                                      trace_cap, G_out);
+}
+
 __global__ __launch_bounds__(256) void extract_diag_kernel(const float* __restrict__ H, int64_t d_in, float* __restrict__ hdiag) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < d_in) hdiag[i] = H[i * d_in + i];
@@ -422,6 +444,12 @@ int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, bool aligned16, 
     return CDQ_OK;
 }
 
+// Columns resident per compute unit: two for the 16 x 16 shape once the layer has more columns than the chip has compute
+// units (measured on 2048 x 16384: loop 184 -> 165 ms), one otherwise.
+int cd_choose_teams(int64_t d_out, int waves, int elems, int vec) {
+    return (waves == 16 && elems == 16 && vec == 4 && d_out > 256) ? 2 : 1;
+}
+
 #define CDQ_CD_CASE(Wv, Ev)                                                                                        \
     if (waves == Wv && elems == Ev) {                                                                              \
         return vec == 4 ? launch_one<Wv, Ev, 4>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, exact_only, \
@@ -432,8 +460,11 @@ int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, bool aligned16, 
 
 int cd_launch(const float* H, const float* hdiag, float* G0, const float* scale, uint8_t* Q, int64_t d_out,
               int64_t d_in, int bits, int64_t group, int64_t T, cdq_col_stats* stats, int waves, int elems, int vec,
-              int exact_only, int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
+              int exact_only, int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st, int teams_per_cu) {
     if (d_out == 0) return CDQ_OK;
+    const bool pair_shape = waves == 16 && elems == 16 && vec == 4;
+    if (teams_per_cu < 0 || teams_per_cu > 2 || (teams_per_cu == 2 && !pair_shape)) return CDQ_EINVAL;
+    if (teams_per_cu == 0) teams_per_cu = cd_choose_teams(d_out, waves, elems, vec);
     if ((int64_t)64 * waves * elems < d_in) return CDQ_EINVAL;
     if (d_out > 0x7fffffffLL || d_in > CDQ_MAX_D_IN) return CDQ_EUNSUPPORTED;
     const int di = (int)d_in, gr = (int)group, ng = (int)(d_in / group);
@@ -445,6 +476,16 @@ int cd_launch(const float* H, const float* hdiag, float* G0, const float* scale,
     }
     // 16 wavefronts with more than 16 coordinates per lane do not fit the 128 registers a lane has there without spilling
     // in the loop (measured at d_in = 24576: 19 us per update); the variant with the Hessian diagonal in LDS does, or nearly
+    if (pair_shape && teams_per_cu == 2) {
+        const size_t lds = sizeof(float) * 64 * 16 * 16;
+        static const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(cd_fused_pair_kernel<16, true>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (rc != hipSuccess) return CDQ_EHIP;
+        hipLaunchKernelGGL((cd_fused_pair_kernel<16, true>), dim3((unsigned)d_out), dim3(1024), lds, st, H, hdiag, G0, scale, Q, di, bits, gr,
+                           gshift, ng, Ti, exact_only, stats, trace, trace_cap, G_out);
+        CDQ_LAUNCH_CHECK();
+        return CDQ_OK;
+    }
     if (waves == 16 && elems == 24 && vec == 4)
         return launch_one<16, 24, 4, true>(H, hdiag, G0, scale, Q, d_out, di, bits, gr, gshift, ng, Ti, exact_only, stats, trace,
                                            trace_cap, G_out, st);

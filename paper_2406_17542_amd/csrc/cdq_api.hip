@@ -160,14 +160,15 @@ int cdq_greedy_cd_ex(const float* H, const float* Wt, const float* scale, const 
     if (rc != CDQ_OK) return rc;
     if (opts != nullptr && opts->ev_loop_begin != nullptr) CDQ_HIP_CHECK(hipEventRecord((hipEvent_t)opts->ev_loop_begin, st));
     rc = cdq::cd_launch(H, hdiag, G0, scale, Q, d_out, d_in, bits, group, T, stats, waves, elems, vec,
-                        (opts != nullptr && opts->exact_scorer_only) ? 1 : 0, opts ? opts->trace : nullptr, opts ? opts->trace_cap : 0, opts ? opts->G_out : nullptr, st);
+                        (opts != nullptr && opts->exact_scorer_only) ? 1 : 0, opts ? opts->trace : nullptr, opts ? opts->trace_cap : 0, opts ? opts->G_out : nullptr, st,
+                        opts ? opts->teams_per_cu : 0);
     if (rc != CDQ_OK) return rc;
     if (opts != nullptr && opts->ev_loop_end != nullptr) CDQ_HIP_CHECK(hipEventRecord((hipEvent_t)opts->ev_loop_end, st));
     return CDQ_OK;
 }
 
 int cdq_greedy_cd_shape(int64_t d_out, int64_t d_in, int64_t group, int aligned16, int32_t* waves_per_column,
-                        int32_t* elems_per_lane) {
+                        int32_t* elems_per_lane, int32_t* teams_per_cu) {
     if (bad_layer(d_out, d_in, group) || waves_per_column == nullptr || elems_per_lane == nullptr) return CDQ_EINVAL;
     if (d_in > CDQ_MAX_D_IN) return CDQ_EUNSUPPORTED;
     int waves = 0, elems = 0, vec = 0;
@@ -175,6 +176,7 @@ int cdq_greedy_cd_shape(int64_t d_out, int64_t d_in, int64_t group, int aligned1
     if (rc != CDQ_OK) return rc;
     *waves_per_column = waves;
     *elems_per_lane = elems;
+    if (teams_per_cu != nullptr) *teams_per_cu = cdq::cd_choose_teams(d_out, waves, elems, vec);
     return CDQ_OK;
 }
 

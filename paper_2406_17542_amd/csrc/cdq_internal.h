@@ -86,10 +86,11 @@ int gather_update_launch(const float* H, const float* scale, uint8_t* Q, float* 
 
 // ---- cd_fused.hip
 int cd_choose_shape(int64_t d_out, int64_t d_in, int64_t group, bool aligned16, int* waves, int* elems, int* vec);
+int cd_choose_teams(int64_t d_out, int waves, int elems, int vec);       // columns resident per compute unit: 1 or 2
 int cd_launch(const float* H, const float* hdiag, float* G0, const float* scale, uint8_t* Q,          // G0 is overwritten
               int64_t d_out, int64_t d_in, int bits, int64_t group, int64_t T, cdq_col_stats* stats,
               int waves, int elems, int vec, int exact_only, int32_t* trace, int64_t trace_cap, float* G_out,
-              hipStream_t st);
+              hipStream_t st, int teams_per_cu = 0);      // 0: choose; 2 only for 16 wavefronts x 16 per lane, 16-byte chunks
 int extract_diag_launch(const float* H, int64_t d_in, float* hdiag, hipStream_t st);
 
 }  // namespace cdq

@@ -113,6 +113,9 @@ def test_launch_shape_query(L):
     assert cdq.greedy_cd_shape(2048, 2048, 2048) == (2, 16)
     assert cdq.greedy_cd_shape(32768, 8192, 8192) == (8, 16)
     assert cdq.greedy_cd_shape(2048, 16384, 16384) == (16, 16)
+    assert cdq.greedy_cd_launch(2048, 16384, 16384) == (16, 16, 2)      # more columns than compute units: two resident per unit
+    assert cdq.greedy_cd_launch(256, 16384, 16384) == (16, 16, 1)
+    assert cdq.greedy_cd_launch(32768, 8192, 8192) == (8, 16, 1)
     assert cdq.greedy_cd_shape(3072, 24576, 24576) == (16, 24)
     assert cdq.greedy_cd_shape(3072, 24576, 24576, aligned16=False) == (16, 32)      # 24 per lane needs 16-byte chunks
     assert cdq.greedy_cd_shape(4608, 36864, 36864) == (16, 36)

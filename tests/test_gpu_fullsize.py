@@ -146,11 +146,12 @@ def test_mlp_up_column_subset(cdq, oracle):
 
 
 def test_mlp_down_column_subset(cdq, oracle):
-    """d_in = 16384 (H is 1 GiB): 256 columns in the full layer's launch shape for the configured T = 16384; the
-    oracle reruns 10 random columns and the 4 with the most moves (several thousand each) for that full budget."""
+    """d_in = 16384 (H is 1 GiB): 512 columns -- more than there are compute units, so the kernel is the one the full layer
+    takes, two columns per compute unit -- for the configured T = 16384; the oracle reruns 10 random columns and the 4 with
+    the most moves (several thousand each) for that full budget."""
     cfg = inputs.CONFIGS["mlp_down"]
-    assert cdq.greedy_cd_shape(256, cfg.d_in, cfg.group) == cdq.greedy_cd_shape(cfg.d_out, cfg.d_in, cfg.group)
-    stats = run_layer(cdq, oracle, cfg, 256, cfg.T, sample_cols=10, include_busiest=4)
+    assert cdq.greedy_cd_shape(512, cfg.d_in, cfg.group) == cdq.greedy_cd_shape(cfg.d_out, cfg.d_in, cfg.group)
+    stats = run_layer(cdq, oracle, cfg, 512, cfg.T, sample_cols=10, include_busiest=4)
     assert stats[:, 0].max() > 2000, "the sample should contain long trajectories"
 
 
@@ -173,15 +174,19 @@ def test_large_owc_init_column_subset(cdq, oracle):
     say("OWC grid search on the GPU")
     scale, zero, Q, gamma, per = cdq.init_owc(Hd, Wd, cfg.bits, cfg.group, 50)
     # bench.py does not ask for the per-column losses, which takes another path through the search: same choice
-    s_b, z_b, Q_b, gamma_b, _ = cdq.init_owc(Hd, Wd, cfg.bits, cfg.group, 50, want_loss=False)
+    # ... and has the search hand over the start gradient of Algorithm 1, which the run below then starts from
+    G0 = torch.empty((d_out, cfg.d_in), dtype=torch.float32, device="cuda")
+    s_b, z_b, Q_b, gamma_b, _ = cdq.init_owc(Hd, Wd, cfg.bits, cfg.group, 50, want_loss=False, G_out=G0)
     assert torch.equal(gamma_b, gamma) and torch.equal(s_b, scale) and torch.equal(Q_b, Q)
+    assert torch.equal(G0, cdq.gradient(Hd, Wd, scale, zero, Q, cfg.group))
     del s_b, z_b, Q_b, gamma_b
     s_rtn, z_rtn, Q_rtn = cdq.init_rtn(Wd, cfg.bits, cfg.group)
     l_rtn = cdq.loss(Hd, Wd, s_rtn, z_rtn, Q_rtn, cfg.group)[0]
     assert torch.all(per <= l_rtn * (1 + 1e-9)), "gamma = 1 is on the grid, so OWC can not be worse than MinMax"
     q0 = Q.cpu().numpy().copy()
     say(f"greedy CD on the GPU, T={T}")
-    out = cdq.greedy_cd(Hd, Wd, scale, zero, Q, cfg.bits, cfg.group, T)
+    out = cdq.greedy_cd(Hd, Wd, scale, zero, Q, cfg.bits, cfg.group, T, G0=G0)
+    del G0
     l1 = cdq.loss(Hd, Wd, scale, zero, Q, cfg.group)[0].cpu().numpy()
     assert np.all(l1 <= per.cpu().numpy() * (1 + 1e-9))
     stats = out["stats"].cpu().numpy()

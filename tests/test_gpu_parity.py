@@ -174,8 +174,9 @@ def layer_with_exact_ties(seed=0, d_in=256, d_out=4, n=2000):
     return H32, Wt, good[:d_out]
 
 
-@pytest.mark.parametrize("waves,elems", [(0, 0), (1, 8), (1, 16), (2, 16), (4, 8), (16, 4), (16, 16), (16, 24), (16, 32), (16, 36)])
-def test_greedy_cd_alternating_between_two_levels_of_equal_loss(cdq, oracle, waves, elems):
+@pytest.mark.parametrize("waves,elems,teams", [(0, 0, 0), (1, 8, 0), (1, 16, 0), (2, 16, 0), (4, 8, 0), (16, 4, 0), (16, 16, 1), (16, 16, 2),
+                                               (16, 24, 0), (16, 32, 0), (16, 36, 0)])
+def test_greedy_cd_alternating_between_two_levels_of_equal_loss(cdq, oracle, waves, elems, teams):
     """Every kernel for 16-byte chunks except the one with 36 coordinates per lane jumps over the rest of the budget once
     the state repeats; that one takes every step; the oracle takes every step.  Same moves, same codes, for even and odd
     budgets, and the same trajectory when it is traced (tracing switches the jump off)."""
@@ -187,7 +188,8 @@ def test_greedy_cd_alternating_between_two_levels_of_equal_loss(cdq, oracle, wav
         ref = oracle.greedy_cd(H32, Wt, a, b, q0, 3, d_in, T)
         assert np.all(ref["moves"] == T), "the case should alternate to the end of every budget"
         Q = dev(q0.copy())
-        out = cdq.greedy_cd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, d_in, T, waves_per_column=waves, elems_per_lane=elems, want_G=True)
+        out = cdq.greedy_cd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, d_in, T, waves_per_column=waves, elems_per_lane=elems, want_G=True,
+                            teams_per_cu=teams)
         st = out["stats"].cpu().numpy()
         assert np.array_equal(st[:, 0], ref["moves"]) and np.all(st[:, 2] == 0), (T, st)
         assert np.array_equal(Q.cpu().numpy(), ref["Q"]), T
@@ -195,10 +197,35 @@ def test_greedy_cd_alternating_between_two_levels_of_equal_loss(cdq, oracle, wav
         assert [int(Q.cpu().numpy()[j, i]) for j, i in enumerate(ties)] == [2 + T % 2] * d_out
     ref = oracle.greedy_cd(H32, Wt, a, b, q0, 3, d_in, 60, trace_cap=60)
     Q = dev(q0.copy())
-    out = cdq.greedy_cd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, d_in, 60, waves_per_column=waves, elems_per_lane=elems, trace_cap=60)
+    out = cdq.greedy_cd(dev(H32), dev(Wt), dev(a), dev(b), Q, 3, d_in, 60, waves_per_column=waves, elems_per_lane=elems, trace_cap=60,
+                        teams_per_cu=teams)
     ti, tu = out["trace"].cpu().numpy().astype(np.int64) >> 6, (out["trace"].cpu().numpy().astype(np.int64) & 63) - 32
     assert np.array_equal(ti, ref["trace_i"]) and np.all(np.abs(tu) == 1) and np.all(tu[:, 1:] == -tu[:, :-1])
     assert np.array_equal(Q.cpu().numpy(), ref["Q"])
+
+
+@pytest.mark.parametrize("d_out,d_in,n,bits,group,T,rq", [(24, 8200, 9000, 3, 8200, 200, False), (9, 8704, 9000, 4, 128, 300, True),
+                                                          (300, 1024, 1500, 2, 1024, 150, True), (5, 64, 256, 3, 64, 40, True)])
+def test_greedy_cd_two_columns_per_compute_unit(cdq, oracle, d_out, d_in, n, bits, group, T, rq):
+    """Algorithm 1 with two columns resident per compute unit (Hessian diagonal in LDS, 64 registers): the oracle's moves,
+    in its order, and its maintained gradient -- for the widths that take this kernel by themselves and, forced, for small ones."""
+    X, Wt = rand_layer(2000 + d_in + bits, d_in, d_out, n, corr=1.0)
+    H32 = oracle.hessian(X).astype(np.float32)
+    a, b, q0 = oracle.init_grid(Wt, bits, group)
+    if rq:
+        q0 = inputs.make_random_codes(d_out, d_in, bits, seed=d_in)
+    ref, Q, stats, trace, G = run_cd_both(cdq, oracle, H32, Wt, a, b, q0, bits, group, T,
+                                          waves_per_column=16, elems_per_lane=16, teams_per_cu=2)
+    nbad = check_cd(oracle, ref, Q, stats, trace, H32, Wt, a, b, q0, bits, group)
+    if nbad == 0:
+        ti, tu = decode_trace(trace)
+        for j in range(d_out):
+            m = ref["moves"][j]
+            assert np.array_equal(ti[j, :m], ref["trace_i"][j, :m])
+        assert np.array_equal(G, ref["G"])
+    with pytest.raises(RuntimeError):                # the option exists for one launch shape only
+        cdq.greedy_cd(dev(H32), dev(Wt), dev(a), dev(b), dev(q0.copy()), bits, group, 1, waves_per_column=8, elems_per_lane=32,
+                      teams_per_cu=2)
 
 
 def test_greedy_cd_alternating_for_a_long_budget(cdq, oracle):
