@@ -223,7 +223,7 @@ __device__ __forceinline__ void cd_fused_body(
         }
         return v != 0;
     };
-    uint32_t prev_move = 0xffffffffu;         // coordinate << 6 | (level change + 32) of the previous move
+    uint32_t undo_move = 0xffffffffu;         // coordinate << 6 | (32 - level change) of the previous move: the move that would undo it
     int snap_t = -1;                          // iteration whose 2g the snapshot holds
 
     for (int t = 0; t < T; ++t) {
@@ -298,7 +298,7 @@ __device__ __forceinline__ void cd_fused_body(
         // ---- the same coordinate moved back: snapshot, or compare with the snapshot of two iterations ago (uniform branches).
         // Two moves that undo each other restore the codes whatever came before, so the comparison of 2g is the whole test.
         const uint32_t this_move = FF ? (klo >> 1) : 0u;
-        if (FF && trace == nullptr && (this_move >> 6) == (prev_move >> 6) && (this_move & 63u) + (prev_move & 63u) == 64u) {
+        if (FF && __builtin_expect(this_move == undo_move, 0) && trace == nullptr) {      // rare: kept out of the straight path
             float* snap = G0 + j * (int64_t)d_in;                        // the start gradient is not needed any more
             bool take = !(snap_t >= 0 && t == snap_t + 1);               // keep the snapshot for the comparison one move on
             if (snap_t >= 0 && t == snap_t + 2) {
@@ -331,7 +331,7 @@ __device__ __forceinline__ void cd_fused_body(
                 snap_t = t;
             }
         }
-        if (FF) prev_move = this_move;
+        if (FF) undo_move = (this_move & ~63u) | (64u - (this_move & 63u));
     }
 
     // ---- write back
