@@ -70,7 +70,7 @@ typedef struct {
                                    Hessian diagonal in LDS, the one chosen for d_in above 16384 */
     int32_t  exact_scorer_only; /* 1 = two-level scorer on every iteration: per coordinate the two levels next to the
                                    parabola's minimiser, both by the formula below -- the arg-min of Algorithm 1 over
-                                   all levels, unconditionally (about 1.3 times the loop time).
+                                   all levels, unconditionally (1.15 to 1.3 times the loop time).
                                    0 (default) = nearest-level scorer: one level per coordinate; the iteration is
                                    redone with the two-level scorer when the winner's minimiser lies within 2^-9 of a
                                    half-integer or no move was found.  A coordinate whose minimiser is farther than
