@@ -230,7 +230,7 @@ class Layer:
         rec(2)
         out = cdq.greedy_cd(self.H, self.Wd, scale, zero, Q, cfg.bits, cfg.group, cfg.T, workspace=self.ws_cd,
                             waves_per_column=self.args.waves, elems_per_lane=self.args.elems,
-                            loop_events=(evs[3], evs[4]) if evs is not None else None, G0=self.G0)
+                            loop_events=(evs[3], evs[4]) if evs is not None else None, G0=self.G0, teams_per_cu=self.args.teams)
         rec(5)
         per, tot = cdq.loss(self.H, self.Wd, scale, zero, Q, cfg.group, workspace=self.ws_l)
         rec(6)
@@ -411,6 +411,7 @@ def main():
                     help="initial grid: the configuration's own, MinMax/RTN, OWC (Eq. 2 grid search) or OWC-CD (Algorithm 3)")
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--elems", type=int, default=0)
+    ap.add_argument("--teams", type=int, default=0, help="columns resident per compute unit for the 16 x 16 launch shape: 0 = library default, 1 or 2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the achievable-bandwidth probes")
     ap.add_argument("--no-parity", action="store_true", help="skip the oracle check of sampled columns")
@@ -450,6 +451,8 @@ def main():
     converged = int(state["stats"][:, 2].sum().item())
     loss_final = float(state["loss"].item())
     shape = (args.waves, args.elems, 1) if args.waves and args.elems else cdq.greedy_cd_launch(cfg.d_out, cfg.d_in, cfg.group)
+    if args.teams:
+        shape = (shape[0], shape[1], args.teams)
 
     achievable = {} if args.no_probes else probes(cfg, layer.H, shape, ev, stream, cdq)
     flop_exec, h_tflops_exec, h_tflops_eff = layer.hessian_rates(stages)

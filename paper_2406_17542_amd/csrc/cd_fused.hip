@@ -168,7 +168,18 @@ __device__ __forceinline__ void cd_fused_body(
                 const float u = rn - qf;
                 const float d = a * u;
                 const float s = d * fmaf(d, hc[v], g2[e]);
-                if (s < bs) { bs = s; bu = u; brf = rf; be = e; }
+                if constexpr (LDSH && (E > 32 || E == 16)) {
+                    // the compare and its four selects as one block: scheduled apart, the compiler keeps every coordinate's
+                    // level change, minimiser and compare mask alive until the end of the chunk, and runs out of registers at 36
+                    // per lane (30 spilled; none this way) and in the 64-register kernel for two columns per compute unit (19
+                    // spilled, 9 this way; loop on 2048 x 16384 176 -> 167 ms).  The kernels in between fit as they are and lose 1 to
+                    // 8 % to the wait state between the compare and the first select, so they keep the plain form.
+                    asm volatile("v_cmp_nlt_f32 vcc, %4, %0\n\ts_nop 1\n\tv_cndmask_b32 %0, %4, %0, vcc\n\tv_cndmask_b32 %1, %5, %1, vcc\n\t"
+                                 "v_cndmask_b32 %2, %6, %2, vcc\n\tv_cndmask_b32 %3, %7, %3, vcc"
+                                 : "+v"(bs), "+v"(bu), "+v"(brf), "+v"(be) : "v"(s), "v"(u), "v"(rf), "n"(e) : "vcc");
+                } else {
+                    if (s < bs) { bs = s; bu = u; brf = rf; be = e; }
+                }
             }
         }
         const float frac = brf - floorf(brf);
@@ -195,8 +206,16 @@ __device__ __forceinline__ void cd_fused_body(
                 const float d0 = a * u0, d1 = a * u1;
                 float s0 = d0 * fmaf(d0, hc[v], g2[e]);
                 const float s1 = d1 * fmaf(d1, hc[v], g2[e]);
-                if (s1 < s0) { s0 = s1; u0 = u1; }      // equal scores keep the lower level
-                if (s0 < bs) { bs = s0; bu = u0; be = e; }
+                if constexpr (LDSH && (E > 32 || E == 16)) {
+                    asm volatile("v_cmp_nlt_f32 vcc, %2, %0\n\ts_nop 1\n\tv_cndmask_b32 %0, %2, %0, vcc\n\tv_cndmask_b32 %1, %3, %1, vcc"
+                                 : "+v"(s0), "+v"(u0) : "v"(s1), "v"(u1) : "vcc");      // equal scores keep the lower level
+                    asm volatile("v_cmp_nlt_f32 vcc, %3, %0\n\ts_nop 1\n\tv_cndmask_b32 %0, %3, %0, vcc\n\tv_cndmask_b32 %1, %4, %1, vcc\n\t"
+                                 "v_cndmask_b32 %2, %5, %2, vcc"
+                                 : "+v"(bs), "+v"(bu), "+v"(be) : "v"(s0), "v"(u0), "n"(e) : "vcc");
+                } else {
+                    if (s1 < s0) { s0 = s1; u0 = u1; }      // equal scores keep the lower level
+                    if (s0 < bs) { bs = s0; bu = u0; be = e; }
+                }
             }
         }
         return team_min(bs, bu, be, 0u);
@@ -208,9 +227,8 @@ __device__ __forceinline__ void cd_fused_body(
     // row of the start gradient; if two moves later the codes are back (the two moves again undid each other) and 2g has
     // exactly the same bits, the state is that of two iterations ago, the loop is periodic from here on, and only the
     // parity of what is left of the budget matters.  Not done when the moves are traced.  Built into every kernel for 16-byte
-    // chunks with up to 24 coordinates per lane and into the 32-per-lane kernel with the diagonal in LDS (FF); the test reads
-    // the snapshot one chunk at a time, so it costs no registers in the loop.  The 36-per-lane kernel is built without: it
-    // spills as it is, and the extra code made it 30 % slower.
+    // chunks except the register kernels with 32 coordinates per lane (FF); the test reads the snapshot one chunk at a time, so
+    // it costs no registers in the loop.
     auto team_all = [&](bool ok) -> bool {
         uint64_t v = (__ballot(ok) == ~0ull) ? 1u : 0u;
         if (W > 1) {
@@ -388,7 +406,7 @@ template <int W, int E, int VEC, bool LDSH = false>
 int launch_one(const float* H, const float* hdiag, float* G0, const float* scale, uint8_t* Q, int64_t d_out,
                int d_in, int bits, int group, int group_shift, int n_grp, int T, int exact_only, cdq_col_stats* stats,
                int32_t* trace, int64_t trace_cap, float* G_out, hipStream_t st) {
-    constexpr bool FF = (VEC == 4 && (E <= 24 || (LDSH && E == 32)));
+    constexpr bool FF = (VEC == 4 && (E <= 24 || LDSH));
     const size_t lds = LDSH ? sizeof(float) * 64 * W * E : 0;
     if (LDSH) {
         static const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(cd_fused_kernel<W, E, VEC, LDSH, FF>),

@@ -177,9 +177,9 @@ def layer_with_exact_ties(seed=0, d_in=256, d_out=4, n=2000):
 @pytest.mark.parametrize("waves,elems,teams", [(0, 0, 0), (1, 8, 0), (1, 16, 0), (2, 16, 0), (4, 8, 0), (16, 4, 0), (16, 16, 1), (16, 16, 2),
                                                (16, 24, 0), (16, 32, 0), (16, 36, 0)])
 def test_greedy_cd_alternating_between_two_levels_of_equal_loss(cdq, oracle, waves, elems, teams):
-    """Every kernel for 16-byte chunks except the one with 36 coordinates per lane jumps over the rest of the budget once
-    the state repeats; that one takes every step; the oracle takes every step.  Same moves, same codes, for even and odd
-    budgets, and the same trajectory when it is traced (tracing switches the jump off)."""
+    """The kernels for 16-byte chunks jump over the rest of the budget once the state repeats; the oracle takes every step.
+    Same moves, same codes, for even and odd budgets, and the same trajectory when it is traced (tracing switches the jump
+    off)."""
     H32, Wt, ties = layer_with_exact_ties()
     d_out, d_in = Wt.shape
     a, b, q0 = oracle.init_grid(Wt, 3, d_in)
