@@ -106,6 +106,34 @@ def test_argument_checks_of_the_wider_entry_points(L):
     assert L.cdq_cyclic_cd(p, p, p, p, p, 0, 256, 3, 256, i64(8), n, n, n, 0, n, 0, n) == 0             # empty layer
 
 
+def test_argument_checks_of_the_new_options(L):
+    """Start gradient handed over, columns per compute unit, the grid search's margin: rejected on the host where wrong."""
+    from paper_2406_17542_amd import cdq
+    p = ctypes.c_void_p(0x1000)
+    n = ctypes.c_void_p(0)
+    EINVAL, EWS, EUNSUP = -1, -2, -4
+    def opts(**kw):
+        o = cdq.CdOptions()
+        for k, v in kw.items():
+            setattr(o, k, v)
+        return ctypes.byref(o)
+    # cdq_greedy_cd_ex(H, Wt, scale, zero, Q, d_out, d_in, bits, group, T, stats, opts, ws, ws_bytes, stream)
+    assert L.cdq_greedy_cd_ex(p, p, p, p, p, 4, 8, 3, 8, 4, n, opts(G0=0x1004), p, 1 << 20, n) == EINVAL        # start gradient not 16-byte aligned
+    assert L.cdq_greedy_cd_ex(p, p, p, p, p, 4, 8, 3, 8, 4, n, opts(G0=0x2000), n, 0, n) == EWS                 # the diagonal still needs room
+    assert L.cdq_greedy_cd_ex(p, p, p, p, p, 4, 8, 3, 8, 4, n, opts(G0=0x2000), p, 16, n) == EWS
+    assert L.cdq_greedy_cd_ex(p, p, p, p, p, 4, 8, 3, 8, 4, n, opts(waves_per_column=3, elems_per_lane=16), p, 1 << 20, n) == EINVAL
+    # cdq_init_owc(H, Wt, d_out, d_in, bits, group, n_gamma, margin, scale, zero, Q, gamma, loss, researched, G_out, ws, ws_bytes, stream)
+    f = ctypes.c_float
+    assert L.cdq_init_owc(p, p, 4, 256, 3, 256, 50, f(-1.0), p, p, p, n, n, n, n, p, 1 << 30, n) == EINVAL      # negative margin
+    assert L.cdq_init_owc(p, p, 4, 256, 3, 256, 50, f(2.0), p, p, p, n, n, n, n, p, 1 << 30, n) == EINVAL
+    assert L.cdq_init_owc(p, p, 4, 256, 3, 128, 50, f(0.0), p, p, p, n, n, n, n, p, 1 << 30, n) == EUNSUP       # one strength per column only
+    assert L.cdq_init_owc(p, p, 4, 256, 3, 256, 0, f(0.0), p, p, p, n, n, n, n, p, 1 << 30, n) == EINVAL        # empty grid
+    assert L.cdq_init_owc(p, p, 4, 256, 3, 256, 50, f(0.0), p, p, p, n, n, n, p, n, 0, n) == EWS                # no workspace
+    assert L.cdq_init_owc(p, p, 0, 256, 3, 256, 50, f(0.0), p, p, p, n, n, n, p, n, 0, n) == 0                  # empty layer
+    # more start-grid workspace than before for the same shape is not required when no gradient is asked for
+    assert cdq.workspace_bytes(cdq.OP_INIT_OWC, 0, 64, 256) >= 64 * 256 * 4
+
+
 def test_launch_shape_query(L):
     """The default launch shape is a host-side rule: 16 coordinates per lane up to d_in = 16384, the kernels with the
     Hessian diagonal in LDS above, and a scalar-load shape when the rows are not 16-byte aligned."""
