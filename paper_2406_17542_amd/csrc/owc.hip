@@ -3,8 +3,9 @@
 //   b = min w,  a(gamma) = gamma (max w - min w)/(2^c - 1),  q = clamp(round((w - b)/a), 0, 2^c - 1)
 // The grid is gamma_k = k/n_gamma, k = 1..n_gamma (gamma = 1 is MinMax; equal losses keep the
 // larger gamma).  A grid point costs one pass of the fp64 loss kernel over all columns; where the fp16 look at all grid
-// points applies (owc_screen.hip) only the few that can win are evaluated that way, a column's candidates one rank at a
-// time, and blocks of columns without a candidate of that rank are skipped.
+// points applies (owc_screen.hip) only the few that can win are evaluated that way: every column's best-screened point in
+// one pass over all columns, the check of the look against that value, the other candidates gathered into dense rows, and
+// what does not fit the rows one rank at a time, blocks of columns without a candidate of that rank skipped.
 #include "cdq_internal.h"
 
 namespace cdq {
@@ -256,14 +257,14 @@ __global__ __launch_bounds__(256) void owc_row_blocks_kernel(const int32_t* __re
 
 constexpr float kScreenMargin = 3e-3f;      // relative; the fp16 evaluation was off by 3e-4 at most on heavy-tailed test layers
 
-// The check that makes the two-stage search safe to use: every column's chosen grid point has been evaluated both ways, so
-// the error of the fp16 look on this column is known there.  Where it exceeds a third of the margin (or is not a number) the
-// look is not trusted for the column: all grid points become its candidates, to be evaluated in fp64 by the rank passes that
-// follow, and the column is counted.  Every other column's candidate list is cleared.
+// The check that makes the two-stage search safe to use: every column's best-screened grid point has been evaluated both
+// ways, so the error of the fp16 look on this column is known there.  Where it exceeds a third of the margin (or is not a
+// number) the look is not trusted for the column: every other grid point becomes a candidate behind the one already
+// evaluated (ranks 1 .. n_gamma - 1, ascending), to be evaluated in fp64 by the rows and rank passes that follow, and the
+// column is counted.
 __global__ __launch_bounds__(256) void owc_guard_kernel(const float* __restrict__ screened, const double* __restrict__ best_loss,
                                                         const float* __restrict__ best_gamma, int64_t d_out, int n_gamma, float margin,
-                                                        int block_rows, int64_t n_blocks, uint8_t* __restrict__ cand,
-                                                        uint8_t* __restrict__ active, int32_t* __restrict__ count) {
+                                                        uint8_t* __restrict__ cand, int32_t* __restrict__ count) {
     const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= d_out) return;
     const float g = best_gamma[j];
@@ -273,11 +274,12 @@ __global__ __launch_bounds__(256) void owc_guard_kernel(const float* __restrict_
     const double exact = best_loss[j], seen = (double)screened[(int64_t)(k - 1) * d_out + j];
     // a residual of zero (exact == 0: a constant column) is screened as zero too
     const bool trusted = (g > 0.0f) && (exact == seen || fabs(exact - seen) <= (double)(margin / 3.0f) * fabs(exact));
-    for (int r = 0; r < n_gamma; ++r) cand[(int64_t)r * d_out + j] = trusted ? (uint8_t)0 : (uint8_t)(r + 1);
-    if (!trusted) {
-        for (int r = 0; r < n_gamma; ++r) active[(int64_t)r * n_blocks + j / block_rows] = 1;
-        atomicAdd(count, 1);
-    }
+    if (trusted) return;
+    cand[j] = (uint8_t)k;                                      // rank 0 stays what was evaluated
+    int r = 1;
+    for (int kk = 1; kk <= n_gamma; ++kk)
+        if (kk != k) cand[(int64_t)(r++) * d_out + j] = (uint8_t)kk;
+    atomicAdd(count, 1);
 }
 
 }  // namespace
@@ -361,8 +363,43 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
         g_changed = extras; g_base = base; g_row_col = row_col; g_total = total; g_row_k = row_k; g_rows_active = rows_active;
         g_Wc = Wc; g_zeros = zeros;
         const int32_t cap = (int32_t)d_out;
+        int32_t* count = total + 1;         // columns that fail the check (the scan clears total only)
         hipLaunchKernelGGL(owc_fill_f32_kernel, col_blocks, t256, 0, st, zeros, d_out, 0.0f);
         CDQ_LAUNCH_CHECK();
+        hipLaunchKernelGGL(owc_fill_f32_kernel, dim3(1), t256, 0, st, (float*)count, (int64_t)1, 0.0f);                   // bits of +0.0f: integer 0
+        CDQ_LAUNCH_CHECK();
+        // rank passes: every column at its r-th candidate, blocks of columns without one skipped
+        auto rank_pass = [&](int r) -> int {
+            hipLaunchKernelGGL(owc_rank_gamma_kernel, col_blocks, t256, 0, st, cand + (int64_t)r * d_out, d_out, n_gamma, rank_gamma);
+            CDQ_LAUNCH_CHECK();
+            hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, 1.0f, (const float*)rank_gamma, trial_scale,
+                               (float*)nullptr, trial_q);
+            CDQ_LAUNCH_CHECK();
+            if (r == 0 && G_out != nullptr) {
+                // every column is in this pass: the whole product, which leaves H e in G_out, with the loss taken from the same sums
+                const int rc2 = gradient_loss_launch(H, Wt, trial_scale, lo, trial_q, d_out, d_in, d_in, G_out, trial_loss, loss_ws, loss_ws_bytes,
+                                                     st, nullptr, nullptr, nullptr);
+                if (rc2 != CDQ_OK) return rc2;
+                CDQ_HIP_CHECK(hipMemcpyAsync(first_gamma, rank_gamma, (size_t)d_out * sizeof(float), hipMemcpyDeviceToDevice, st));
+                g_from_first_pass = true;
+            } else {
+                const int rc2 = loss_launch(H, Wt, trial_scale, lo, trial_q, d_out, d_in, d_in, trial_loss, nullptr, loss_ws, loss_ws_bytes, st,
+                                            active + (int64_t)r * n_blocks);
+                if (rc2 != CDQ_OK) return rc2;
+            }
+            hipLaunchKernelGGL(owc_update_best_ranked_kernel, col_blocks, t256, 0, st, (const double*)trial_loss, (const float*)rank_gamma,
+                               d_out, best_loss, best_gamma);
+            CDQ_LAUNCH_CHECK();
+            return CDQ_OK;
+        };
+        // 1. every column's best-screened grid point, in fp64
+        rc = rank_pass(0);
+        if (rc != CDQ_OK) return rc;
+        // 2. the check of the fp16 look: a column that fails it gets every other grid point as a candidate
+        hipLaunchKernelGGL(owc_guard_kernel, col_blocks, t256, 0, st, screened, (const double*)best_loss, (const float*)best_gamma, d_out, n_gamma,
+                           margin, cand, count);
+        CDQ_LAUNCH_CHECK();
+        // 3. the candidates beyond the first, gathered into dense rows for one pass of the loss kernel ...
         hipLaunchKernelGGL(owc_count_extras_kernel, col_blocks, t256, 0, st, cand, d_out, n_gamma, first, extras);
         CDQ_LAUNCH_CHECK();
         hipLaunchKernelGGL(owc_scan_extras_kernel, dim3(1), dim3(1024), 0, st, (const int32_t*)extras, d_out, base, total);
@@ -382,62 +419,19 @@ int owc_launch(const float* H, const float* Wt, int64_t d_out, int64_t d_in, int
                                first, block_rows, n_blocks, (const int32_t*)total, active, rows_active);
             CDQ_LAUNCH_CHECK();
         }
-        for (int r = 0; r < n_gamma; ++r) {
-            if (r == 0) {                  // the gathered rows, one pass (the order of the passes does not matter to the result)
-                hipLaunchKernelGGL(owc_row_residual_kernel, cols, t256, 0, st, Wt, d_in, bits, (const float*)lo, (const float*)hi, n_gamma,
-                                   (const int32_t*)row_col, (const uint8_t*)row_k, (const int32_t*)total, Wc);
-                CDQ_LAUNCH_CHECK();
-                rc = loss_launch(H, Wc, zeros, zeros, trial_q, d_out, d_in, d_in, row_loss, nullptr, loss_ws, loss_ws_bytes, st, rows_active);
-                if (rc != CDQ_OK) return rc;
-                hipLaunchKernelGGL(owc_update_best_rows_kernel, col_blocks, t256, 0, st, (const double*)row_loss, (const uint8_t*)row_k,
-                                   (const int32_t*)extras, (const int32_t*)base, cap, n_gamma, d_out, best_loss, best_gamma);
-                CDQ_LAUNCH_CHECK();
-            }
-            hipLaunchKernelGGL(owc_rank_gamma_kernel, col_blocks, t256, 0, st, cand + (int64_t)r * d_out, d_out, n_gamma, rank_gamma);
-            CDQ_LAUNCH_CHECK();
-            hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, 1.0f, (const float*)rank_gamma, trial_scale,
-                               (float*)nullptr, trial_q);
-            CDQ_LAUNCH_CHECK();
-            if (r == 0 && G_out != nullptr) {
-                // every column is in this pass: the whole product, which leaves H e in G_out, with the loss taken from the same sums
-                rc = gradient_loss_launch(H, Wt, trial_scale, lo, trial_q, d_out, d_in, d_in, G_out, trial_loss, loss_ws, loss_ws_bytes, st,
-                                          nullptr, nullptr, nullptr);
-                if (rc != CDQ_OK) return rc;
-                CDQ_HIP_CHECK(hipMemcpyAsync(first_gamma, rank_gamma, (size_t)d_out * sizeof(float), hipMemcpyDeviceToDevice, st));
-                g_from_first_pass = true;
-            } else {
-                rc = loss_launch(H, Wt, trial_scale, lo, trial_q, d_out, d_in, d_in, trial_loss, nullptr, loss_ws, loss_ws_bytes, st,
-                                 active + (int64_t)r * n_blocks);
-                if (rc != CDQ_OK) return rc;
-            }
-            hipLaunchKernelGGL(owc_update_best_ranked_kernel, col_blocks, t256, 0, st, (const double*)trial_loss, (const float*)rank_gamma,
-                               d_out, best_loss, best_gamma);
-            CDQ_LAUNCH_CHECK();
-        }
-        // the check of the fp16 look, and the exhaustive search for the columns that fail it (idle launches otherwise)
-        int32_t* count = total;             // the rows are done with: reuse the counter
-        hipLaunchKernelGGL(owc_fill_f32_kernel, dim3(1), t256, 0, st, (float*)count, (int64_t)1, 0.0f);                   // bits of +0.0f: integer 0
+        hipLaunchKernelGGL(owc_row_residual_kernel, cols, t256, 0, st, Wt, d_in, bits, (const float*)lo, (const float*)hi, n_gamma,
+                           (const int32_t*)row_col, (const uint8_t*)row_k, (const int32_t*)total, Wc);
         CDQ_LAUNCH_CHECK();
-        {
-            const int64_t flags = (int64_t)n_gamma * n_blocks;
-            hipLaunchKernelGGL(owc_fill_u8_kernel, dim3((unsigned)((flags + 255) / 256)), t256, 0, st, active, flags, (uint8_t)0);
-            CDQ_LAUNCH_CHECK();
-        }
-        hipLaunchKernelGGL(owc_guard_kernel, col_blocks, t256, 0, st, screened, (const double*)best_loss, (const float*)best_gamma, d_out, n_gamma,
-                           margin, block_rows, n_blocks, cand, active, count);
+        rc = loss_launch(H, Wc, zeros, zeros, trial_q, d_out, d_in, d_in, row_loss, nullptr, loss_ws, loss_ws_bytes, st, rows_active);
+        if (rc != CDQ_OK) return rc;
+        hipLaunchKernelGGL(owc_update_best_rows_kernel, col_blocks, t256, 0, st, (const double*)row_loss, (const uint8_t*)row_k,
+                           (const int32_t*)extras, (const int32_t*)base, cap, n_gamma, d_out, best_loss, best_gamma);
         CDQ_LAUNCH_CHECK();
-        for (int r = 0; r < n_gamma; ++r) {
-            hipLaunchKernelGGL(owc_rank_gamma_kernel, col_blocks, t256, 0, st, cand + (int64_t)r * d_out, d_out, n_gamma, rank_gamma);
-            CDQ_LAUNCH_CHECK();
-            hipLaunchKernelGGL(owc_quantize_kernel, cols, t256, 0, st, Wt, d_in, bits, lo, hi, 1.0f, (const float*)rank_gamma, trial_scale,
-                               (float*)nullptr, trial_q);
-            CDQ_LAUNCH_CHECK();
-            rc = loss_launch(H, Wt, trial_scale, lo, trial_q, d_out, d_in, d_in, trial_loss, nullptr, loss_ws, loss_ws_bytes, st,
-                             active + (int64_t)r * n_blocks);
+        // 4. ... and what did not fit the rows (more candidates than columns: only when many columns fail the check), rank by
+        // rank; idle launches otherwise
+        for (int r = 1; r < n_gamma; ++r) {
+            rc = rank_pass(r);
             if (rc != CDQ_OK) return rc;
-            hipLaunchKernelGGL(owc_update_best_ranked_kernel, col_blocks, t256, 0, st, (const double*)trial_loss, (const float*)rank_gamma,
-                               d_out, best_loss, best_gamma);
-            CDQ_LAUNCH_CHECK();
         }
         if (researched != nullptr) CDQ_HIP_CHECK(hipMemcpyAsync(researched, count, sizeof(int32_t), hipMemcpyDeviceToDevice, st));
     } else {
