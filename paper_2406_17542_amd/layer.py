@@ -136,17 +136,19 @@ def main():
     ap.add_argument("--t-div", type=int, default=1, help="run CD for d_in / t_div iterations (appendix: d_in/8 suffices)")
     ap.add_argument("--bcd", action="store_true", help="also run BCD (k=2, d_in iterations) from CD's result where it is supported")
     ap.add_argument("--init", default="owc", choices=["rtn", "owc"], help="Section 4: per-channel CD starts from OWC")
-    ap.add_argument("--layers", default="ffn1,ffn2")
+    ap.add_argument("--layers", default="ffn1,ffn2", help="comma-separated: ffn1, ffn1_gate (same shape as ffn1, other weights), ffn2")
     args = ap.parse_args()
     d_model, d_ff = MODEL_SHAPES[args.model]
     rows = []
     for name in args.layers.split(","):
-        d_in, d_out = (d_model, d_ff) if name == "ffn1" else (d_ff, d_model)
+        if name not in ("ffn1", "ffn1_gate", "ffn2"):
+            raise SystemExit(f"unknown layer {name!r}: ffn1, ffn1_gate or ffn2")
+        d_in, d_out = (d_model, d_ff) if name in ("ffn1", "ffn1_gate") else (d_ff, d_model)
         if d_in > cdq.MAX_D_IN:
             rows.append({"layer": name, "d_in": d_in, "d_out": d_out, "skipped": f"d_in above the fused loop's limit of {cdq.MAX_D_IN}"})
             print(json.dumps(rows[-1]), flush=True)
             continue
-        Wt = torch.from_numpy(inputs.make_wt(d_out, d_in, seed=1)).cuda()
+        Wt = torch.from_numpy(inputs.make_wt(d_out, d_in, seed=7 if name == "ffn1_gate" else 1)).cuda()
         parts = None
         if args.bcd and d_in <= 65534:
             parts = torch.from_numpy(inputs.make_partitions(d_in, d_in, seed=2)).cuda()
