@@ -792,14 +792,21 @@ def test_greedy_cd_scorers_agree(cdq, oracle, bits, group, rq):
 
 
 def test_greedy_cd_dead_channel_and_diagonal(cdq, oracle):
-    # dead input channel: never selected, no NaN
+    # dead input channels (H_ii = 0, a zero row of H): never selected, no NaN -- in every kernel family, with both scorers
+    # (the kernels that keep the diagonal in LDS divide by the curvature without a guard and rely on the comparison with a
+    # score that is not a number being false)
     X, Wt = rand_layer(5, 64, 8, 300)
     X[:, 9] = 0
+    X[:, 40] = 0
     H32 = oracle.hessian(X).astype(np.float32)
     a, b, _ = oracle.init_grid(Wt, 3, 64)
     q0 = inputs.make_random_codes(8, 64, 3, seed=1)
-    ref, Q, stats, trace, G = run_cd_both(cdq, oracle, H32, Wt, a, b, q0, 3, 64, 200)
-    assert np.array_equal(Q, ref["Q"]) and np.array_equal(Q[:, 9], q0[:, 9]) and np.isfinite(G).all()
+    for waves, elems, teams in ((0, 0, 0), (1, 16, 0), (16, 16, 1), (16, 16, 2), (16, 24, 0), (16, 32, 0), (16, 36, 0)):
+        for exact in (False, True):
+            ref, Q, stats, trace, G = run_cd_both(cdq, oracle, H32, Wt, a, b, q0, 3, 64, 200, waves_per_column=waves, elems_per_lane=elems,
+                                                  teams_per_cu=teams, exact_scorer_only=exact)
+            assert np.array_equal(Q, ref["Q"]) and np.array_equal(Q[:, [9, 40]], q0[:, [9, 40]]) and np.isfinite(G).all(), (waves, elems, teams, exact)
+            assert np.array_equal(stats[:, 0], ref["moves"]) and np.array_equal(G, ref["G"])
     # diagonal H: CD from arbitrary codes lands exactly on round-to-nearest
     Hdiag = np.diag(np.random.default_rng(2).uniform(0.5, 4, 64)).astype(np.float32)
     a, b, q_rtn = oracle.init_grid(Wt, 4, 64)
