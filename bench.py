@@ -32,11 +32,14 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # wavefront instructions the chip can issue to its vector ALUs per second: 256 CUs x 4 SIMDs, one fp32 instruction
 # of a 64-wide wavefront every 4 cycles, 2.4 GHz
 VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4
-# vector-ALU instructions of the loop kernel per wavefront and iteration at 16 coordinates per lane (SQ_INSTS_VALU
-# over the iterations of attn_proj: 13 per coordinate for the score and the running arg-min, 1 per coordinate for the
-# update, the rest reduction and bookkeeping); scaled by coordinates per lane for other shapes.  A model, and a low one:
-# the same counter gives 321 on `large` and 343 on `mlp_down`, whose kernels carry the period-2 bookkeeping
-VALU_PER_WAVE_ITER_AT_16 = 290.0
+# vector-ALU issue slots of the loop kernels per wavefront and iteration at 16 coordinates per lane, from SQ_INSTS_VALU
+# (profiles/cd_loop_sq_counters.txt): 319 instructions in the register kernels (13 per coordinate for the score and the
+# running arg-min, 1 per coordinate for the update, the rest reduction and bookkeeping); 405 in the kernel for two columns
+# per compute unit, 16 of them v_rcp_f32, which takes four slots; 304 with one or two wavefronts per column (attn_proj).
+# Scaled by coordinates per lane for other shapes: a model (the 2-bit grouped layer needs fewer, so its figure reads high).
+VALU_PER_WAVE_ITER_AT_16 = 320.0
+VALU_PER_WAVE_ITER_NARROW = 304.0
+VALU_PER_WAVE_ITER_PAIR = 405.0 + 3.0 * 16.0
 
 
 class HipEvents:
@@ -279,7 +282,8 @@ def loop_roofline(cfg, mode, moves, loop_ms, shape, gather_gbs):
     gbs = cd_bytes / (loop_ms * 1e-3) * 1e-9
     waves, elems, teams_per_cu = shape
     kernel = "cd_fused_pair_kernel" if teams_per_cu == 2 else "cd_fused_kernel"
-    valu_per_update = waves * VALU_PER_WAVE_ITER_AT_16 * elems / 16.0
+    per_wave = VALU_PER_WAVE_ITER_PAIR if teams_per_cu == 2 else VALU_PER_WAVE_ITER_NARROW if waves <= 2 else VALU_PER_WAVE_ITER_AT_16
+    valu_per_update = waves * per_wave * elems / 16.0
     valu_rate = moves * valu_per_update / (loop_ms * 1e-3)
     traffic, source = load_traffic("cd_fused_kernel", f"{cfg.name}:{mode}")
     r = {"kernel": kernel, "bound": "hbm" if h_bytes > INFINITY_CACHE_BYTES else "cache",
@@ -287,8 +291,8 @@ def loop_roofline(cfg, mode, moves, loop_ms, shape, gather_gbs):
          "traffic": traffic, "algorithmic_bytes_per_launch": cd_bytes, "avg_launch_ms": loop_ms,
          "launch_shape": {"wavefronts_per_column": waves, "coordinates_per_lane": elems,
                           "columns_resident_per_cu": teams_per_cu * max(1, 16 // waves)},
-         "valu_issue": {"instr_per_update_model": valu_per_update, "achieved_instr_per_s": valu_rate,
-                        "chip_issue_rate_instr_per_s": VALU_ISSUE_PEAK, "frac": valu_rate / VALU_ISSUE_PEAK}}
+         "valu_issue": {"issue_slots_per_update_model": valu_per_update, "achieved_slots_per_s": valu_rate,
+                        "chip_issue_rate_slots_per_s": VALU_ISSUE_PEAK, "frac": valu_rate / VALU_ISSUE_PEAK}}
     if traffic is not None:
         r["traffic_source"] = source
         r["traffic_over_algorithmic"] = traffic / cd_bytes if cd_bytes else None
